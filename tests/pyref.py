@@ -1,0 +1,165 @@
+"""Brute-force definitions in Python big integers, for tiny cases only.
+
+This is the yardstick the CPU oracle is pinned against: every function is the
+definition in the paper evaluated term by term (Section 3.3 for multilinear
+extensions and sumcheck rounds, Section 4 for the tlookup summand), with
+`hashlib` as the hash.  Cost is exponential; keep n <= 5.
+"""
+import hashlib
+import itertools
+
+Z = -0xd201000000010000
+R = Z ** 4 - Z ** 2 + 1          # BLS12-381 scalar field order
+
+
+def bits_msb_first(x, n):
+    return [(x >> (n - 1 - t)) & 1 for t in range(n)]
+
+
+def eq(u, w):
+    """e~(u, w) = prod_t (u_t w_t + (1-u_t)(1-w_t)) for field points u, w."""
+    acc = 1
+    for a, b in zip(u, w):
+        acc = acc * ((a * b + (1 - a) * (1 - b)) % R) % R
+    return acc
+
+
+def mle(arr, point):
+    """arr~(point) = sum_x e~(point, bits(x)) arr[x]; point[0] is the top index bit."""
+    n = len(point)
+    assert len(arr) == 1 << n
+    return sum(eq(point, bits_msb_first(x, n)) * arr[x] for x in range(1 << n)) % R
+
+
+class Transcript:
+    def __init__(self, init):
+        self.state = hashlib.sha256(init).digest()
+
+    def absorb(self, tag, data):
+        self.state = hashlib.sha256(self.state + tag.encode() + len(data).to_bytes(8, "little") + data).digest()
+
+    def challenge(self, tag):
+        t = tag.encode()
+        h0 = hashlib.sha256(self.state + t + b"\x00").digest()
+        h1 = hashlib.sha256(self.state + t + b"\x01").digest()
+        self.state = hashlib.sha256(self.state + t + b"\x02").digest()
+        return int.from_bytes(h0 + h1, "big") % R
+
+
+def fr_bytes(x):
+    return int(x % R).to_bytes(32, "little")
+
+
+def m_digest(counts, leaf=128):
+    leaves = b""
+    for base in range(0, len(counts), leaf):
+        leaves += hashlib.sha256(b"".join(int(c).to_bytes(4, "little") for c in counts[base:base + leaf])).digest()
+    return hashlib.sha256(leaves).digest()
+
+
+def round_poly(f, prefix, nvars, X):
+    """g_k(X) = sum over rest in {0,1}^(nvars-k-1) of f(prefix, X, rest)."""
+    k = len(prefix)
+    total = 0
+    for rest in itertools.product((0, 1), repeat=nvars - k - 1):
+        total += f(list(prefix) + [X] + list(rest))
+    return total % R
+
+
+def tlookup_proof(seed, S, T):
+    """The whole tlookup proof from the definitions; S, T lists of ints mod R."""
+    D, N = len(S), len(T)
+    n, l = D.bit_length() - 1, N.bit_length() - 1
+    h = n - l
+    first = {}
+    for j, t in enumerate(T):
+        first.setdefault(t, j)
+    m = [0] * N
+    for s in S:
+        m[first[s]] += 1
+    tr = Transcript(b"zkmi/tlookup/v1" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little"))
+    md = m_digest(m)
+    tr.absorb("m", md)
+    beta = tr.challenge("beta")
+    A = [pow(beta + s, -1, R) for s in S]
+    B = [pow(beta + t, -1, R) for t in T]
+    alpha = tr.challenge("alpha")
+    u = [tr.challenge("u") for _ in range(n)]
+    scale = pow(pow(2, h, R), -1, R)
+
+    def f(w):
+        wt = w[h:]
+        left = mle(A, w) * ((alpha * eq(u, w) % R) * ((mle(S, w) + beta) % R) + 1) % R
+        right = scale * mle(B, wt) % R * ((alpha * alpha % R) * eq(u[h:], wt) % R * ((mle(T, wt) + beta) % R) - mle(m, wt)) % R
+        return (left + right) % R
+
+    out = b"ZKTL" + (1).to_bytes(4, "little") + D.to_bytes(8, "little") + N.to_bytes(8, "little") + md
+    v = []
+    polys = []
+    for k in range(n):
+        g = [round_poly(f, v, n, X) for X in range(5)]
+        polys.append(g)
+        msg = b"".join(fr_bytes(y) for y in g[:4])
+        out += msg
+        tr.absorb("g", msg)
+        v.append(tr.challenge("r"))
+    vt = v[h:]
+    fin = [mle(A, v), mle(S, v), mle(B, vt), mle(m, vt), mle(T, vt)]
+    out += b"".join(fr_bytes(y) for y in fin)
+    return out, {"beta": beta, "alpha": alpha, "u": u, "v": v, "m": m, "A": A, "B": B, "polys": polys, "f": f}
+
+
+def _ceil_log2(v):
+    return max((v - 1).bit_length(), 0)
+
+
+def product_rounds(tr, a, b):
+    """Rounds of sum_x a(x) b(x) from the definition; returns (bytes, challenges)."""
+    d = len(a).bit_length() - 1
+    f = lambda w: mle(a, w) * mle(b, w) % R
+    out, r = b"", []
+    for k in range(d):
+        g = [round_poly(f, r, d, X) for X in range(3)]
+        msg = b"".join(fr_bytes(y) for y in g)
+        out += msg
+        tr.absorb("g", msg)
+        r.append(tr.challenge("r"))
+    fin = fr_bytes(mle(a, r)) + fr_bytes(mle(b, r))
+    tr.absorb("final", fin)
+    return out + fin, r
+
+
+def product_proof(seed, a, b, claim):
+    d = len(a).bit_length() - 1
+    tr = Transcript(b"zkmi/sumcheck-product/v1" + seed + d.to_bytes(8, "little"))
+    tr.absorb("claim", fr_bytes(claim))
+    body, r = product_rounds(tr, a, b)
+    return b"ZKSP" + (1).to_bytes(4, "little") + d.to_bytes(8, "little") + fr_bytes(claim) + body, r
+
+
+def matmul_proof(seed, X, W):
+    """X, W: lists of rows of Python ints (signed).  Everything from the definitions:
+    the claim is the multilinear extension of the integer product X W at (u, v)."""
+    D0, D1, D2 = len(X), len(W), len(W[0])
+    n0, n1, n2 = _ceil_log2(D0), _ceil_log2(D1), _ceil_log2(D2)
+    tr = Transcript(b"zkmi/matmul/v1" + seed + b"".join(d.to_bytes(8, "little") for d in (D0, D1, D2)))
+    u = [tr.challenge("u") for _ in range(n0)]
+    v = [tr.challenge("v") for _ in range(n2)]
+    Y = [[sum(X[i][k] * W[k][j] for k in range(D1)) for j in range(D2)] for i in range(D0)]
+
+    def padded(M, rows, cols, nr, nc):
+        flat = [0] * ((1 << nr) * (1 << nc))
+        for i in range(rows):
+            for j in range(cols):
+                flat[i * (1 << nc) + j] = M[i][j] % R
+        return flat
+
+    claim = mle(padded(Y, D0, D2, n0, n2), u + v)
+    Xp, Wp = padded(X, D0, D1, n0, n1), padded(W, D1, D2, n1, n2)
+    a = [mle(Xp, u + bits_msb_first(k, n1)) for k in range(1 << n1)]
+    b = [mle(Wp, bits_msb_first(k, n1) + v) for k in range(1 << n1)]
+    tr.absorb("claim", fr_bytes(claim))
+    body, r = product_rounds(tr, a, b)
+    head = b"ZKMM" + (1).to_bytes(4, "little") + b"".join(d.to_bytes(8, "little") for d in (D0, D1, D2))
+    return head + fr_bytes(claim) + body, {"u": u, "v": v, "r": r, "claim": claim, "Y": Y,
+                                           "Xr": mle(Xp, u + r), "Wr": mle(Wp, r + v)}
