@@ -1,0 +1,247 @@
+/*
+ * zkmi -- tlookup / sumcheck prover hot path of zkLLM on one AMD MI355X (gfx950).
+ *
+ * C boundary of the device library.  Every entry point is plain C: pointers
+ * (each comment says host or device), sizes, no C++ or framework types.
+ *
+ * Field.  All arithmetic is in the BLS12-381 scalar field Fr (the paper's
+ * implementation field, Section 7.2), r = z^4 - z^2 + 1, z = -0xd201000000010000.
+ *
+ * Host scalars   : fr_t, eight 32-bit limbs, least significant first, the
+ *                  canonical integer in [0, r).  Not Montgomery form.
+ * Device vectors : fr_vec, limb-major structure of arrays in MONTGOMERY form
+ *                  (x * 2^256 mod r, always fully reduced): limb k of element i
+ *                  is limbs[k * stride + i], stride >= n.  A wavefront reading
+ *                  one limb of 64 consecutive elements reads 256 contiguous bytes.
+ *
+ * Ownership.  The caller owns every buffer: inputs, outputs and workspace.  No
+ * entry point allocates device memory; `*_workspace_bytes` says how much
+ * workspace a call needs.  Inputs are not modified unless the comment says "in
+ * place".  `stream` is a hipStream_t passed as void* (NULL = the null stream);
+ * all device work of a call is enqueued on it.  Calls that return host values
+ * (proofs, sums, error codes that depend on data) synchronise that stream
+ * before returning; the others only enqueue.
+ *
+ * Errors.  Every function returns ZK_OK or a negative code; nothing is thrown.
+ * On error the contents of output buffers are unspecified.
+ *
+ * Index and variable order (the paper fixes PyTorch flattening and 0-based
+ * indices in Section 3.1; the bit order is this library's reading): element x
+ * of a vector of 2^n entries has bits x = sum b_t 2^t; a point is written
+ * (w_0, ..., w_{n-1}) with w_0 belonging to the TOP bit b_{n-1}.  Sumcheck
+ * rounds bind w_0 first.
+ *
+ * Fiat-Shamir.  The paper's protocols are interactive; here verifier messages
+ * come from a SHA-256 transcript:
+ *   absorb(tag, data): state <- SHA256(state || tag || LE64(len) || data)
+ *   challenge(tag)   : c = (SHA256(state||tag||0x00) || SHA256(state||tag||0x01))
+ *                          as a 512-bit big-endian integer, mod r;
+ *                      state <- SHA256(state || tag || 0x02)
+ * Field elements enter the transcript and the proofs as 32 little-endian bytes
+ * of the canonical integer.
+ */
+#ifndef ZKMI_H
+#define ZKMI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ZK_OK = 0,
+    ZK_E_BADARG = -1,       /* null pointer, bad size, D or N not a power of two, N > D */
+    ZK_E_NOT_IN_TABLE = -2, /* some S_i is not an entry of T */
+    ZK_E_ZERO_DENOM = -3,   /* an element to invert is zero (beta + S_i = 0 or beta + T_j = 0) */
+    ZK_E_REJECT = -4,       /* verifiers only: the proof does not verify */
+    ZK_E_BUFSZ = -5,        /* proof buffer or workspace too small */
+    ZK_E_HIP = -6           /* a HIP runtime call failed */
+};
+
+typedef struct {
+    uint32_t l[8];
+} fr_t;
+
+typedef struct {
+    uint32_t* limbs; /* device */
+    size_t n;        /* number of elements */
+    size_t stride;   /* distance, in uint32_t, between consecutive limb planes */
+} fr_vec;
+
+/* ---- field library ------------------------------------------------------- */
+
+/* Constants of the field as the library uses them, for checking against an
+ * independent computation: modulus r, 2^256 mod r, 2^512 mod r (canonical
+ * limbs) and -r^-1 mod 2^32.  All host pointers. */
+int fr_constants(fr_t* modulus, fr_t* mont_r, fr_t* mont_r2, uint32_t* neg_inv32);
+
+/* dst_i = src_i embedded in Fr: x >= 0 is x, x < 0 is r - |x| (fixed-point
+ * tensors are "discretized into a finite field", Section 3.3).  src: device. */
+int fr_from_i32(fr_vec dst, const int32_t* src, size_t n, void* stream);
+
+/* Conversion between device vectors and canonical array-of-structures form
+ * (element i = 8 consecutive little-endian uint32_t, value < r).  aos: device.
+ * fr_from_canonical does not check that the input is < r. */
+int fr_from_canonical(fr_vec dst, const uint32_t* aos, size_t n, void* stream);
+int fr_to_canonical(uint32_t* aos, fr_vec src, size_t n, void* stream);
+
+/* Elementwise dst = a (op) b over dst.n elements; dst may alias a or b. */
+int fr_add(fr_vec dst, fr_vec a, fr_vec b, void* stream);
+int fr_sub(fr_vec dst, fr_vec a, fr_vec b, void* stream);
+int fr_mul(fr_vec dst, fr_vec a, fr_vec b, void* stream);
+
+/* dst = x + s, dst = x * s, dst = x + s * y with a host scalar s.  fr_axpy is
+ * the pair-table combination X + rho Y of Section 4 (last paragraph). */
+int fr_add_scalar(fr_vec dst, fr_vec x, const fr_t* s, void* stream);
+int fr_mul_scalar(fr_vec dst, fr_vec x, const fr_t* s, void* stream);
+int fr_axpy(fr_vec dst, fr_vec x, const fr_t* s, fr_vec y, void* stream);
+
+/* dst_i = 1 / src_i for all i (the inverse vectors A and B of Section 4 are
+ * this applied to beta + S and beta + T).  One field inversion in total, on the
+ * host; everything else is products on the device.  dst may alias src.
+ * Returns ZK_E_ZERO_DENOM if any src_i is zero.  Synchronises the stream. */
+size_t fr_batch_inverse_workspace_bytes(size_t n);
+int fr_batch_inverse(fr_vec dst, fr_vec src, void* ws, size_t ws_bytes, void* stream);
+
+/* *out = sum_i a_i (host, canonical).  Synchronises the stream. */
+size_t fr_sum_workspace_bytes(size_t n);
+int fr_sum(fr_t* out, fr_vec a, void* ws, size_t ws_bytes, void* stream);
+
+/* dst_x = e~(u, x) = prod_t (u_t x_t + (1-u_t)(1-x_t)) for all x in
+ * {0,1}^nvars (Section 3.3; the product, which restricts to the equality
+ * indicator on bits).  u: host, nvars elements; dst.n = 2^nvars. */
+int fr_eq_table(fr_vec dst, const fr_t* u, int nvars, void* stream);
+
+/* *out = a~(point), the multilinear extension of a (2^nvars elements) at a host
+ * point (Section 3.3).  Synchronises the stream. */
+size_t fr_mle_eval_workspace_bytes(int nvars);
+int fr_mle_eval(fr_t* out, fr_vec a, const fr_t* point, int nvars, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- tlookup (Section 4, Protocol 1) ---------------------------------------- */
+
+/* What the prover also reports, for checks: the challenges and the two sides of
+ * the log-derivative identity sum_i A_i = sum_j m_j B_j at beta. */
+typedef struct {
+    fr_t beta, alpha;
+    fr_t sum_A, sum_mB;
+    uint64_t bad_index; /* on ZK_E_NOT_IN_TABLE: the smallest i with S_i outside T */
+} tlookup_aux;
+
+/* Tensors standing in for the openings of the commitments in tlookup_verify.
+ * Any member may be empty (limbs == NULL / m == NULL): that claim is then not
+ * checked against its tensor. */
+typedef struct {
+    fr_vec S;          /* D elements, device */
+    fr_vec A;          /* D elements, device */
+    fr_vec B;          /* N elements, device */
+    const uint32_t* m; /* N counts, device */
+} tlookup_witness;
+
+typedef struct {
+    fr_t A_v, S_v, B_vp, m_vp, T_vp; /* claimed values at v and v' = v_[log2(D/N):] */
+    fr_t v[32];                      /* the sumcheck point, log2 D entries used */
+    int nvars;
+} tlookup_claims;
+
+/* m_j = |{i : S_i = T_j}| as 32-bit counts (Section 4).  If T has equal entries
+ * an S_i is counted at the lowest such j.  idx (device, D entries) may give the
+ * table row of every S_i; S_i == T[idx_i] is still checked.  With idx == NULL
+ * rows are found through a hash table of T built in the workspace.
+ * m: device, N counters, overwritten.  *bad_index (host, may be NULL) receives
+ * the smallest offending i on ZK_E_NOT_IN_TABLE.  Synchronises the stream. */
+size_t tlookup_workspace_bytes(size_t D, size_t N);
+int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T, void* ws, size_t ws_bytes,
+                           uint64_t* bad_index, void* stream);
+
+/* Proof that every element of S (D elements) is an entry of T (N elements);
+ * D, N powers of two, N <= D <= 2^31 (Protocol 1, "Require").  Steps: multiplicities,
+ * beta, A = 1/(beta+S), B = 1/(beta+T), alpha, u, then the sumcheck of
+ *   alpha + alpha^2 = sum_{x = i (+) j} A(x)(alpha e~(u,x)(S(x)+beta) + 1)
+ *                     + (N/D) B(j)(alpha^2 e~(u_[h:],j)(T(j)+beta) - m(j)),  h = log2(D/N),
+ * round polynomials sent as their values at X = 0,1,2,3, and the five final
+ * claims A~(v), S~(v), B~(v'), m~(v'), T~(v').  The commitments of Protocol 1
+ * are outside this library: `seed` (host, 32 bytes) stands in for those of T
+ * and S, a digest of m for that of m.
+ *
+ * Transcript: SHA256("zkmi/tlookup/v1" || seed || LE64 D || LE64 N); absorb("m",
+ * digest) ; beta = challenge("beta"); alpha = challenge("alpha"); u_t =
+ * challenge("u"), t = 0..n-1; per round absorb("g", 4 values), r = challenge("r");
+ * absorb("final", 5 claims).  digest(m) = SHA256 of the concatenated SHA256
+ * digests of the leaves of 128 counts, each count 4 little-endian bytes.
+ *
+ * Proof (host buffer, tlookup_proof_bytes(D) bytes):
+ *   "ZKTL" | u32 1 | LE64 D | LE64 N | digest(m) | n x 4 elements | 5 elements.
+ * *len (host) receives the size, also on ZK_E_BUFSZ.  aux: host, may be NULL.
+ * ws: device, at least tlookup_workspace_bytes(D, N).  Synchronises the stream. */
+size_t tlookup_proof_bytes(size_t D);
+int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
+                  size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
+
+/* As tlookup_prove with beta replaced by *forced_beta (host) after the
+ * transcript has produced its own: the only way to reach the completeness
+ * failure of Protocol 1 (beta + S_i = 0, Section 6.3) deliberately.  For tests. */
+int tlookup_prove_with_beta(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
+                            uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
+                            void* stream);
+
+/* Verifier: replays the transcript, checks g_k(0) + g_k(1) against the running
+ * claim in every round and the final identity, recomputes T~(v') from the public
+ * table (device), and, for each tensor given in *witness, recomputes that claim
+ * from the tensor (standing in for the proofs of evaluation on commitments,
+ * which are outside this library).  Returns ZK_OK (accept) or ZK_E_REJECT.
+ * claims: host, may be NULL.  ws: device, tlookup_verify_workspace_bytes(D, N). */
+size_t tlookup_verify_workspace_bytes(size_t D, size_t N);
+int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
+                   const tlookup_witness* witness, tlookup_claims* claims, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- product sumcheck and matrix multiplication (Sections 3.3, 6.1.1) -------- */
+
+/* Sumcheck of sum_{x in {0,1}^d} a(x) b(x) = claim over vectors of 2^d elements
+ * (device, both folded IN PLACE: on return element 0 of each holds its final
+ * value, the rest is scratch).  Round polynomials (degree 2) are sent as values
+ * at X = 0,1,2.  Transcript: SHA256("zkmi/sumcheck-product/v1" || seed || LE64 d);
+ * absorb("claim", claim); per round absorb("g", 3 values), r = challenge("r");
+ * absorb("final", a~(r), b~(r)).
+ * Proof: "ZKSP" | u32 1 | LE64 d | claim | d x 3 elements | a~(r) | b~(r). */
+size_t sumcheck_product_proof_bytes(size_t n);
+size_t sumcheck_product_workspace_bytes(size_t n);
+int sumcheck_prove_product(const uint8_t seed[32], fr_vec a, fr_vec b, const fr_t* claim, uint8_t* proof, size_t cap,
+                           size_t* len, void* ws, size_t ws_bytes, void* stream);
+
+/* Host-only verifier of the above: round consistency and last claim =
+ * a~(r) b~(r) as stated in the proof.  final_claims (host, may be NULL)
+ * receives a~(r), b~(r); point (host, may be NULL) the d challenges. */
+int sumcheck_verify_product(const uint8_t seed[32], const uint8_t* proof, size_t len, size_t n, fr_t final_claims[2],
+                            fr_t* point);
+
+/* Proof of Y = X W for X (D0 x D1) and W (D1 x D2), row-major device vectors
+ * (element (i,k) of X at index i*D1 + k), following Section 6.1.1:
+ *   Y~(u,v) = sum_{k in {0,1}^ceil(log2 D1)} X~(u,k) W~(k,v).
+ * Dimensions need not be powers of two (zero padding, Section 3.3).  Transcript:
+ * SHA256("zkmi/matmul/v1" || seed || LE64 D0 || LE64 D1 || LE64 D2); u_t =
+ * challenge("u") x ceil(log2 D0), v_t = challenge("v") x ceil(log2 D2); the
+ * library forms a_k = X~(u,k), b_k = W~(k,v) and the claim sum_k a_k b_k, then
+ * absorb("claim") and the product-sumcheck rounds.
+ * Proof: "ZKMM" | u32 1 | LE64 D0 | LE64 D1 | LE64 D2 | claim | d x 3 elements
+ *        | X~(u,r) | W~(r,v),  d = ceil(log2 D1). */
+size_t matmul_proof_bytes(size_t D1);
+size_t matmul_workspace_bytes(size_t D0, size_t D1, size_t D2);
+int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1, fr_vec W, size_t D2, uint8_t* proof,
+                          size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream);
+
+/* Verifier of the above: rounds and last claim as in sumcheck_verify_product;
+ * for each of Y (D0 x D2), X, W given (device, may be empty) the corresponding
+ * claim Y~(u,v), X~(u,r), W~(r,v) is recomputed from the tensor. */
+size_t matmul_verify_workspace_bytes(size_t D0, size_t D1, size_t D2);
+int matmul_sumcheck_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, size_t D0, size_t D1, size_t D2,
+                           fr_vec Y, fr_vec X, fr_vec W, void* ws, size_t ws_bytes, void* stream);
+
+/* Library version (major * 100 + minor). */
+int zkmi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZKMI_H */

@@ -1,0 +1,210 @@
+// Batched inversion by the product trick, arranged for a GPU:
+//
+//   down pass  : every thread multiplies up its K elements (stride 256 within a
+//                block, so loads stay coalesced), storing the running products,
+//                and emits its total into the next, 256*K times smaller, level;
+//   top        : one workgroup scans the last level (<= 256 values); the host
+//                inverts the single grand total (the only field inversion);
+//   up pass    : each thread receives the inverse of its own total and walks
+//                back over its elements: out_j = inv * prefix_{j-1}, inv *= x_j.
+//
+// Cost: about 3 multiplications per element plus a geometric tail.  A zero
+// anywhere makes the grand total zero, which is how it is detected.
+#include "internal.h"
+
+namespace zkmi {
+
+static const int kBiK = 16;  // elements per thread per level
+
+__device__ __forceinline__ Fr bi_load(const uint32_t* __restrict__ src, size_t ss, size_t i, bool shifted,
+                                      const Fr& shift) {
+    Fr x = fr_load(src, ss, i);
+    return shifted ? fr_add(x, shift) : x;
+}
+
+// prefix_i = product of this thread's elements up to and including i; the
+// thread's total goes to next[tid].
+__global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__ src, size_t ss, size_t n, int shifted,
+                                                    Fr shift, uint32_t* __restrict__ prefix, size_t ps,
+                                                    uint32_t* __restrict__ next, size_t ns) {
+    size_t tid = blockIdx.x * (size_t)kBlock + threadIdx.x;
+    size_t base = blockIdx.x * (size_t)kBlock * kBiK + threadIdx.x;
+    Fr acc = fr_one();
+    bool first = true;
+    for (int j = 0; j < kBiK; ++j) {
+        size_t i = base + (size_t)j * kBlock;
+        if (i < n) {
+            Fr x = bi_load(src, ss, i, shifted, shift);
+            acc = first ? x : fr_mul(acc, x);
+            first = false;
+            fr_store(prefix, ps, i, acc);
+        }
+    }
+    fr_store(next, ns, tid, acc);
+}
+
+// inv_next[tid] = inverse of this thread's total.  out may be the prefix buffer.
+__global__ void __launch_bounds__(kBlock) k_bi_up(const uint32_t* __restrict__ src, size_t ss, size_t n, int shifted,
+                                                  Fr shift, const uint32_t* prefix, size_t ps,
+                                                  const uint32_t* __restrict__ inv_next, size_t is, uint32_t* out,
+                                                  size_t os) {
+    size_t tid = blockIdx.x * (size_t)kBlock + threadIdx.x;
+    size_t base = blockIdx.x * (size_t)kBlock * kBiK + threadIdx.x;
+    Fr inv = fr_load(inv_next, is, tid);
+    for (int j = kBiK - 1; j >= 0; --j) {
+        size_t i = base + (size_t)j * kBlock;
+        if (i < n) {
+            if (j > 0) {
+                Fr before = fr_load(prefix, ps, i - kBlock);
+                Fr x = bi_load(src, ss, i, shifted, shift);
+                fr_store(out, os, i, fr_mul(inv, before));
+                inv = fr_mul(inv, x);
+            } else {
+                fr_store(out, os, i, inv);
+            }
+        }
+    }
+}
+
+// Inclusive scan of products over one workgroup (Hillis-Steele in LDS).
+__device__ __forceinline__ Fr block_scan_mul(Fr v, uint32_t* lds, bool reverse) {
+    const int t = threadIdx.x;
+    for (int off = 1; off < kBlock; off <<= 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) lds[k * kBlock + t] = v.l[k];
+        __syncthreads();
+        int partner = reverse ? t + off : t - off;
+        if (partner >= 0 && partner < kBlock) {
+            Fr o;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o.l[k] = lds[k * kBlock + partner];
+            v = fr_mul(v, o);
+        }
+        __syncthreads();
+    }
+    return v;
+}
+
+// Grand total of the last level (n <= 256) to total_words (Montgomery limbs).
+__global__ void __launch_bounds__(kBlock) k_bi_top_total(const uint32_t* __restrict__ src, size_t ss, size_t n,
+                                                         int shifted, Fr shift, uint32_t* total_words) {
+    __shared__ uint32_t lds[8 * kBlock];
+    Fr x = threadIdx.x < n ? bi_load(src, ss, threadIdx.x, shifted, shift) : fr_one();
+    Fr p = block_scan_mul(x, lds, false);
+    if (threadIdx.x == kBlock - 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) total_words[k] = p.l[k];
+    }
+}
+
+// out_t = inv_total * (product of the others) for the last level.
+__global__ void __launch_bounds__(kBlock) k_bi_top_finish(const uint32_t* __restrict__ src, size_t ss, size_t n,
+                                                          int shifted, Fr shift, Fr inv_total, uint32_t* out,
+                                                          size_t os) {
+    __shared__ uint32_t lds[8 * kBlock];
+    const int t = threadIdx.x;
+    Fr x = (size_t)t < n ? bi_load(src, ss, t, shifted, shift) : fr_one();
+    Fr pre = block_scan_mul(x, lds, false);  // x_0 .. x_t
+    Fr suf = block_scan_mul(x, lds, true);   // x_t .. x_255
+    // exclusive neighbours through LDS
+#pragma unroll
+    for (int k = 0; k < 8; ++k) lds[k * kBlock + t] = pre.l[k];
+    __syncthreads();
+    Fr before = fr_one();
+    if (t > 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) before.l[k] = lds[k * kBlock + t - 1];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 8; ++k) lds[k * kBlock + t] = suf.l[k];
+    __syncthreads();
+    Fr after = fr_one();
+    if (t < kBlock - 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) after.l[k] = lds[k * kBlock + t + 1];
+    }
+    if ((size_t)t < n) fr_store(out, os, t, fr_mul(inv_total, fr_mul(before, after)));
+}
+
+static size_t bi_next_size(size_t n) { return div_up(n, (size_t)kBlock * kBiK) * kBlock; }
+
+size_t batch_inverse_scratch_bytes(size_t n) {
+    Carver cv(nullptr, 0);
+    size_t m = n;
+    while (m > (size_t)kBlock) {
+        m = bi_next_size(m);
+        cv.limbs(m);  // level values
+        cv.limbs(m);  // level prefixes, then inverses
+    }
+    return cv.used();
+}
+
+int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride, size_t n,
+                      const host::F& shift, Carver& cv, Mailbox* mb, hipStream_t stream) {
+    if (n == 0) return ZK_OK;
+    struct Level {
+        const uint32_t* x;
+        size_t xs;
+        uint32_t* p;
+        size_t ps;
+        size_t n;
+        int shifted;
+    };
+    Level lv[16];
+    int depth = 0;
+    int shifted0 = host::is_zero(shift) ? 0 : 1;
+    Fr sh = to_dev(shift);
+    lv[0] = Level{src, src_stride, dst, dst_stride, n, shifted0};
+    while (lv[depth].n > (size_t)kBlock) {
+        size_t m = bi_next_size(lv[depth].n);
+        uint32_t* x = cv.limbs(m);
+        uint32_t* p = cv.limbs(m);
+        if (!x || !p) return ZK_E_BUFSZ;
+        const Level& cur = lv[depth];
+        hipLaunchKernelGGL(k_bi_down, dim3((unsigned)(m / kBlock)), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n,
+                           cur.shifted, sh, cur.p, cur.ps, x, m);
+        ++depth;
+        lv[depth] = Level{x, m, p, m, m, 0};
+    }
+    const Level& top = lv[depth];
+    hipLaunchKernelGGL(k_bi_top_total, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, sh,
+                       mb->words);
+    ZK_HIP_TRY(hipGetLastError());
+    ZK_HIP_TRY(hipStreamSynchronize(stream));
+    host::F total = from_dev(mb->words);
+    if (host::is_zero(total)) return ZK_E_ZERO_DENOM;
+    Fr inv_total = to_dev(host::inv(total));
+    hipLaunchKernelGGL(k_bi_top_finish, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, sh,
+                       inv_total, top.p, top.ps);
+    for (int d = depth - 1; d >= 0; --d) {
+        const Level& cur = lv[d];
+        const Level& up = lv[d + 1];
+        hipLaunchKernelGGL(k_bi_up, dim3((unsigned)(up.n / kBlock)), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n,
+                           cur.shifted, sh, cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps);
+    }
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+}  // namespace zkmi
+
+using namespace zkmi;
+
+extern "C" {
+
+size_t fr_batch_inverse_workspace_bytes(size_t n) { return batch_inverse_scratch_bytes(n); }
+
+int fr_batch_inverse(fr_vec dst, fr_vec src, void* ws, size_t ws_bytes, void* stream) {
+    size_t n = dst.n;
+    if (!vec_ok(dst, n) || !vec_ok(src, n)) return ZK_E_BADARG;
+    if (n == 0) return ZK_OK;
+    if (dst.limbs == src.limbs) return ZK_E_BADARG;
+    if (!ws || ws_bytes < batch_inverse_scratch_bytes(n)) return ZK_E_BUFSZ;
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    return batch_inverse_run(dst.limbs, dst.stride, src.limbs, src.stride, n, host::zero(), cv, mb, as_stream(stream));
+}
+
+}  // extern "C"

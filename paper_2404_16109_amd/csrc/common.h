@@ -1,0 +1,99 @@
+// Shared host-side plumbing of the library: error handling, argument checks,
+// workspace carving and the pinned "mailbox" through which kernels hand small
+// results (sums, round values, flags) to the host.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/zkmi.h"
+#include "fr_dev.h"
+#include "host_fr.h"
+
+#define ZK_HIP_TRY(expr)                         \
+    do {                                         \
+        if ((expr) != hipSuccess) return ZK_E_HIP; \
+    } while (0)
+
+#define ZK_TRY(expr)              \
+    do {                          \
+        int zk_rc_ = (expr);      \
+        if (zk_rc_ != ZK_OK) return zk_rc_; \
+    } while (0)
+
+namespace zkmi {
+
+static const int kBlock = 256;  // threads per workgroup: four wavefronts
+
+inline bool vec_ok(const fr_vec& v, size_t n) { return v.limbs != nullptr && v.n >= n && v.stride >= v.n; }
+inline bool is_pow2(size_t v) { return v != 0 && (v & (v - 1)) == 0; }
+inline int log2_floor(size_t v) {
+    int n = 0;
+    while ((v >> n) > 1) ++n;
+    return n;
+}
+inline int log2_ceil(size_t v) {
+    int n = 0;
+    while (((size_t)1 << n) < v) ++n;
+    return n;
+}
+inline size_t div_up(size_t a, size_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t a, size_t b) { return div_up(a, b) * b; }
+
+// Bump allocator over the caller's workspace; every block is 256-byte aligned.
+// With base == nullptr it only measures.
+class Carver {
+public:
+    Carver(void* base, size_t bytes) : base_((uint8_t*)base), cap_(bytes), used_(0) {
+        // the caller's pointer need not be aligned
+        size_t mis = (size_t)((uintptr_t)base_ & 255);
+        if (base_ && mis) used_ = 256 - mis;
+    }
+    void* take(size_t bytes) {
+        size_t off = used_;
+        used_ = align_up(used_ + bytes, 256);
+        if (!base_) return nullptr;
+        if (used_ > cap_) return nullptr;
+        return base_ + off;
+    }
+    uint32_t* limbs(size_t n_elements) { return (uint32_t*)take(n_elements * 32); }
+    size_t used() const { return used_ + 256; }  // slack for an unaligned base
+    bool overflow() const { return base_ != nullptr && used_ > cap_; }
+
+private:
+    uint8_t* base_;
+    size_t cap_, used_;
+};
+
+// Pinned, device-visible host memory, one per host thread, allocated on first
+// use and kept: kernels write small results into it directly and the host reads
+// them after synchronising the stream.
+struct Mailbox {
+    uint32_t* words = nullptr;  // kMailboxWords uint32_t
+    uint8_t* bulk = nullptr;    // staging for larger copies (leaf digests)
+    size_t bulk_bytes = 0;
+};
+static const size_t kMailboxWords = 1024;
+
+int mailbox_get(Mailbox** out);
+int mailbox_bulk(Mailbox* mb, size_t bytes);
+
+inline hipStream_t as_stream(void* s) { return (hipStream_t)s; }
+
+// Montgomery scalar as a kernel argument.
+inline Fr to_dev(const host::F& a) {
+    Fr o;
+    host::to_device_limbs(o.l, a);
+    return o;
+}
+inline host::F from_dev(const uint32_t limbs[8]) { return host::from_device_limbs(limbs); }
+
+// Launch geometry for an elementwise pass over n items.
+inline unsigned grid_for(size_t n, size_t per_block = kBlock, size_t max_blocks = (size_t)1 << 20) {
+    size_t g = div_up(n, per_block);
+    if (g > max_blocks) g = max_blocks;
+    if (g == 0) g = 1;
+    return (unsigned)g;
+}
+
+}  // namespace zkmi

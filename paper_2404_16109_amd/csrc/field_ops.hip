@@ -1,0 +1,182 @@
+// Elementwise field kernels and their C entry points: embedding of integers,
+// conversions between canonical and Montgomery limb-major form, add/sub/mul and
+// the scalar variants.
+#include "common.h"
+
+namespace zkmi {
+
+int mailbox_get(Mailbox** out) {
+    static thread_local Mailbox mb;
+    if (!mb.words) {
+        void* p = nullptr;
+        ZK_HIP_TRY(hipHostMalloc(&p, kMailboxWords * sizeof(uint32_t), hipHostMallocDefault));
+        mb.words = (uint32_t*)p;
+    }
+    *out = &mb;
+    return ZK_OK;
+}
+
+int mailbox_bulk(Mailbox* mb, size_t bytes) {
+    if (mb->bulk_bytes >= bytes) return ZK_OK;
+    if (mb->bulk) (void)hipHostFree(mb->bulk);
+    mb->bulk = nullptr;
+    mb->bulk_bytes = 0;
+    void* p = nullptr;
+    size_t want = align_up(bytes, 1 << 16);
+    ZK_HIP_TRY(hipHostMalloc(&p, want, hipHostMallocDefault));
+    mb->bulk = (uint8_t*)p;
+    mb->bulk_bytes = want;
+    return ZK_OK;
+}
+
+// x >= 0 -> x, x < 0 -> r - |x|, in Montgomery form.
+__global__ void __launch_bounds__(kBlock) k_from_i32(uint32_t* __restrict__ dst, size_t stride,
+                                                     const int32_t* __restrict__ src, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        int32_t x = src[i];
+        uint32_t mag = x < 0 ? (0u - (uint32_t)x) : (uint32_t)x;
+        Fr m = fr_from_u32(mag);
+        if (x < 0) m = fr_neg(m);
+        fr_store(dst, stride, i, m);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) k_from_canonical(uint32_t* __restrict__ dst, size_t stride,
+                                                           const uint32_t* __restrict__ aos, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        Fr c;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) c.l[k] = aos[i * 8 + k];
+        fr_store(dst, stride, i, fr_to_mont(c));
+    }
+}
+
+__global__ void __launch_bounds__(kBlock) k_to_canonical(uint32_t* __restrict__ aos, const uint32_t* __restrict__ src,
+                                                         size_t stride, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        Fr c = fr_from_mont(fr_load(src, stride, i));
+#pragma unroll
+        for (int k = 0; k < 8; ++k) aos[i * 8 + k] = c.l[k];
+    }
+}
+
+enum { OP_ADD = 0, OP_SUB = 1, OP_MUL = 2 };
+
+template <int OP>
+__global__ void __launch_bounds__(kBlock) k_binary(uint32_t* dst, size_t ds, const uint32_t* a, size_t as,
+                                                   const uint32_t* b, size_t bs, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        Fr x = fr_load(a, as, i), y = fr_load(b, bs, i);
+        Fr z = OP == OP_ADD ? fr_add(x, y) : OP == OP_SUB ? fr_sub(x, y) : fr_mul(x, y);
+        fr_store(dst, ds, i, z);
+    }
+}
+
+enum { SC_ADD = 0, SC_MUL = 1, SC_AXPY = 2 };
+
+template <int OP>
+__global__ void __launch_bounds__(kBlock) k_scalar(uint32_t* dst, size_t ds, const uint32_t* x, size_t xs, Fr s,
+                                                   const uint32_t* y, size_t ys, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        Fr a = fr_load(x, xs, i);
+        Fr z;
+        if (OP == SC_ADD) z = fr_add(a, s);
+        else if (OP == SC_MUL) z = fr_mul(a, s);
+        else z = fr_add(a, fr_mul(s, fr_load(y, ys, i)));
+        fr_store(dst, ds, i, z);
+    }
+}
+
+template <int OP>
+static int launch_binary(fr_vec dst, fr_vec a, fr_vec b, void* stream) {
+    size_t n = dst.n;
+    if (!vec_ok(dst, n) || !vec_ok(a, n) || !vec_ok(b, n)) return ZK_E_BADARG;
+    if (n == 0) return ZK_OK;
+    hipLaunchKernelGGL(k_binary<OP>, dim3(grid_for(n)), dim3(kBlock), 0, as_stream(stream), dst.limbs, dst.stride,
+                       a.limbs, a.stride, b.limbs, b.stride, n);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+template <int OP>
+static int launch_scalar(fr_vec dst, fr_vec x, const fr_t* s, const fr_vec* y, void* stream) {
+    size_t n = dst.n;
+    if (!s || !vec_ok(dst, n) || !vec_ok(x, n) || (y && !vec_ok(*y, n))) return ZK_E_BADARG;
+    if (!host::canonical_in_range(*s)) return ZK_E_BADARG;
+    if (n == 0) return ZK_OK;
+    Fr sm = to_dev(host::from_canonical(*s));
+    hipLaunchKernelGGL(k_scalar<OP>, dim3(grid_for(n)), dim3(kBlock), 0, as_stream(stream), dst.limbs, dst.stride,
+                       x.limbs, x.stride, sm, y ? y->limbs : nullptr, y ? y->stride : 0, n);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+}  // namespace zkmi
+
+using namespace zkmi;
+
+extern "C" {
+
+int zkmi_version(void) { return 100; }
+
+int fr_constants(fr_t* modulus, fr_t* mont_r, fr_t* mont_r2, uint32_t* neg_inv32) {
+    if (!modulus || !mont_r || !mont_r2 || !neg_inv32) return ZK_E_BADARG;
+    const uint32_t r[8] = {ZK_R0, ZK_R1, ZK_R2, ZK_R3, ZK_R4, ZK_R5, ZK_R6, ZK_R7};
+    const uint32_t one[8] = {ZK_ONE0, ZK_ONE1, ZK_ONE2, ZK_ONE3, ZK_ONE4, ZK_ONE5, ZK_ONE6, ZK_ONE7};
+    const uint32_t rr[8] = {ZK_RR0, ZK_RR1, ZK_RR2, ZK_RR3, ZK_RR4, ZK_RR5, ZK_RR6, ZK_RR7};
+    for (int k = 0; k < 8; ++k) {
+        modulus->l[k] = r[k];
+        mont_r->l[k] = one[k];
+        mont_r2->l[k] = rr[k];
+    }
+    *neg_inv32 = 0xffffffffu;
+    // the host glue carries its own copies; they must agree
+    for (int k = 0; k < 4; ++k) {
+        if (host::kMod[k] != ((uint64_t)r[2 * k] | ((uint64_t)r[2 * k + 1] << 32))) return ZK_E_BADARG;
+        if (host::kOne[k] != ((uint64_t)one[2 * k] | ((uint64_t)one[2 * k + 1] << 32))) return ZK_E_BADARG;
+        if (host::kRR[k] != ((uint64_t)rr[2 * k] | ((uint64_t)rr[2 * k + 1] << 32))) return ZK_E_BADARG;
+    }
+    return ZK_OK;
+}
+
+int fr_from_i32(fr_vec dst, const int32_t* src, size_t n, void* stream) {
+    if (!src || !vec_ok(dst, n)) return ZK_E_BADARG;
+    if (n == 0) return ZK_OK;
+    hipLaunchKernelGGL(k_from_i32, dim3(grid_for(n)), dim3(kBlock), 0, as_stream(stream), dst.limbs, dst.stride, src, n);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+int fr_from_canonical(fr_vec dst, const uint32_t* aos, size_t n, void* stream) {
+    if (!aos || !vec_ok(dst, n)) return ZK_E_BADARG;
+    if (n == 0) return ZK_OK;
+    hipLaunchKernelGGL(k_from_canonical, dim3(grid_for(n)), dim3(kBlock), 0, as_stream(stream), dst.limbs, dst.stride,
+                       aos, n);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+int fr_to_canonical(uint32_t* aos, fr_vec src, size_t n, void* stream) {
+    if (!aos || !vec_ok(src, n)) return ZK_E_BADARG;
+    if (n == 0) return ZK_OK;
+    hipLaunchKernelGGL(k_to_canonical, dim3(grid_for(n)), dim3(kBlock), 0, as_stream(stream), aos, src.limbs,
+                       src.stride, n);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+int fr_add(fr_vec dst, fr_vec a, fr_vec b, void* stream) { return launch_binary<OP_ADD>(dst, a, b, stream); }
+int fr_sub(fr_vec dst, fr_vec a, fr_vec b, void* stream) { return launch_binary<OP_SUB>(dst, a, b, stream); }
+int fr_mul(fr_vec dst, fr_vec a, fr_vec b, void* stream) { return launch_binary<OP_MUL>(dst, a, b, stream); }
+
+int fr_add_scalar(fr_vec dst, fr_vec x, const fr_t* s, void* stream) {
+    return launch_scalar<SC_ADD>(dst, x, s, nullptr, stream);
+}
+int fr_mul_scalar(fr_vec dst, fr_vec x, const fr_t* s, void* stream) {
+    return launch_scalar<SC_MUL>(dst, x, s, nullptr, stream);
+}
+int fr_axpy(fr_vec dst, fr_vec x, const fr_t* s, fr_vec y, void* stream) {
+    return launch_scalar<SC_AXPY>(dst, x, s, &y, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,52 @@
+// Launchers shared between the translation units of the library.
+#pragma once
+#include "common.h"
+
+namespace zkmi {
+
+// ---- batch inversion ------------------------------------------------------
+// dst_i = 1 / (src_i + shift) for i < n (shift in Montgomery form; pass zero for
+// a plain inverse).  dst must not overlap src.  Scratch comes from `cv`.
+// Synchronises the stream once (the single field inversion is done on the host).
+size_t batch_inverse_scratch_bytes(size_t n);
+int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride, size_t n,
+                      const host::F& shift, Carver& cv, Mailbox* mb, hipStream_t stream);
+
+// ---- sums -----------------------------------------------------------------
+// Partial sums buffer for reductions: up to kMaxPartialBlocks blocks.
+static const unsigned kMaxPartialBlocks = 1024;
+
+// Adds up `nv` interleaved per-block partial values (block b, value q at
+// element b*nv + q of `partials`, limb-major with stride pstride) and writes
+// the nv totals, Montgomery limbs, to out_words (device-visible host memory
+// or device memory): value q at out_words[8q .. 8q+8).
+void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
+                      hipStream_t stream);
+
+// sum_i a_i into mailbox words [0, 8).
+size_t sum_scratch_bytes(size_t n);
+int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, uint32_t* out_words, hipStream_t stream);
+
+// ---- eq tables --------------------------------------------------------------
+// dst_x = prod_{t < nvars} (u_t x_t + (1-u_t)(1-x_t)), x in {0,1}^nvars, first
+// variable = top bit.  u: host, Montgomery.
+int eq_table_run(uint32_t* dst, size_t stride, const host::F* u, int nvars, hipStream_t stream);
+
+// ---- multilinear evaluation ---------------------------------------------------
+// a~(point) into out_words[0, 8) (Montgomery); a is not modified.
+size_t mle_scratch_bytes(int nvars);
+int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, uint32_t* out_words,
+                 hipStream_t stream);
+
+// Copies the leading `n` elements of a limb-major vector.
+void launch_copy(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t n, hipStream_t stream);
+
+// One folding pass: dst_p = src_p + r (src_{p+half} - src_p), p < half.
+void launch_fold(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t half, const host::F& r,
+                 hipStream_t stream);
+
+// ---- product sumcheck rounds (shared by sumcheck_prove_product and matmul) ----
+// Runs d rounds over a, b (2^d elements each, folded in place), writing 3 values
+// per round and the two final values to `out` (canonical bytes) and driving the
+// transcript.  Needs product_rounds_scratch_bytes(n) of scratch.
+}  // namespace zkmi

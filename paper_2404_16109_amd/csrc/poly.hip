@@ -1,0 +1,221 @@
+// Sums, eq tables, folding and multilinear evaluation (Section 3.3 of the paper:
+// tensors as functions on the Boolean cube and their multilinear extensions).
+#include "internal.h"
+#include "reduce_dev.h"
+
+namespace zkmi {
+
+// ---- sums -------------------------------------------------------------------
+
+__global__ void __launch_bounds__(kBlock) k_sum_partial(const uint32_t* __restrict__ a, size_t stride, size_t n,
+                                                        uint32_t* __restrict__ partials, size_t pstride) {
+    __shared__ uint32_t lds[4 * 8];
+    Fr acc[1] = {fr_zero()};
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock)
+        acc[0] = fr_add(acc[0], fr_load(a, stride, i));
+    block_sum<1, 4>(acc, lds);
+    if (threadIdx.x == 0) fr_store(partials, pstride, blockIdx.x, acc[0]);
+}
+
+// One workgroup adds up nblocks*nv partial values; value q of block b sits at
+// element b*nv + q.  Totals go out as raw Montgomery limbs.
+__global__ void __launch_bounds__(kBlock) k_final_sum(const uint32_t* __restrict__ partials, size_t pstride,
+                                                      unsigned nblocks, int nv, uint32_t* out_words) {
+    __shared__ uint32_t lds[4 * 8];
+    for (int q = 0; q < nv; ++q) {
+        Fr acc[1] = {fr_zero()};
+        for (unsigned b = threadIdx.x; b < nblocks; b += kBlock)
+            acc[0] = fr_add(acc[0], fr_load(partials, pstride, (size_t)b * nv + q));
+        block_sum<1, 4>(acc, lds);
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc[0].l[k];
+        }
+    }
+}
+
+void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
+                      hipStream_t stream) {
+    hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(kBlock), 0, stream, partials, pstride, nblocks, nv, out_words);
+}
+
+size_t sum_scratch_bytes(size_t) {
+    Carver cv(nullptr, 0);
+    cv.limbs(kMaxPartialBlocks);
+    return cv.used();
+}
+
+int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, uint32_t* out_words, hipStream_t stream) {
+    uint32_t* partials = cv.limbs(kMaxPartialBlocks);
+    if (!partials) return ZK_E_BUFSZ;
+    unsigned blocks = grid_for(n, kBlock * 8, kMaxPartialBlocks);
+    hipLaunchKernelGGL(k_sum_partial, dim3(blocks), dim3(kBlock), 0, stream, a, stride, n, partials,
+                       (size_t)kMaxPartialBlocks);
+    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, out_words, stream);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+// ---- eq tables ----------------------------------------------------------------
+
+struct EqArgs {
+    Fr u[32];    // the point, Montgomery
+    Fr top[16];  // e~ over the first `ntop` variables, computed on the host
+};
+
+// Thread x_lo computes the product over the low nvars-ntop variables once and
+// writes one entry per value of the top bits.
+__global__ void __launch_bounds__(kBlock) k_eq_table(uint32_t* __restrict__ dst, size_t stride, EqArgs args, int nvars,
+                                                     int ntop) {
+    const int nlow = nvars - ntop;
+    const size_t low_count = (size_t)1 << nlow;
+    const Fr one = fr_one();
+    for (size_t x = blockIdx.x * (size_t)kBlock + threadIdx.x; x < low_count; x += (size_t)gridDim.x * kBlock) {
+        Fr acc = one;
+        for (int t = ntop; t < nvars; ++t) {
+            unsigned bit = (unsigned)(x >> (nvars - 1 - t)) & 1u;
+            Fr f = bit ? args.u[t] : fr_sub(one, args.u[t]);
+            acc = (t == ntop) ? f : fr_mul(acc, f);
+        }
+        for (int hi = 0; hi < (1 << ntop); ++hi) {
+            Fr v = nlow ? fr_mul(acc, args.top[hi]) : args.top[hi];
+            fr_store(dst, stride, ((size_t)hi << nlow) + x, v);
+        }
+    }
+}
+
+int eq_table_run(uint32_t* dst, size_t stride, const host::F* u, int nvars, hipStream_t stream) {
+    if (nvars < 0 || nvars > 31) return ZK_E_BADARG;
+    EqArgs args;
+    int ntop = nvars < 4 ? nvars : 4;
+    host::F top[16];
+    top[0] = host::one();
+    for (int t = 0; t < ntop; ++t) {
+        // append variable t below the ones already in the table
+        for (int x = (1 << t) - 1; x >= 0; --x) {
+            host::F hi = host::mul(top[x], u[t]);
+            top[2 * x + 1] = hi;
+            top[2 * x] = host::sub(top[x], hi);
+        }
+    }
+    for (int i = 0; i < 16; ++i) args.top[i] = to_dev(i < (1 << ntop) ? top[i] : host::zero());
+    for (int t = 0; t < 32; ++t) args.u[t] = to_dev(t < nvars ? u[t] : host::zero());
+    size_t low_count = (size_t)1 << (nvars - ntop);
+    hipLaunchKernelGGL(k_eq_table, dim3(grid_for(low_count)), dim3(kBlock), 0, stream, dst, stride, args, nvars, ntop);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+// ---- copy / fold / evaluation ----------------------------------------------------
+
+__global__ void __launch_bounds__(kBlock) k_copy(uint32_t* __restrict__ dst, size_t ds,
+                                                 const uint32_t* __restrict__ src, size_t ss, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) dst[k * ds + i] = src[k * ss + i];
+    }
+}
+
+void launch_copy(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t n, hipStream_t stream) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(k_copy, dim3(grid_for(n)), dim3(kBlock), 0, stream, dst, ds, src, ss, n);
+}
+
+__global__ void __launch_bounds__(kBlock) k_fold(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t half,
+                                                 Fr r) {
+    for (size_t p = blockIdx.x * (size_t)kBlock + threadIdx.x; p < half; p += (size_t)gridDim.x * kBlock) {
+        Fr a0 = fr_load(src, ss, p), a1 = fr_load(src, ss, p + half);
+        fr_store(dst, ds, p, fr_fold(a0, a1, r));
+    }
+}
+
+void launch_fold(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t half, const host::F& r,
+                 hipStream_t stream) {
+    if (half == 0) return;
+    hipLaunchKernelGGL(k_fold, dim3(grid_for(half)), dim3(kBlock), 0, stream, dst, ds, src, ss, half, to_dev(r));
+}
+
+__global__ void k_emit(const uint32_t* __restrict__ a, size_t stride, size_t index, uint32_t* out_words) {
+    if (threadIdx.x < 8) out_words[threadIdx.x] = a[threadIdx.x * stride + index];
+}
+
+size_t mle_scratch_bytes(int nvars) {
+    Carver cv(nullptr, 0);
+    if (nvars >= 1) cv.limbs((size_t)1 << (nvars - 1));
+    return cv.used();
+}
+
+int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, uint32_t* out_words,
+                 hipStream_t stream) {
+    if (nvars == 0) {
+        hipLaunchKernelGGL(k_emit, dim3(1), dim3(64), 0, stream, a, stride, (size_t)0, out_words);
+        ZK_HIP_TRY(hipGetLastError());
+        return ZK_OK;
+    }
+    size_t half = (size_t)1 << (nvars - 1);
+    uint32_t* buf = cv.limbs(half);
+    if (!buf) return ZK_E_BUFSZ;
+    launch_fold(buf, half, a, stride, half, point[0], stream);
+    for (int t = 1; t < nvars; ++t) {
+        half >>= 1;
+        launch_fold(buf, (size_t)1 << (nvars - 1), buf, (size_t)1 << (nvars - 1), half, point[t], stream);
+    }
+    hipLaunchKernelGGL(k_emit, dim3(1), dim3(64), 0, stream, buf, (size_t)1 << (nvars - 1), (size_t)0, out_words);
+    ZK_HIP_TRY(hipGetLastError());
+    return ZK_OK;
+}
+
+}  // namespace zkmi
+
+using namespace zkmi;
+
+extern "C" {
+
+size_t fr_sum_workspace_bytes(size_t n) { return sum_scratch_bytes(n); }
+
+int fr_sum(fr_t* out, fr_vec a, void* ws, size_t ws_bytes, void* stream) {
+    if (!out || (a.n && !vec_ok(a, a.n))) return ZK_E_BADARG;
+    if (a.n == 0) {
+        memset(out, 0, sizeof *out);
+        return ZK_OK;
+    }
+    if (!ws || ws_bytes < sum_scratch_bytes(a.n)) return ZK_E_BUFSZ;
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    ZK_TRY(sum_run(a.limbs, a.stride, a.n, cv, mb->words, as_stream(stream)));
+    ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
+    *out = host::to_canonical(from_dev(mb->words));
+    return ZK_OK;
+}
+
+int fr_eq_table(fr_vec dst, const fr_t* u, int nvars, void* stream) {
+    if (nvars < 0 || nvars > 31 || (nvars && !u) || !vec_ok(dst, (size_t)1 << nvars)) return ZK_E_BADARG;
+    host::F um[32];
+    for (int t = 0; t < nvars; ++t) {
+        if (!host::canonical_in_range(u[t])) return ZK_E_BADARG;
+        um[t] = host::from_canonical(u[t]);
+    }
+    return eq_table_run(dst.limbs, dst.stride, um, nvars, as_stream(stream));
+}
+
+size_t fr_mle_eval_workspace_bytes(int nvars) { return mle_scratch_bytes(nvars); }
+
+int fr_mle_eval(fr_t* out, fr_vec a, const fr_t* point, int nvars, void* ws, size_t ws_bytes, void* stream) {
+    if (!out || nvars < 0 || nvars > 31 || (nvars && !point) || !vec_ok(a, (size_t)1 << nvars)) return ZK_E_BADARG;
+    if (nvars && (!ws || ws_bytes < mle_scratch_bytes(nvars))) return ZK_E_BUFSZ;
+    host::F pm[32];
+    for (int t = 0; t < nvars; ++t) {
+        if (!host::canonical_in_range(point[t])) return ZK_E_BADARG;
+        pm[t] = host::from_canonical(point[t]);
+    }
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    ZK_TRY(mle_eval_run(a.limbs, a.stride, nvars, pm, cv, mb->words, as_stream(stream)));
+    ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
+    *out = host::to_canonical(from_dev(mb->words));
+    return ZK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,593 @@
+// tlookup prover and verifier (Section 4 of the paper, Protocol 1), host
+// orchestration.  All arithmetic on tensors runs in the kernels of
+// tlookup_kernels.h, batch_inverse.hip and poly.hip; the host only drives the
+// Fiat-Shamir transcript and turns the handful of sums a round returns into
+// the round polynomial.
+//
+// How a round is computed.  With x = (X, rest) after binding k variables,
+//   e~(u, x) = c_k * e~(u_k, X) * e_rest(rest),   c_k = prod_{t<k} e~(u_t, r_t),
+// so the data side of g_k is  alpha c_k e~(u_k, X) q(X) + sA(X)  with
+//   q(X) = sum_rest e_rest A(X,rest) (S(X,rest)+beta)   (degree 2 in X),
+//   sA(X) = sum_rest A(X,rest)                          (degree 1),
+// and e_rest never has to be folded: it is looked up in two small tables (low
+// and high remaining variables).  The table side is the constant
+// 2^-(k+1) * c_B while the variable being bound is not one of the table's, and
+// 2^-h (alpha^2 c'_k e~(u_k,X) qT(X) - bm(X)) afterwards.
+#include "internal.h"
+#include "tlookup_kernels.h"
+#include "transcript.h"
+
+namespace zkmi {
+
+static const int kLoBits = 12;  // low eq table covers up to this many variables
+
+// Pool of eq tables for a point u of n variables.
+//   suffix[s], s = 0..min(kLoBits, n-1): e~ over the last s variables;
+//   high[k], for rounds k with n-k-1 > kLoBits: e~ over variables k+1 .. n-kLoBits-1.
+struct EqPool {
+    uint32_t* pool = nullptr;
+    size_t stride = 0;
+    uint32_t suffix_off[kLoBits + 1];
+    uint32_t high_off[32];
+    int n = 0;
+
+    static size_t entries(int n) {
+        size_t total = 0;
+        int smax = n - 1 < kLoBits ? n - 1 : kLoBits;
+        for (int s = 0; s <= smax; ++s) total += (size_t)1 << s;
+        for (int k = 0; k < n; ++k) {
+            int rest = n - k - 1;
+            if (rest > kLoBits) total += (size_t)1 << (rest - kLoBits);
+        }
+        return total ? total : 1;
+    }
+
+    // Weights of round k (remaining variables k+1 .. n-1).
+    EqSplit round(int k) const {
+        int rest = n - k - 1;
+        EqSplit e;
+        e.pool = pool;
+        e.stride = stride;
+        e.lbits = rest < kLoBits ? rest : kLoBits;
+        e.lo_off = suffix_off[e.lbits];
+        e.has_hi = rest > kLoBits;
+        e.hi_off = e.has_hi ? high_off[k] : 0;
+        return e;
+    }
+};
+
+static int eq_pool_build(EqPool& ep, const host::F* u, int n, Carver& cv, hipStream_t stream) {
+    ep.n = n;
+    ep.stride = EqPool::entries(n);
+    ep.pool = cv.limbs(ep.stride);
+    if (!ep.pool) return ZK_E_BUFSZ;
+    EqPoolArgs args;
+    memset(&args, 0, sizeof args);
+    for (int t = 0; t < n; ++t) args.u[t] = to_dev(u[t]);
+    int q = 0;
+    uint32_t off = 0;
+    int smax = n - 1 < kLoBits ? n - 1 : kLoBits;
+    for (int s = 0; s <= smax; ++s) {
+        ep.suffix_off[s] = off;
+        args.offset[q] = off;
+        args.var0[q] = (uint8_t)(n - s);
+        args.nvars[q] = (uint8_t)s;
+        off += 1u << s;
+        ++q;
+    }
+    if (n == 0) ep.suffix_off[0] = 0;
+    for (int k = 0; k < n; ++k) {
+        int rest = n - k - 1;
+        if (rest <= kLoBits) continue;
+        ep.high_off[k] = off;
+        args.offset[q] = off;
+        args.var0[q] = (uint8_t)(k + 1);
+        args.nvars[q] = (uint8_t)(rest - kLoBits);
+        off += 1u << (rest - kLoBits);
+        ++q;
+    }
+    args.ntables = q;
+    args.total = off;
+    if (q > 64) return ZK_E_BADARG;
+    if (off) {
+        hipLaunchKernelGGL(k_eq_pool, dim3(grid_for(off)), dim3(kBlock), 0, stream, ep.pool, ep.stride, args);
+        ZK_HIP_TRY(hipGetLastError());
+    }
+    return ZK_OK;
+}
+
+// Quadratic through value(0), value(1) and leading coefficient, at X = 0..3.
+static void quad_values(host::F out[4], const host::F& v0, const host::F& v1, const host::F& lead) {
+    using namespace host;
+    out[0] = v0;
+    out[1] = v1;
+    F lead2 = add(lead, lead);
+    out[2] = add(sub(add(v1, v1), v0), lead2);                                 // 2 v1 - v0 + 2 lead
+    out[3] = add(sub(add(add(v1, v1), v1), add(v0, v0)), add(add(lead2, lead2), lead2));  // 3 v1 - 2 v0 + 6 lead
+}
+
+// Line through value(0), value(1) at X = 0..3.
+static void line_values(host::F out[4], const host::F& v0, const host::F& v1) {
+    using namespace host;
+    F d = sub(v1, v0);
+    out[0] = v0;
+    out[1] = v1;
+    out[2] = add(v1, d);
+    out[3] = add(out[2], d);
+}
+
+// ---- workspace layout -------------------------------------------------------------
+
+struct ProveWs {
+    uint32_t* A;        // D
+    uint32_t* Sf;       // D/2
+    uint32_t* B;        // N
+    uint32_t* Tf;       // N/2
+    uint32_t* M;        // N
+    uint32_t* m;        // N counts
+    uint32_t* slots;    // hash of T
+    uint32_t cap_mask;
+    uint32_t* canon;    // N
+    uint32_t* flags;    // [0] duplicate flag, [2..3] smallest bad index (64-bit)
+    uint32_t* leaves;   // nleaves * 8 words
+    uint32_t nleaves;
+    uint32_t* partD;    // kMaxPartialBlocks * 5
+    uint32_t* partT;    // kMaxPartialBlocks * 6
+};
+
+static uint32_t hash_capacity(size_t N) {
+    size_t cap = 64;
+    while (cap < 2 * N) cap <<= 1;
+    return (uint32_t)cap;
+}
+
+static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
+    w.A = cv.limbs(D);
+    w.Sf = cv.limbs(D / 2 ? D / 2 : 1);
+    w.B = cv.limbs(N);
+    w.Tf = cv.limbs(N / 2 ? N / 2 : 1);
+    w.M = cv.limbs(N);
+    w.m = (uint32_t*)cv.take(N * 4);
+    uint32_t cap = hash_capacity(N);
+    w.cap_mask = cap - 1;
+    w.slots = (uint32_t*)cv.take((size_t)cap * 4);
+    w.canon = (uint32_t*)cv.take(N * 4);
+    w.flags = (uint32_t*)cv.take(64);
+    w.nleaves = (uint32_t)div_up(N, kLeafCounts);
+    w.leaves = (uint32_t*)cv.take((size_t)w.nleaves * 32);
+    w.partD = cv.limbs((size_t)kMaxPartialBlocks * 5);
+    w.partT = cv.limbs((size_t)kMaxPartialBlocks * 6);
+    return ZK_OK;
+}
+
+static size_t prove_ws_bytes(size_t D, size_t N) {
+    Carver cv(nullptr, 0);
+    ProveWs w;
+    carve_prove(w, cv, D, N);
+    cv.limbs(EqPool::entries(log2_floor(D)));
+    size_t inv_d = batch_inverse_scratch_bytes(D), inv_n = batch_inverse_scratch_bytes(N);
+    cv.take(inv_d > inv_n ? inv_d : inv_n);
+    return cv.used();
+}
+
+// Multiplicities into w.m (and the digest leaves into w.leaves).  Returns
+// ZK_E_NOT_IN_TABLE with *bad_index set if some S_i is not in T.
+static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_t D, size_t N, uint64_t* bad_index,
+                      Mailbox* mb, hipStream_t stream) {
+    uint32_t cap = w.cap_mask + 1;
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(cap)), dim3(kBlock), 0, stream, w.slots, (size_t)cap, kEmptySlot);
+    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.m, N, 0u);
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags, (size_t)2, 0u);
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags + 2, (size_t)2, 0xffffffffu);
+    hipLaunchKernelGGL(k_hash_build, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.slots, w.cap_mask, T.limbs, T.stride,
+                       (uint32_t)N, w.flags);
+    hipLaunchKernelGGL(k_canon_rows, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.canon, w.slots, w.cap_mask, T.limbs,
+                       T.stride, (uint32_t)N);
+    hipLaunchKernelGGL(k_count, dim3(grid_for(D, kBlock, 8192)), dim3(kBlock), 0, stream, w.m, S.limbs, S.stride, D, idx,
+                       T.limbs, T.stride, (uint32_t)N, w.slots, w.cap_mask, w.canon, w.flags,
+                       (unsigned long long*)(w.flags + 2));
+    hipLaunchKernelGGL(k_leaf_digests, dim3((unsigned)div_up(w.nleaves, 64)), dim3(64), 0, stream, w.leaves, w.m,
+                       (uint32_t)N, w.nleaves);
+    ZK_HIP_TRY(hipGetLastError());
+    ZK_TRY(mailbox_bulk(mb, (size_t)w.nleaves * 32 + 16));
+    ZK_HIP_TRY(hipMemcpyAsync(mb->bulk, w.flags, 16, hipMemcpyDeviceToHost, stream));
+    ZK_HIP_TRY(hipMemcpyAsync(mb->bulk + 16, w.leaves, (size_t)w.nleaves * 32, hipMemcpyDeviceToHost, stream));
+    ZK_HIP_TRY(hipStreamSynchronize(stream));
+    uint64_t bad;
+    memcpy(&bad, mb->bulk + 8, 8);
+    if (bad != UINT64_MAX) {
+        if (bad_index) *bad_index = bad;
+        return ZK_E_NOT_IN_TABLE;
+    }
+    return ZK_OK;
+}
+
+static void digest_of_leaves(uint8_t out[32], const uint8_t* leaves, uint32_t nleaves) {
+    host::Sha256 h;
+    h.update(leaves, (size_t)nleaves * 32);
+    h.finish(out);
+}
+
+static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
+                      uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
+                      void* stream_v) {
+    using namespace host;
+    const size_t D = S.n, N = T.n;
+    if (!seed || !is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
+    if (!vec_ok(S, D) || !vec_ok(T, N)) return ZK_E_BADARG;
+    if (forced_beta && !canonical_in_range(*forced_beta)) return ZK_E_BADARG;
+    const int n = log2_floor(D), l = log2_floor(N), h = n - l;
+    const size_t need = tlookup_proof_bytes(D);
+    if (len) *len = need;
+    if (!proof || cap < need) return ZK_E_BUFSZ;
+    if (!ws || ws_bytes < prove_ws_bytes(D, N)) return ZK_E_BUFSZ;
+    hipStream_t stream = as_stream(stream_v);
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    ProveWs w;
+    carve_prove(w, cv, D, N);
+    if (cv.overflow()) return ZK_E_BUFSZ;
+
+    // -- Prep: multiplicities and their digest ------------------------------------
+    uint64_t bad = 0;
+    int rc = count_rows(w, S, idx, T, D, N, &bad, mb, stream);
+    if (rc == ZK_E_NOT_IN_TABLE && aux) aux->bad_index = bad;
+    ZK_TRY(rc);
+    uint8_t md[32];
+    digest_of_leaves(md, mb->bulk + 16, w.nleaves);
+
+    uint64_t dims[2] = {D, N};
+    Transcript tr("zkmi/tlookup/v1", seed, dims, 2);
+    tr.absorb("m", md, 32);
+
+    // -- Prove: beta, inverse vectors ------------------------------------------------
+    F beta = tr.challenge("beta");
+    if (forced_beta) beta = from_canonical(*forced_beta);
+    hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.M, N, w.m, N);
+    {
+        Carver inv_cv = cv;  // scratch reused by the two inversions
+        ZK_TRY(batch_inverse_run(w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb, stream));
+    }
+    {
+        Carver inv_cv = cv;
+        ZK_TRY(batch_inverse_run(w.A, D, S.limbs, S.stride, D, beta, inv_cv, mb, stream));
+    }
+
+    F alpha = tr.challenge("alpha");
+    F alpha2 = sqr(alpha);
+    F u[32];
+    for (int t = 0; t < n; ++t) u[t] = tr.challenge("u");
+
+    EqPool ep;
+    ZK_TRY(eq_pool_build(ep, u, n, cv, stream));
+
+    // -- table-side constants -----------------------------------------------------------
+    // c1 = sum_j e'_j B_j (T_j+beta), c2 = sum_j m_j B_j.  e' = e~(u_[h:], .) is the
+    // weight table of "round h-1" (remaining variables h .. n-1); with h = 0 no
+    // round needs the constant, only c2 is reported.
+    F c1 = zero(), c2 = zero();
+    {
+        TableConstArgs a;
+        a.B = w.B; a.bs = N;
+        a.T = T.limbs; a.ts = T.stride;
+        a.M = w.M; a.ms = N;
+        a.N = N;
+        a.beta = to_dev(beta);
+        if (h >= 1) {
+            a.eq = ep.round(h - 1);
+        } else {
+            // weights unused for the reported sum; point at the one-entry table
+            a.eq = EqSplit{ep.pool, ep.stride, ep.suffix_off[0], 0, 0, 0};
+        }
+        a.partials = w.partT;
+        a.pstride = (size_t)kMaxPartialBlocks * 6;
+        unsigned blocks = grid_for(N, kBlock * 4, kMaxPartialBlocks);
+        hipLaunchKernelGGL(k_table_const, dim3(blocks), dim3(kBlock), 0, stream, a);
+        launch_final_sum(w.partT, (size_t)kMaxPartialBlocks * 6, blocks, 2, mb->words, stream);
+        ZK_HIP_TRY(hipGetLastError());
+        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        c1 = from_dev(mb->words);
+        c2 = from_dev(mb->words + 8);
+    }
+    F cB = sub(mul(alpha2, c1), c2);
+
+    // -- header ------------------------------------------------------------------------------
+    uint8_t* out = proof;
+    memcpy(out, "ZKTL", 4);
+    out[4] = 1; out[5] = out[6] = out[7] = 0;
+    put_le64(out + 8, D);
+    put_le64(out + 16, N);
+    memcpy(out + 24, md, 32);
+    out += 56;
+
+    // -- rounds ------------------------------------------------------------------------------
+    F scale = one();  // 2^-h
+    {
+        F half = inv(from_u64(2));
+        for (int i = 0; i < h; ++i) scale = mul(scale, half);
+    }
+    const F inv2 = inv(from_u64(2));
+    F half_pow = one();       // 2^-(k+1) in round k
+    F cD = one(), cT = one();  // products of e~(u_t, r_t) over bound variables
+    F r_prev = zero();
+    F sum_A = zero();
+    for (int k = 0; k < n; ++k) {
+        const size_t half = (size_t)1 << (n - k - 1);
+        size_t span = half / kMaxPartialBlocks;
+        if (span < (size_t)kBlock * 4) span = (size_t)kBlock * 4;
+        if (span > half) span = half;
+        const unsigned blocks = (unsigned)(half / span);
+        const bool table_round = k >= h;
+
+        DataRoundArgs d;
+        d.A = PairArray{w.A, D, w.A, D};
+        if (k <= 1) d.S = PairArray{S.limbs, S.stride, w.Sf, D / 2};
+        else d.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
+        d.half = half;
+        d.block_span = span;
+        d.fold = k > 0;
+        d.r_prev = to_dev(r_prev);
+        d.beta = to_dev(beta);
+        d.eq = ep.round(k);
+        d.partials = w.partD;
+        d.pstride = (size_t)kMaxPartialBlocks * 5;
+        hipLaunchKernelGGL(k_round_data, dim3(blocks), dim3(kBlock), 0, stream, d);
+        launch_final_sum(w.partD, d.pstride, blocks, 5, mb->words, stream);
+        if (table_round) {
+            TableRoundArgs t;
+            t.B = PairArray{w.B, N, w.B, N};
+            if (k <= h + 1) t.T = PairArray{T.limbs, T.stride, w.Tf, N / 2};
+            else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
+            t.M = PairArray{w.M, N, w.M, N};
+            t.half = half;
+            t.block_span = span;
+            t.fold = k > h;
+            t.r_prev = d.r_prev;
+            t.beta = d.beta;
+            t.eq = d.eq;
+            t.partials = w.partT;
+            t.pstride = (size_t)kMaxPartialBlocks * 6;
+            hipLaunchKernelGGL(k_round_table, dim3(blocks), dim3(kBlock), 0, stream, t);
+            launch_final_sum(w.partT, t.pstride, blocks, 6, mb->words + 40, stream);
+        }
+        ZK_HIP_TRY(hipGetLastError());
+        ZK_HIP_TRY(hipStreamSynchronize(stream));
+
+        F q0 = from_dev(mb->words), q1 = from_dev(mb->words + 8), qi = from_dev(mb->words + 16);
+        F sA0 = from_dev(mb->words + 24), sA1 = from_dev(mb->words + 32);
+        if (k == 0) sum_A = add(sA0, sA1);
+        F e[4], q[4], sa[4], g[4];
+        line_values(e, sub(one(), u[k]), u[k]);
+        quad_values(q, q0, q1, qi);
+        line_values(sa, sA0, sA1);
+        F wD = mul(alpha, cD);
+        half_pow = mul(half_pow, inv2);
+        F tq[4], tm[4];
+        F wT = zero();
+        if (table_round) {
+            quad_values(tq, from_dev(mb->words + 40), from_dev(mb->words + 48), from_dev(mb->words + 56));
+            quad_values(tm, from_dev(mb->words + 64), from_dev(mb->words + 72), from_dev(mb->words + 80));
+            wT = mul(alpha2, cT);
+        }
+        F table_const = mul(cB, half_pow);
+        for (int X = 0; X < 4; ++X) {
+            F data = add(mul(mul(wD, e[X]), q[X]), sa[X]);
+            F table = table_round ? mul(scale, sub(mul(mul(wT, e[X]), tq[X]), tm[X])) : table_const;
+            g[X] = add(data, table);
+            to_bytes(out + 32 * X, g[X]);
+        }
+        tr.absorb("g", out, 128);
+        out += 128;
+        F r = tr.challenge("r");
+        F er = add(mul(sub(one(), u[k]), sub(one(), r)), mul(u[k], r));
+        cD = mul(cD, er);
+        if (table_round) cT = mul(cT, er);
+        r_prev = r;
+    }
+
+    // -- final claims --------------------------------------------------------------------------
+    {
+        FinalArgs f;
+        f.count = 5;
+        f.r = to_dev(r_prev);
+        const bool d_fold = n >= 1, t_fold = l >= 1;
+        // A, S, B, m, T in the order of the proof
+        f.p[0] = w.A; f.stride[0] = D; f.fold[0] = d_fold;
+        if (n <= 1) { f.p[1] = S.limbs; f.stride[1] = S.stride; }
+        else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
+        f.fold[1] = d_fold;
+        f.p[2] = w.B; f.stride[2] = N; f.fold[2] = t_fold;
+        f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
+        if (l <= 1) { f.p[4] = T.limbs; f.stride[4] = T.stride; }
+        else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
+        f.fold[4] = t_fold;
+        hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words);
+        ZK_HIP_TRY(hipGetLastError());
+        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        F fin[5];
+        for (int i = 0; i < 5; ++i) {
+            fin[i] = from_dev(mb->words + 8 * i);
+            to_bytes(out + 32 * i, fin[i]);
+        }
+        tr.absorb("final", out, 160);
+        if (n == 0) sum_A = fin[0];
+    }
+    if (aux) {
+        aux->beta = to_canonical(beta);
+        aux->alpha = to_canonical(alpha);
+        aux->sum_A = to_canonical(sum_A);
+        aux->sum_mB = to_canonical(c2);
+        aux->bad_index = 0;
+    }
+    return ZK_OK;
+}
+
+// ---- verifier ----------------------------------------------------------------------------------
+
+static size_t verify_ws_bytes(size_t D, size_t N) {
+    Carver cv(nullptr, 0);
+    cv.limbs(N);                                   // m as field elements
+    cv.take(div_up(N, kLeafCounts) * 32);          // leaf digests
+    cv.take(mle_scratch_bytes(log2_floor(D)));
+    return cv.used();
+}
+
+static int verify_impl(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
+                       const tlookup_witness* wit, tlookup_claims* claims, void* ws, size_t ws_bytes, void* stream_v) {
+    using namespace host;
+    const size_t N = T.n;
+    if (!seed || !proof || !is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31) || !vec_ok(T, N))
+        return ZK_E_BADARG;
+    if (!ws || ws_bytes < verify_ws_bytes(D, N)) return ZK_E_BUFSZ;
+    const int n = log2_floor(D), l = log2_floor(N), h = n - l;
+    if (len != tlookup_proof_bytes(D)) return ZK_E_REJECT;
+    if (memcmp(proof, "ZKTL\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
+    if (get_le64(proof + 8) != D || get_le64(proof + 16) != N) return ZK_E_REJECT;
+    const uint8_t* body = proof + 56;
+    F el[4 * 32 + 5];
+    const int nel = 4 * n + 5;
+    for (int i = 0; i < nel; ++i)
+        if (!from_bytes(&el[i], body + 32 * i)) return ZK_E_REJECT;
+
+    uint64_t dims[2] = {D, N};
+    Transcript tr("zkmi/tlookup/v1", seed, dims, 2);
+    tr.absorb("m", proof + 24, 32);
+    F beta = tr.challenge("beta");
+    F alpha = tr.challenge("alpha");
+    F alpha2 = sqr(alpha);
+    F u[32], v[32];
+    for (int t = 0; t < n; ++t) u[t] = tr.challenge("u");
+    F claim = add(alpha, alpha2);
+    for (int k = 0; k < n; ++k) {
+        const F* g = &el[4 * k];
+        if (!equal(add(g[0], g[1]), claim)) return ZK_E_REJECT;
+        tr.absorb("g", body + 128 * k, 128);
+        v[k] = tr.challenge("r");
+        claim = interpolate_at(g, 4, v[k]);
+    }
+    const F* fin = &el[4 * n];
+    tr.absorb("final", body + 128 * n, 160);
+    F scale = one();
+    {
+        F half = inv(from_u64(2));
+        for (int i = 0; i < h; ++i) scale = mul(scale, half);
+    }
+    F e_full = eq_point(u, v, n), e_tab = eq_point(u + h, v + h, l);
+    F lhs = mul(fin[0], add(mul(mul(alpha, e_full), add(fin[1], beta)), one()));
+    F rhs = mul(scale, mul(fin[2], sub(mul(mul(alpha2, e_tab), add(fin[4], beta)), fin[3])));
+    if (!equal(add(lhs, rhs), claim)) return ZK_E_REJECT;
+
+    // claims against tensors
+    hipStream_t stream = as_stream(stream_v);
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    uint32_t* Mfr = cv.limbs(N);
+    uint32_t nleaves = (uint32_t)div_up(N, kLeafCounts);
+    uint32_t* leaves = (uint32_t*)cv.take((size_t)nleaves * 32);
+    auto check = [&](const uint32_t* a, size_t stride, int nv, const F* pt, const F& want, int* ok) -> int {
+        Carver scratch = cv;
+        ZK_TRY(mle_eval_run(a, stride, nv, pt, scratch, mb->words, stream));
+        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        *ok = equal(from_dev(mb->words), want) ? 1 : 0;
+        return ZK_OK;
+    };
+    int ok = 0;
+    ZK_TRY(check(T.limbs, T.stride, l, v + h, fin[4], &ok));
+    if (!ok) return ZK_E_REJECT;
+    if (wit) {
+        if (wit->S.limbs) {
+            if (!vec_ok(wit->S, D)) return ZK_E_BADARG;
+            ZK_TRY(check(wit->S.limbs, wit->S.stride, n, v, fin[1], &ok));
+            if (!ok) return ZK_E_REJECT;
+        }
+        if (wit->A.limbs) {
+            if (!vec_ok(wit->A, D)) return ZK_E_BADARG;
+            ZK_TRY(check(wit->A.limbs, wit->A.stride, n, v, fin[0], &ok));
+            if (!ok) return ZK_E_REJECT;
+        }
+        if (wit->B.limbs) {
+            if (!vec_ok(wit->B, N)) return ZK_E_BADARG;
+            ZK_TRY(check(wit->B.limbs, wit->B.stride, l, v + h, fin[2], &ok));
+            if (!ok) return ZK_E_REJECT;
+        }
+        if (wit->m) {
+            hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, Mfr, N, wit->m, N);
+            hipLaunchKernelGGL(k_leaf_digests, dim3((unsigned)div_up(nleaves, 64)), dim3(64), 0, stream, leaves, wit->m,
+                               (uint32_t)N, nleaves);
+            ZK_TRY(mailbox_bulk(mb, (size_t)nleaves * 32));
+            ZK_HIP_TRY(hipMemcpyAsync(mb->bulk, leaves, (size_t)nleaves * 32, hipMemcpyDeviceToHost, stream));
+            ZK_TRY(check(Mfr, N, l, v + h, fin[3], &ok));
+            if (!ok) return ZK_E_REJECT;
+            uint8_t md[32];
+            digest_of_leaves(md, mb->bulk, nleaves);
+            if (memcmp(md, proof + 24, 32) != 0) return ZK_E_REJECT;
+        }
+    }
+    if (claims) {
+        memset(claims, 0, sizeof *claims);
+        claims->A_v = to_canonical(fin[0]);
+        claims->S_v = to_canonical(fin[1]);
+        claims->B_vp = to_canonical(fin[2]);
+        claims->m_vp = to_canonical(fin[3]);
+        claims->T_vp = to_canonical(fin[4]);
+        claims->nvars = n;
+        for (int t = 0; t < n; ++t) claims->v[t] = to_canonical(v[t]);
+    }
+    return ZK_OK;
+}
+
+}  // namespace zkmi
+
+using namespace zkmi;
+
+extern "C" {
+
+size_t tlookup_proof_bytes(size_t D) { return 56 + (size_t)log2_floor(D ? D : 1) * 128 + 160; }
+
+size_t tlookup_workspace_bytes(size_t D, size_t N) {
+    if (!is_pow2(D) || !is_pow2(N) || N > D) return 0;
+    return prove_ws_bytes(D, N);
+}
+
+int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T, void* ws, size_t ws_bytes,
+                           uint64_t* bad_index, void* stream) {
+    const size_t D = S.n, N = T.n;
+    if (!m || D == 0 || N == 0 || N > ((size_t)1 << 31) || !vec_ok(S, D) || !vec_ok(T, N)) return ZK_E_BADARG;
+    if (!is_pow2(D) || !is_pow2(N) || N > D) return ZK_E_BADARG;
+    if (!ws || ws_bytes < prove_ws_bytes(D, N)) return ZK_E_BUFSZ;
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    ProveWs w;
+    carve_prove(w, cv, D, N);
+    ZK_TRY(count_rows(w, S, idx, T, D, N, bad_index, mb, as_stream(stream)));
+    ZK_HIP_TRY(hipMemcpyAsync(m, w.m, N * 4, hipMemcpyDeviceToDevice, as_stream(stream)));
+    ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
+    return ZK_OK;
+}
+
+int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
+                  size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
+    return prove_impl(seed, S, idx, T, nullptr, proof, cap, len, aux, ws, ws_bytes, stream);
+}
+
+int tlookup_prove_with_beta(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
+                            uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
+                            void* stream) {
+    if (!forced_beta) return ZK_E_BADARG;
+    return prove_impl(seed, S, idx, T, forced_beta, proof, cap, len, aux, ws, ws_bytes, stream);
+}
+
+size_t tlookup_verify_workspace_bytes(size_t D, size_t N) {
+    if (!is_pow2(D) || !is_pow2(N) || N > D) return 0;
+    return verify_ws_bytes(D, N);
+}
+
+int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
+                   const tlookup_witness* witness, tlookup_claims* claims, void* ws, size_t ws_bytes, void* stream) {
+    return verify_impl(seed, proof, len, T, D, witness, claims, ws, ws_bytes, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,396 @@
+// Kernels of the tlookup prover (Section 4 of the paper, Protocol 1): table
+// hashing and multiplicity counting, the leaf digests of m, pooled eq tables,
+// and the sumcheck round kernels for the data side (A, S) and the table side
+// (B, T, m) of the tlookup identity.
+#pragma once
+#include "common.h"
+#include "reduce_dev.h"
+
+namespace zkmi {
+
+// ---- table rows by value: open-addressing hash of T -----------------------------
+
+static const uint32_t kEmptySlot = 0xffffffffu;
+
+__device__ __forceinline__ uint32_t fr_hash(const Fr& a) {
+    uint32_t h = a.l[0] * 0x9e3779b1u;
+    h = (h ^ a.l[1]) * 0x85ebca77u;
+    h = (h ^ a.l[2]) * 0xc2b2ae3du;
+    h = (h ^ a.l[3]) * 0x27d4eb2fu;
+    h = (h ^ a.l[4]) * 0x165667b1u;
+    h = (h ^ a.l[5]) * 0x9e3779b1u;
+    h = (h ^ a.l[6]) * 0x85ebca77u;
+    h = (h ^ a.l[7]) * 0xc2b2ae3du;
+    return h ^ (h >> 15);
+}
+
+// Every row j claims the first slot of its probe sequence that is empty or holds
+// a row with the same value; equal values meet in one slot and the lowest row
+// wins.  Slots never empty again and the value class of a slot never changes, so
+// all rows of one value walk the same sequence to the same slot.
+static __global__ void __launch_bounds__(kBlock) k_hash_build(uint32_t* slots, uint32_t cap_mask,
+                                                       const uint32_t* __restrict__ T, size_t ts, uint32_t N,
+                                                       uint32_t* dup_flag) {
+    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock) {
+        Fr v = fr_load(T, ts, j);
+        uint32_t pos = fr_hash(v) & cap_mask;
+        for (uint32_t step = 0; step <= cap_mask; ++step) {
+            uint32_t cur = atomicCAS(&slots[pos], kEmptySlot, j);
+            if (cur == kEmptySlot) break;  // claimed
+            if (fr_equal(fr_load(T, ts, cur), v)) {
+                atomicMin(&slots[pos], j);
+                atomicOr(dup_flag, 1u);
+                break;
+            }
+            pos = (pos + 1) & cap_mask;
+        }
+    }
+}
+
+// Row of the table holding value v (lowest row of equal ones), or kEmptySlot.
+__device__ __forceinline__ uint32_t hash_find(const uint32_t* __restrict__ slots, uint32_t cap_mask,
+                                              const uint32_t* __restrict__ T, size_t ts, const Fr& v) {
+    uint32_t pos = fr_hash(v) & cap_mask;
+    for (uint32_t step = 0; step <= cap_mask; ++step) {
+        uint32_t cur = slots[pos];
+        if (cur == kEmptySlot) return kEmptySlot;
+        if (fr_equal(fr_load(T, ts, cur), v)) return cur;
+        pos = (pos + 1) & cap_mask;
+    }
+    return kEmptySlot;
+}
+
+// canon[j] = lowest row with the value of row j.
+static __global__ void __launch_bounds__(kBlock) k_canon_rows(uint32_t* __restrict__ canon, const uint32_t* __restrict__ slots,
+                                                       uint32_t cap_mask, const uint32_t* __restrict__ T, size_t ts,
+                                                       uint32_t N) {
+    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock)
+        canon[j] = hash_find(slots, cap_mask, T, ts, fr_load(T, ts, j));
+}
+
+// m[row(S_i)] += 1.  With idx the row is given and only checked; without, it is
+// found through the hash.  The smallest offending i ends up in *bad.
+static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint32_t* __restrict__ S, size_t ss, size_t D,
+                                                  const uint32_t* __restrict__ idx, const uint32_t* __restrict__ T,
+                                                  size_t ts, uint32_t N, const uint32_t* __restrict__ slots,
+                                                  uint32_t cap_mask, const uint32_t* __restrict__ canon,
+                                                  const uint32_t* __restrict__ dup_flag, unsigned long long* bad) {
+    const bool dups = *dup_flag != 0;
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < D; i += (size_t)gridDim.x * kBlock) {
+        Fr v = fr_load(S, ss, i);
+        uint32_t row;
+        if (idx) {
+            row = idx[i];
+            if (row >= N || !fr_equal(fr_load(T, ts, row), v)) row = kEmptySlot;
+            else if (dups) row = canon[row];
+        } else {
+            row = hash_find(slots, cap_mask, T, ts, v);
+        }
+        if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
+        else atomicAdd(&m[row], 1u);
+    }
+}
+
+static __global__ void __launch_bounds__(kBlock) k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) p[i] = v;
+}
+
+static __global__ void __launch_bounds__(kBlock) k_counts_to_fr(uint32_t* __restrict__ dst, size_t ds,
+                                                         const uint32_t* __restrict__ m, size_t N) {
+    for (size_t j = blockIdx.x * (size_t)kBlock + threadIdx.x; j < N; j += (size_t)gridDim.x * kBlock)
+        fr_store(dst, ds, j, fr_from_u32(m[j]));
+}
+
+// ---- SHA-256 of the leaves of m ---------------------------------------------------
+
+static const uint32_t kLeafCounts = 128;
+
+__device__ __forceinline__ uint32_t rotr(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
+
+static __constant__ const uint32_t kShaK[64] = {
+    0x428a2f98u, 0x71374491u, 0xb5c0fbcfu, 0xe9b5dba5u, 0x3956c25bu, 0x59f111f1u, 0x923f82a4u, 0xab1c5ed5u,
+    0xd807aa98u, 0x12835b01u, 0x243185beu, 0x550c7dc3u, 0x72be5d74u, 0x80deb1feu, 0x9bdc06a7u, 0xc19bf174u,
+    0xe49b69c1u, 0xefbe4786u, 0x0fc19dc6u, 0x240ca1ccu, 0x2de92c6fu, 0x4a7484aau, 0x5cb0a9dcu, 0x76f988dau,
+    0x983e5152u, 0xa831c66du, 0xb00327c8u, 0xbf597fc7u, 0xc6e00bf3u, 0xd5a79147u, 0x06ca6351u, 0x14292967u,
+    0x27b70a85u, 0x2e1b2138u, 0x4d2c6dfcu, 0x53380d13u, 0x650a7354u, 0x766a0abbu, 0x81c2c92eu, 0x92722c85u,
+    0xa2bfe8a1u, 0xa81a664bu, 0xc24b8b70u, 0xc76c51a3u, 0xd192e819u, 0xd6990624u, 0xf40e3585u, 0x106aa070u,
+    0x19a4c116u, 0x1e376c08u, 0x2748774cu, 0x34b0bcb5u, 0x391c0cb3u, 0x4ed8aa4au, 0x5b9cca4fu, 0x682e6ff3u,
+    0x748f82eeu, 0x78a5636fu, 0x84c87814u, 0x8cc70208u, 0x90befffau, 0xa4506cebu, 0xbef9a3f7u, 0xc67178f2u};
+
+// One thread per leaf: SHA-256 of up to 128 counts as 4-byte little-endian
+// words.  Digest bytes go out in order, 32 per leaf.
+static __global__ void __launch_bounds__(64) k_leaf_digests(uint32_t* __restrict__ out, const uint32_t* __restrict__ m,
+                                                     uint32_t N, uint32_t nleaves) {
+    uint32_t leaf = blockIdx.x * 64 + threadIdx.x;
+    if (leaf >= nleaves) return;
+    uint32_t base = leaf * kLeafCounts;
+    uint32_t cnt = N - base < kLeafCounts ? N - base : kLeafCounts;
+    uint32_t nblk = (cnt + 3 + 15) / 16;
+    uint32_t h[8] = {0x6a09e667u, 0xbb67ae85u, 0x3c6ef372u, 0xa54ff53au, 0x510e527fu, 0x9b05688cu, 0x1f83d9abu,
+                     0x5be0cd19u};
+    for (uint32_t b = 0; b < nblk; ++b) {
+        uint32_t w[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            uint32_t pos = b * 16 + i;
+            uint32_t v = 0;
+            if (pos < cnt) v = __builtin_bswap32(m[base + pos]);
+            else if (pos == cnt) v = 0x80000000u;
+            else if (pos == nblk * 16 - 1) v = cnt * 32;  // message length in bits
+            w[i] = v;
+        }
+        uint32_t s[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s[i] = h[i];
+#pragma unroll
+        for (int i = 0; i < 64; ++i) {
+            if (i >= 16) {
+                uint32_t x = w[(i + 1) & 15], y = w[(i + 14) & 15];
+                w[i & 15] += (rotr(x, 7) ^ rotr(x, 18) ^ (x >> 3)) + w[(i + 9) & 15] +
+                             (rotr(y, 17) ^ rotr(y, 19) ^ (y >> 10));
+            }
+            uint32_t t1 = s[7] + (rotr(s[4], 6) ^ rotr(s[4], 11) ^ rotr(s[4], 25)) + ((s[4] & s[5]) ^ (~s[4] & s[6])) +
+                          kShaK[i] + w[i & 15];
+            uint32_t t2 = (rotr(s[0], 2) ^ rotr(s[0], 13) ^ rotr(s[0], 22)) +
+                          ((s[0] & s[1]) ^ (s[0] & s[2]) ^ (s[1] & s[2]));
+            s[7] = s[6]; s[6] = s[5]; s[5] = s[4]; s[4] = s[3] + t1;
+            s[3] = s[2]; s[2] = s[1]; s[1] = s[0]; s[0] = t1 + t2;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) h[i] += s[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) out[leaf * 8 + i] = __builtin_bswap32(h[i]);
+}
+
+// ---- pooled eq tables ----------------------------------------------------------------
+
+// Table q covers variables [var0, var0 + nvars) of the point and occupies
+// elements [offset, offset + 2^nvars) of the pool.
+struct EqPoolArgs {
+    Fr u[32];
+    uint32_t offset[64];
+    uint8_t var0[64];
+    uint8_t nvars[64];
+    int ntables;
+    uint32_t total;
+};
+
+static __global__ void __launch_bounds__(kBlock) k_eq_pool(uint32_t* __restrict__ pool, size_t stride, EqPoolArgs args) {
+    const Fr one = fr_one();
+    for (uint32_t g = blockIdx.x * kBlock + threadIdx.x; g < args.total; g += gridDim.x * kBlock) {
+        int q = 0;
+        while (q + 1 < args.ntables && args.offset[q + 1] <= g) ++q;
+        uint32_t x = g - args.offset[q];
+        int nv = args.nvars[q], v0 = args.var0[q];
+        Fr acc = one;
+        for (int t = 0; t < nv; ++t) {
+            unsigned bit = (x >> (nv - 1 - t)) & 1u;
+            Fr f = bit ? args.u[v0 + t] : fr_sub(one, args.u[v0 + t]);
+            acc = t == 0 ? f : fr_mul(acc, f);
+        }
+        fr_store(pool, stride, g, acc);
+    }
+}
+
+// ---- sumcheck rounds ---------------------------------------------------------------------
+
+// Weights of a round: the pair with index p (the remaining variables after the
+// one being bound) has weight lo[p & (2^lbits - 1)] * hi[p >> lbits]; `hi` is
+// null when the low table covers every remaining variable.
+struct EqSplit {
+    const uint32_t* pool;
+    size_t stride;
+    uint32_t lo_off;
+    uint32_t hi_off;
+    int lbits;
+    int has_hi;
+};
+
+struct PairArray {
+    const uint32_t* src;
+    size_t ss;
+    uint32_t* dst;
+    size_t ds;
+};
+
+// Loads the pair (x0, x1) of index p for this round.  Without folding the
+// array has 2*half entries.  With folding it has 4*half: the previous variable
+// is bound to r first, the folded entries are written back (to dst) and
+// returned.
+__device__ __forceinline__ void load_pair(const PairArray& a, size_t p, size_t half, bool fold, const Fr& r, Fr& x0,
+                                          Fr& x1) {
+    if (!fold) {
+        x0 = fr_load(a.src, a.ss, p);
+        x1 = fr_load(a.src, a.ss, p + half);
+    } else {
+        Fr y0 = fr_load(a.src, a.ss, p), y1 = fr_load(a.src, a.ss, p + half);
+        Fr y2 = fr_load(a.src, a.ss, p + 2 * half), y3 = fr_load(a.src, a.ss, p + 3 * half);
+        x0 = fr_fold(y0, y2, r);
+        x1 = fr_fold(y1, y3, r);
+        fr_store(a.dst, a.ds, p, x0);
+        fr_store(a.dst, a.ds, p + half, x1);
+    }
+}
+
+struct DataRoundArgs {
+    PairArray A, S;
+    size_t half;        // pairs in this round
+    size_t block_span;  // pairs per workgroup (power of two)
+    int fold;
+    Fr r_prev, beta;
+    EqSplit eq;
+    uint32_t* partials;  // 5 values per workgroup
+    size_t pstride;
+};
+
+// Data side of one round.  With w the weight of a pair and (A0, A1), (S0, S1)
+// its entries, the workgroup sums
+//   q0 = w A0 (S0+beta), q1 = w A1 (S1+beta), qinf = w (A1-A0)(S1-S0), sA0 = A0, sA1 = A1,
+// from which the host forms  alpha c e~(u_k, X) q(X) + sA(X).
+static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
+    __shared__ uint32_t lds[4 * 5 * 8];
+    Fr tot[5];
+#pragma unroll
+    for (int q = 0; q < 5; ++q) tot[q] = fr_zero();
+    const size_t start = blockIdx.x * g.block_span;
+    const size_t lo_size = (size_t)1 << g.eq.lbits;
+    const size_t sub_span = g.block_span < lo_size ? g.block_span : lo_size;
+    for (size_t sub = 0; sub < g.block_span; sub += sub_span) {
+        Fr q0 = fr_zero(), q1 = fr_zero(), qi = fr_zero();
+        for (size_t p = start + sub + threadIdx.x; p < start + sub + sub_span; p += kBlock) {
+            Fr a0, a1, s0, s1;
+            load_pair(g.A, p, g.half, g.fold, g.r_prev, a0, a1);
+            load_pair(g.S, p, g.half, g.fold, g.r_prev, s0, s1);
+            Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & (lo_size - 1)));
+            tot[3] = fr_add(tot[3], a0);
+            tot[4] = fr_add(tot[4], a1);
+            Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
+            q0 = fr_add(q0, fr_mul(wa0, fr_add(s0, g.beta)));
+            q1 = fr_add(q1, fr_mul(wa1, fr_add(s1, g.beta)));
+            qi = fr_add(qi, fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
+        }
+        if (g.eq.has_hi) {
+            Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + ((start + sub) >> g.eq.lbits));
+            q0 = fr_mul(q0, hf);
+            q1 = fr_mul(q1, hf);
+            qi = fr_mul(qi, hf);
+        }
+        tot[0] = fr_add(tot[0], q0);
+        tot[1] = fr_add(tot[1], q1);
+        tot[2] = fr_add(tot[2], qi);
+    }
+    block_sum<5, 4>(tot, lds);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int q = 0; q < 5; ++q) fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 5 + q, tot[q]);
+    }
+}
+
+struct TableRoundArgs {
+    PairArray B, T, M;
+    size_t half;
+    size_t block_span;
+    int fold;
+    Fr r_prev, beta;
+    EqSplit eq;
+    uint32_t* partials;  // 6 values per workgroup
+    size_t pstride;
+};
+
+// Table side of one round (once the table's own variables are being bound):
+//   t0 = w B0 (T0+beta), t1 = w B1 (T1+beta), tinf = w (B1-B0)(T1-T0),
+//   m0 = B0 M0, m1 = B1 M1, minf = (B1-B0)(M1-M0).
+static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g) {
+    __shared__ uint32_t lds[4 * 6 * 8];
+    Fr tot[6];
+#pragma unroll
+    for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
+    const size_t start = blockIdx.x * g.block_span;
+    const size_t lo_size = (size_t)1 << g.eq.lbits;
+    const size_t sub_span = g.block_span < lo_size ? g.block_span : lo_size;
+    for (size_t sub = 0; sub < g.block_span; sub += sub_span) {
+        Fr q0 = fr_zero(), q1 = fr_zero(), qi = fr_zero();
+        for (size_t p = start + sub + threadIdx.x; p < start + sub + sub_span; p += kBlock) {
+            Fr b0, b1, t0, t1, m0, m1;
+            load_pair(g.B, p, g.half, g.fold, g.r_prev, b0, b1);
+            load_pair(g.T, p, g.half, g.fold, g.r_prev, t0, t1);
+            load_pair(g.M, p, g.half, g.fold, g.r_prev, m0, m1);
+            Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & (lo_size - 1)));
+            tot[3] = fr_add(tot[3], fr_mul(b0, m0));
+            tot[4] = fr_add(tot[4], fr_mul(b1, m1));
+            tot[5] = fr_add(tot[5], fr_mul(fr_sub(b1, b0), fr_sub(m1, m0)));
+            Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
+            q0 = fr_add(q0, fr_mul(wb0, fr_add(t0, g.beta)));
+            q1 = fr_add(q1, fr_mul(wb1, fr_add(t1, g.beta)));
+            qi = fr_add(qi, fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
+        }
+        if (g.eq.has_hi) {
+            Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + ((start + sub) >> g.eq.lbits));
+            q0 = fr_mul(q0, hf);
+            q1 = fr_mul(q1, hf);
+            qi = fr_mul(qi, hf);
+        }
+        tot[0] = fr_add(tot[0], q0);
+        tot[1] = fr_add(tot[1], q1);
+        tot[2] = fr_add(tot[2], qi);
+    }
+    block_sum<6, 4>(tot, lds);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int q = 0; q < 6; ++q) fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 6 + q, tot[q]);
+    }
+}
+
+// Sums over the whole table, before any of its variables is bound:
+//   c1 = sum_j e'_j B_j (T_j + beta),  c2 = sum_j B_j M_j,
+// with e'_j = lo[j & mask] * hi[j >> lbits].
+struct TableConstArgs {
+    const uint32_t* B; size_t bs;
+    const uint32_t* T; size_t ts;
+    const uint32_t* M; size_t ms;
+    size_t N;
+    Fr beta;
+    EqSplit eq;
+    uint32_t* partials;  // 2 values per workgroup
+    size_t pstride;
+};
+
+static __global__ void __launch_bounds__(kBlock) k_table_const(TableConstArgs g) {
+    __shared__ uint32_t lds[4 * 2 * 8];
+    Fr tot[2] = {fr_zero(), fr_zero()};
+    const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
+    for (size_t j = blockIdx.x * (size_t)kBlock + threadIdx.x; j < g.N; j += (size_t)gridDim.x * kBlock) {
+        Fr b = fr_load(g.B, g.bs, j), t = fr_load(g.T, g.ts, j), m = fr_load(g.M, g.ms, j);
+        Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (j & lo_mask));
+        if (g.eq.has_hi) w = fr_mul(w, fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + (j >> g.eq.lbits)));
+        tot[0] = fr_add(tot[0], fr_mul(fr_mul(w, b), fr_add(t, g.beta)));
+        tot[1] = fr_add(tot[1], fr_mul(b, m));
+    }
+    block_sum<2, 4>(tot, lds);
+    if (threadIdx.x == 0) {
+        fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 2, tot[0]);
+        fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 2 + 1, tot[1]);
+    }
+}
+
+// Final values: each of up to five arrays is either a single entry or a pair
+// still to be bound to the last challenge.  Value q goes to out_words[8q..8q+8).
+struct FinalArgs {
+    const uint32_t* p[5];
+    size_t stride[5];
+    int fold[5];
+    int count;
+    Fr r;
+};
+
+static __global__ void k_final_values(FinalArgs g, uint32_t* out_words) {
+    int q = threadIdx.x;
+    if (q >= g.count) return;
+    Fr v = fr_load(g.p[q], g.stride[q], 0);
+    if (g.fold[q]) v = fr_fold(v, fr_load(g.p[q], g.stride[q], 1), g.r);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) out_words[8 * q + k] = v.l[k];
+}
+
+}  // namespace zkmi

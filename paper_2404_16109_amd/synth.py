@@ -117,3 +117,15 @@ def attention_segments(heads=40, rows=2048, cols=2048, logD=28, logN=16, sigma=6
         out.append({"name": "c5-attn-seg%d" % k, "D": D, "N": N, "idx": idx, "tx": tx, "ty": ty, "real": real,
                     "seed": seed_bytes("c5s%d" % k)})
     return out
+
+
+BLS12_381_R = 0x73eda753299d7d483339d80809a1d80553bda402fffe5bfeffffffff00000001
+
+
+def pair_combiner(seed):
+    """The verifier's random combiner rho of a pair table (an input to both
+    implementations): a hash of the workload seed, reduced into the field."""
+    import hashlib
+    st = hashlib.sha256(b"zkmi/rho/v1" + bytes(seed)).digest()
+    wide = hashlib.sha256(st + b"rho\x00").digest() + hashlib.sha256(st + b"rho\x01").digest()
+    return int.from_bytes(wide, "big") % BLS12_381_R
