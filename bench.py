@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of the tlookup prover hot path on one MI355X.
+
+A "step" is one whole `tlookup_prove` call (multiplicities, digest of m, both
+batch inversions, eq tables, all sumcheck rounds with folding, transcript) on
+the 7B-FFN activation-table workload: D = 2^25 elements (2048 x 11008
+activations padded), N = 2^16 table rows, inputs resident in HBM as limb-major
+Montgomery vectors.  Prints one JSON line.
+
+The work model behind `value` is fixed (it does not follow the
+implementation): 10 field multiplications per element of S and per table row
+(3 for the batched inversion, 5 to evaluate a round's sums per pair and 2 to
+fold it, pairs summing to D over all rounds).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MAD_PER_S = 256 * 64 * 2.4e9      # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit multiply-add per lane per clock
+MADS_PER_FR_MUL = 112                   # 64 for the 8x8-limb product + 48 for the reduction (two of r's limbs need no multiplier)
+ROUND_DATA_FR_MUL_PER_PAIR_EVAL = 5
+ROUND_DATA_FR_MUL_PER_PAIR_FOLD = 4     # two arrays, two folded entries per pair
+
+
+def fr_mul_model(D, N):
+    return 10 * D + 10 * N
+
+
+def round_data_fr_mul(D):
+    """Field multiplications the data-side round kernel needs over one prove:
+    round k has D/2^(k+1) pairs; every round evaluates, all but the first fold."""
+    n = D.bit_length() - 1
+    total = 0
+    for k in range(n):
+        pairs = D >> (k + 1)
+        total += ROUND_DATA_FR_MUL_PER_PAIR_EVAL * pairs
+        if k > 0:
+            total += ROUND_DATA_FR_MUL_PER_PAIR_FOLD * pairs
+    return total
+
+
+def measured_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
+    counter summary, if there is one (lines `FETCH_BYTES_PER_LAUNCH=` /
+    `WRITE_BYTES_PER_LAUNCH=`)."""
+    path = os.path.join(ROOT, "profiles", "round_data_c3_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        for key in ("FETCH_BYTES_PER_LAUNCH", "WRITE_BYTES_PER_LAUNCH"):
+            if line.startswith(key + "="):
+                vals[key] = float(line.split("=", 1)[1])
+    if len(vals) == 2:
+        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
+    return None
+
+
+def cpu_baseline(logD, logN):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the
+    same workload (same generator, smaller D)."""
+    import numpy as np
+    from oracle import pyoracle as orc
+    from paper_2404_16109_amd import synth
+    cfg = synth.activation_table(rows=1 << (logD - 11), cols=2048, logD=logD, logN=logN)
+    T = orc.fr_from_i64(cfg["tx"])
+    rho = orc.to_bytes([synth.pair_combiner(cfg["seed"])])[0]
+    T = orc.fr_axpy(T, rho, orc.fr_from_i64(cfg["ty"]))
+    S = T[cfg["idx"].astype(np.int64)]
+    threads = orc.default_threads()
+    t0 = time.perf_counter()
+    rc, proof, _ = orc.tlookup_prove(cfg["seed"], S, T, threads=threads)
+    dt = time.perf_counter() - t0
+    assert rc == 0
+    return {"value": fr_mul_model(1 << logD, 1 << logN) / dt, "unit": "Fr-mul/s", "cores": threads, "kind": "oracle",
+            "sample": "oracle tlookup_prove on the same generator at D=2^%d, N=2^%d: %.1f s wall" % (logD, logN, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--logD", type=int, default=25)
+    ap.add_argument("--logN", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-logD", type=int, default=19)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path needs no second GPU and none is used); "
+                 "run with --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2404_16109_amd as zk
+    from paper_2404_16109_amd import synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    D, N = 1 << args.logD, 1 << args.logN
+    rows = 2048 if args.logD >= 25 else max(1, (D * 11) // (16 * 2048))
+    cols = 11008 if args.logD >= 25 else 2048
+    cfg = synth.activation_table(rows=rows, cols=cols, logD=args.logD, logN=args.logN)
+
+    # inputs into HBM: T = T_X + rho T_Y, S = T[idx] (the looked-up activations)
+    T = zk.Vec(N)
+    assert zk.fr_from_i32(T, torch.from_numpy(cfg["tx"].astype(np.int32)).cuda()) == 0
+    Y = zk.Vec(N)
+    assert zk.fr_from_i32(Y, torch.from_numpy(cfg["ty"].astype(np.int32)).cuda()) == 0
+    assert zk.fr_axpy(T, T, synth.pair_combiner(cfg["seed"]), Y) == 0
+    idx = torch.from_numpy(cfg["idx"].astype(np.int32)).cuda()
+    S = zk.Vec(D)
+    chunk = 1 << 22
+    for s in range(0, D, chunk):
+        S.data[:, s:s + chunk] = T.data[:, :N].index_select(1, idx[s:s + chunk].long())
+    ws = torch.empty(zk.tlookup_workspace_bytes(D, N), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        rc, proof, info = zk.tlookup_prove(cfg["seed"], S, idx, T, ws=ws)
+        assert rc == 0, rc
+        return proof, info
+
+    first = None
+    for _ in range(args.warmup):
+        first, _ = step()
+    zk.zkmi_profile_reset()
+    zk.zkmi_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        proof, info = step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    zk.zkmi_profile_enable(False)
+    assert first is None or proof == first            # exact arithmetic: every run gives the same bytes
+    assert info["sum_A"] == info["sum_mB"]            # log-derivative identity at beta
+
+    ms = dt * 1e3 / args.steps
+    phases = {}
+    for name in ("total", "count", "inverse", "round_data", "round_table"):
+        rc, recs, total_ms = zk.zkmi_profile_query(name)
+        phases[name] = {"records": recs, "ms_per_step": total_ms / args.steps}
+    rd = phases["round_data"]
+    launches = rd["records"] / args.steps
+    avg_launch_s = rd["ms_per_step"] * 1e-3 / max(launches, 1)
+    mads_per_launch = round_data_fr_mul(D) * MADS_PER_FR_MUL / max(launches, 1)
+    achieved = mads_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
+    out = {
+        "metric": "tlookup_prove Fr-mul/s at D=2^%d, N=2^%d (wall ms in ms_per_step)" % (args.logD, args.logN),
+        "value": fr_mul_model(D, N) / (ms * 1e-3),
+        "unit": "Fr-mul/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32x8 (255-bit Montgomery integers)", "data": "synthetic",
+        "config": {"workload": "config 3: tlookup SwiGLU/activation pair table at 7B-FFN shape, "
+                               "%d x %d activations padded to D=2^%d, N=2^%d" % (rows, cols, args.logD, args.logN),
+                   "D": D, "N": N, "proof_bytes": len(proof), "fr_mul_model": fr_mul_model(D, N)},
+        "phases_ms": {k: round(v["ms_per_step"], 4) for k, v in phases.items()},
+        "roofline": {"bound": "alu", "kernel": "k_round_data",
+                     "achieved": achieved / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
+                     "frac": achieved / PEAK_MAD_PER_S, "traffic": measured_traffic(),
+                     "launches_per_step": launches, "avg_launch_ms": avg_launch_s * 1e3,
+                     "algorithmic_bytes_per_launch": (D * 32 * 2 + (D * 32 * 2) * 1.5) / max(launches, 1),
+                     "hbm_GBps_algorithmic": (D * 32 * 2 * 2.5) / (rd["ms_per_step"] * 1e-3) / 1e9 if rd["ms_per_step"] else 0.0},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_logD, min(args.logN, args.cpu_logD))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

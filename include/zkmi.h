@@ -100,7 +100,7 @@ int fr_axpy(fr_vec dst, fr_vec x, const fr_t* s, fr_vec y, void* stream);
 
 /* dst_i = 1 / src_i for all i (the inverse vectors A and B of Section 4 are
  * this applied to beta + S and beta + T).  One field inversion in total, on the
- * host; everything else is products on the device.  dst may alias src.
+ * host; everything else is products on the device.  dst must not overlap src.
  * Returns ZK_E_ZERO_DENOM if any src_i is zero.  Synchronises the stream. */
 size_t fr_batch_inverse_workspace_bytes(size_t n);
 int fr_batch_inverse(fr_vec dst, fr_vec src, void* ws, size_t ws_bytes, void* stream);
@@ -237,6 +237,20 @@ int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1
 size_t matmul_verify_workspace_bytes(size_t D0, size_t D1, size_t D2);
 int matmul_sumcheck_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, size_t D0, size_t D1, size_t D2,
                            fr_vec Y, fr_vec X, fr_vec W, void* ws, size_t ws_bytes, void* stream);
+
+/* ---- measurement support ------------------------------------------------------
+ * For benchmarks: the library can time its own phases with HIP events recorded
+ * on the caller's stream (so that kernels are timed where they are launched).
+ * State is per host thread.  Phases: "total" (a whole tlookup_prove call),
+ * "count" (multiplicities and digest leaves), "inverse" (both batch inversions),
+ * "round_data" (the data-side round kernel alone, one record per launch),
+ * "round_table" (the table-side round kernel alone).
+ * zkmi_profile_query returns the number of records and their summed duration in
+ * milliseconds; call it after the stream has been synchronised.  Unknown phase:
+ * ZK_E_BADARG. */
+int zkmi_profile_enable(int on);
+int zkmi_profile_reset(void);
+int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms);
 
 /* Library version (major * 100 + minor). */
 int zkmi_version(void);

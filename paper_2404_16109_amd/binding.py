@@ -46,6 +46,9 @@ def _load():
     P = ctypes.POINTER
     sigs = {
         "zkmi_version": (i32, []),
+        "zkmi_profile_enable": (i32, [i32]),
+        "zkmi_profile_reset": (i32, []),
+        "zkmi_profile_query": (i32, [ctypes.c_char_p, P(ctypes.c_uint64), P(ctypes.c_double)]),
         "fr_constants": (i32, [P(fr_t), P(fr_t), P(fr_t), P(ctypes.c_uint32)]),
         "fr_from_i32": (i32, [fr_vec, vp, sz, vp]),
         "fr_from_canonical": (i32, [fr_vec, vp, sz, vp]),
@@ -88,7 +91,7 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ["zkmi_version", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
+EXPORTS = ["zkmi_version", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
@@ -151,6 +154,21 @@ def _ws(nbytes):
 
 def zkmi_version():
     return _lib.zkmi_version()
+
+
+def zkmi_profile_enable(on):
+    return _lib.zkmi_profile_enable(1 if on else 0)
+
+
+def zkmi_profile_reset():
+    return _lib.zkmi_profile_reset()
+
+
+def zkmi_profile_query(phase):
+    """Returns (rc, records, total_ms)."""
+    n, ms = ctypes.c_uint64(0), ctypes.c_double(0.0)
+    rc = _lib.zkmi_profile_query(phase.encode(), ctypes.byref(n), ctypes.byref(ms))
+    return rc, n.value, ms.value
 
 
 def fr_constants():

@@ -80,6 +80,18 @@ int mailbox_bulk(Mailbox* mb, size_t bytes);
 
 inline hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
+// Optional timing of phases with HIP events on the caller's stream (see
+// zkmi_profile_* in the public header).  A scope records one start/stop pair.
+enum ProfilePhase { kProfTotal = 0, kProfCount, kProfInverse, kProfRoundData, kProfRoundTable, kProfPhases };
+int profile_open(int phase, hipStream_t stream);   // returns a record handle or -1 when profiling is off
+void profile_close(int handle, hipStream_t stream);
+struct ProfileScope {
+    ProfileScope(int phase, hipStream_t stream) : stream_(stream), handle_(profile_open(phase, stream)) {}
+    ~ProfileScope() { profile_close(handle_, stream_); }
+    hipStream_t stream_;
+    int handle_;
+};
+
 // Montgomery scalar as a kernel argument.
 inline Fr to_dev(const host::F& a) {
     Fr o;

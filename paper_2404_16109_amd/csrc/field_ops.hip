@@ -1,6 +1,10 @@
 // Elementwise field kernels and their C entry points: embedding of integers,
 // conversions between canonical and Montgomery limb-major form, add/sub/mul and
 // the scalar variants.
+#include <string.h>
+
+#include <vector>
+
 #include "common.h"
 
 namespace zkmi {
@@ -27,6 +31,62 @@ int mailbox_bulk(Mailbox* mb, size_t bytes) {
     mb->bulk = (uint8_t*)p;
     mb->bulk_bytes = want;
     return ZK_OK;
+}
+
+// ---- phase timing ----------------------------------------------------------------------
+
+namespace {
+struct ProfileRecord {
+    int phase;
+    hipEvent_t start, stop;
+};
+struct ProfileState {
+    bool on = false;
+    std::vector<hipEvent_t> pool;  // events created so far
+    size_t used = 0;
+    std::vector<ProfileRecord> open_records;
+    double ms[kProfPhases] = {0};
+    uint64_t count[kProfPhases] = {0};
+};
+ProfileState& profile_state() {
+    static thread_local ProfileState st;
+    return st;
+}
+hipEvent_t profile_event(ProfileState& st) {
+    if (st.used == st.pool.size()) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        st.pool.push_back(e);
+    }
+    return st.pool[st.used++];
+}
+void profile_resolve(ProfileState& st) {
+    for (const ProfileRecord& r : st.open_records) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.stop) == hipSuccess && hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+            st.ms[r.phase] += ms;
+            st.count[r.phase] += 1;
+        }
+    }
+    st.open_records.clear();
+    st.used = 0;
+}
+}  // namespace
+
+int profile_open(int phase, hipStream_t stream) {
+    ProfileState& st = profile_state();
+    if (!st.on) return -1;
+    hipEvent_t a = profile_event(st), b = profile_event(st);
+    if (!a || !b) return -1;
+    if (hipEventRecord(a, stream) != hipSuccess) return -1;
+    st.open_records.push_back(ProfileRecord{phase, a, b});
+    return (int)st.open_records.size() - 1;
+}
+
+void profile_close(int handle, hipStream_t stream) {
+    if (handle < 0) return;
+    ProfileState& st = profile_state();
+    if ((size_t)handle < st.open_records.size()) (void)hipEventRecord(st.open_records[handle].stop, stream);
 }
 
 // x >= 0 -> x, x < 0 -> r - |x|, in Montgomery form.
@@ -118,6 +178,36 @@ using namespace zkmi;
 extern "C" {
 
 int zkmi_version(void) { return 100; }
+
+int zkmi_profile_enable(int on) {
+    profile_state().on = on != 0;
+    return ZK_OK;
+}
+
+int zkmi_profile_reset(void) {
+    ProfileState& st = profile_state();
+    profile_resolve(st);
+    for (int p = 0; p < kProfPhases; ++p) {
+        st.ms[p] = 0;
+        st.count[p] = 0;
+    }
+    return ZK_OK;
+}
+
+int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms) {
+    static const char* names[kProfPhases] = {"total", "count", "inverse", "round_data", "round_table"};
+    if (!phase || !records || !total_ms) return ZK_E_BADARG;
+    ProfileState& st = profile_state();
+    profile_resolve(st);
+    for (int p = 0; p < kProfPhases; ++p) {
+        if (strcmp(phase, names[p]) == 0) {
+            *records = st.count[p];
+            *total_ms = st.ms[p];
+            return ZK_OK;
+        }
+    }
+    return ZK_E_BADARG;
+}
 
 int fr_constants(fr_t* modulus, fr_t* mont_r, fr_t* mont_r2, uint32_t* neg_inv32) {
     if (!modulus || !mont_r || !mont_r2 || !neg_inv32) return ZK_E_BADARG;

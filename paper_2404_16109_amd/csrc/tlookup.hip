@@ -229,9 +229,15 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     carve_prove(w, cv, D, N);
     if (cv.overflow()) return ZK_E_BUFSZ;
 
+    ProfileScope prof_total(kProfTotal, stream);
+
     // -- Prep: multiplicities and their digest ------------------------------------
     uint64_t bad = 0;
-    int rc = count_rows(w, S, idx, T, D, N, &bad, mb, stream);
+    int rc;
+    {
+        ProfileScope prof(kProfCount, stream);
+        rc = count_rows(w, S, idx, T, D, N, &bad, mb, stream);
+    }
     if (rc == ZK_E_NOT_IN_TABLE && aux) aux->bad_index = bad;
     ZK_TRY(rc);
     uint8_t md[32];
@@ -246,10 +252,12 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     if (forced_beta) beta = from_canonical(*forced_beta);
     hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.M, N, w.m, N);
     {
+        ProfileScope prof(kProfInverse, stream);
         Carver inv_cv = cv;  // scratch reused by the two inversions
         ZK_TRY(batch_inverse_run(w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb, stream));
     }
     {
+        ProfileScope prof(kProfInverse, stream);
         Carver inv_cv = cv;
         ZK_TRY(batch_inverse_run(w.A, D, S.limbs, S.stride, D, beta, inv_cv, mb, stream));
     }
@@ -332,7 +340,10 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         d.eq = ep.round(k);
         d.partials = w.partD;
         d.pstride = (size_t)kMaxPartialBlocks * 5;
-        hipLaunchKernelGGL(k_round_data, dim3(blocks), dim3(kBlock), 0, stream, d);
+        {
+            ProfileScope prof(kProfRoundData, stream);
+            hipLaunchKernelGGL(k_round_data, dim3(blocks), dim3(kBlock), 0, stream, d);
+        }
         launch_final_sum(w.partD, d.pstride, blocks, 5, mb->words, stream);
         if (table_round) {
             TableRoundArgs t;
@@ -348,7 +359,10 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
             t.eq = d.eq;
             t.partials = w.partT;
             t.pstride = (size_t)kMaxPartialBlocks * 6;
-            hipLaunchKernelGGL(k_round_table, dim3(blocks), dim3(kBlock), 0, stream, t);
+            {
+                ProfileScope prof(kProfRoundTable, stream);
+                hipLaunchKernelGGL(k_round_table, dim3(blocks), dim3(kBlock), 0, stream, t);
+            }
             launch_final_sum(w.partT, t.pstride, blocks, 6, mb->words + 40, stream);
         }
         ZK_HIP_TRY(hipGetLastError());

@@ -68,6 +68,28 @@ static __global__ void __launch_bounds__(kBlock) k_canon_rows(uint32_t* __restri
         canon[j] = hash_find(slots, cap_mask, T, ts, fr_load(T, ts, j));
 }
 
+// Adds one to m[row] for every active lane with a valid row.  Activation
+// tensors repeat values heavily (padding, saturated or popular entries), and
+// atomics to one address serialise, so lanes of a wavefront that hit the same
+// row are merged first: a few rounds of "take the first pending lane's row,
+// count the lanes that share it, one atomic for all of them", then plain atomics
+// for whatever rows are left.
+__device__ __forceinline__ void count_merged(uint32_t* m, uint32_t row, bool valid) {
+    bool pending = valid;
+#pragma unroll 1
+    for (int round = 0; round < 8; ++round) {
+        unsigned long long todo = __ballot(pending);
+        if (todo == 0) return;
+        int leader = __ffsll((long long)todo) - 1;
+        uint32_t lead_row = __shfl(row, leader, 64);
+        bool mine = pending && row == lead_row;
+        unsigned long long same = __ballot(mine);
+        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&m[lead_row], (uint32_t)__popcll(same));
+        pending = pending && !mine;
+    }
+    if (pending) atomicAdd(&m[row], 1u);
+}
+
 // m[row(S_i)] += 1.  With idx the row is given and only checked; without, it is
 // found through the hash.  The smallest offending i ends up in *bad.
 static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint32_t* __restrict__ S, size_t ss, size_t D,
@@ -76,18 +98,26 @@ static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint
                                                   uint32_t cap_mask, const uint32_t* __restrict__ canon,
                                                   const uint32_t* __restrict__ dup_flag, unsigned long long* bad) {
     const bool dups = *dup_flag != 0;
-    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < D; i += (size_t)gridDim.x * kBlock) {
-        Fr v = fr_load(S, ss, i);
-        uint32_t row;
-        if (idx) {
-            row = idx[i];
-            if (row >= N || !fr_equal(fr_load(T, ts, row), v)) row = kEmptySlot;
-            else if (dups) row = canon[row];
-        } else {
-            row = hash_find(slots, cap_mask, T, ts, v);
+    // every lane of a wavefront runs the same number of iterations, so the
+    // cross-lane steps in count_merged see whole wavefronts
+    const size_t per_pass = (size_t)gridDim.x * kBlock;
+    const size_t passes = (D + per_pass - 1) / per_pass;
+    for (size_t pass = 0; pass < passes; ++pass) {
+        size_t i = pass * per_pass + blockIdx.x * (size_t)kBlock + threadIdx.x;
+        bool in_range = i < D;
+        uint32_t row = kEmptySlot;
+        if (in_range) {
+            Fr v = fr_load(S, ss, i);
+            if (idx) {
+                row = idx[i];
+                if (row >= N || !fr_equal(fr_load(T, ts, row), v)) row = kEmptySlot;
+                else if (dups) row = canon[row];
+            } else {
+                row = hash_find(slots, cap_mask, T, ts, v);
+            }
+            if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
         }
-        if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
-        else atomicAdd(&m[row], 1u);
+        count_merged(m, row, in_range && row != kEmptySlot);
     }
 }
 
