@@ -124,50 +124,204 @@ __device__ __forceinline__ Fr fr_neg(const Fr& a) { return fr_sub(fr_zero(), a);
 
 __device__ __forceinline__ Fr fr_double(const Fr& a) { return fr_add(a, a); }
 
-// Montgomery product a * b / 2^256 mod r (coarsely integrated operand scanning,
-// one row of a*b_i then one reduction step per i).
-__device__ __forceinline__ Fr fr_mul(const Fr& a, const Fr& b) {
-    const uint32_t r[8] = {ZK_R0, ZK_R1, ZK_R2, ZK_R3, ZK_R4, ZK_R5, ZK_R6, ZK_R7};
-    uint32_t t[10];
-#pragma unroll
-    for (int k = 0; k < 10; ++k) t[k] = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        uint64_t c = 0;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint64_t p = (uint64_t)a.l[j] * b.l[i] + t[j] + c;
-            t[j] = (uint32_t)p;
-            c = p >> 32;
-        }
-        uint64_t s = (uint64_t)t[8] + c;
-        t[8] = (uint32_t)s;
-        t[9] = (uint32_t)(s >> 32);
-        // quotient digit m = t0 * (-r^-1) = -t0; t0 + m*r0 = 2^32 * [t0 != 0]
-        uint32_t m = 0u - t[0];
-        c = (t[0] != 0) ? 1u : 0u;
-#pragma unroll
-        for (int j = 1; j < 8; ++j) {
-            uint64_t p = (uint64_t)m * r[j] + t[j] + c;
-            t[j - 1] = (uint32_t)p;
-            c = p >> 32;
-        }
-        s = (uint64_t)t[8] + c;
-        t[7] = (uint32_t)s;
-        t[8] = t[9] + (uint32_t)(s >> 32);
+// acc (64 bits) and ex (overflow count) form a 96-bit column accumulator.
+// fr_macN adds N limb products to it: each v_mad_u64_u32 leaves the carry out of
+// bit 63 in VCC and the v_addc_co_u32 behind it folds that carry into ex, two
+// full-rate instructions per limb product.  A whole column goes into one asm
+// statement so that the compiler's hazard padding between statements is paid
+// once per column, not once per product.  The K variants take wave-uniform
+// second factors (limbs of r) from scalar registers.
+#define ZK_MAC(x, y) "v_mad_u64_u32 %0, vcc, %" #x ", %" #y ", %0\n\tv_addc_co_u32 %1, vcc, 0, %1, vcc\n\t"
+__device__ __forceinline__ void fr_mac1(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0) {
+    asm(ZK_MAC(2, 3) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0) : "vcc");
+}
+__device__ __forceinline__ void fr_mack1(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0) {
+    asm(ZK_MAC(2, 3) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0) : "vcc");
+}
+__device__ __forceinline__ void fr_mac2(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1) : "vcc");
+}
+__device__ __forceinline__ void fr_mack2(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1) : "vcc");
+}
+__device__ __forceinline__ void fr_mac3(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2) : "vcc");
+}
+__device__ __forceinline__ void fr_mack3(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2) : "vcc");
+}
+__device__ __forceinline__ void fr_mac4(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3) : "vcc");
+}
+__device__ __forceinline__ void fr_mack4(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3) : "vcc");
+}
+__device__ __forceinline__ void fr_mac5(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4) : "vcc");
+}
+__device__ __forceinline__ void fr_mack5(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4) : "vcc");
+}
+__device__ __forceinline__ void fr_mac6(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5) : "vcc");
+}
+__device__ __forceinline__ void fr_mack6(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5) : "vcc");
+}
+__device__ __forceinline__ void fr_mac7(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6) : "vcc");
+}
+__device__ __forceinline__ void fr_mack7(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6) : "vcc");
+}
+__device__ __forceinline__ void fr_mac8(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6, uint32_t x7, uint32_t y7) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6), "v"(x7), "v"(y7) : "vcc");
+}
+__device__ __forceinline__ void fr_mack8(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6, uint32_t x7, uint32_t y7) {
+    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6), "v"(x7), "s"(y7) : "vcc");
+}
+
+// Adds a_lo..a_hi times the matching b limbs of column c (indices j, c-j).
+template <int C, int LO, int N>
+__device__ __forceinline__ void fr_col_products(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* b) {
+    if constexpr (N == 1) fr_mac1(acc, ex, a[LO], b[C - LO]);
+    if constexpr (N == 2) fr_mac2(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1]);
+    if constexpr (N == 3) fr_mac3(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2]);
+    if constexpr (N == 4)
+        fr_mac4(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3]);
+    if constexpr (N == 5)
+        fr_mac5(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
+                a[LO + 4], b[C - LO - 4]);
+    if constexpr (N == 6)
+        fr_mac6(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
+                a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5]);
+    if constexpr (N == 7)
+        fr_mac7(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
+                a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5], a[LO + 6], b[C - LO - 6]);
+    if constexpr (N == 8)
+        fr_mac8(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
+                a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5], a[LO + 6], b[C - LO - 6], a[LO + 7], b[C - LO - 7]);
+}
+
+// Adds m_lo..m_hi times the matching limbs of r of column c (indices i, c-i).
+template <int C, int LO, int N>
+__device__ __forceinline__ void fr_col_reductions(uint64_t& acc, uint32_t& ex, const uint32_t* m) {
+    constexpr uint32_t r[8] = {ZK_R0, ZK_R1, ZK_R2, ZK_R3, ZK_R4, ZK_R5, ZK_R6, ZK_R7};
+    if constexpr (N == 1) fr_mack1(acc, ex, m[LO], r[C - LO]);
+    if constexpr (N == 2) fr_mack2(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1]);
+    if constexpr (N == 3) fr_mack3(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2]);
+    if constexpr (N == 4)
+        fr_mack4(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3]);
+    if constexpr (N == 5)
+        fr_mack5(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
+                 m[LO + 4], r[C - LO - 4]);
+    if constexpr (N == 6)
+        fr_mack6(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
+                 m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5]);
+    if constexpr (N == 7)
+        fr_mack7(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
+                 m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5], m[LO + 6], r[C - LO - 6]);
+    if constexpr (N == 8)
+        fr_mack8(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
+                 m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5], m[LO + 6], r[C - LO - 6], m[LO + 7], r[C - LO - 7]);
+}
+
+// Next column: drop the finished low word.
+__device__ __forceinline__ void fr_col_shift(uint64_t& acc, uint32_t& ex) {
+    acc = (acc >> 32) | ((uint64_t)ex << 32);
+    ex = 0;
+}
+
+// Same as fr_col_products with the b limbs wave-uniform (scalar registers).
+template <int C, int LO, int N>
+__device__ __forceinline__ void fr_col_products_k(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* k) {
+    if constexpr (N == 1) fr_mack1(acc, ex, a[LO], k[C - LO]);
+    if constexpr (N == 2) fr_mack2(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1]);
+    if constexpr (N == 3) fr_mack3(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2]);
+    if constexpr (N == 4)
+        fr_mack4(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3]);
+    if constexpr (N == 5)
+        fr_mack5(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
+                 a[LO + 4], k[C - LO - 4]);
+    if constexpr (N == 6)
+        fr_mack6(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
+                 a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5]);
+    if constexpr (N == 7)
+        fr_mack7(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
+                 a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5], a[LO + 6], k[C - LO - 6]);
+    if constexpr (N == 8)
+        fr_mack8(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
+                 a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5], a[LO + 6], k[C - LO - 6], a[LO + 7], k[C - LO - 7]);
+}
+
+template <bool UNIFORM_B, int C>
+__device__ __forceinline__ void fr_mul_low_column(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* b,
+                                                  uint32_t* m) {
+    if constexpr (C > 0) {
+        if constexpr (UNIFORM_B) fr_col_products_k<C, 0, C + 1>(acc, ex, a, b);
+        else fr_col_products<C, 0, C + 1>(acc, ex, a, b);
+        fr_col_reductions<C, 0, C>(acc, ex, m);
     }
+    m[C] = 0u - (uint32_t)acc;
+    fr_mack1(acc, ex, m[C], 1u);
+    fr_col_shift(acc, ex);
+}
+
+template <bool UNIFORM_B, int C>
+__device__ __forceinline__ void fr_mul_high_column(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* b,
+                                                   const uint32_t* m, uint32_t* t) {
+    if constexpr (UNIFORM_B) fr_col_products_k<C, C - 7, 15 - C>(acc, ex, a, b);
+    else fr_col_products<C, C - 7, 15 - C>(acc, ex, a, b);
+    fr_col_reductions<C, C - 7, 15 - C>(acc, ex, m);
+    t[C - 8] = (uint32_t)acc;
+    fr_col_shift(acc, ex);
+}
+
+// Montgomery product a * b / 2^256 mod r, column by column (product scanning with
+// the reduction interleaved): column c collects a_j b_(c-j) and m_i r_(c-i); for
+// c < 8 the digit m_c = -column (r = 1 mod 2^32) is chosen so that its r_0 term
+// clears the column's low word.  128 multiply-adds, each with one carry fold.
+template <bool UNIFORM_B>
+__device__ __forceinline__ Fr fr_mul_impl(const Fr& a, const Fr& b) {
+    uint32_t m[8];
+    uint32_t t[8];
+    uint64_t acc = (uint64_t)a.l[0] * b.l[0];  // column 0 has a single product
+    uint32_t ex = 0;
+    fr_mul_low_column<UNIFORM_B, 0>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 1>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 2>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 3>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 4>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 5>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 6>(acc, ex, a.l, b.l, m);
+    fr_mul_low_column<UNIFORM_B, 7>(acc, ex, a.l, b.l, m);
+    fr_mul_high_column<UNIFORM_B, 8>(acc, ex, a.l, b.l, m, t);
+    fr_mul_high_column<UNIFORM_B, 9>(acc, ex, a.l, b.l, m, t);
+    fr_mul_high_column<UNIFORM_B, 10>(acc, ex, a.l, b.l, m, t);
+    fr_mul_high_column<UNIFORM_B, 11>(acc, ex, a.l, b.l, m, t);
+    fr_mul_high_column<UNIFORM_B, 12>(acc, ex, a.l, b.l, m, t);
+    fr_mul_high_column<UNIFORM_B, 13>(acc, ex, a.l, b.l, m, t);
+    fr_mul_high_column<UNIFORM_B, 14>(acc, ex, a.l, b.l, m, t);
+    // column 15 holds only what was carried up; the result is < 2r < 2^256
+    t[7] = (uint32_t)acc;
     return fr_reduce_once(t);
 }
+
+__device__ __forceinline__ Fr fr_mul(const Fr& a, const Fr& b) { return fr_mul_impl<false>(a, b); }
+
+// a * k for a wave-uniform k (a kernel argument or a constant): its limbs stay in
+// scalar registers and cost no vector registers.
+__device__ __forceinline__ Fr fr_mul_uniform(const Fr& a, const Fr& k) { return fr_mul_impl<true>(a, k); }
 
 __device__ __forceinline__ Fr fr_sqr(const Fr& a) { return fr_mul(a, a); }
 
 // canonical integer (8 limbs, < 2^256) -> Montgomery form
-__device__ __forceinline__ Fr fr_to_mont(const Fr& canonical) { return fr_mul(canonical, fr_rr()); }
+__device__ __forceinline__ Fr fr_to_mont(const Fr& canonical) { return fr_mul_uniform(canonical, fr_rr()); }
 
 // Montgomery form -> canonical integer in [0, r)
 __device__ __forceinline__ Fr fr_from_mont(const Fr& a) {
     Fr one = Fr{{1, 0, 0, 0, 0, 0, 0, 0}};
-    return fr_mul(a, one);
+    return fr_mul_uniform(a, one);
 }
 
 // Small unsigned integer -> Montgomery form.
@@ -183,21 +337,36 @@ struct VecView {
     size_t stride;
 };
 
+// The element's address is kept per lane in vector registers and stepped from
+// one limb plane to the next; holding eight scalar plane pointers per array
+// instead would exhaust the scalar register file in kernels that touch several
+// arrays.
 __device__ __forceinline__ Fr fr_load(const uint32_t* __restrict__ p, size_t stride, size_t i) {
+    const uint32_t* q = p + i;
+    asm("" : "+v"(q));
     Fr a;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) a.l[k] = p[k * stride + i];
+    for (int k = 0; k < 8; ++k) {
+        a.l[k] = *q;
+        q += stride;
+    }
     return a;
 }
 
 __device__ __forceinline__ void fr_store(uint32_t* __restrict__ p, size_t stride, size_t i, const Fr& a) {
+    uint32_t* q = p + i;
+    asm("" : "+v"(q));
 #pragma unroll
-    for (int k = 0; k < 8; ++k) p[k * stride + i] = a.l[k];
+    for (int k = 0; k < 8; ++k) {
+        *q = a.l[k];
+        q += stride;
+    }
 }
 
-// a0 + r * (a1 - a0): one variable of a multilinear extension bound to r.
+// a0 + r * (a1 - a0): one variable of a multilinear extension bound to r, the
+// same r for the whole wavefront.
 __device__ __forceinline__ Fr fr_fold(const Fr& a0, const Fr& a1, const Fr& r) {
-    return fr_add(a0, fr_mul(r, fr_sub(a1, a0)));
+    return fr_add(a0, fr_mul_uniform(fr_sub(a1, a0), r));
 }
 
 }  // namespace zkmi

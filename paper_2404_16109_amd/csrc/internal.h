@@ -14,7 +14,7 @@ int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, siz
 
 // ---- sums -----------------------------------------------------------------
 // Partial sums buffer for reductions: up to kMaxPartialBlocks blocks.
-static const unsigned kMaxPartialBlocks = 1024;
+static const unsigned kMaxPartialBlocks = 4096;
 
 // Adds up `nv` interleaved per-block partial values (block b, value q at
 // element b*nv + q of `partials`, limb-major with stride pstride) and writes

@@ -12,21 +12,21 @@ struct ProductRoundArgs {
     PairArray a, b;
     size_t half;
     size_t block_span;
-    int fold;
     Fr r_prev;
     uint32_t* partials;  // 3 values per workgroup
     size_t pstride;
 };
 
 // g(0) = sum a0 b0, g(1) = sum a1 b1 and the leading coefficient sum (a1-a0)(b1-b0).
+template <bool FOLD>
 __global__ void __launch_bounds__(kBlock) k_round_product(ProductRoundArgs g) {
     __shared__ uint32_t lds[4 * 3 * 8];
     Fr tot[3] = {fr_zero(), fr_zero(), fr_zero()};
     const size_t start = blockIdx.x * g.block_span;
     for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
         Fr a0, a1, b0, b1;
-        load_pair(g.a, p, g.half, g.fold, g.r_prev, a0, a1);
-        load_pair(g.b, p, g.half, g.fold, g.r_prev, b0, b1);
+        load_pair<FOLD>(g.a, p, g.half, g.r_prev, a0, a1);
+        load_pair<FOLD>(g.b, p, g.half, g.r_prev, b0, b1);
         tot[0] = fr_add(tot[0], fr_mul(a0, b0));
         tot[1] = fr_add(tot[1], fr_mul(a1, b1));
         tot[2] = fr_add(tot[2], fr_mul(fr_sub(a1, a0), fr_sub(b1, b0)));
@@ -73,11 +73,11 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         g.b = PairArray{b, bs, b, bs};
         g.half = half;
         g.block_span = span;
-        g.fold = k > 0;
         g.r_prev = to_dev(r_prev);
         g.partials = partials;
         g.pstride = pstride;
-        hipLaunchKernelGGL(k_round_product, dim3(blocks), dim3(kBlock), 0, stream, g);
+        if (k > 0) hipLaunchKernelGGL(k_round_product<true>, dim3(blocks), dim3(kBlock), 0, stream, g);
+        else hipLaunchKernelGGL(k_round_product<false>, dim3(blocks), dim3(kBlock), 0, stream, g);
         launch_final_sum(partials, pstride, blocks, 3, mb->words, stream);
         ZK_HIP_TRY(hipGetLastError());
         ZK_HIP_TRY(hipStreamSynchronize(stream));

@@ -322,8 +322,11 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     F sum_A = zero();
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
+        const EqSplit eq = ep.round(k);
+        // a workgroup's pairs must share the high factor of their weights
         size_t span = half / kMaxPartialBlocks;
         if (span < (size_t)kBlock * 4) span = (size_t)kBlock * 4;
+        if (eq.has_hi && span > ((size_t)1 << eq.lbits)) span = (size_t)1 << eq.lbits;
         if (span > half) span = half;
         const unsigned blocks = (unsigned)(half / span);
         const bool table_round = k >= h;
@@ -334,15 +337,15 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         else d.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
         d.half = half;
         d.block_span = span;
-        d.fold = k > 0;
         d.r_prev = to_dev(r_prev);
         d.beta = to_dev(beta);
-        d.eq = ep.round(k);
+        d.eq = eq;
         d.partials = w.partD;
         d.pstride = (size_t)kMaxPartialBlocks * 5;
         {
             ProfileScope prof(kProfRoundData, stream);
-            hipLaunchKernelGGL(k_round_data, dim3(blocks), dim3(kBlock), 0, stream, d);
+            if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
+            else hipLaunchKernelGGL(k_round_data<false>, dim3(blocks), dim3(kBlock), 0, stream, d);
         }
         launch_final_sum(w.partD, d.pstride, blocks, 5, mb->words, stream);
         if (table_round) {
@@ -353,7 +356,6 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
             t.M = PairArray{w.M, N, w.M, N};
             t.half = half;
             t.block_span = span;
-            t.fold = k > h;
             t.r_prev = d.r_prev;
             t.beta = d.beta;
             t.eq = d.eq;
@@ -361,7 +363,8 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
             t.pstride = (size_t)kMaxPartialBlocks * 6;
             {
                 ProfileScope prof(kProfRoundTable, stream);
-                hipLaunchKernelGGL(k_round_table, dim3(blocks), dim3(kBlock), 0, stream, t);
+                if (k > h) hipLaunchKernelGGL(k_round_table<true>, dim3(blocks), dim3(kBlock), 0, stream, t);
+                else hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
             }
             launch_final_sum(w.partT, t.pstride, blocks, 6, mb->words + 40, stream);
         }

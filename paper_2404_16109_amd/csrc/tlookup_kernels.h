@@ -246,19 +246,23 @@ struct PairArray {
 
 // Loads the pair (x0, x1) of index p for this round.  Without folding the
 // array has 2*half entries.  With folding it has 4*half: the previous variable
-// is bound to r first, the folded entries are written back (to dst) and
-// returned.
-__device__ __forceinline__ void load_pair(const PairArray& a, size_t p, size_t half, bool fold, const Fr& r, Fr& x0,
-                                          Fr& x1) {
-    if (!fold) {
+// is bound to r first (r is wave-uniform), the folded entries are written back
+// (to dst) and returned.
+template <bool FOLD>
+__device__ __forceinline__ void load_pair(const PairArray& a, size_t p, size_t half, const Fr& r, Fr& x0, Fr& x1) {
+    if constexpr (!FOLD) {
         x0 = fr_load(a.src, a.ss, p);
         x1 = fr_load(a.src, a.ss, p + half);
     } else {
-        Fr y0 = fr_load(a.src, a.ss, p), y1 = fr_load(a.src, a.ss, p + half);
-        Fr y2 = fr_load(a.src, a.ss, p + 2 * half), y3 = fr_load(a.src, a.ss, p + 3 * half);
-        x0 = fr_fold(y0, y2, r);
-        x1 = fr_fold(y1, y3, r);
+        {
+            Fr y0 = fr_load(a.src, a.ss, p), y2 = fr_load(a.src, a.ss, p + 2 * half);
+            x0 = fr_fold(y0, y2, r);
+        }
         fr_store(a.dst, a.ds, p, x0);
+        {
+            Fr y1 = fr_load(a.src, a.ss, p + half), y3 = fr_load(a.src, a.ss, p + 3 * half);
+            x1 = fr_fold(y1, y3, r);
+        }
         fr_store(a.dst, a.ds, p + half, x1);
     }
 }
@@ -266,8 +270,7 @@ __device__ __forceinline__ void load_pair(const PairArray& a, size_t p, size_t h
 struct DataRoundArgs {
     PairArray A, S;
     size_t half;        // pairs in this round
-    size_t block_span;  // pairs per workgroup (power of two)
-    int fold;
+    size_t block_span;  // pairs per workgroup (power of two, at most 2^eq.lbits when eq.has_hi)
     Fr r_prev, beta;
     EqSplit eq;
     uint32_t* partials;  // 5 values per workgroup
@@ -277,41 +280,37 @@ struct DataRoundArgs {
 // Data side of one round.  With w the weight of a pair and (A0, A1), (S0, S1)
 // its entries, the workgroup sums
 //   q0 = w A0 (S0+beta), q1 = w A1 (S1+beta), qinf = w (A1-A0)(S1-S0), sA0 = A0, sA1 = A1,
-// from which the host forms  alpha c e~(u_k, X) q(X) + sA(X).
+// from which the host forms  alpha c e~(u_k, X) q(X) + sA(X).  All pairs of a
+// workgroup share the high-variable factor of their weight, which is applied
+// once to the workgroup's sums.
+template <bool FOLD>
 static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
     __shared__ uint32_t lds[4 * 5 * 8];
     Fr tot[5];
 #pragma unroll
     for (int q = 0; q < 5; ++q) tot[q] = fr_zero();
     const size_t start = blockIdx.x * g.block_span;
-    const size_t lo_size = (size_t)1 << g.eq.lbits;
-    const size_t sub_span = g.block_span < lo_size ? g.block_span : lo_size;
-    for (size_t sub = 0; sub < g.block_span; sub += sub_span) {
-        Fr q0 = fr_zero(), q1 = fr_zero(), qi = fr_zero();
-        for (size_t p = start + sub + threadIdx.x; p < start + sub + sub_span; p += kBlock) {
-            Fr a0, a1, s0, s1;
-            load_pair(g.A, p, g.half, g.fold, g.r_prev, a0, a1);
-            load_pair(g.S, p, g.half, g.fold, g.r_prev, s0, s1);
-            Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & (lo_size - 1)));
-            tot[3] = fr_add(tot[3], a0);
-            tot[4] = fr_add(tot[4], a1);
-            Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
-            q0 = fr_add(q0, fr_mul(wa0, fr_add(s0, g.beta)));
-            q1 = fr_add(q1, fr_mul(wa1, fr_add(s1, g.beta)));
-            qi = fr_add(qi, fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
-        }
-        if (g.eq.has_hi) {
-            Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + ((start + sub) >> g.eq.lbits));
-            q0 = fr_mul(q0, hf);
-            q1 = fr_mul(q1, hf);
-            qi = fr_mul(qi, hf);
-        }
-        tot[0] = fr_add(tot[0], q0);
-        tot[1] = fr_add(tot[1], q1);
-        tot[2] = fr_add(tot[2], qi);
+    const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
+        Fr a0, a1, s0, s1;
+        load_pair<FOLD>(g.A, p, g.half, g.r_prev, a0, a1);
+        load_pair<FOLD>(g.S, p, g.half, g.r_prev, s0, s1);
+        Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
+        tot[3] = fr_add(tot[3], a0);
+        tot[4] = fr_add(tot[4], a1);
+        Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
+        tot[0] = fr_add(tot[0], fr_mul(wa0, fr_add(s0, g.beta)));
+        tot[1] = fr_add(tot[1], fr_mul(wa1, fr_add(s1, g.beta)));
+        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
     }
     block_sum<5, 4>(tot, lds);
     if (threadIdx.x == 0) {
+        if (g.eq.has_hi) {
+            Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + (start >> g.eq.lbits));
+            tot[0] = fr_mul(tot[0], hf);
+            tot[1] = fr_mul(tot[1], hf);
+            tot[2] = fr_mul(tot[2], hf);
+        }
 #pragma unroll
         for (int q = 0; q < 5; ++q) fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 5 + q, tot[q]);
     }
@@ -321,7 +320,6 @@ struct TableRoundArgs {
     PairArray B, T, M;
     size_t half;
     size_t block_span;
-    int fold;
     Fr r_prev, beta;
     EqSplit eq;
     uint32_t* partials;  // 6 values per workgroup
@@ -331,42 +329,40 @@ struct TableRoundArgs {
 // Table side of one round (once the table's own variables are being bound):
 //   t0 = w B0 (T0+beta), t1 = w B1 (T1+beta), tinf = w (B1-B0)(T1-T0),
 //   m0 = B0 M0, m1 = B1 M1, minf = (B1-B0)(M1-M0).
+template <bool FOLD>
 static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g) {
     __shared__ uint32_t lds[4 * 6 * 8];
     Fr tot[6];
 #pragma unroll
     for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
     const size_t start = blockIdx.x * g.block_span;
-    const size_t lo_size = (size_t)1 << g.eq.lbits;
-    const size_t sub_span = g.block_span < lo_size ? g.block_span : lo_size;
-    for (size_t sub = 0; sub < g.block_span; sub += sub_span) {
-        Fr q0 = fr_zero(), q1 = fr_zero(), qi = fr_zero();
-        for (size_t p = start + sub + threadIdx.x; p < start + sub + sub_span; p += kBlock) {
-            Fr b0, b1, t0, t1, m0, m1;
-            load_pair(g.B, p, g.half, g.fold, g.r_prev, b0, b1);
-            load_pair(g.T, p, g.half, g.fold, g.r_prev, t0, t1);
-            load_pair(g.M, p, g.half, g.fold, g.r_prev, m0, m1);
-            Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & (lo_size - 1)));
+    const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
+        Fr b0, b1;
+        load_pair<FOLD>(g.B, p, g.half, g.r_prev, b0, b1);
+        {
+            Fr m0, m1;
+            load_pair<FOLD>(g.M, p, g.half, g.r_prev, m0, m1);
             tot[3] = fr_add(tot[3], fr_mul(b0, m0));
             tot[4] = fr_add(tot[4], fr_mul(b1, m1));
             tot[5] = fr_add(tot[5], fr_mul(fr_sub(b1, b0), fr_sub(m1, m0)));
-            Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
-            q0 = fr_add(q0, fr_mul(wb0, fr_add(t0, g.beta)));
-            q1 = fr_add(q1, fr_mul(wb1, fr_add(t1, g.beta)));
-            qi = fr_add(qi, fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
         }
-        if (g.eq.has_hi) {
-            Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + ((start + sub) >> g.eq.lbits));
-            q0 = fr_mul(q0, hf);
-            q1 = fr_mul(q1, hf);
-            qi = fr_mul(qi, hf);
-        }
-        tot[0] = fr_add(tot[0], q0);
-        tot[1] = fr_add(tot[1], q1);
-        tot[2] = fr_add(tot[2], qi);
+        Fr t0, t1;
+        load_pair<FOLD>(g.T, p, g.half, g.r_prev, t0, t1);
+        Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
+        Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
+        tot[0] = fr_add(tot[0], fr_mul(wb0, fr_add(t0, g.beta)));
+        tot[1] = fr_add(tot[1], fr_mul(wb1, fr_add(t1, g.beta)));
+        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
     }
     block_sum<6, 4>(tot, lds);
     if (threadIdx.x == 0) {
+        if (g.eq.has_hi) {
+            Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + (start >> g.eq.lbits));
+            tot[0] = fr_mul(tot[0], hf);
+            tot[1] = fr_mul(tot[1], hf);
+            tot[2] = fr_mul(tot[2], hf);
+        }
 #pragma unroll
         for (int q = 0; q < 6; ++q) fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 6 + q, tot[q]);
     }
