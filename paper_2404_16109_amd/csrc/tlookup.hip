@@ -128,12 +128,18 @@ struct ProveWs {
     uint32_t* slots;    // hash of T
     uint32_t cap_mask;
     uint32_t* canon;    // N
+    uint4* rows;        // N rows of T, eight words each
+    uint32_t* hist;     // per-workgroup histograms (tables of up to 2^16 rows), else null
+    uint32_t hist_parts;
     uint32_t* flags;    // [0] duplicate flag, [2..3] smallest bad index (64-bit)
     uint32_t* leaves;   // nleaves * 8 words
     uint32_t nleaves;
     uint32_t* partD;    // kMaxPartialBlocks * 5
     uint32_t* partT;    // kMaxPartialBlocks * 6
 };
+
+static const size_t kLdsHistMaxRows = (size_t)1 << 16;  // packed 16-bit counters: 128 KiB of LDS
+static const uint32_t kHistParts = 256;                // one workgroup per compute unit
 
 static uint32_t hash_capacity(size_t N) {
     size_t cap = 64;
@@ -152,6 +158,9 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.cap_mask = cap - 1;
     w.slots = (uint32_t*)cv.take((size_t)cap * 4);
     w.canon = (uint32_t*)cv.take(N * 4);
+    w.rows = (uint4*)cv.take(N * 32);
+    w.hist_parts = N <= kLdsHistMaxRows ? kHistParts : 0;
+    w.hist = w.hist_parts ? (uint32_t*)cv.take((size_t)w.hist_parts * N * 4) : nullptr;
     w.flags = (uint32_t*)cv.take(64);
     w.nleaves = (uint32_t)div_up(N, kLeafCounts);
     w.leaves = (uint32_t*)cv.take((size_t)w.nleaves * 32);
@@ -181,11 +190,28 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
     hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags + 2, (size_t)2, 0xffffffffu);
     hipLaunchKernelGGL(k_hash_build, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.slots, w.cap_mask, T.limbs, T.stride,
                        (uint32_t)N, w.flags);
-    hipLaunchKernelGGL(k_canon_rows, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.canon, w.slots, w.cap_mask, T.limbs,
-                       T.stride, (uint32_t)N);
-    hipLaunchKernelGGL(k_count, dim3(grid_for(D, kBlock, 8192)), dim3(kBlock), 0, stream, w.m, S.limbs, S.stride, D, idx,
-                       T.limbs, T.stride, (uint32_t)N, w.slots, w.cap_mask, w.canon, w.flags,
-                       (unsigned long long*)(w.flags + 2));
+    hipLaunchKernelGGL(k_canon_rows, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.canon, w.rows, w.slots, w.cap_mask,
+                       T.limbs, T.stride, (uint32_t)N);
+    if (w.hist) {
+        // LDS histograms: every workgroup takes a contiguous share of S
+        static thread_local bool lds_limit_raised = false;
+        const size_t lds_bytes = ((N + 1) / 2) * 4;
+        if (!lds_limit_raised) {
+            ZK_HIP_TRY(hipFuncSetAttribute((const void*)k_count_lds, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(((kLdsHistMaxRows + 1) / 2) * 4)));
+            lds_limit_raised = true;
+        }
+        size_t per_block = align_up(div_up(D, w.hist_parts), kHistThreads);
+        hipLaunchKernelGGL(k_count_lds, dim3(w.hist_parts), dim3(kHistThreads), lds_bytes, stream, w.m, w.hist, S.limbs,
+                           S.stride, D, per_block, idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots, w.cap_mask,
+                           w.canon, w.flags, (unsigned long long*)(w.flags + 2));
+        hipLaunchKernelGGL(k_hist_reduce, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.m, w.hist, w.hist_parts,
+                           (uint32_t)N);
+    } else {
+        hipLaunchKernelGGL(k_count, dim3(grid_for(D, kBlock, 8192)), dim3(kBlock), 0, stream, w.m, S.limbs, S.stride, D,
+                           idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots, w.cap_mask, w.canon, w.flags,
+                           (unsigned long long*)(w.flags + 2));
+    }
     hipLaunchKernelGGL(k_leaf_digests, dim3((unsigned)div_up(w.nleaves, 64)), dim3(64), 0, stream, w.leaves, w.m,
                        (uint32_t)N, w.nleaves);
     ZK_HIP_TRY(hipGetLastError());

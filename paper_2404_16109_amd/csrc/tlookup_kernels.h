@@ -60,21 +60,47 @@ __device__ __forceinline__ uint32_t hash_find(const uint32_t* __restrict__ slots
     return kEmptySlot;
 }
 
-// canon[j] = lowest row with the value of row j.
-static __global__ void __launch_bounds__(kBlock) k_canon_rows(uint32_t* __restrict__ canon, const uint32_t* __restrict__ slots,
-                                                       uint32_t cap_mask, const uint32_t* __restrict__ T, size_t ts,
-                                                       uint32_t N) {
-    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock)
-        canon[j] = hash_find(slots, cap_mask, T, ts, fr_load(T, ts, j));
+// canon[j] = lowest row with the value of row j; rows[j] = row j of T as eight
+// consecutive words, so that a lookup by row number is one 32-byte access
+// instead of eight accesses to eight limb planes.
+static __global__ void __launch_bounds__(kBlock) k_canon_rows(uint32_t* __restrict__ canon, uint4* __restrict__ rows,
+                                                       const uint32_t* __restrict__ slots, uint32_t cap_mask,
+                                                       const uint32_t* __restrict__ T, size_t ts, uint32_t N) {
+    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock) {
+        Fr v = fr_load(T, ts, j);
+        canon[j] = hash_find(slots, cap_mask, T, ts, v);
+        rows[2 * j] = make_uint4(v.l[0], v.l[1], v.l[2], v.l[3]);
+        rows[2 * j + 1] = make_uint4(v.l[4], v.l[5], v.l[6], v.l[7]);
+    }
 }
 
-// Adds one to m[row] for every active lane with a valid row.  Activation
-// tensors repeat values heavily (padding, saturated or popular entries), and
-// atomics to one address serialise, so lanes of a wavefront that hit the same
-// row are merged first: a few rounds of "take the first pending lane's row,
-// count the lanes that share it, one atomic for all of them", then plain atomics
-// for whatever rows are left.
-__device__ __forceinline__ void count_merged(uint32_t* m, uint32_t row, bool valid) {
+// A wavefront's running total for the row it keeps meeting (wave-uniform).
+// Long runs of one row (padding, saturated activations) would otherwise become
+// a stream of atomics to a single address, which the memory system serialises.
+struct HotRun {
+    uint32_t row = kEmptySlot;
+    uint32_t count = 0;
+    __device__ __forceinline__ void add(uint32_t* m, uint32_t r, uint32_t c) {
+        if (r == row) {
+            count += c;
+        } else {
+            flush(m);
+            row = r;
+            count = c;
+        }
+    }
+    __device__ __forceinline__ void flush(uint32_t* m) {
+        if (count && (threadIdx.x & 63) == 0) atomicAdd(&m[row], count);
+        count = 0;
+    }
+};
+
+// Adds one to m[row] for every active lane with a valid row.  Lanes of a
+// wavefront that hit the same row are merged first: a few rounds of "take the
+// first pending lane's row, count the lanes that share it", runs of half a
+// wavefront or more going to the wavefront's running total and shorter ones to
+// one atomic each, then plain atomics for whatever rows are left.
+__device__ __forceinline__ void count_merged(uint32_t* m, uint32_t row, bool valid, HotRun& hot) {
     bool pending = valid;
 #pragma unroll 1
     for (int round = 0; round < 8; ++round) {
@@ -83,8 +109,9 @@ __device__ __forceinline__ void count_merged(uint32_t* m, uint32_t row, bool val
         int leader = __ffsll((long long)todo) - 1;
         uint32_t lead_row = __shfl(row, leader, 64);
         bool mine = pending && row == lead_row;
-        unsigned long long same = __ballot(mine);
-        if ((int)(threadIdx.x & 63) == leader) atomicAdd(&m[lead_row], (uint32_t)__popcll(same));
+        uint32_t run = (uint32_t)__popcll(__ballot(mine));
+        if (run >= 32) hot.add(m, lead_row, run);
+        else if ((int)(threadIdx.x & 63) == leader) atomicAdd(&m[lead_row], run);
         pending = pending && !mine;
     }
     if (pending) atomicAdd(&m[row], 1u);
@@ -94,7 +121,8 @@ __device__ __forceinline__ void count_merged(uint32_t* m, uint32_t row, bool val
 // found through the hash.  The smallest offending i ends up in *bad.
 static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint32_t* __restrict__ S, size_t ss, size_t D,
                                                   const uint32_t* __restrict__ idx, const uint32_t* __restrict__ T,
-                                                  size_t ts, uint32_t N, const uint32_t* __restrict__ slots,
+                                                  size_t ts, const uint4* __restrict__ rows, uint32_t N,
+                                                  const uint32_t* __restrict__ slots,
                                                   uint32_t cap_mask, const uint32_t* __restrict__ canon,
                                                   const uint32_t* __restrict__ dup_flag, unsigned long long* bad) {
     const bool dups = *dup_flag != 0;
@@ -102,6 +130,7 @@ static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint
     // cross-lane steps in count_merged see whole wavefronts
     const size_t per_pass = (size_t)gridDim.x * kBlock;
     const size_t passes = (D + per_pass - 1) / per_pass;
+    HotRun hot;
     for (size_t pass = 0; pass < passes; ++pass) {
         size_t i = pass * per_pass + blockIdx.x * (size_t)kBlock + threadIdx.x;
         bool in_range = i < D;
@@ -110,14 +139,119 @@ static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint
             Fr v = fr_load(S, ss, i);
             if (idx) {
                 row = idx[i];
-                if (row >= N || !fr_equal(fr_load(T, ts, row), v)) row = kEmptySlot;
-                else if (dups) row = canon[row];
+                if (row < N) {
+                    uint4 lo = rows[2 * (size_t)row], hi = rows[2 * (size_t)row + 1];
+                    uint32_t diff = (lo.x ^ v.l[0]) | (lo.y ^ v.l[1]) | (lo.z ^ v.l[2]) | (lo.w ^ v.l[3]) |
+                                    (hi.x ^ v.l[4]) | (hi.y ^ v.l[5]) | (hi.z ^ v.l[6]) | (hi.w ^ v.l[7]);
+                    if (diff) row = kEmptySlot;
+                    else if (dups) row = canon[row];
+                } else {
+                    row = kEmptySlot;
+                }
             } else {
                 row = hash_find(slots, cap_mask, T, ts, v);
             }
             if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
         }
-        count_merged(m, row, in_range && row != kEmptySlot);
+        count_merged(m, row, in_range && row != kEmptySlot, hot);
+    }
+    hot.flush(m);
+}
+
+// ---- multiplicities through workgroup-private histograms in LDS ---------------------
+//
+// For tables of up to 2^16 rows the counters of a workgroup fit in LDS as packed
+// 16-bit pairs (128 KiB at 2^16 rows, of the 160 KiB a gfx950 compute unit has),
+// which takes the counting off the device-wide atomics.  A workgroup walks its
+// share of S in passes short enough that no 16-bit counter can overflow, and
+// after each pass adds its counters into a 32-bit histogram of its own in HBM
+// (plain loads and stores, nobody else touches it); a second kernel adds the
+// workgroups' histograms up.  Runs of one row that fill half a wavefront or more
+// (padding, saturated activations) are kept in a per-wavefront running total and
+// go straight to the result, so they do not eat into the 16-bit budget.
+static const int kHistThreads = 1024;
+static const uint32_t kHistPass = 60 * 1024;  // elements per pass, < 2^16
+
+static __global__ void __launch_bounds__(kHistThreads)
+k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict__ S, size_t ss, size_t D,
+            size_t per_block, const uint32_t* __restrict__ idx, const uint32_t* __restrict__ T, size_t ts,
+            const uint4* __restrict__ rows, uint32_t N, const uint32_t* __restrict__ slots, uint32_t cap_mask,
+            const uint32_t* __restrict__ canon, const uint32_t* __restrict__ dup_flag, unsigned long long* bad) {
+    extern __shared__ uint32_t hist[];  // (N+1)/2 words, two 16-bit counters each
+    const uint32_t words = (N + 1) / 2;
+    const bool dups = *dup_flag != 0;
+    uint32_t* mine_part = part + (size_t)blockIdx.x * N;
+    const size_t begin = blockIdx.x * per_block;
+    const size_t end = begin + per_block < D ? begin + per_block : D;
+    bool first = true;
+    HotRun hot;
+    for (size_t pass_begin = begin; pass_begin < end || first; pass_begin += kHistPass) {
+        for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) hist[w] = 0;
+        __syncthreads();
+        const size_t pass_end = pass_begin + kHistPass < end ? pass_begin + kHistPass : end;
+        // whole wavefronts iterate together so that the cross-lane merge sees all 64 lanes
+        for (size_t base = pass_begin; base < pass_end; base += kHistThreads) {
+            size_t i = base + threadIdx.x;
+            bool in_range = i < pass_end;
+            uint32_t row = kEmptySlot;
+            if (in_range) {
+                Fr v = fr_load(S, ss, i);
+                if (idx) {
+                    row = idx[i];
+                    if (row < N) {
+                        uint4 lo = rows[2 * (size_t)row], hi = rows[2 * (size_t)row + 1];
+                        uint32_t diff = (lo.x ^ v.l[0]) | (lo.y ^ v.l[1]) | (lo.z ^ v.l[2]) | (lo.w ^ v.l[3]) |
+                                        (hi.x ^ v.l[4]) | (hi.y ^ v.l[5]) | (hi.z ^ v.l[6]) | (hi.w ^ v.l[7]);
+                        if (diff) row = kEmptySlot;
+                        else if (dups) row = canon[row];
+                    } else {
+                        row = kEmptySlot;
+                    }
+                } else {
+                    row = hash_find(slots, cap_mask, T, ts, v);
+                }
+                if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
+            }
+            bool pending = in_range && row != kEmptySlot;
+#pragma unroll 1
+            for (int round = 0; round < 4; ++round) {
+                unsigned long long todo = __ballot(pending);
+                if (todo == 0) break;
+                int leader = __ffsll((long long)todo) - 1;
+                uint32_t lead_row = __shfl(row, leader, 64);
+                bool same_row = pending && row == lead_row;
+                uint32_t run = (uint32_t)__popcll(__ballot(same_row));
+                if (run >= 32) hot.add(m, lead_row, run);
+                else if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[lead_row >> 1], run << (16 * (lead_row & 1)));
+                pending = pending && !same_row;
+            }
+            if (pending) atomicAdd(&hist[row >> 1], 1u << (16 * (row & 1)));
+        }
+        __syncthreads();
+        for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) {
+            uint32_t v = hist[w];
+            uint32_t c0 = v & 0xffffu, c1 = v >> 16;
+            if (first) {
+                mine_part[2 * w] = c0;
+                if (2 * w + 1 < N) mine_part[2 * w + 1] = c1;
+            } else if (v) {
+                mine_part[2 * w] += c0;
+                if (2 * w + 1 < N) mine_part[2 * w + 1] += c1;
+            }
+        }
+        __syncthreads();
+        first = false;
+    }
+    hot.flush(m);
+}
+
+// m[j] += sum over workgroups of their histograms.
+static __global__ void __launch_bounds__(kBlock) k_hist_reduce(uint32_t* __restrict__ m, const uint32_t* __restrict__ part,
+                                                        uint32_t nparts, uint32_t N) {
+    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock) {
+        uint32_t acc = m[j];
+        for (uint32_t b = 0; b < nparts; ++b) acc += part[(size_t)b * N + j];
+        m[j] = acc;
     }
 }
 

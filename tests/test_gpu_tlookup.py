@@ -22,10 +22,11 @@ def zk():
 
 
 def _random_instance(orc, zk, rng, D, N, dup=False):
-    T = []
+    T, seen = [], set()
     while len(T) < N:
         t = rng.randrange(R)
-        if t not in T:
+        if t not in seen:
+            seen.add(t)
             T.append(t)
     if dup and N >= 4:
         T[N - 1] = T[1]
@@ -49,7 +50,8 @@ def _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx):
 
 @pytest.mark.parametrize("D,N,dup", [(1, 1, False), (2, 1, False), (2, 2, False), (8, 1, False), (8, 8, True),
                                      (16, 4, False), (64, 2, False), (1 << 10, 1 << 4, True), (1 << 13, 1 << 13, False),
-                                     (1 << 15, 1 << 8, False), (1 << 16, 1 << 14, True)])
+                                     (1 << 15, 1 << 8, False), (1 << 16, 1 << 14, True),
+                                     (1 << 17, 1 << 17, False)])
 def test_proof_bytes_equal_oracle(zk, orc, D, N, dup):
     rng = random.Random(1000 + D + N)
     Sb, Tb, Sv, Tv, idx = _random_instance(orc, zk, rng, D, N, dup)
