@@ -23,7 +23,8 @@ sys.path.insert(0, ROOT)
 
 PEAK_MAD_PER_S = 256 * 64 * 2.4e9      # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit multiply-add per lane per clock
 MADS_PER_FR_MUL = 112                   # 64 for the 8x8-limb product + 48 for the reduction (two of r's limbs need no multiplier)
-ROUND_DATA_FR_MUL_PER_PAIR_EVAL = 5
+ROUND_DATA_FR_MUL_FIRST = 2             # first round: only the leading coefficient, A (S+beta) = 1 gives the rest
+ROUND_DATA_FR_MUL_PER_PAIR_EVAL = 5     # two to weight A0, A1, three products
 ROUND_DATA_FR_MUL_PER_PAIR_FOLD = 4     # two arrays, two folded entries per pair
 
 
@@ -33,14 +34,28 @@ def fr_mul_model(D, N):
 
 def round_data_fr_mul(D):
     """Field multiplications the data-side round kernel needs over one prove:
-    round k has D/2^(k+1) pairs; every round evaluates, all but the first fold."""
+    round k has D/2^(k+1) pairs; the first round needs 2 per pair, every later
+    round 5 to evaluate and 4 to fold."""
     n = D.bit_length() - 1
     total = 0
     for k in range(n):
         pairs = D >> (k + 1)
-        total += ROUND_DATA_FR_MUL_PER_PAIR_EVAL * pairs
-        if k > 0:
-            total += ROUND_DATA_FR_MUL_PER_PAIR_FOLD * pairs
+        if k == 0:
+            total += ROUND_DATA_FR_MUL_FIRST * pairs
+        else:
+            total += (ROUND_DATA_FR_MUL_PER_PAIR_EVAL + ROUND_DATA_FR_MUL_PER_PAIR_FOLD) * pairs
+    return total
+
+
+def round_data_bytes(D):
+    """HBM bytes the data-side round kernel has to move over one prove: round 0
+    reads A and S (2 x 32 B x D); round k >= 1 reads 2^(n-k+1) entries of each
+    and writes half as many."""
+    n = D.bit_length() - 1
+    total = 2 * 32 * D
+    for k in range(1, n):
+        entries = D >> (k - 1)
+        total += 2 * 32 * entries + 2 * 32 * (entries // 2)
     return total
 
 
@@ -90,6 +105,9 @@ def main():
     ap.add_argument("--logN", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-logD", type=int, default=19)
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (reads 2^30 B, writes 2^30 B) so that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path needs no second GPU and none is used); "
@@ -126,6 +144,14 @@ def main():
         rc, proof, info = zk.tlookup_prove(cfg["seed"], S, idx, T, ws=ws)
         assert rc == 0, rc
         return proof, info
+
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     first = None
     for _ in range(args.warmup):
@@ -167,8 +193,8 @@ def main():
                      "achieved": achieved / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
                      "frac": achieved / PEAK_MAD_PER_S, "traffic": measured_traffic(),
                      "launches_per_step": launches, "avg_launch_ms": avg_launch_s * 1e3,
-                     "algorithmic_bytes_per_launch": (D * 32 * 2 + (D * 32 * 2) * 1.5) / max(launches, 1),
-                     "hbm_GBps_algorithmic": (D * 32 * 2 * 2.5) / (rd["ms_per_step"] * 1e-3) / 1e9 if rd["ms_per_step"] else 0.0},
+                     "algorithmic_bytes_per_launch": round_data_bytes(D) / max(launches, 1),
+                     "hbm_GBps_algorithmic": round_data_bytes(D) / (rd["ms_per_step"] * 1e-3) / 1e9 if rd["ms_per_step"] else 0.0},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_logD, min(args.logN, args.cpu_logD))

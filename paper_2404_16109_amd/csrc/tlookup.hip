@@ -134,9 +134,17 @@ struct ProveWs {
     uint32_t* flags;    // [0] duplicate flag, [2..3] smallest bad index (64-bit)
     uint32_t* leaves;   // nleaves * 8 words
     uint32_t nleaves;
-    uint32_t* partD;    // kMaxPartialBlocks * 5
-    uint32_t* partT;    // kMaxPartialBlocks * 6
+    size_t part_blocks; // capacity of the two partial-sum buffers, in workgroups
+    uint32_t* partD;    // part_blocks * 5
+    uint32_t* partT;    // part_blocks * 6
 };
+
+// Most workgroups a round kernel can be launched with: spans never shrink below
+// 2^kLoBits pairs while high weight tables are in use.
+static size_t round_blocks_max(size_t D) {
+    size_t by_span = (D / 2) >> kLoBits;
+    return by_span > kMaxPartialBlocks ? by_span : kMaxPartialBlocks;
+}
 
 static const size_t kLdsHistMaxRows = (size_t)1 << 16;  // packed 16-bit counters: 128 KiB of LDS
 static const uint32_t kHistParts = 256;                // one workgroup per compute unit
@@ -164,8 +172,9 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.flags = (uint32_t*)cv.take(64);
     w.nleaves = (uint32_t)div_up(N, kLeafCounts);
     w.leaves = (uint32_t*)cv.take((size_t)w.nleaves * 32);
-    w.partD = cv.limbs((size_t)kMaxPartialBlocks * 5);
-    w.partT = cv.limbs((size_t)kMaxPartialBlocks * 6);
+    w.part_blocks = round_blocks_max(D);
+    w.partD = cv.limbs(w.part_blocks * 5);
+    w.partT = cv.limbs(w.part_blocks * 6);
     return ZK_OK;
 }
 
@@ -315,10 +324,10 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
             a.eq = EqSplit{ep.pool, ep.stride, ep.suffix_off[0], 0, 0, 0};
         }
         a.partials = w.partT;
-        a.pstride = (size_t)kMaxPartialBlocks * 6;
+        a.pstride = w.part_blocks * 6;
         unsigned blocks = grid_for(N, kBlock * 4, kMaxPartialBlocks);
         hipLaunchKernelGGL(k_table_const, dim3(blocks), dim3(kBlock), 0, stream, a);
-        launch_final_sum(w.partT, (size_t)kMaxPartialBlocks * 6, blocks, 2, mb->words, stream);
+        launch_final_sum(w.partT, a.pstride, blocks, 2, mb->words, stream);
         ZK_HIP_TRY(hipGetLastError());
         ZK_HIP_TRY(hipStreamSynchronize(stream));
         c1 = from_dev(mb->words);
@@ -355,6 +364,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         if (eq.has_hi && span > ((size_t)1 << eq.lbits)) span = (size_t)1 << eq.lbits;
         if (span > half) span = half;
         const unsigned blocks = (unsigned)(half / span);
+        if (blocks > w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
         const bool table_round = k >= h;
 
         DataRoundArgs d;
@@ -367,7 +377,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         d.beta = to_dev(beta);
         d.eq = eq;
         d.partials = w.partD;
-        d.pstride = (size_t)kMaxPartialBlocks * 5;
+        d.pstride = w.part_blocks * 5;
         {
             ProfileScope prof(kProfRoundData, stream);
             if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
@@ -386,7 +396,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
             t.beta = d.beta;
             t.eq = d.eq;
             t.partials = w.partT;
-            t.pstride = (size_t)kMaxPartialBlocks * 6;
+            t.pstride = w.part_blocks * 6;
             {
                 ProfileScope prof(kProfRoundTable, stream);
                 if (k > h) hipLaunchKernelGGL(k_round_table<true>, dim3(blocks), dim3(kBlock), 0, stream, t);
@@ -398,6 +408,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         ZK_HIP_TRY(hipStreamSynchronize(stream));
 
         F q0 = from_dev(mb->words), q1 = from_dev(mb->words + 8), qi = from_dev(mb->words + 16);
+        if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
         F sA0 = from_dev(mb->words + 24), sA1 = from_dev(mb->words + 32);
         if (k == 0) sum_A = add(sA0, sA1);
         F e[4], q[4], sa[4], g[4];

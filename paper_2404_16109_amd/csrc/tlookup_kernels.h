@@ -417,6 +417,11 @@ struct DataRoundArgs {
 // from which the host forms  alpha c e~(u_k, X) q(X) + sA(X).  All pairs of a
 // workgroup share the high-variable factor of their weight, which is applied
 // once to the workgroup's sums.
+//
+// FOLD = false is the first round, straight after the inversion: there
+// A_i (S_i + beta) = 1 for every i, so q0 = q1 = sum of the weights = 1 and only
+// qinf and the sums of A are computed (q0 and q1 are written as zero and set by
+// the host).
 template <bool FOLD>
 static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
     __shared__ uint32_t lds[4 * 5 * 8];
@@ -432,17 +437,23 @@ static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
         Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
         tot[3] = fr_add(tot[3], a0);
         tot[4] = fr_add(tot[4], a1);
-        Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
-        tot[0] = fr_add(tot[0], fr_mul(wa0, fr_add(s0, g.beta)));
-        tot[1] = fr_add(tot[1], fr_mul(wa1, fr_add(s1, g.beta)));
-        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
+        if constexpr (FOLD) {
+            Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
+            tot[0] = fr_add(tot[0], fr_mul(wa0, fr_add(s0, g.beta)));
+            tot[1] = fr_add(tot[1], fr_mul(wa1, fr_add(s1, g.beta)));
+            tot[2] = fr_add(tot[2], fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
+        } else {
+            tot[2] = fr_add(tot[2], fr_mul(w, fr_mul(fr_sub(a1, a0), fr_sub(s1, s0))));
+        }
     }
     block_sum<5, 4>(tot, lds);
     if (threadIdx.x == 0) {
         if (g.eq.has_hi) {
             Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + (start >> g.eq.lbits));
-            tot[0] = fr_mul(tot[0], hf);
-            tot[1] = fr_mul(tot[1], hf);
+            if constexpr (FOLD) {
+                tot[0] = fr_mul(tot[0], hf);
+                tot[1] = fr_mul(tot[1], hf);
+            }
             tot[2] = fr_mul(tot[2], hf);
         }
 #pragma unroll
