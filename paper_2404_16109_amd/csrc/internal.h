@@ -23,6 +23,11 @@ static const unsigned kMaxPartialBlocks = 4096;
 void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
                       hipStream_t stream);
 
+// Same for two partial arrays at once: nv1 values per block from the first, then
+// nv2 from the second (nv2 may be 0); totals at out_words[8q..], first array first.
+void launch_final_sum2(const uint32_t* part1, size_t pstride1, int nv1, const uint32_t* part2, size_t pstride2, int nv2,
+                       unsigned nblocks, uint32_t* out_words, hipStream_t stream);
+
 // sum_i a_i into mailbox words [0, 8).
 size_t sum_scratch_bytes(size_t n);
 int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, uint32_t* out_words, hipStream_t stream);

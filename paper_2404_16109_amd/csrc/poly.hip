@@ -34,6 +34,33 @@ __global__ void __launch_bounds__(kBlock) k_final_sum(const uint32_t* __restrict
     }
 }
 
+// Value q of the launch (blockIdx.x = q, one workgroup per value) comes from the
+// first array while q < nv1 and from the second afterwards.
+__global__ void __launch_bounds__(kBlock) k_final_sum2(const uint32_t* __restrict__ part1, size_t pstride1, int nv1,
+                                                       const uint32_t* __restrict__ part2, size_t pstride2, int nv2,
+                                                       unsigned nblocks, uint32_t* out_words) {
+    __shared__ uint32_t lds[4 * 8];
+    const int q = blockIdx.x;
+    const bool first = q < nv1;
+    const uint32_t* part = first ? part1 : part2;
+    const size_t pstride = first ? pstride1 : pstride2;
+    const int nv = first ? nv1 : nv2, qq = first ? q : q - nv1;
+    Fr acc[1] = {fr_zero()};
+    for (unsigned b = threadIdx.x; b < nblocks; b += kBlock)
+        acc[0] = fr_add(acc[0], fr_load(part, pstride, (size_t)b * nv + qq));
+    block_sum<1, 4>(acc, lds);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc[0].l[k];
+    }
+}
+
+void launch_final_sum2(const uint32_t* part1, size_t pstride1, int nv1, const uint32_t* part2, size_t pstride2, int nv2,
+                       unsigned nblocks, uint32_t* out_words, hipStream_t stream) {
+    hipLaunchKernelGGL(k_final_sum2, dim3(nv1 + nv2), dim3(kBlock), 0, stream, part1, pstride1, nv1, part2, pstride2, nv2,
+                       nblocks, out_words);
+}
+
 void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
                       hipStream_t stream) {
     hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(kBlock), 0, stream, partials, pstride, nblocks, nv, out_words);

@@ -214,8 +214,9 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
         hipLaunchKernelGGL(k_count_lds, dim3(w.hist_parts), dim3(kHistThreads), lds_bytes, stream, w.m, w.hist, S.limbs,
                            S.stride, D, per_block, idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots, w.cap_mask,
                            w.canon, w.flags, (unsigned long long*)(w.flags + 2));
-        hipLaunchKernelGGL(k_hist_reduce, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.m, w.hist, w.hist_parts,
-                           (uint32_t)N);
+        const uint32_t group = 16;
+        hipLaunchKernelGGL(k_hist_reduce, dim3((unsigned)div_up(N, kBlock), (unsigned)div_up(w.hist_parts, group)),
+                           dim3(kBlock), 0, stream, w.m, w.hist, w.hist_parts, group, (uint32_t)N);
     } else {
         hipLaunchKernelGGL(k_count, dim3(grid_for(D, kBlock, 8192)), dim3(kBlock), 0, stream, w.m, S.limbs, S.stride, D,
                            idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots, w.cap_mask, w.canon, w.flags,
@@ -358,14 +359,17 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
         const EqSplit eq = ep.round(k);
-        // a workgroup's pairs must share the high factor of their weights
+        const bool table_round = k >= h;
+        const bool small = k > 0 && half <= kSmallPairs;
+        // pairs per workgroup: a workgroup's pairs must share the high factor of
+        // their weights; small rounds get one pair per thread
         size_t span = half / kMaxPartialBlocks;
-        if (span < (size_t)kBlock * 4) span = (size_t)kBlock * 4;
+        size_t span_min = half <= ((size_t)1 << 15) ? (size_t)kBlock : (size_t)kBlock * 4;
+        if (span < span_min) span = span_min;
         if (eq.has_hi && span > ((size_t)1 << eq.lbits)) span = (size_t)1 << eq.lbits;
         if (span > half) span = half;
         const unsigned blocks = (unsigned)(half / span);
         if (blocks > w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
-        const bool table_round = k >= h;
 
         DataRoundArgs d;
         d.A = PairArray{w.A, D, w.A, D};
@@ -378,31 +382,43 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         d.eq = eq;
         d.partials = w.partD;
         d.pstride = w.part_blocks * 5;
-        {
+        TableRoundArgs t;
+        t.B = PairArray{w.B, N, w.B, N};
+        if (k <= h + 1) t.T = PairArray{T.limbs, T.stride, w.Tf, N / 2};
+        else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
+        t.M = PairArray{w.M, N, w.M, N};
+        t.half = half;
+        t.block_span = span;
+        t.r_prev = d.r_prev;
+        t.beta = d.beta;
+        t.eq = eq;
+        t.partials = w.partT;
+        t.pstride = w.part_blocks * 6;
+
+        if (small) {
+            // one workgroup, one launch, sums straight to the host
             ProfileScope prof(kProfRoundData, stream);
-            if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
-            else hipLaunchKernelGGL(k_round_data<false>, dim3(blocks), dim3(kBlock), 0, stream, d);
-        }
-        launch_final_sum(w.partD, d.pstride, blocks, 5, mb->words, stream);
-        if (table_round) {
-            TableRoundArgs t;
-            t.B = PairArray{w.B, N, w.B, N};
-            if (k <= h + 1) t.T = PairArray{T.limbs, T.stride, w.Tf, N / 2};
-            else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
-            t.M = PairArray{w.M, N, w.M, N};
-            t.half = half;
-            t.block_span = span;
-            t.r_prev = d.r_prev;
-            t.beta = d.beta;
-            t.eq = d.eq;
-            t.partials = w.partT;
-            t.pstride = w.part_blocks * 6;
+            if (!table_round) hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words);
+            else if (k == h) hipLaunchKernelGGL(k_round_small<1>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words);
+            else hipLaunchKernelGGL(k_round_small<2>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words);
+        } else if (table_round && k > 0) {
             {
-                ProfileScope prof(kProfRoundTable, stream);
-                if (k > h) hipLaunchKernelGGL(k_round_table<true>, dim3(blocks), dim3(kBlock), 0, stream, t);
-                else hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
+                ProfileScope prof(kProfRoundData, stream);
+                if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
+                else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
             }
-            launch_final_sum(w.partT, t.pstride, blocks, 6, mb->words + 40, stream);
+            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, stream);
+        } else {
+            {
+                ProfileScope prof(kProfRoundData, stream);
+                if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
+                else hipLaunchKernelGGL(k_round_data<false>, dim3(blocks), dim3(kBlock), 0, stream, d);
+            }
+            if (table_round) {  // only with k == 0, i.e. D == N
+                ProfileScope prof(kProfRoundTable, stream);
+                hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
+            }
+            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, table_round ? 6 : 0, blocks, mb->words, stream);
         }
         ZK_HIP_TRY(hipGetLastError());
         ZK_HIP_TRY(hipStreamSynchronize(stream));

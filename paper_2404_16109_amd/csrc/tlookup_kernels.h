@@ -245,14 +245,17 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
     hot.flush(m);
 }
 
-// m[j] += sum over workgroups of their histograms.
+// m[j] += sum over workgroups of their histograms; blockIdx.y selects a group of
+// `group` histograms, so that the additions of one row are spread over several
+// threads.
 static __global__ void __launch_bounds__(kBlock) k_hist_reduce(uint32_t* __restrict__ m, const uint32_t* __restrict__ part,
-                                                        uint32_t nparts, uint32_t N) {
-    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock) {
-        uint32_t acc = m[j];
-        for (uint32_t b = 0; b < nparts; ++b) acc += part[(size_t)b * N + j];
-        m[j] = acc;
-    }
+                                                        uint32_t nparts, uint32_t group, uint32_t N) {
+    uint32_t j = blockIdx.x * kBlock + threadIdx.x;
+    if (j >= N) return;
+    uint32_t b0 = blockIdx.y * group, b1 = b0 + group < nparts ? b0 + group : nparts;
+    uint32_t acc = 0;
+    for (uint32_t b = b0; b < b1; ++b) acc += part[(size_t)b * N + j];
+    if (acc) atomicAdd(&m[j], acc);
 }
 
 static __global__ void __launch_bounds__(kBlock) k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
@@ -412,40 +415,43 @@ struct DataRoundArgs {
 };
 
 // Data side of one round.  With w the weight of a pair and (A0, A1), (S0, S1)
-// its entries, the workgroup sums
+// its entries, the sums are
 //   q0 = w A0 (S0+beta), q1 = w A1 (S1+beta), qinf = w (A1-A0)(S1-S0), sA0 = A0, sA1 = A1,
-// from which the host forms  alpha c e~(u_k, X) q(X) + sA(X).  All pairs of a
-// workgroup share the high-variable factor of their weight, which is applied
-// once to the workgroup's sums.
+// from which the host forms  alpha c e~(u_k, X) q(X) + sA(X).
 //
 // FOLD = false is the first round, straight after the inversion: there
 // A_i (S_i + beta) = 1 for every i, so q0 = q1 = sum of the weights = 1 and only
-// qinf and the sums of A are computed (q0 and q1 are written as zero and set by
-// the host).
+// qinf and the sums of A are computed (q0 and q1 stay zero and are set by the
+// host).
 template <bool FOLD>
-static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
-    __shared__ uint32_t lds[4 * 5 * 8];
+__device__ __forceinline__ void data_pair(const DataRoundArgs& g, size_t p, size_t lo_mask, Fr (&tot)[5]) {
+    Fr a0, a1, s0, s1;
+    load_pair<FOLD>(g.A, p, g.half, g.r_prev, a0, a1);
+    load_pair<FOLD>(g.S, p, g.half, g.r_prev, s0, s1);
+    Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
+    tot[3] = fr_add(tot[3], a0);
+    tot[4] = fr_add(tot[4], a1);
+    if constexpr (FOLD) {
+        Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
+        tot[0] = fr_add(tot[0], fr_mul(wa0, fr_add(s0, g.beta)));
+        tot[1] = fr_add(tot[1], fr_mul(wa1, fr_add(s1, g.beta)));
+        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
+    } else {
+        tot[2] = fr_add(tot[2], fr_mul(w, fr_mul(fr_sub(a1, a0), fr_sub(s1, s0))));
+    }
+}
+
+// One workgroup's share of the data side: block_span consecutive pairs, which
+// all share the high-variable factor of their weight; it is applied once to the
+// workgroup's sums.
+template <bool FOLD>
+__device__ __forceinline__ void round_data_block(const DataRoundArgs& g, unsigned block, uint32_t* lds) {
     Fr tot[5];
 #pragma unroll
     for (int q = 0; q < 5; ++q) tot[q] = fr_zero();
-    const size_t start = blockIdx.x * g.block_span;
+    const size_t start = block * g.block_span;
     const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
-    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
-        Fr a0, a1, s0, s1;
-        load_pair<FOLD>(g.A, p, g.half, g.r_prev, a0, a1);
-        load_pair<FOLD>(g.S, p, g.half, g.r_prev, s0, s1);
-        Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
-        tot[3] = fr_add(tot[3], a0);
-        tot[4] = fr_add(tot[4], a1);
-        if constexpr (FOLD) {
-            Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
-            tot[0] = fr_add(tot[0], fr_mul(wa0, fr_add(s0, g.beta)));
-            tot[1] = fr_add(tot[1], fr_mul(wa1, fr_add(s1, g.beta)));
-            tot[2] = fr_add(tot[2], fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
-        } else {
-            tot[2] = fr_add(tot[2], fr_mul(w, fr_mul(fr_sub(a1, a0), fr_sub(s1, s0))));
-        }
-    }
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) data_pair<FOLD>(g, p, lo_mask, tot);
     block_sum<5, 4>(tot, lds);
     if (threadIdx.x == 0) {
         if (g.eq.has_hi) {
@@ -457,8 +463,14 @@ static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
             tot[2] = fr_mul(tot[2], hf);
         }
 #pragma unroll
-        for (int q = 0; q < 5; ++q) fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 5 + q, tot[q]);
+        for (int q = 0; q < 5; ++q) fr_store(g.partials, g.pstride, (size_t)block * 5 + q, tot[q]);
     }
+}
+
+template <bool FOLD>
+static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
+    __shared__ uint32_t lds[4 * 6 * 8];
+    round_data_block<FOLD>(g, blockIdx.x, lds);
 }
 
 struct TableRoundArgs {
@@ -475,31 +487,33 @@ struct TableRoundArgs {
 //   t0 = w B0 (T0+beta), t1 = w B1 (T1+beta), tinf = w (B1-B0)(T1-T0),
 //   m0 = B0 M0, m1 = B1 M1, minf = (B1-B0)(M1-M0).
 template <bool FOLD>
-static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g) {
-    __shared__ uint32_t lds[4 * 6 * 8];
+__device__ __forceinline__ void table_pair(const TableRoundArgs& g, size_t p, size_t lo_mask, Fr (&tot)[6]) {
+    Fr b0, b1;
+    load_pair<FOLD>(g.B, p, g.half, g.r_prev, b0, b1);
+    {
+        Fr m0, m1;
+        load_pair<FOLD>(g.M, p, g.half, g.r_prev, m0, m1);
+        tot[3] = fr_add(tot[3], fr_mul(b0, m0));
+        tot[4] = fr_add(tot[4], fr_mul(b1, m1));
+        tot[5] = fr_add(tot[5], fr_mul(fr_sub(b1, b0), fr_sub(m1, m0)));
+    }
+    Fr t0, t1;
+    load_pair<FOLD>(g.T, p, g.half, g.r_prev, t0, t1);
+    Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
+    Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
+    tot[0] = fr_add(tot[0], fr_mul(wb0, fr_add(t0, g.beta)));
+    tot[1] = fr_add(tot[1], fr_mul(wb1, fr_add(t1, g.beta)));
+    tot[2] = fr_add(tot[2], fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
+}
+
+template <bool FOLD>
+__device__ __forceinline__ void round_table_block(const TableRoundArgs& g, unsigned block, uint32_t* lds) {
     Fr tot[6];
 #pragma unroll
     for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
-    const size_t start = blockIdx.x * g.block_span;
+    const size_t start = block * g.block_span;
     const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
-    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
-        Fr b0, b1;
-        load_pair<FOLD>(g.B, p, g.half, g.r_prev, b0, b1);
-        {
-            Fr m0, m1;
-            load_pair<FOLD>(g.M, p, g.half, g.r_prev, m0, m1);
-            tot[3] = fr_add(tot[3], fr_mul(b0, m0));
-            tot[4] = fr_add(tot[4], fr_mul(b1, m1));
-            tot[5] = fr_add(tot[5], fr_mul(fr_sub(b1, b0), fr_sub(m1, m0)));
-        }
-        Fr t0, t1;
-        load_pair<FOLD>(g.T, p, g.half, g.r_prev, t0, t1);
-        Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
-        Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
-        tot[0] = fr_add(tot[0], fr_mul(wb0, fr_add(t0, g.beta)));
-        tot[1] = fr_add(tot[1], fr_mul(wb1, fr_add(t1, g.beta)));
-        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
-    }
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) table_pair<FOLD>(g, p, lo_mask, tot);
     block_sum<6, 4>(tot, lds);
     if (threadIdx.x == 0) {
         if (g.eq.has_hi) {
@@ -509,7 +523,79 @@ static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g)
             tot[2] = fr_mul(tot[2], hf);
         }
 #pragma unroll
-        for (int q = 0; q < 6; ++q) fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 6 + q, tot[q]);
+        for (int q = 0; q < 6; ++q) fr_store(g.partials, g.pstride, (size_t)block * 6 + q, tot[q]);
+    }
+}
+
+template <bool FOLD>
+static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g) {
+    __shared__ uint32_t lds[4 * 6 * 8];
+    round_table_block<FOLD>(g, blockIdx.x, lds);
+}
+
+// A round that binds one of the table's variables, both sides in one launch:
+// workgroups with blockIdx.y = 0 do the data side, blockIdx.y = 1 the table side.
+// The data arrays have been folded at least once by then.
+template <bool FOLD_T>
+static __global__ void __launch_bounds__(kBlock) k_round_both(DataRoundArgs d, TableRoundArgs t) {
+    __shared__ uint32_t lds[4 * 6 * 8];
+    if (blockIdx.y == 0) round_data_block<true>(d, blockIdx.x, lds);
+    else round_table_block<FOLD_T>(t, blockIdx.x, lds);
+}
+
+// The last rounds (at most 512 pairs): one workgroup of 1024 threads does the
+// whole round, data pairs on threads 0..511 and table pairs on threads 512..1023,
+// and writes the eleven sums straight to out_words (value q at words 8q..8q+7,
+// data sums first), so the round costs a single launch.  TABLE: 0 = the table is
+// not being bound yet, 1 = first table round (nothing to fold), 2 = fold.
+static const int kSmallThreads = 1024;
+static const size_t kSmallPairs = 512;
+
+template <int TABLE>
+static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundArgs d, TableRoundArgs t,
+                                                                     uint32_t* out_words) {
+    __shared__ uint32_t lds[16 * 6 * 8];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const bool data_side = threadIdx.x < 512;
+    const size_t p = data_side ? threadIdx.x : threadIdx.x - 512;
+    const size_t lo_mask = ((size_t)1 << d.eq.lbits) - 1;
+    Fr tot[6];
+#pragma unroll
+    for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
+    if (data_side) {
+        if (p < d.half) {
+            Fr five[5] = {fr_zero(), fr_zero(), fr_zero(), fr_zero(), fr_zero()};
+            data_pair<true>(d, p, lo_mask, five);
+#pragma unroll
+            for (int q = 0; q < 5; ++q) tot[q] = five[q];
+        }
+    } else if (TABLE != 0) {
+        if (p < t.half) table_pair<TABLE == 2>(t, p, lo_mask, tot);
+    }
+#pragma unroll
+    for (int q = 0; q < 6; ++q) {
+        tot[q] = wave_sum(tot[q]);
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) lds[(wave * 6 + q) * 8 + k] = tot[q].l[k];
+        }
+    }
+    __syncthreads();
+    // thread q adds up data value q over wavefronts 0..7, thread 512+q table value q over 8..15
+    const int q = data_side ? threadIdx.x : threadIdx.x - 512;
+    const int nvals = data_side ? 5 : (TABLE != 0 ? 6 : 0);
+    if (q < nvals) {
+        const int w0 = data_side ? 0 : 8;
+        Fr acc = fr_zero();
+        for (int w = w0; w < w0 + 8; ++w) {
+            Fr o;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) o.l[k] = lds[(w * 6 + q) * 8 + k];
+            acc = fr_add(acc, o);
+        }
+        const int slot = data_side ? q : 5 + q;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) out_words[8 * slot + k] = acc.l[k];
     }
 }
 
