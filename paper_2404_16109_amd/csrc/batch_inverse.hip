@@ -87,13 +87,16 @@ __device__ __forceinline__ Fr block_scan_mul(Fr v, uint32_t* lds, bool reverse) 
 
 // Grand total of the last level (n <= 256) to total_words (Montgomery limbs).
 __global__ void __launch_bounds__(kBlock) k_bi_top_total(const uint32_t* __restrict__ src, size_t ss, size_t n,
-                                                         int shifted, Fr shift, uint32_t* total_words) {
+                                                         int shifted, Fr shift, uint32_t* total_words,
+                                                         uint32_t* flag_words, uint32_t seq) {
     __shared__ uint32_t lds[8 * kBlock];
     Fr x = threadIdx.x < n ? bi_load(src, ss, threadIdx.x, shifted, shift) : fr_one();
     Fr p = block_scan_mul(x, lds, false);
     if (threadIdx.x == kBlock - 1) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) total_words[k] = p.l[k];
+        mailbox_written();
+        mailbox_publish(flag_words, seq);
     }
 }
 
@@ -140,51 +143,58 @@ size_t batch_inverse_scratch_bytes(size_t n) {
     return cv.used();
 }
 
-int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride, size_t n,
-                      const host::F& shift, Carver& cv, Mailbox* mb, hipStream_t stream) {
-    if (n == 0) return ZK_OK;
-    struct Level {
-        const uint32_t* x;
-        size_t xs;
-        uint32_t* p;
-        size_t ps;
-        size_t n;
-        int shifted;
-    };
-    Level lv[16];
-    int depth = 0;
+int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride,
+                        size_t n, const host::F& shift, Carver& cv, uint32_t* total_words, uint32_t* flag_words,
+                        uint32_t seq, hipStream_t stream) {
+    typedef BatchInverseJob::Level Level;
+    job.depth = 0;
+    job.shift = to_dev(shift);
     int shifted0 = host::is_zero(shift) ? 0 : 1;
-    Fr sh = to_dev(shift);
-    lv[0] = Level{src, src_stride, dst, dst_stride, n, shifted0};
-    while (lv[depth].n > (size_t)kBlock) {
-        size_t m = bi_next_size(lv[depth].n);
+    job.lv[0] = Level{src, src_stride, dst, dst_stride, n, shifted0};
+    while (job.lv[job.depth].n > (size_t)kBlock) {
+        size_t m = bi_next_size(job.lv[job.depth].n);
         uint32_t* x = cv.limbs(m);
         uint32_t* p = cv.limbs(m);
         if (!x || !p) return ZK_E_BUFSZ;
-        const Level& cur = lv[depth];
+        const Level& cur = job.lv[job.depth];
         hipLaunchKernelGGL(k_bi_down, dim3((unsigned)(m / kBlock)), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n,
-                           cur.shifted, sh, cur.p, cur.ps, x, m);
-        ++depth;
-        lv[depth] = Level{x, m, p, m, m, 0};
+                           cur.shifted, job.shift, cur.p, cur.ps, x, m);
+        ++job.depth;
+        job.lv[job.depth] = Level{x, m, p, m, m, 0};
     }
-    const Level& top = lv[depth];
-    hipLaunchKernelGGL(k_bi_top_total, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, sh,
-                       mb->words);
+    const Level& top = job.lv[job.depth];
+    hipLaunchKernelGGL(k_bi_top_total, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, job.shift,
+                       total_words, flag_words, seq);
     ZK_HIP_TRY(hipGetLastError());
-    ZK_HIP_TRY(hipStreamSynchronize(stream));
-    host::F total = from_dev(mb->words);
-    if (host::is_zero(total)) return ZK_E_ZERO_DENOM;
-    Fr inv_total = to_dev(host::inv(total));
-    hipLaunchKernelGGL(k_bi_top_finish, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, sh,
-                       inv_total, top.p, top.ps);
-    for (int d = depth - 1; d >= 0; --d) {
-        const Level& cur = lv[d];
-        const Level& up = lv[d + 1];
+    return ZK_OK;
+}
+
+int batch_inverse_end(const BatchInverseJob& job, const host::F& inv_total, hipStream_t stream) {
+    typedef BatchInverseJob::Level Level;
+    const Level& top = job.lv[job.depth];
+    hipLaunchKernelGGL(k_bi_top_finish, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, job.shift,
+                       to_dev(inv_total), top.p, top.ps);
+    for (int d = job.depth - 1; d >= 0; --d) {
+        const Level& cur = job.lv[d];
+        const Level& up = job.lv[d + 1];
         hipLaunchKernelGGL(k_bi_up, dim3((unsigned)(up.n / kBlock)), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n,
-                           cur.shifted, sh, cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps);
+                           cur.shifted, job.shift, cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps);
     }
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
+}
+
+int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride, size_t n,
+                      const host::F& shift, Carver& cv, Mailbox* mb, hipStream_t stream) {
+    if (n == 0) return ZK_OK;
+    BatchInverseJob job;
+    uint32_t seq = mb->next_seq();
+    ZK_TRY(batch_inverse_begin(job, dst, dst_stride, src, src_stride, n, shift, cv, mb->words + kMailboxInvA, mb->words,
+                               seq, stream));
+    ZK_TRY(mailbox_wait(mb, seq, stream));
+    host::F total = from_dev(mb->words + kMailboxInvA);
+    if (host::is_zero(total)) return ZK_E_ZERO_DENOM;
+    return batch_inverse_end(job, host::inv(total), stream);
 }
 
 }  // namespace zkmi
@@ -204,7 +214,9 @@ int fr_batch_inverse(fr_vec dst, fr_vec src, void* ws, size_t ws_bytes, void* st
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
     Carver cv(ws, ws_bytes);
-    return batch_inverse_run(dst.limbs, dst.stride, src.limbs, src.stride, n, host::zero(), cv, mb, as_stream(stream));
+    ZK_TRY(batch_inverse_run(dst.limbs, dst.stride, src.limbs, src.stride, n, host::zero(), cv, mb, as_stream(stream)));
+    ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
+    return ZK_OK;
 }
 
 }  // extern "C"

@@ -68,15 +68,33 @@ private:
 // Pinned, device-visible host memory, one per host thread, allocated on first
 // use and kept: kernels write small results into it directly and the host reads
 // them after synchronising the stream.
+//
+// Completion is signalled through the mailbox too: the kernel that writes the
+// last result of a step stores a sequence number into the flag word after a
+// system-scope fence, and the host spins on that word.  This hands a round's
+// sums to the host a few microseconds after they are computed instead of after
+// the stream's completion signal has made its way through the runtime.
 struct Mailbox {
     uint32_t* words = nullptr;  // kMailboxWords uint32_t
     uint8_t* bulk = nullptr;    // staging for larger copies (leaf digests)
     size_t bulk_bytes = 0;
+    uint32_t seq = 0;           // last sequence number handed out
+    uint32_t next_seq() {
+        seq = seq == 0xfffffffeu ? 1 : seq + 1;
+        return seq;
+    }
 };
 static const size_t kMailboxWords = 1024;
+static const size_t kMailboxFlag = 1016;    // the flag word
+static const size_t kMailboxInvB = 960;     // grand total of the table-side inversion
+static const size_t kMailboxInvA = 968;     // grand total of the data-side inversion
+static const size_t kMailboxTableC = 976;   // the two table-side constants
 
 int mailbox_get(Mailbox** out);
 int mailbox_bulk(Mailbox* mb, size_t bytes);
+// Waits until the flag shows `seq` (spinning, then falling back to
+// synchronising the stream).
+int mailbox_wait(Mailbox* mb, uint32_t seq, hipStream_t stream);
 
 inline hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
@@ -99,6 +117,16 @@ inline Fr to_dev(const host::F& a) {
     return o;
 }
 inline host::F from_dev(const uint32_t limbs[8]) { return host::from_device_limbs(limbs); }
+
+// Device side of the completion protocol.  Every thread that writes result words
+// calls mailbox_written() after its stores; one thread calls mailbox_publish()
+// once all writers are known to be done (same thread, or after a barrier).
+__device__ __forceinline__ void mailbox_written() { __threadfence_system(); }
+__device__ __forceinline__ void mailbox_publish(uint32_t* words, uint32_t seq) {
+    if (seq == 0) return;
+    __threadfence_system();
+    __hip_atomic_store(&words[kMailboxFlag], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
 
 // Launch geometry for an elementwise pass over n items.
 inline unsigned grid_for(size_t n, size_t per_block = kBlock, size_t max_blocks = (size_t)1 << 20) {

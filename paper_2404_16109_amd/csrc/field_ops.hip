@@ -3,6 +3,8 @@
 // the scalar variants.
 #include <string.h>
 
+#include <atomic>
+#include <chrono>
 #include <vector>
 
 #include "common.h"
@@ -15,9 +17,30 @@ int mailbox_get(Mailbox** out) {
         void* p = nullptr;
         ZK_HIP_TRY(hipHostMalloc(&p, kMailboxWords * sizeof(uint32_t), hipHostMallocDefault));
         mb.words = (uint32_t*)p;
+        memset(mb.words, 0, kMailboxWords * sizeof(uint32_t));
     }
     *out = &mb;
     return ZK_OK;
+}
+
+int mailbox_wait(Mailbox* mb, uint32_t seq, hipStream_t stream) {
+    volatile uint32_t* flag = mb->words + kMailboxFlag;
+    // about 20 ms of spinning covers every kernel of the library; beyond that
+    // (or if the flag never comes) the stream's own completion decides
+    const auto start = std::chrono::steady_clock::now();
+    for (;;) {
+        for (int spin = 0; spin < 2048; ++spin) {
+            if (*flag == seq) {
+                std::atomic_thread_fence(std::memory_order_acquire);
+                return ZK_OK;
+            }
+            __builtin_ia32_pause();
+        }
+        if (std::chrono::steady_clock::now() - start > std::chrono::milliseconds(20)) break;
+    }
+    ZK_HIP_TRY(hipStreamSynchronize(stream));
+    std::atomic_thread_fence(std::memory_order_acquire);
+    return *flag == seq ? ZK_OK : ZK_E_HIP;
 }
 
 int mailbox_bulk(Mailbox* mb, size_t bytes) {

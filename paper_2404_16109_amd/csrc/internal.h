@@ -12,6 +12,28 @@ size_t batch_inverse_scratch_bytes(size_t n);
 int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride, size_t n,
                       const host::F& shift, Carver& cv, Mailbox* mb, hipStream_t stream);
 
+// The same in two halves, so that several inversions can share one wait:
+// `begin` runs the down passes and leaves the grand total (Montgomery limbs) at
+// total_words, publishing `seq` if it is not zero; `end` takes the inverse of
+// that total and runs the up passes.
+struct BatchInverseJob {
+    struct Level {
+        const uint32_t* x;
+        size_t xs;
+        uint32_t* p;
+        size_t ps;
+        size_t n;
+        int shifted;
+    };
+    Level lv[16];
+    int depth = 0;
+    Fr shift;
+};
+int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride,
+                        size_t n, const host::F& shift, Carver& cv, uint32_t* total_words, uint32_t* flag_words,
+                        uint32_t seq, hipStream_t stream);
+int batch_inverse_end(const BatchInverseJob& job, const host::F& inv_total, hipStream_t stream);
+
 // ---- sums -----------------------------------------------------------------
 // Partial sums buffer for reductions: up to kMaxPartialBlocks blocks.
 static const unsigned kMaxPartialBlocks = 4096;
@@ -20,17 +42,18 @@ static const unsigned kMaxPartialBlocks = 4096;
 // element b*nv + q of `partials`, limb-major with stride pstride) and writes
 // the nv totals, Montgomery limbs, to out_words (device-visible host memory
 // or device memory): value q at out_words[8q .. 8q+8).
+// `words` is the mailbox the flag lives in; seq != 0 publishes completion.
 void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
-                      hipStream_t stream);
+                      uint32_t* words, uint32_t seq, hipStream_t stream);
 
 // Same for two partial arrays at once: nv1 values per block from the first, then
 // nv2 from the second (nv2 may be 0); totals at out_words[8q..], first array first.
 void launch_final_sum2(const uint32_t* part1, size_t pstride1, int nv1, const uint32_t* part2, size_t pstride2, int nv2,
-                       unsigned nblocks, uint32_t* out_words, hipStream_t stream);
+                       unsigned nblocks, uint32_t* out_words, uint32_t* words, uint32_t seq, hipStream_t stream);
 
 // sum_i a_i into mailbox words [0, 8).
 size_t sum_scratch_bytes(size_t n);
-int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, uint32_t* out_words, hipStream_t stream);
+int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, Mailbox* mb, uint32_t seq, hipStream_t stream);
 
 // ---- eq tables --------------------------------------------------------------
 // dst_x = prod_{t < nvars} (u_t x_t + (1-u_t)(1-x_t)), x in {0,1}^nvars, first
@@ -40,8 +63,8 @@ int eq_table_run(uint32_t* dst, size_t stride, const host::F* u, int nvars, hipS
 // ---- multilinear evaluation ---------------------------------------------------
 // a~(point) into out_words[0, 8) (Montgomery); a is not modified.
 size_t mle_scratch_bytes(int nvars);
-int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, uint32_t* out_words,
-                 hipStream_t stream);
+int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, Mailbox* mb,
+                 uint32_t seq, hipStream_t stream);
 
 // Copies the leading `n` elements of a limb-major vector.
 void launch_copy(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t n, hipStream_t stream);

@@ -17,53 +17,45 @@ __global__ void __launch_bounds__(kBlock) k_sum_partial(const uint32_t* __restri
     if (threadIdx.x == 0) fr_store(partials, pstride, blockIdx.x, acc[0]);
 }
 
-// One workgroup adds up nblocks*nv partial values; value q of block b sits at
-// element b*nv + q.  Totals go out as raw Montgomery limbs.
-__global__ void __launch_bounds__(kBlock) k_final_sum(const uint32_t* __restrict__ partials, size_t pstride,
-                                                      unsigned nblocks, int nv, uint32_t* out_words) {
-    __shared__ uint32_t lds[4 * 8];
-    for (int q = 0; q < nv; ++q) {
-        Fr acc[1] = {fr_zero()};
-        for (unsigned b = threadIdx.x; b < nblocks; b += kBlock)
-            acc[0] = fr_add(acc[0], fr_load(partials, pstride, (size_t)b * nv + q));
-        block_sum<1, 4>(acc, lds);
-        if (threadIdx.x == 0) {
+// One workgroup of sixteen wavefronts adds up the per-workgroup partial values of
+// a round: wavefront q sums value q (the first nv1 values come from the first
+// array, the rest from the second; value v of workgroup b sits at element
+// b*nv + v of its array).  Totals go out as raw Montgomery limbs, value q at
+// out_words[8q..8q+7]; then completion is published.
+static const int kFinalThreads = 1024;
+
+__global__ void __launch_bounds__(kFinalThreads) k_final_sum2(const uint32_t* __restrict__ part1, size_t pstride1, int nv1,
+                                                              const uint32_t* __restrict__ part2, size_t pstride2, int nv2,
+                                                              unsigned nblocks, uint32_t* out_words, uint32_t* words,
+                                                              uint32_t seq) {
+    const int q = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (q < nv1 + nv2) {
+        const bool first = q < nv1;
+        const uint32_t* part = first ? part1 : part2;
+        const size_t pstride = first ? pstride1 : pstride2;
+        const int nv = first ? nv1 : nv2, qq = first ? q : q - nv1;
+        Fr acc = fr_zero();
+        for (unsigned b = lane; b < nblocks; b += 64) acc = fr_add(acc, fr_load(part, pstride, (size_t)b * nv + qq));
+        acc = wave_sum(acc);
+        if (lane == 0) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc[0].l[k];
+            for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc.l[k];
+            mailbox_written();
         }
     }
-}
-
-// Value q of the launch (blockIdx.x = q, one workgroup per value) comes from the
-// first array while q < nv1 and from the second afterwards.
-__global__ void __launch_bounds__(kBlock) k_final_sum2(const uint32_t* __restrict__ part1, size_t pstride1, int nv1,
-                                                       const uint32_t* __restrict__ part2, size_t pstride2, int nv2,
-                                                       unsigned nblocks, uint32_t* out_words) {
-    __shared__ uint32_t lds[4 * 8];
-    const int q = blockIdx.x;
-    const bool first = q < nv1;
-    const uint32_t* part = first ? part1 : part2;
-    const size_t pstride = first ? pstride1 : pstride2;
-    const int nv = first ? nv1 : nv2, qq = first ? q : q - nv1;
-    Fr acc[1] = {fr_zero()};
-    for (unsigned b = threadIdx.x; b < nblocks; b += kBlock)
-        acc[0] = fr_add(acc[0], fr_load(part, pstride, (size_t)b * nv + qq));
-    block_sum<1, 4>(acc, lds);
-    if (threadIdx.x == 0) {
-#pragma unroll
-        for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc[0].l[k];
-    }
+    __syncthreads();
+    if (threadIdx.x == 0) mailbox_publish(words, seq);
 }
 
 void launch_final_sum2(const uint32_t* part1, size_t pstride1, int nv1, const uint32_t* part2, size_t pstride2, int nv2,
-                       unsigned nblocks, uint32_t* out_words, hipStream_t stream) {
-    hipLaunchKernelGGL(k_final_sum2, dim3(nv1 + nv2), dim3(kBlock), 0, stream, part1, pstride1, nv1, part2, pstride2, nv2,
-                       nblocks, out_words);
+                       unsigned nblocks, uint32_t* out_words, uint32_t* words, uint32_t seq, hipStream_t stream) {
+    hipLaunchKernelGGL(k_final_sum2, dim3(1), dim3(kFinalThreads), 0, stream, part1, pstride1, nv1, part2, pstride2, nv2,
+                       nblocks, out_words, words, seq);
 }
 
 void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
-                      hipStream_t stream) {
-    hipLaunchKernelGGL(k_final_sum, dim3(1), dim3(kBlock), 0, stream, partials, pstride, nblocks, nv, out_words);
+                      uint32_t* words, uint32_t seq, hipStream_t stream) {
+    launch_final_sum2(partials, pstride, nv, nullptr, 0, 0, nblocks, out_words, words, seq, stream);
 }
 
 size_t sum_scratch_bytes(size_t) {
@@ -72,13 +64,13 @@ size_t sum_scratch_bytes(size_t) {
     return cv.used();
 }
 
-int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, uint32_t* out_words, hipStream_t stream) {
+int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, Mailbox* mb, uint32_t seq, hipStream_t stream) {
     uint32_t* partials = cv.limbs(kMaxPartialBlocks);
     if (!partials) return ZK_E_BUFSZ;
     unsigned blocks = grid_for(n, kBlock * 8, kMaxPartialBlocks);
     hipLaunchKernelGGL(k_sum_partial, dim3(blocks), dim3(kBlock), 0, stream, a, stride, n, partials,
                        (size_t)kMaxPartialBlocks);
-    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, out_words, stream);
+    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, mb->words, mb->words, seq, stream);
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
 }
@@ -162,8 +154,13 @@ void launch_fold(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_
     hipLaunchKernelGGL(k_fold, dim3(grid_for(half)), dim3(kBlock), 0, stream, dst, ds, src, ss, half, to_dev(r));
 }
 
-__global__ void k_emit(const uint32_t* __restrict__ a, size_t stride, size_t index, uint32_t* out_words) {
-    if (threadIdx.x < 8) out_words[threadIdx.x] = a[threadIdx.x * stride + index];
+__global__ void k_emit(const uint32_t* __restrict__ a, size_t stride, size_t index, uint32_t* words, uint32_t seq) {
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) words[k] = a[k * stride + index];
+        mailbox_written();
+        mailbox_publish(words, seq);
+    }
 }
 
 size_t mle_scratch_bytes(int nvars) {
@@ -172,10 +169,10 @@ size_t mle_scratch_bytes(int nvars) {
     return cv.used();
 }
 
-int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, uint32_t* out_words,
-                 hipStream_t stream) {
+int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, Mailbox* mb,
+                 uint32_t seq, hipStream_t stream) {
     if (nvars == 0) {
-        hipLaunchKernelGGL(k_emit, dim3(1), dim3(64), 0, stream, a, stride, (size_t)0, out_words);
+        hipLaunchKernelGGL(k_emit, dim3(1), dim3(64), 0, stream, a, stride, (size_t)0, mb->words, seq);
         ZK_HIP_TRY(hipGetLastError());
         return ZK_OK;
     }
@@ -187,7 +184,7 @@ int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* poi
         half >>= 1;
         launch_fold(buf, (size_t)1 << (nvars - 1), buf, (size_t)1 << (nvars - 1), half, point[t], stream);
     }
-    hipLaunchKernelGGL(k_emit, dim3(1), dim3(64), 0, stream, buf, (size_t)1 << (nvars - 1), (size_t)0, out_words);
+    hipLaunchKernelGGL(k_emit, dim3(1), dim3(64), 0, stream, buf, (size_t)1 << (nvars - 1), (size_t)0, mb->words, seq);
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
 }
@@ -210,7 +207,9 @@ int fr_sum(fr_t* out, fr_vec a, void* ws, size_t ws_bytes, void* stream) {
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
     Carver cv(ws, ws_bytes);
-    ZK_TRY(sum_run(a.limbs, a.stride, a.n, cv, mb->words, as_stream(stream)));
+    uint32_t seq = mb->next_seq();
+    ZK_TRY(sum_run(a.limbs, a.stride, a.n, cv, mb, seq, as_stream(stream)));
+    ZK_TRY(mailbox_wait(mb, seq, as_stream(stream)));
     ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
     *out = host::to_canonical(from_dev(mb->words));
     return ZK_OK;
@@ -239,7 +238,9 @@ int fr_mle_eval(fr_t* out, fr_vec a, const fr_t* point, int nvars, void* ws, siz
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
     Carver cv(ws, ws_bytes);
-    ZK_TRY(mle_eval_run(a.limbs, a.stride, nvars, pm, cv, mb->words, as_stream(stream)));
+    uint32_t seq = mb->next_seq();
+    ZK_TRY(mle_eval_run(a.limbs, a.stride, nvars, pm, cv, mb, seq, as_stream(stream)));
+    ZK_TRY(mailbox_wait(mb, seq, as_stream(stream)));
     ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
     *out = host::to_canonical(from_dev(mb->words));
     return ZK_OK;

@@ -78,9 +78,10 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         g.pstride = pstride;
         if (k > 0) hipLaunchKernelGGL(k_round_product<true>, dim3(blocks), dim3(kBlock), 0, stream, g);
         else hipLaunchKernelGGL(k_round_product<false>, dim3(blocks), dim3(kBlock), 0, stream, g);
-        launch_final_sum(partials, pstride, blocks, 3, mb->words, stream);
+        const uint32_t seq = mb->next_seq();
+        launch_final_sum(partials, pstride, blocks, 3, mb->words, mb->words, seq, stream);
         ZK_HIP_TRY(hipGetLastError());
-        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        ZK_TRY(mailbox_wait(mb, seq, stream));
         F g0 = from_dev(mb->words), g1 = from_dev(mb->words + 8), lead = from_dev(mb->words + 16);
         if (!claim_done) {
             to_bytes(claim_bytes, add(g0, g1));
@@ -101,9 +102,11 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
     f.r = to_dev(r_prev);
     f.p[0] = a; f.stride[0] = as; f.fold[0] = d >= 1;
     f.p[1] = b; f.stride[1] = bs; f.fold[1] = d >= 1;
-    hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words);
+    const uint32_t seq = mb->next_seq();
+    hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words, seq);
     ZK_HIP_TRY(hipGetLastError());
-    ZK_HIP_TRY(hipStreamSynchronize(stream));
+    ZK_TRY(mailbox_wait(mb, seq, stream));
+    ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device
     F fa = from_dev(mb->words), fb = from_dev(mb->words + 8);
     if (!claim_done) {  // d == 0: the sum is the single product
         to_bytes(claim_bytes, mul(fa, fb));
@@ -227,7 +230,7 @@ static int dot_run(const uint32_t* x, size_t xs, const uint32_t* y, size_t ys, s
     unsigned blocks = grid_for(n, kBlock * 4, kMaxPartialBlocks);
     hipLaunchKernelGGL(k_dot_partial, dim3(blocks), dim3(kBlock), 0, stream, x, xs, y, ys, n, partials,
                        (size_t)kMaxPartialBlocks);
-    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, out_words, stream);
+    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, out_words, out_words, 0, stream);
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
 }

@@ -183,8 +183,7 @@ static size_t prove_ws_bytes(size_t D, size_t N) {
     ProveWs w;
     carve_prove(w, cv, D, N);
     cv.limbs(EqPool::entries(log2_floor(D)));
-    size_t inv_d = batch_inverse_scratch_bytes(D), inv_n = batch_inverse_scratch_bytes(N);
-    cv.take(inv_d > inv_n ? inv_d : inv_n);
+    cv.take(batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N));
     return cv.used();
 }
 
@@ -288,14 +287,22 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     if (forced_beta) beta = from_canonical(*forced_beta);
     hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.M, N, w.m, N);
     {
-        ProfileScope prof(kProfInverse, stream);
-        Carver inv_cv = cv;  // scratch reused by the two inversions
-        ZK_TRY(batch_inverse_run(w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb, stream));
-    }
-    {
+        // both inversions share one wait: down passes of B and A, one round trip,
+        // one host inversion (of the product of the two grand totals), up passes
         ProfileScope prof(kProfInverse, stream);
         Carver inv_cv = cv;
-        ZK_TRY(batch_inverse_run(w.A, D, S.limbs, S.stride, D, beta, inv_cv, mb, stream));
+        BatchInverseJob job_b, job_a;
+        uint32_t seq = mb->next_seq();
+        ZK_TRY(batch_inverse_begin(job_b, w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb->words + kMailboxInvB, mb->words,
+                                   0, stream));
+        ZK_TRY(batch_inverse_begin(job_a, w.A, D, S.limbs, S.stride, D, beta, inv_cv, mb->words + kMailboxInvA, mb->words,
+                                   seq, stream));
+        ZK_TRY(mailbox_wait(mb, seq, stream));
+        F total_b = from_dev(mb->words + kMailboxInvB), total_a = from_dev(mb->words + kMailboxInvA);
+        if (is_zero(total_b) || is_zero(total_a)) return ZK_E_ZERO_DENOM;
+        F inv_both = inv(mul(total_a, total_b));
+        ZK_TRY(batch_inverse_end(job_b, mul(inv_both, total_a), stream));
+        ZK_TRY(batch_inverse_end(job_a, mul(inv_both, total_b), stream));
     }
 
     F alpha = tr.challenge("alpha");
@@ -328,13 +335,18 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         a.pstride = w.part_blocks * 6;
         unsigned blocks = grid_for(N, kBlock * 4, kMaxPartialBlocks);
         hipLaunchKernelGGL(k_table_const, dim3(blocks), dim3(kBlock), 0, stream, a);
-        launch_final_sum(w.partT, a.pstride, blocks, 2, mb->words, stream);
+        // read back together with the first round's sums (or the final values)
+        launch_final_sum(w.partT, a.pstride, blocks, 2, mb->words + kMailboxTableC, mb->words, 0, stream);
         ZK_HIP_TRY(hipGetLastError());
-        ZK_HIP_TRY(hipStreamSynchronize(stream));
-        c1 = from_dev(mb->words);
-        c2 = from_dev(mb->words + 8);
     }
-    F cB = sub(mul(alpha2, c1), c2);
+    bool table_consts_read = false;
+    auto read_table_consts = [&]() {
+        if (table_consts_read) return;
+        c1 = from_dev(mb->words + kMailboxTableC);
+        c2 = from_dev(mb->words + kMailboxTableC + 8);
+        table_consts_read = true;
+    };
+    F cB = zero();
 
     // -- header ------------------------------------------------------------------------------
     uint8_t* out = proof;
@@ -395,19 +407,23 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         t.partials = w.partT;
         t.pstride = w.part_blocks * 6;
 
+        const uint32_t seq = mb->next_seq();
         if (small) {
             // one workgroup, one launch, sums straight to the host
             ProfileScope prof(kProfRoundData, stream);
-            if (!table_round) hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words);
-            else if (k == h) hipLaunchKernelGGL(k_round_small<1>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words);
-            else hipLaunchKernelGGL(k_round_small<2>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words);
+            if (!table_round)
+                hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words, seq);
+            else if (k == h)
+                hipLaunchKernelGGL(k_round_small<1>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words, seq);
+            else
+                hipLaunchKernelGGL(k_round_small<2>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words, seq);
         } else if (table_round && k > 0) {
             {
                 ProfileScope prof(kProfRoundData, stream);
                 if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
                 else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
             }
-            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, stream);
+            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, mb->words, seq, stream);
         } else {
             {
                 ProfileScope prof(kProfRoundData, stream);
@@ -418,10 +434,13 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
                 ProfileScope prof(kProfRoundTable, stream);
                 hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
             }
-            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, table_round ? 6 : 0, blocks, mb->words, stream);
+            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, table_round ? 6 : 0, blocks, mb->words,
+                              mb->words, seq, stream);
         }
         ZK_HIP_TRY(hipGetLastError());
-        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        ZK_TRY(mailbox_wait(mb, seq, stream));
+        read_table_consts();
+        cB = sub(mul(alpha2, c1), c2);
 
         F q0 = from_dev(mb->words), q1 = from_dev(mb->words + 8), qi = from_dev(mb->words + 16);
         if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
@@ -472,9 +491,12 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         if (l <= 1) { f.p[4] = T.limbs; f.stride[4] = T.stride; }
         else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
         f.fold[4] = t_fold;
-        hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words);
+        const uint32_t seq = mb->next_seq();
+        hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words, seq);
         ZK_HIP_TRY(hipGetLastError());
-        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        ZK_TRY(mailbox_wait(mb, seq, stream));
+        ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device
+        read_table_consts();
         F fin[5];
         for (int i = 0; i < 5; ++i) {
             fin[i] = from_dev(mb->words + 8 * i);
@@ -558,7 +580,9 @@ static int verify_impl(const uint8_t seed[32], const uint8_t* proof, size_t len,
     uint32_t* leaves = (uint32_t*)cv.take((size_t)nleaves * 32);
     auto check = [&](const uint32_t* a, size_t stride, int nv, const F* pt, const F& want, int* ok) -> int {
         Carver scratch = cv;
-        ZK_TRY(mle_eval_run(a, stride, nv, pt, scratch, mb->words, stream));
+        uint32_t seq = mb->next_seq();
+        ZK_TRY(mle_eval_run(a, stride, nv, pt, scratch, mb, seq, stream));
+        ZK_TRY(mailbox_wait(mb, seq, stream));
         ZK_HIP_TRY(hipStreamSynchronize(stream));
         *ok = equal(from_dev(mb->words), want) ? 1 : 0;
         return ZK_OK;

@@ -553,7 +553,7 @@ static const size_t kSmallPairs = 512;
 
 template <int TABLE>
 static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundArgs d, TableRoundArgs t,
-                                                                     uint32_t* out_words) {
+                                                                     uint32_t* out_words, uint32_t seq) {
     __shared__ uint32_t lds[16 * 6 * 8];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const bool data_side = threadIdx.x < 512;
@@ -596,7 +596,10 @@ static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundA
         const int slot = data_side ? q : 5 + q;
 #pragma unroll
         for (int k = 0; k < 8; ++k) out_words[8 * slot + k] = acc.l[k];
+        mailbox_written();
     }
+    __syncthreads();
+    if (threadIdx.x == 0) mailbox_publish(out_words, seq);
 }
 
 // Sums over the whole table, before any of its variables is bound:
@@ -641,13 +644,17 @@ struct FinalArgs {
     Fr r;
 };
 
-static __global__ void k_final_values(FinalArgs g, uint32_t* out_words) {
+static __global__ void k_final_values(FinalArgs g, uint32_t* out_words, uint32_t seq) {
     int q = threadIdx.x;
-    if (q >= g.count) return;
-    Fr v = fr_load(g.p[q], g.stride[q], 0);
-    if (g.fold[q]) v = fr_fold(v, fr_load(g.p[q], g.stride[q], 1), g.r);
+    if (q < g.count) {
+        Fr v = fr_load(g.p[q], g.stride[q], 0);
+        if (g.fold[q]) v = fr_fold(v, fr_load(g.p[q], g.stride[q], 1), g.r);
 #pragma unroll
-    for (int k = 0; k < 8; ++k) out_words[8 * q + k] = v.l[k];
+        for (int k = 0; k < 8; ++k) out_words[8 * q + k] = v.l[k];
+        mailbox_written();
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) mailbox_publish(out_words, seq);
 }
 
 }  // namespace zkmi
