@@ -313,6 +313,86 @@ __device__ __forceinline__ Fr fr_mul(const Fr& a, const Fr& b) { return fr_mul_i
 // scalar registers and cost no vector registers.
 __device__ __forceinline__ Fr fr_mul_uniform(const Fr& a, const Fr& k) { return fr_mul_impl<true>(a, k); }
 
+// ---- sums of products without intermediate reductions ---------------------------
+//
+// A sum of Montgomery products sum_i a_i b_i / 2^256 needs only one reduction:
+// the 512-bit integer products are added up first.  FrWide holds such a sum as
+// sixteen limbs with the invariant (upper half) < r, i.e. value < r * 2^256, which
+// is what a single Montgomery reduction can take; after each addition the upper
+// half is brought back below r by one conditional subtraction (the product adds
+// less than 0.46 r to it).
+struct FrWide {
+    uint32_t l[16];
+};
+
+__device__ __forceinline__ FrWide fr_wide_zero() {
+    FrWide w;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) w.l[k] = 0;
+    return w;
+}
+
+template <int C>
+__device__ __forceinline__ void fr_wide_column(uint64_t& acc, uint32_t& ex, FrWide& w, const uint32_t* a,
+                                               const uint32_t* b) {
+    if constexpr (C < 8) fr_col_products<C, 0, C + 1>(acc, ex, a, b);
+    else fr_col_products<C, C - 7, 15 - C>(acc, ex, a, b);
+    fr_mack1(acc, ex, w.l[C], 1u);
+    w.l[C] = (uint32_t)acc;
+    fr_col_shift(acc, ex);
+}
+
+// w += a * b (as integers), keeping the invariant.
+__device__ __forceinline__ void fr_wide_mac(FrWide& w, const Fr& a, const Fr& b) {
+    uint64_t acc = 0;
+    uint32_t ex = 0;
+    fr_wide_column<0>(acc, ex, w, a.l, b.l);
+    fr_wide_column<1>(acc, ex, w, a.l, b.l);
+    fr_wide_column<2>(acc, ex, w, a.l, b.l);
+    fr_wide_column<3>(acc, ex, w, a.l, b.l);
+    fr_wide_column<4>(acc, ex, w, a.l, b.l);
+    fr_wide_column<5>(acc, ex, w, a.l, b.l);
+    fr_wide_column<6>(acc, ex, w, a.l, b.l);
+    fr_wide_column<7>(acc, ex, w, a.l, b.l);
+    fr_wide_column<8>(acc, ex, w, a.l, b.l);
+    fr_wide_column<9>(acc, ex, w, a.l, b.l);
+    fr_wide_column<10>(acc, ex, w, a.l, b.l);
+    fr_wide_column<11>(acc, ex, w, a.l, b.l);
+    fr_wide_column<12>(acc, ex, w, a.l, b.l);
+    fr_wide_column<13>(acc, ex, w, a.l, b.l);
+    fr_wide_column<14>(acc, ex, w, a.l, b.l);
+    w.l[15] += (uint32_t)acc;  // upper half stays below 1.46 r < 2^256: no carry out
+    Fr hi = fr_reduce_once(&w.l[8]);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w.l[8 + k] = hi.l[k];
+}
+
+// w / 2^256 mod r, fully reduced: the reduction half of a Montgomery product.
+__device__ __forceinline__ Fr fr_wide_reduce(const FrWide& w) {
+    uint32_t m[8];
+    uint32_t t[8];
+    uint64_t acc = 0;
+    uint32_t ex = 0;
+    // column c < 8: w_c + sum_{i<c} m_i r_(c-i), then m_c clears it
+#define ZK_WIDE_LOW(C)                                              \
+    fr_mack1(acc, ex, w.l[C], 1u);                                  \
+    if constexpr (C > 0) fr_col_reductions<C, 0, C>(acc, ex, m);    \
+    m[C] = 0u - (uint32_t)acc;                                      \
+    fr_mack1(acc, ex, m[C], 1u);                                    \
+    fr_col_shift(acc, ex);
+    ZK_WIDE_LOW(0) ZK_WIDE_LOW(1) ZK_WIDE_LOW(2) ZK_WIDE_LOW(3) ZK_WIDE_LOW(4) ZK_WIDE_LOW(5) ZK_WIDE_LOW(6) ZK_WIDE_LOW(7)
+#undef ZK_WIDE_LOW
+#define ZK_WIDE_HIGH(C)                                             \
+    fr_mack1(acc, ex, w.l[C], 1u);                                  \
+    fr_col_reductions<C, C - 7, 15 - C>(acc, ex, m);                \
+    t[C - 8] = (uint32_t)acc;                                       \
+    fr_col_shift(acc, ex);
+    ZK_WIDE_HIGH(8) ZK_WIDE_HIGH(9) ZK_WIDE_HIGH(10) ZK_WIDE_HIGH(11) ZK_WIDE_HIGH(12) ZK_WIDE_HIGH(13) ZK_WIDE_HIGH(14)
+#undef ZK_WIDE_HIGH
+    t[7] = (uint32_t)acc + w.l[15];  // result < 2r < 2^256
+    return fr_reduce_once(t);
+}
+
 __device__ __forceinline__ Fr fr_sqr(const Fr& a) { return fr_mul(a, a); }
 
 // canonical integer (8 limbs, < 2^256) -> Montgomery form

@@ -42,14 +42,16 @@ static const unsigned kMaxPartialBlocks = 4096;
 // element b*nv + q of `partials`, limb-major with stride pstride) and writes
 // the nv totals, Montgomery limbs, to out_words (device-visible host memory
 // or device memory): value q at out_words[8q .. 8q+8).
-// `words` is the mailbox the flag lives in; seq != 0 publishes completion.
+// `words` is the mailbox the flag lives in; seq != 0 publishes completion, for
+// which `ticket` (one zeroed word of device memory, left zero) is needed.
 void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
-                      uint32_t* words, uint32_t seq, hipStream_t stream);
+                      uint32_t* words, uint32_t seq, uint32_t* ticket, hipStream_t stream);
 
 // Same for two partial arrays at once: nv1 values per block from the first, then
 // nv2 from the second (nv2 may be 0); totals at out_words[8q..], first array first.
 void launch_final_sum2(const uint32_t* part1, size_t pstride1, int nv1, const uint32_t* part2, size_t pstride2, int nv2,
-                       unsigned nblocks, uint32_t* out_words, uint32_t* words, uint32_t seq, hipStream_t stream);
+                       unsigned nblocks, uint32_t* out_words, uint32_t* words, uint32_t seq, uint32_t* ticket,
+                       hipStream_t stream);
 
 // sum_i a_i into mailbox words [0, 8).
 size_t sum_scratch_bytes(size_t n);
@@ -65,6 +67,9 @@ int eq_table_run(uint32_t* dst, size_t stride, const host::F* u, int nvars, hipS
 size_t mle_scratch_bytes(int nvars);
 int mle_eval_run(const uint32_t* a, size_t stride, int nvars, const host::F* point, Carver& cv, Mailbox* mb,
                  uint32_t seq, hipStream_t stream);
+
+// p[0..n) = v (a kernel, so that it can sit in a captured graph).
+void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t stream);
 
 // Copies the leading `n` elements of a limb-major vector.
 void launch_copy(uint32_t* dst, size_t ds, const uint32_t* src, size_t ss, size_t n, hipStream_t stream);

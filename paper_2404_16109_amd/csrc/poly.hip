@@ -7,6 +7,15 @@ namespace zkmi {
 
 // ---- sums -------------------------------------------------------------------
 
+__global__ void k_fill_words(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+void launch_fill_u32(uint32_t* p, size_t n, uint32_t v, hipStream_t stream) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(k_fill_words, dim3(grid_for(n)), dim3(kBlock), 0, stream, p, n, v);
+}
+
 __global__ void __launch_bounds__(kBlock) k_sum_partial(const uint32_t* __restrict__ a, size_t stride, size_t n,
                                                         uint32_t* __restrict__ partials, size_t pstride) {
     __shared__ uint32_t lds[4 * 8];
@@ -17,60 +26,70 @@ __global__ void __launch_bounds__(kBlock) k_sum_partial(const uint32_t* __restri
     if (threadIdx.x == 0) fr_store(partials, pstride, blockIdx.x, acc[0]);
 }
 
-// One workgroup of sixteen wavefronts adds up the per-workgroup partial values of
-// a round: wavefront q sums value q (the first nv1 values come from the first
-// array, the rest from the second; value v of workgroup b sits at element
-// b*nv + v of its array).  Totals go out as raw Montgomery limbs, value q at
-// out_words[8q..8q+7]; then completion is published.
+// Adds up the per-workgroup partial values of a round, one workgroup per value
+// (the first nv1 values come from the first array, the rest from the second;
+// value v of workgroup b sits at element b*nv + v of its array).  Totals go out as
+// raw Montgomery limbs, value q at out_words[8q..8q+7].  The workgroup that
+// finishes last (a ticket counter in device memory, left at zero again) publishes
+// completion.
 static const int kFinalThreads = 1024;
 
 __global__ void __launch_bounds__(kFinalThreads) k_final_sum2(const uint32_t* __restrict__ part1, size_t pstride1, int nv1,
                                                               const uint32_t* __restrict__ part2, size_t pstride2, int nv2,
                                                               unsigned nblocks, uint32_t* out_words, uint32_t* words,
-                                                              uint32_t seq) {
-    const int q = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    if (q < nv1 + nv2) {
-        const bool first = q < nv1;
-        const uint32_t* part = first ? part1 : part2;
-        const size_t pstride = first ? pstride1 : pstride2;
-        const int nv = first ? nv1 : nv2, qq = first ? q : q - nv1;
-        Fr acc = fr_zero();
-        for (unsigned b = lane; b < nblocks; b += 64) acc = fr_add(acc, fr_load(part, pstride, (size_t)b * nv + qq));
-        acc = wave_sum(acc);
-        if (lane == 0) {
+                                                              uint32_t seq, uint32_t* ticket) {
+    __shared__ uint32_t lds[16 * 8];
+    const int q = blockIdx.x;
+    const bool first = q < nv1;
+    const uint32_t* part = first ? part1 : part2;
+    const size_t pstride = first ? pstride1 : pstride2;
+    const int nv = first ? nv1 : nv2, qq = first ? q : q - nv1;
+    Fr acc[1] = {fr_zero()};
+    for (unsigned b = threadIdx.x; b < nblocks; b += kFinalThreads)
+        acc[0] = fr_add(acc[0], fr_load(part, pstride, (size_t)b * nv + qq));
+    block_sum<1, 16>(acc, lds);
+    if (threadIdx.x == 0) {
 #pragma unroll
-            for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc.l[k];
-            mailbox_written();
+        for (int k = 0; k < 8; ++k) out_words[8 * q + k] = acc[0].l[k];
+        mailbox_written();
+        if (seq != 0) {
+            unsigned done = atomicAdd(ticket, 1u);
+            if (done == gridDim.x - 1) {
+                *ticket = 0;
+                mailbox_publish(words, seq);
+            }
         }
     }
-    __syncthreads();
-    if (threadIdx.x == 0) mailbox_publish(words, seq);
 }
 
 void launch_final_sum2(const uint32_t* part1, size_t pstride1, int nv1, const uint32_t* part2, size_t pstride2, int nv2,
-                       unsigned nblocks, uint32_t* out_words, uint32_t* words, uint32_t seq, hipStream_t stream) {
-    hipLaunchKernelGGL(k_final_sum2, dim3(1), dim3(kFinalThreads), 0, stream, part1, pstride1, nv1, part2, pstride2, nv2,
-                       nblocks, out_words, words, seq);
+                       unsigned nblocks, uint32_t* out_words, uint32_t* words, uint32_t seq, uint32_t* ticket,
+                       hipStream_t stream) {
+    hipLaunchKernelGGL(k_final_sum2, dim3(nv1 + nv2), dim3(kFinalThreads), 0, stream, part1, pstride1, nv1, part2, pstride2,
+                       nv2, nblocks, out_words, words, seq, ticket);
 }
 
 void launch_final_sum(const uint32_t* partials, size_t pstride, unsigned nblocks, int nv, uint32_t* out_words,
-                      uint32_t* words, uint32_t seq, hipStream_t stream) {
-    launch_final_sum2(partials, pstride, nv, nullptr, 0, 0, nblocks, out_words, words, seq, stream);
+                      uint32_t* words, uint32_t seq, uint32_t* ticket, hipStream_t stream) {
+    launch_final_sum2(partials, pstride, nv, nullptr, 0, 0, nblocks, out_words, words, seq, ticket, stream);
 }
 
 size_t sum_scratch_bytes(size_t) {
     Carver cv(nullptr, 0);
     cv.limbs(kMaxPartialBlocks);
+    cv.take(256);  // ticket
     return cv.used();
 }
 
 int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, Mailbox* mb, uint32_t seq, hipStream_t stream) {
     uint32_t* partials = cv.limbs(kMaxPartialBlocks);
-    if (!partials) return ZK_E_BUFSZ;
+    uint32_t* ticket = (uint32_t*)cv.take(256);
+    if (!partials || !ticket) return ZK_E_BUFSZ;
+    launch_fill_u32(ticket, 1, 0u, stream);
     unsigned blocks = grid_for(n, kBlock * 8, kMaxPartialBlocks);
     hipLaunchKernelGGL(k_sum_partial, dim3(blocks), dim3(kBlock), 0, stream, a, stride, n, partials,
                        (size_t)kMaxPartialBlocks);
-    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, mb->words, mb->words, seq, stream);
+    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, mb->words, mb->words, seq, ticket, stream);
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
 }

@@ -41,6 +41,7 @@ __global__ void __launch_bounds__(kBlock) k_round_product(ProductRoundArgs g) {
 static size_t product_scratch_bytes() {
     Carver cv(nullptr, 0);
     cv.limbs((size_t)kMaxPartialBlocks * 3);
+    cv.take(256);  // ticket of the final sums
     return cv.used();
 }
 
@@ -53,7 +54,9 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
                               hipStream_t stream) {
     using namespace host;
     uint32_t* partials = cv.limbs((size_t)kMaxPartialBlocks * 3);
-    if (!partials) return ZK_E_BUFSZ;
+    uint32_t* ticket = (uint32_t*)cv.take(256);
+    if (!partials || !ticket) return ZK_E_BUFSZ;
+    launch_fill_u32(ticket, 1, 0u, stream);
     const size_t pstride = (size_t)kMaxPartialBlocks * 3;
     F r_prev = zero();
     bool claim_done = false;
@@ -79,7 +82,7 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         if (k > 0) hipLaunchKernelGGL(k_round_product<true>, dim3(blocks), dim3(kBlock), 0, stream, g);
         else hipLaunchKernelGGL(k_round_product<false>, dim3(blocks), dim3(kBlock), 0, stream, g);
         const uint32_t seq = mb->next_seq();
-        launch_final_sum(partials, pstride, blocks, 3, mb->words, mb->words, seq, stream);
+        launch_final_sum(partials, pstride, blocks, 3, mb->words, mb->words, seq, ticket, stream);
         ZK_HIP_TRY(hipGetLastError());
         ZK_TRY(mailbox_wait(mb, seq, stream));
         F g0 = from_dev(mb->words), g1 = from_dev(mb->words + 8), lead = from_dev(mb->words + 16);
@@ -230,7 +233,7 @@ static int dot_run(const uint32_t* x, size_t xs, const uint32_t* y, size_t ys, s
     unsigned blocks = grid_for(n, kBlock * 4, kMaxPartialBlocks);
     hipLaunchKernelGGL(k_dot_partial, dim3(blocks), dim3(kBlock), 0, stream, x, xs, y, ys, n, partials,
                        (size_t)kMaxPartialBlocks);
-    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, out_words, out_words, 0, stream);
+    launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, out_words, out_words, 0, nullptr, stream);
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
 }
@@ -296,6 +299,7 @@ size_t matmul_workspace_bytes(size_t D0, size_t D1, size_t D2) {
     MatmulWs w;
     carve_matmul(w, cv, D0, D1, D2);
     cv.limbs((size_t)kMaxPartialBlocks * 3);  // round partial sums (prover)
+    cv.take(256);                             // ticket of the final sums
     cv.limbs(w.P2);                           // column sums of Y (verifier)
     cv.limbs(w.P1);                           // e~(r, .) (verifier)
     return cv.used();

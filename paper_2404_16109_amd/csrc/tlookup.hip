@@ -131,7 +131,7 @@ struct ProveWs {
     uint4* rows;        // N rows of T, eight words each
     uint32_t* hist;     // per-workgroup histograms (tables of up to 2^16 rows), else null
     uint32_t hist_parts;
-    uint32_t* flags;    // [0] duplicate flag, [2..3] smallest bad index (64-bit)
+    uint32_t* flags;    // [0] duplicate flag, [1] ticket of the final sums, [2..3] smallest bad index (64-bit)
     uint32_t* leaves;   // nleaves * 8 words
     uint32_t nleaves;
     size_t part_blocks; // capacity of the two partial-sum buffers, in workgroups
@@ -336,7 +336,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         unsigned blocks = grid_for(N, kBlock * 4, kMaxPartialBlocks);
         hipLaunchKernelGGL(k_table_const, dim3(blocks), dim3(kBlock), 0, stream, a);
         // read back together with the first round's sums (or the final values)
-        launch_final_sum(w.partT, a.pstride, blocks, 2, mb->words + kMailboxTableC, mb->words, 0, stream);
+        launch_final_sum(w.partT, a.pstride, blocks, 2, mb->words + kMailboxTableC, mb->words, 0, w.flags + 1, stream);
         ZK_HIP_TRY(hipGetLastError());
     }
     bool table_consts_read = false;
@@ -423,7 +423,8 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
                 if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
                 else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
             }
-            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, mb->words, seq, stream);
+            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, mb->words, seq, w.flags + 1,
+                              stream);
         } else {
             {
                 ProfileScope prof(kProfRoundData, stream);
@@ -435,7 +436,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
                 hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
             }
             launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, table_round ? 6 : 0, blocks, mb->words,
-                              mb->words, seq, stream);
+                              mb->words, seq, w.flags + 1, stream);
         }
         ZK_HIP_TRY(hipGetLastError());
         ZK_TRY(mailbox_wait(mb, seq, stream));

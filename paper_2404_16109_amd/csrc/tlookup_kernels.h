@@ -189,43 +189,58 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
         for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) hist[w] = 0;
         __syncthreads();
         const size_t pass_end = pass_begin + kHistPass < end ? pass_begin + kHistPass : end;
-        // whole wavefronts iterate together so that the cross-lane merge sees all 64 lanes
-        for (size_t base = pass_begin; base < pass_end; base += kHistThreads) {
-            size_t i = base + threadIdx.x;
-            bool in_range = i < pass_end;
-            uint32_t row = kEmptySlot;
-            if (in_range) {
-                Fr v = fr_load(S, ss, i);
-                if (idx) {
-                    row = idx[i];
-                    if (row < N) {
-                        uint4 lo = rows[2 * (size_t)row], hi = rows[2 * (size_t)row + 1];
-                        uint32_t diff = (lo.x ^ v.l[0]) | (lo.y ^ v.l[1]) | (lo.z ^ v.l[2]) | (lo.w ^ v.l[3]) |
-                                        (hi.x ^ v.l[4]) | (hi.y ^ v.l[5]) | (hi.z ^ v.l[6]) | (hi.w ^ v.l[7]);
-                        if (diff) row = kEmptySlot;
-                        else if (dups) row = canon[row];
-                    } else {
-                        row = kEmptySlot;
-                    }
-                } else {
-                    row = hash_find(slots, cap_mask, T, ts, v);
+        // whole wavefronts iterate together so that the cross-lane merge sees all 64
+        // lanes; two elements per thread per trip keep more loads in flight
+        for (size_t base = pass_begin; base < pass_end; base += 2 * kHistThreads) {
+            size_t i[2] = {base + threadIdx.x, base + kHistThreads + threadIdx.x};
+            bool in_range[2] = {i[0] < pass_end, i[1] < pass_end};
+            uint32_t row[2] = {kEmptySlot, kEmptySlot};
+            Fr v[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                if (in_range[e]) {
+                    if (idx) row[e] = idx[i[e]];
+                    v[e] = fr_load(S, ss, i[e]);
                 }
-                if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
             }
-            bool pending = in_range && row != kEmptySlot;
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                if (!in_range[e]) continue;
+                if (idx) {
+                    uint32_t r = row[e];
+                    if (r < N) {
+                        uint4 lo = rows[2 * (size_t)r], hi = rows[2 * (size_t)r + 1];
+                        uint32_t diff = (lo.x ^ v[e].l[0]) | (lo.y ^ v[e].l[1]) | (lo.z ^ v[e].l[2]) | (lo.w ^ v[e].l[3]) |
+                                        (hi.x ^ v[e].l[4]) | (hi.y ^ v[e].l[5]) | (hi.z ^ v[e].l[6]) | (hi.w ^ v[e].l[7]);
+                        if (diff) r = kEmptySlot;
+                        else if (dups) r = canon[r];
+                    } else {
+                        r = kEmptySlot;
+                    }
+                    row[e] = r;
+                } else {
+                    row[e] = hash_find(slots, cap_mask, T, ts, v[e]);
+                }
+                if (row[e] == kEmptySlot) atomicMin(bad, (unsigned long long)i[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                bool pending = in_range[e] && row[e] != kEmptySlot;
 #pragma unroll 1
-            for (int round = 0; round < 4; ++round) {
-                unsigned long long todo = __ballot(pending);
-                if (todo == 0) break;
-                int leader = __ffsll((long long)todo) - 1;
-                uint32_t lead_row = __shfl(row, leader, 64);
-                bool same_row = pending && row == lead_row;
-                uint32_t run = (uint32_t)__popcll(__ballot(same_row));
-                if (run >= 32) hot.add(m, lead_row, run);
-                else if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[lead_row >> 1], run << (16 * (lead_row & 1)));
-                pending = pending && !same_row;
+                for (int round = 0; round < 4; ++round) {
+                    unsigned long long todo = __ballot(pending);
+                    if (todo == 0) break;
+                    int leader = __ffsll((long long)todo) - 1;
+                    uint32_t lead_row = __shfl(row[e], leader, 64);
+                    bool same_row = pending && row[e] == lead_row;
+                    uint32_t run = (uint32_t)__popcll(__ballot(same_row));
+                    if (run >= 32) hot.add(m, lead_row, run);
+                    else if ((int)(threadIdx.x & 63) == leader)
+                        atomicAdd(&hist[lead_row >> 1], run << (16 * (lead_row & 1)));
+                    pending = pending && !same_row;
+                }
+                if (pending) atomicAdd(&hist[row[e] >> 1], 1u << (16 * (row[e] & 1)));
             }
-            if (pending) atomicAdd(&hist[row >> 1], 1u << (16 * (row & 1)));
         }
         __syncthreads();
         for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) {
@@ -423,21 +438,62 @@ struct DataRoundArgs {
 // A_i (S_i + beta) = 1 for every i, so q0 = q1 = sum of the weights = 1 and only
 // qinf and the sums of A are computed (q0 and q1 stay zero and are set by the
 // host).
-template <bool FOLD>
-__device__ __forceinline__ void data_pair(const DataRoundArgs& g, size_t p, size_t lo_mask, Fr (&tot)[5]) {
+// The three weighted sums are sums of products: they are accumulated as
+// unreduced 512-bit integers and reduced once per thread.  In the streaming
+// kernels the three 16-limb accumulators of a thread live in LDS (48 KiB per
+// workgroup, limb-major so that lanes hit distinct banks) and only pass through
+// registers while one product is added: holding them in registers would cost a
+// third of the kernel's occupancy.
+struct WideInLds {
+    // volatile: the accesses stay where they are written, so that at most one
+    // accumulator is in registers at a time
+    volatile uint32_t* base;  // [3][16][kBlock]
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int k = 0; k < 48; ++k) base[k * kBlock + threadIdx.x] = 0;
+    }
+    __device__ __forceinline__ FrWide load(int which) const {
+        FrWide w;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) w.l[k] = base[(which * 16 + k) * kBlock + threadIdx.x];
+        return w;
+    }
+    __device__ __forceinline__ void mac(int which, const Fr& a, const Fr& b) {
+        FrWide w = load(which);
+        fr_wide_mac(w, a, b);
+#pragma unroll
+        for (int k = 0; k < 16; ++k) base[(which * 16 + k) * kBlock + threadIdx.x] = w.l[k];
+    }
+    __device__ __forceinline__ Fr finish(int which) const { return fr_wide_reduce(load(which)); }
+};
+
+// The same three accumulators in registers, for kernels with one pair per thread.
+struct WideInRegs {
+    FrWide w[3];
+    __device__ __forceinline__ void clear() {
+        w[0] = fr_wide_zero();
+        w[1] = fr_wide_zero();
+        w[2] = fr_wide_zero();
+    }
+    __device__ __forceinline__ void mac(int which, const Fr& a, const Fr& b) { fr_wide_mac(w[which], a, b); }
+    __device__ __forceinline__ Fr finish(int which) const { return fr_wide_reduce(w[which]); }
+};
+
+template <bool FOLD, class Wide>
+__device__ __forceinline__ void data_pair(const DataRoundArgs& g, size_t p, size_t lo_mask, Wide& wide, Fr& sA0, Fr& sA1) {
     Fr a0, a1, s0, s1;
     load_pair<FOLD>(g.A, p, g.half, g.r_prev, a0, a1);
     load_pair<FOLD>(g.S, p, g.half, g.r_prev, s0, s1);
     Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
-    tot[3] = fr_add(tot[3], a0);
-    tot[4] = fr_add(tot[4], a1);
+    sA0 = fr_add(sA0, a0);
+    sA1 = fr_add(sA1, a1);
     if constexpr (FOLD) {
         Fr wa0 = fr_mul(w, a0), wa1 = fr_mul(w, a1);
-        tot[0] = fr_add(tot[0], fr_mul(wa0, fr_add(s0, g.beta)));
-        tot[1] = fr_add(tot[1], fr_mul(wa1, fr_add(s1, g.beta)));
-        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wa1, wa0), fr_sub(s1, s0)));
+        wide.mac(0, wa0, fr_add(s0, g.beta));
+        wide.mac(1, wa1, fr_add(s1, g.beta));
+        wide.mac(2, fr_sub(wa1, wa0), fr_sub(s1, s0));
     } else {
-        tot[2] = fr_add(tot[2], fr_mul(w, fr_mul(fr_sub(a1, a0), fr_sub(s1, s0))));
+        wide.mac(2, w, fr_mul(fr_sub(a1, a0), fr_sub(s1, s0)));
     }
 }
 
@@ -445,13 +501,21 @@ __device__ __forceinline__ void data_pair(const DataRoundArgs& g, size_t p, size
 // all share the high-variable factor of their weight; it is applied once to the
 // workgroup's sums.
 template <bool FOLD>
-__device__ __forceinline__ void round_data_block(const DataRoundArgs& g, unsigned block, uint32_t* lds) {
+__device__ __forceinline__ void round_data_block(const DataRoundArgs& g, unsigned block, uint32_t* lds,
+                                                 uint32_t* wide_lds) {
+    (void)wide_lds;
+    WideInRegs wide;
+    wide.clear();
     Fr tot[5];
-#pragma unroll
-    for (int q = 0; q < 5; ++q) tot[q] = fr_zero();
+    tot[3] = fr_zero();
+    tot[4] = fr_zero();
     const size_t start = block * g.block_span;
     const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
-    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) data_pair<FOLD>(g, p, lo_mask, tot);
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock)
+        data_pair<FOLD>(g, p, lo_mask, wide, tot[3], tot[4]);
+    tot[0] = FOLD ? wide.finish(0) : fr_zero();
+    tot[1] = FOLD ? wide.finish(1) : fr_zero();
+    tot[2] = wide.finish(2);
     block_sum<5, 4>(tot, lds);
     if (threadIdx.x == 0) {
         if (g.eq.has_hi) {
@@ -467,10 +531,23 @@ __device__ __forceinline__ void round_data_block(const DataRoundArgs& g, unsigne
     }
 }
 
+// The first round streams 128 bytes per pair for two multiplications and wants
+// many wavefronts in flight; the folding rounds are bound by instruction issue
+// and carry three 16-limb accumulators, for which three wavefronts per SIMD is
+// the register budget asked of the compiler.
 template <bool FOLD>
-static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g) {
+static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g);
+
+template <>
+__global__ void __launch_bounds__(kBlock) k_round_data<false>(DataRoundArgs g) {
     __shared__ uint32_t lds[4 * 6 * 8];
-    round_data_block<FOLD>(g, blockIdx.x, lds);
+    round_data_block<false>(g, blockIdx.x, lds, nullptr);
+}
+
+template <>
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 3))) k_round_data<true>(DataRoundArgs g) {
+    __shared__ uint32_t lds[4 * 6 * 8];
+    round_data_block<true>(g, blockIdx.x, lds, nullptr);
 }
 
 struct TableRoundArgs {
@@ -539,7 +616,7 @@ static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g)
 template <bool FOLD_T>
 static __global__ void __launch_bounds__(kBlock) k_round_both(DataRoundArgs d, TableRoundArgs t) {
     __shared__ uint32_t lds[4 * 6 * 8];
-    if (blockIdx.y == 0) round_data_block<true>(d, blockIdx.x, lds);
+    if (blockIdx.y == 0) round_data_block<true>(d, blockIdx.x, lds, nullptr);
     else round_table_block<FOLD_T>(t, blockIdx.x, lds);
 }
 
@@ -564,10 +641,12 @@ static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundA
     for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
     if (data_side) {
         if (p < d.half) {
-            Fr five[5] = {fr_zero(), fr_zero(), fr_zero(), fr_zero(), fr_zero()};
-            data_pair<true>(d, p, lo_mask, five);
-#pragma unroll
-            for (int q = 0; q < 5; ++q) tot[q] = five[q];
+            WideInRegs wide;
+            wide.clear();
+            data_pair<true>(d, p, lo_mask, wide, tot[3], tot[4]);
+            tot[0] = wide.finish(0);
+            tot[1] = wide.finish(1);
+            tot[2] = wide.finish(2);
         }
     } else if (TABLE != 0) {
         if (p < t.half) table_pair<TABLE == 2>(t, p, lo_mask, tot);
