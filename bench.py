@@ -96,6 +96,39 @@ def cpu_baseline(logD, logN):
             "sample": "oracle tlookup_prove on the same generator at D=2^%d, N=2^%d: %.1f s wall" % (logD, logN, dt)}
 
 
+def bench_matmul(args, zk, synth, torch, np):
+    """Secondary timing: the matmul proof of Section 6.1.1 at the 13B-layer shape."""
+    cfg = synth.matmul_operands()
+    X, W = cfg["X"], cfg["W"]
+    D0, D1 = X.shape
+    D2 = W.shape[1]
+    vx, vw = zk.Vec(D0 * D1), zk.Vec(D1 * D2)
+    assert zk.fr_from_i32(vx, torch.from_numpy(X.astype(np.int32).reshape(-1)).cuda()) == 0
+    assert zk.fr_from_i32(vw, torch.from_numpy(W.astype(np.int32).reshape(-1)).cuda()) == 0
+    ws = torch.empty(zk.matmul_workspace_bytes(D0, D1, D2), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    first = None
+    for _ in range(args.warmup):
+        rc, first = zk.matmul_sumcheck_prove(cfg["seed"], vx, D0, D1, vw, D2, ws=ws)
+        assert rc == 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rc, proof = zk.matmul_sumcheck_prove(cfg["seed"], vx, D0, D1, vw, D2, ws=ws)
+        assert rc == 0
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert first is None or proof == first
+    muls = D0 * D1 + D1 * D2
+    print(json.dumps({
+        "metric": "matmul_sumcheck_prove Fr-mul/s at 2048x5120x5120 (secondary timing)",
+        "value": muls / (ms * 1e-3), "unit": "Fr-mul/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32x8 (255-bit Montgomery integers)", "data": "synthetic",
+        "config": {"workload": "config 4: Y = X W with X 2048x5120, W 5120x5120 (int16 values embedded in Fr)",
+                   "fr_mul_model": muls, "bytes_read": 32 * muls, "GBps": 32 * muls / (ms * 1e-3) / 1e9}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +138,9 @@ def main():
     ap.add_argument("--logN", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-logD", type=int, default=19)
+    ap.add_argument("--workload", choices=["c3", "c4"], default="c3",
+                    help="c3: tlookup at D=2^25, N=2^16 (the headline metric); c4: matmul sumcheck 2048x5120x5120 "
+                         "(secondary timing)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 2^30 B, writes 2^30 B) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -121,6 +157,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    if args.workload == "c4":
+        return bench_matmul(args, zk, synth, torch, np)
     D, N = 1 << args.logD, 1 << args.logN
     rows = 2048 if args.logD >= 25 else max(1, (D * 11) // (16 * 2048))
     cols = 11008 if args.logD >= 25 else 2048

@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests load what is built; they build only if nothing is
+    lib = os.path.join(ROOT, "paper_2404_16109_amd", "libzkmi.so")
+    if not os.path.exists(lib):
+        from paper_2404_16109_amd import build as hip_build
+        hip_build.build()
 
 
 @pytest.fixture(scope="session")
