@@ -122,6 +122,7 @@ struct ProveWs {
     uint32_t* A;        // D
     uint32_t* Sf;       // D/2
     uint32_t* B;        // N
+    uint32_t* Bf;       // N/2: B is folded back and forth between B and Bf
     uint32_t* Tf;       // N/2
     uint32_t* M;        // N
     uint32_t* m;        // N counts
@@ -159,6 +160,7 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.A = cv.limbs(D);
     w.Sf = cv.limbs(D / 2 ? D / 2 : 1);
     w.B = cv.limbs(N);
+    w.Bf = cv.limbs(N / 2 ? N / 2 : 1);
     w.Tf = cv.limbs(N / 2 ? N / 2 : 1);
     w.M = cv.limbs(N);
     w.m = (uint32_t*)cv.take(N * 4);
@@ -368,6 +370,8 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     F cD = one(), cT = one();  // products of e~(u_t, r_t) over bound variables
     F r_prev = zero();
     F sum_A = zero();
+    uint32_t* b_cur = w.B;
+    size_t b_cur_stride = N;
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
         const EqSplit eq = ep.round(k);
@@ -375,9 +379,8 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         const bool small = k > 0 && half <= kSmallPairs;
         // pairs per workgroup: a workgroup's pairs must share the high factor of
         // their weights; small rounds get one pair per thread
-        size_t span = half / kMaxPartialBlocks;
-        size_t span_min = half <= ((size_t)1 << 15) ? (size_t)kBlock : (size_t)kBlock * 4;
-        if (span < span_min) span = span_min;
+        size_t span = half / 2048;  // about 2048 workgroups where the round is large enough
+        if (span < (size_t)kBlock) span = (size_t)kBlock;
         if (eq.has_hi && span > ((size_t)1 << eq.lbits)) span = (size_t)1 << eq.lbits;
         if (span > half) span = half;
         const unsigned blocks = (unsigned)(half / span);
@@ -395,7 +398,14 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         d.partials = w.partD;
         d.pstride = w.part_blocks * 5;
         TableRoundArgs t;
-        t.B = PairArray{w.B, N, w.B, N};
+        // B alternates between its two buffers on every fold (it has two readers)
+        if (k > h) {
+            uint32_t* other = b_cur == w.B ? w.Bf : w.B;
+            size_t other_stride = b_cur == w.B ? N / 2 : N;
+            t.B = PairArray{b_cur, b_cur_stride, other, other_stride};
+        } else {
+            t.B = PairArray{b_cur, b_cur_stride, b_cur, b_cur_stride};
+        }
         if (k <= h + 1) t.T = PairArray{T.limbs, T.stride, w.Tf, N / 2};
         else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
         t.M = PairArray{w.M, N, w.M, N};
@@ -420,8 +430,8 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         } else if (table_round && k > 0) {
             {
                 ProfileScope prof(kProfRoundData, stream);
-                if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
-                else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 2), dim3(kBlock), 0, stream, d, t);
+                if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
+                else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
             }
             launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, mb->words, seq, w.flags + 1,
                               stream);
@@ -439,6 +449,10 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
                               mb->words, seq, w.flags + 1, stream);
         }
         ZK_HIP_TRY(hipGetLastError());
+        if (k > h) {
+            b_cur = t.B.dst;
+            b_cur_stride = t.B.ds;
+        }
         ZK_TRY(mailbox_wait(mb, seq, stream));
         read_table_consts();
         cB = sub(mul(alpha2, c1), c2);
@@ -487,7 +501,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         if (n <= 1) { f.p[1] = S.limbs; f.stride[1] = S.stride; }
         else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
         f.fold[1] = d_fold;
-        f.p[2] = w.B; f.stride[2] = N; f.fold[2] = t_fold;
+        f.p[2] = b_cur; f.stride[2] = b_cur_stride; f.fold[2] = t_fold;
         f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
         if (l <= 1) { f.p[4] = T.limbs; f.stride[4] = T.stride; }
         else { f.p[4] = w.Tf; f.stride[4] = N / 2; }

@@ -400,7 +400,7 @@ struct PairArray {
 // array has 2*half entries.  With folding it has 4*half: the previous variable
 // is bound to r first (r is wave-uniform), the folded entries are written back
 // (to dst) and returned.
-template <bool FOLD>
+template <bool FOLD, bool STORE = true>
 __device__ __forceinline__ void load_pair(const PairArray& a, size_t p, size_t half, const Fr& r, Fr& x0, Fr& x1) {
     if constexpr (!FOLD) {
         x0 = fr_load(a.src, a.ss, p);
@@ -410,12 +410,12 @@ __device__ __forceinline__ void load_pair(const PairArray& a, size_t p, size_t h
             Fr y0 = fr_load(a.src, a.ss, p), y2 = fr_load(a.src, a.ss, p + 2 * half);
             x0 = fr_fold(y0, y2, r);
         }
-        fr_store(a.dst, a.ds, p, x0);
+        if constexpr (STORE) fr_store(a.dst, a.ds, p, x0);
         {
             Fr y1 = fr_load(a.src, a.ss, p + half), y3 = fr_load(a.src, a.ss, p + 3 * half);
             x1 = fr_fold(y1, y3, r);
         }
-        fr_store(a.dst, a.ds, p + half, x1);
+        if constexpr (STORE) fr_store(a.dst, a.ds, p + half, x1);
     }
 }
 
@@ -563,83 +563,96 @@ struct TableRoundArgs {
 // Table side of one round (once the table's own variables are being bound):
 //   t0 = w B0 (T0+beta), t1 = w B1 (T1+beta), tinf = w (B1-B0)(T1-T0),
 //   m0 = B0 M0, m1 = B1 M1, minf = (B1-B0)(M1-M0).
-template <bool FOLD>
+// The two groups of sums share only B, so they can be computed by different
+// threads (PART 1: the T sums, PART 2: the m sums, PART 0: both), which halves the
+// dependent chain of multiplications in the rounds that are bound by latency.
+// For that B is folded from one buffer into another (both parts read the
+// unfolded entries; only PART 0 and PART 1 store the folded ones).
+template <bool FOLD, int PART>
 __device__ __forceinline__ void table_pair(const TableRoundArgs& g, size_t p, size_t lo_mask, Fr (&tot)[6]) {
     Fr b0, b1;
-    load_pair<FOLD>(g.B, p, g.half, g.r_prev, b0, b1);
-    {
+    load_pair<FOLD, PART != 2>(g.B, p, g.half, g.r_prev, b0, b1);
+    if constexpr (PART != 1) {
         Fr m0, m1;
         load_pair<FOLD>(g.M, p, g.half, g.r_prev, m0, m1);
         tot[3] = fr_add(tot[3], fr_mul(b0, m0));
         tot[4] = fr_add(tot[4], fr_mul(b1, m1));
         tot[5] = fr_add(tot[5], fr_mul(fr_sub(b1, b0), fr_sub(m1, m0)));
     }
-    Fr t0, t1;
-    load_pair<FOLD>(g.T, p, g.half, g.r_prev, t0, t1);
-    Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
-    Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
-    tot[0] = fr_add(tot[0], fr_mul(wb0, fr_add(t0, g.beta)));
-    tot[1] = fr_add(tot[1], fr_mul(wb1, fr_add(t1, g.beta)));
-    tot[2] = fr_add(tot[2], fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
+    if constexpr (PART != 2) {
+        Fr t0, t1;
+        load_pair<FOLD>(g.T, p, g.half, g.r_prev, t0, t1);
+        Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
+        Fr wb0 = fr_mul(w, b0), wb1 = fr_mul(w, b1);
+        tot[0] = fr_add(tot[0], fr_mul(wb0, fr_add(t0, g.beta)));
+        tot[1] = fr_add(tot[1], fr_mul(wb1, fr_add(t1, g.beta)));
+        tot[2] = fr_add(tot[2], fr_mul(fr_sub(wb1, wb0), fr_sub(t1, t0)));
+    }
 }
 
-template <bool FOLD>
+template <bool FOLD, int PART>
 __device__ __forceinline__ void round_table_block(const TableRoundArgs& g, unsigned block, uint32_t* lds) {
     Fr tot[6];
 #pragma unroll
     for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
     const size_t start = block * g.block_span;
     const size_t lo_mask = ((size_t)1 << g.eq.lbits) - 1;
-    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) table_pair<FOLD>(g, p, lo_mask, tot);
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock)
+        table_pair<FOLD, PART>(g, p, lo_mask, tot);
     block_sum<6, 4>(tot, lds);
     if (threadIdx.x == 0) {
-        if (g.eq.has_hi) {
+        if (PART != 2 && g.eq.has_hi) {
             Fr hf = fr_load(g.eq.pool, g.eq.stride, g.eq.hi_off + (start >> g.eq.lbits));
             tot[0] = fr_mul(tot[0], hf);
             tot[1] = fr_mul(tot[1], hf);
             tot[2] = fr_mul(tot[2], hf);
         }
 #pragma unroll
-        for (int q = 0; q < 6; ++q) fr_store(g.partials, g.pstride, (size_t)block * 6 + q, tot[q]);
+        for (int q = 0; q < 6; ++q) {
+            const bool mine = PART == 0 || (PART == 1 ? q < 3 : q >= 3);
+            if (mine) fr_store(g.partials, g.pstride, (size_t)block * 6 + q, tot[q]);
+        }
     }
 }
 
 template <bool FOLD>
 static __global__ void __launch_bounds__(kBlock) k_round_table(TableRoundArgs g) {
     __shared__ uint32_t lds[4 * 6 * 8];
-    round_table_block<FOLD>(g, blockIdx.x, lds);
+    round_table_block<FOLD, 0>(g, blockIdx.x, lds);
 }
 
-// A round that binds one of the table's variables, both sides in one launch:
-// workgroups with blockIdx.y = 0 do the data side, blockIdx.y = 1 the table side.
-// The data arrays have been folded at least once by then.
+// A round that binds one of the table's variables, all of it in one launch:
+// workgroups with blockIdx.y = 0 do the data side, 1 the T sums and 2 the m sums
+// of the table side.  The data arrays have been folded at least once by then.
 template <bool FOLD_T>
 static __global__ void __launch_bounds__(kBlock) k_round_both(DataRoundArgs d, TableRoundArgs t) {
     __shared__ uint32_t lds[4 * 6 * 8];
     if (blockIdx.y == 0) round_data_block<true>(d, blockIdx.x, lds, nullptr);
-    else round_table_block<FOLD_T>(t, blockIdx.x, lds);
+    else if (blockIdx.y == 1) round_table_block<FOLD_T, 1>(t, blockIdx.x, lds);
+    else round_table_block<FOLD_T, 2>(t, blockIdx.x, lds);
 }
 
-// The last rounds (at most 512 pairs): one workgroup of 1024 threads does the
-// whole round, data pairs on threads 0..511 and table pairs on threads 512..1023,
-// and writes the eleven sums straight to out_words (value q at words 8q..8q+7,
-// data sums first), so the round costs a single launch.  TABLE: 0 = the table is
-// not being bound yet, 1 = first table round (nothing to fold), 2 = fold.
-static const int kSmallThreads = 1024;
-static const size_t kSmallPairs = 512;
+// The last rounds (at most 256 pairs): one workgroup does the whole round, data
+// pairs on threads 0..255, the T sums of the table side on threads 256..511 and
+// its m sums on threads 512..767, and writes the eleven sums straight to
+// out_words (value q at words 8q..8q+7, data sums first), so the round costs a
+// single launch.  TABLE: 0 = the table is not being bound yet, 1 = first table
+// round (nothing to fold), 2 = fold.
+static const int kSmallThreads = 768;
+static const size_t kSmallPairs = 256;
 
 template <int TABLE>
 static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundArgs d, TableRoundArgs t,
                                                                      uint32_t* out_words, uint32_t seq) {
-    __shared__ uint32_t lds[16 * 6 * 8];
+    __shared__ uint32_t lds[12 * 6 * 8];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const bool data_side = threadIdx.x < 512;
-    const size_t p = data_side ? threadIdx.x : threadIdx.x - 512;
+    const int group = threadIdx.x >> 8;  // 0 data, 1 table T sums, 2 table m sums
+    const size_t p = threadIdx.x & 255;
     const size_t lo_mask = ((size_t)1 << d.eq.lbits) - 1;
     Fr tot[6];
 #pragma unroll
     for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
-    if (data_side) {
+    if (group == 0) {
         if (p < d.half) {
             WideInRegs wide;
             wide.clear();
@@ -648,8 +661,9 @@ static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundA
             tot[1] = wide.finish(1);
             tot[2] = wide.finish(2);
         }
-    } else if (TABLE != 0) {
-        if (p < t.half) table_pair<TABLE == 2>(t, p, lo_mask, tot);
+    } else if (TABLE != 0 && p < t.half) {
+        if (group == 1) table_pair<TABLE == 2, 1>(t, p, lo_mask, tot);
+        else table_pair<TABLE == 2, 2>(t, p, lo_mask, tot);
     }
 #pragma unroll
     for (int q = 0; q < 6; ++q) {
@@ -660,19 +674,20 @@ static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundA
         }
     }
     __syncthreads();
-    // thread q adds up data value q over wavefronts 0..7, thread 512+q table value q over 8..15
-    const int q = data_side ? threadIdx.x : threadIdx.x - 512;
-    const int nvals = data_side ? 5 : (TABLE != 0 ? 6 : 0);
-    if (q < nvals) {
-        const int w0 = data_side ? 0 : 8;
+    // thread `slot` adds up output value `slot` over the four wavefronts of its group:
+    // 0..4 data sums, 5..7 the T sums (accumulators 0..2 of group 1), 8..10 the m sums
+    // (accumulators 3..5 of group 2)
+    const int slot = threadIdx.x;
+    if (slot < (TABLE != 0 ? 11 : 5)) {
+        const int g = slot < 5 ? 0 : slot < 8 ? 1 : 2;
+        const int q = slot < 5 ? slot : slot - 5;
         Fr acc = fr_zero();
-        for (int w = w0; w < w0 + 8; ++w) {
+        for (int w = 4 * g; w < 4 * g + 4; ++w) {
             Fr o;
 #pragma unroll
             for (int k = 0; k < 8; ++k) o.l[k] = lds[(w * 6 + q) * 8 + k];
             acc = fr_add(acc, o);
         }
-        const int slot = data_side ? q : 5 + q;
 #pragma unroll
         for (int k = 0; k < 8; ++k) out_words[8 * slot + k] = acc.l[k];
         mailbox_written();
