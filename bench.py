@@ -207,6 +207,17 @@ def main():
     assert info["sum_A"] == info["sum_mB"]            # log-derivative identity at beta
 
     ms = dt * 1e3 / args.steps
+    # beside the headline: the same proof with A read off the table-side inverses
+    ws_rows = ws
+    for _ in range(2):
+        rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws_rows)
+        assert rc == 0 and proof_rows == proof
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws_rows)
+    torch.cuda.synchronize()
+    ms_rows = (time.perf_counter() - t0) * 1e3 / args.steps
     phases = {}
     for name in ("total", "count", "inverse", "round_data", "round_table"):
         rc, recs, total_ms = zk.zkmi_profile_query(name)
@@ -227,6 +238,7 @@ def main():
                                "%d x %d activations padded to D=2^%d, N=2^%d" % (rows, cols, args.logD, args.logN),
                    "D": D, "N": N, "proof_bytes": len(proof), "fr_mul_model": fr_mul_model(D, N)},
         "phases_ms": {k: round(v["ms_per_step"], 4) for k, v in phases.items()},
+        "by_rows_ms_per_step": ms_rows,
         "roofline": {"bound": "alu", "kernel": "k_round_data",
                      "achieved": achieved / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
                      "frac": achieved / PEAK_MAD_PER_S, "traffic": measured_traffic(),

@@ -179,6 +179,15 @@ size_t tlookup_proof_bytes(size_t D);
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
 
+/* The same proof, byte for byte, for callers that know the table row of every
+ * element (idx is required): once S_i = T[idx_i] has been checked, A_i = 1/(beta + S_i)
+ * is the table-side inverse B[idx_i], so only the N table entries are inverted and
+ * A is gathered from them instead of inverting D elements.  Not what the
+ * benchmark's headline times (that is tlookup_prove, with the D-element
+ * inversion); reported beside it. */
+int tlookup_prove_by_rows(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
+                          size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
+
 /* As tlookup_prove with beta replaced by *forced_beta (host) after the
  * transcript has produced its own: the only way to reach the completeness
  * failure of Protocol 1 (beta + S_i = 0, Section 6.3) deliberately.  For tests. */

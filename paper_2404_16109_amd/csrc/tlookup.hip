@@ -245,7 +245,9 @@ static void digest_of_leaves(uint8_t out[32], const uint8_t* leaves, uint32_t nl
     h.finish(out);
 }
 
+// by_rows: form A as B[idx_i] instead of inverting beta + S_i (idx required).
 static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
+                      bool by_rows,
                       uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
                       void* stream_v) {
     using namespace host;
@@ -253,6 +255,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     if (!seed || !is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
     if (!vec_ok(S, D) || !vec_ok(T, N)) return ZK_E_BADARG;
     if (forced_beta && !canonical_in_range(*forced_beta)) return ZK_E_BADARG;
+    if (by_rows && !idx) return ZK_E_BADARG;
     const int n = log2_floor(D), l = log2_floor(N), h = n - l;
     const size_t need = tlookup_proof_bytes(D);
     if (len) *len = need;
@@ -288,7 +291,7 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     F beta = tr.challenge("beta");
     if (forced_beta) beta = from_canonical(*forced_beta);
     hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.M, N, w.m, N);
-    {
+    if (!by_rows) {
         // both inversions share one wait: down passes of B and A, one round trip,
         // one host inversion (of the product of the two grand totals), up passes
         ProfileScope prof(kProfInverse, stream);
@@ -305,6 +308,15 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         F inv_both = inv(mul(total_a, total_b));
         ZK_TRY(batch_inverse_end(job_b, mul(inv_both, total_a), stream));
         ZK_TRY(batch_inverse_end(job_a, mul(inv_both, total_b), stream));
+    } else {
+        // every S_i has been checked to equal T[idx_i]: invert the table side only
+        // and read A off it (a zero beta + S_i is a zero beta + T[idx_i])
+        ProfileScope prof(kProfInverse, stream);
+        Carver inv_cv = cv;
+        ZK_TRY(batch_inverse_run(w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb, stream));
+        hipLaunchKernelGGL(k_rows_of, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.rows, w.B, N, (uint32_t)N);
+        hipLaunchKernelGGL(k_gather_rows, dim3(grid_for(D, kBlock, 16384)), dim3(kBlock), 0, stream, w.A, D, D, idx, w.rows);
+        ZK_HIP_TRY(hipGetLastError());
     }
 
     F alpha = tr.challenge("alpha");
@@ -679,14 +691,20 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
 
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
-    return prove_impl(seed, S, idx, T, nullptr, proof, cap, len, aux, ws, ws_bytes, stream);
+    return prove_impl(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, ws_bytes, stream);
+}
+
+int tlookup_prove_by_rows(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
+                          size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
+    if (!idx) return ZK_E_BADARG;
+    return prove_impl(seed, S, idx, T, nullptr, true, proof, cap, len, aux, ws, ws_bytes, stream);
 }
 
 int tlookup_prove_with_beta(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
                             uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
                             void* stream) {
     if (!forced_beta) return ZK_E_BADARG;
-    return prove_impl(seed, S, idx, T, forced_beta, proof, cap, len, aux, ws, ws_bytes, stream);
+    return prove_impl(seed, S, idx, T, forced_beta, false, proof, cap, len, aux, ws, ws_bytes, stream);
 }
 
 size_t tlookup_verify_workspace_bytes(size_t D, size_t N) {

@@ -273,6 +273,29 @@ static __global__ void __launch_bounds__(kBlock) k_hist_reduce(uint32_t* __restr
     if (acc) atomicAdd(&m[j], acc);
 }
 
+// A_i = B[row_i]: with the row of every S_i known and checked, 1/(beta + S_i) is
+// the table-side inverse of that row.  B is read row-major (one 32-byte access per
+// element) from a copy written by k_rows_of.
+static __global__ void __launch_bounds__(kBlock) k_rows_of(uint4* __restrict__ rows, const uint32_t* __restrict__ B,
+                                                    size_t bs, uint32_t N) {
+    for (uint32_t j = blockIdx.x * kBlock + threadIdx.x; j < N; j += gridDim.x * kBlock) {
+        Fr v = fr_load(B, bs, j);
+        rows[2 * j] = make_uint4(v.l[0], v.l[1], v.l[2], v.l[3]);
+        rows[2 * j + 1] = make_uint4(v.l[4], v.l[5], v.l[6], v.l[7]);
+    }
+}
+
+static __global__ void __launch_bounds__(kBlock) k_gather_rows(uint32_t* __restrict__ A, size_t as, size_t D,
+                                                        const uint32_t* __restrict__ idx,
+                                                        const uint4* __restrict__ rows) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < D; i += (size_t)gridDim.x * kBlock) {
+        size_t r = idx[i];
+        uint4 lo = rows[2 * r], hi = rows[2 * r + 1];
+        Fr v = Fr{{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w}};
+        fr_store(A, as, i, v);
+    }
+}
+
 static __global__ void __launch_bounds__(kBlock) k_fill_u32(uint32_t* p, size_t n, uint32_t v) {
     for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) p[i] = v;
 }

@@ -57,6 +57,8 @@ def test_proof_bytes_equal_oracle(zk, orc, D, N, dup):
     Sb, Tb, Sv, Tv, idx = _random_instance(orc, zk, rng, D, N, dup)
     seed = rng.randbytes(32)
     _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx)          # rows given
+    rc, proof3, info3 = zk.tlookup_prove_by_rows(seed, Sv, idx, Tv)   # A read off the table-side inverses
+    assert rc == 0 and proof3 == orc.tlookup_prove(seed, Sb, Tb)[1] and info3["sum_A"] == info3["sum_mB"]
     rc, proof2, _ = zk.tlookup_prove(seed, Sv, None, Tv)  # rows found by the library
     assert rc == 0 and proof2 == orc.tlookup_prove(seed, Sb, Tb)[1]
     # inputs are not modified
@@ -121,6 +123,8 @@ def test_not_in_table_reports_smallest_index(zk, orc):
         assert rc == zk.ZK_E_NOT_IN_TABLE == rc_o and bad == bad_o == 777
         rc, _, info = zk.tlookup_prove(b"\x01" * 32, Sv, given, Tv)
         assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 777
+    assert zk.tlookup_prove_by_rows(b"\x01" * 32, Sv, idx, Tv)[0] == zk.ZK_E_NOT_IN_TABLE
+    assert zk.tlookup_prove_by_rows(b"\x01" * 32, Sv, None, Tv)[0] == zk.ZK_E_BADARG
     # a wrong row hint is an error even if the value is in the table
     wrong = idx.clone()
     wrong[5] = (wrong[5] + 1) % 64
