@@ -141,6 +141,7 @@ def main():
     ap.add_argument("--workload", choices=["c3", "c4"], default="c3",
                     help="c3: tlookup at D=2^25, N=2^16 (the headline metric); c4: matmul sumcheck 2048x5120x5120 "
                          "(secondary timing)")
+    ap.add_argument("--no-by-rows", action="store_true", help="skip the tlookup_prove_by_rows timing beside the headline")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 2^30 B, writes 2^30 B) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -208,16 +209,17 @@ def main():
 
     ms = dt * 1e3 / args.steps
     # beside the headline: the same proof with A read off the table-side inverses
-    ws_rows = ws
-    for _ in range(2):
-        rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws_rows)
-        assert rc == 0 and proof_rows == proof
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws_rows)
-    torch.cuda.synchronize()
-    ms_rows = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_rows = None
+    if not args.no_by_rows:
+        for _ in range(2):
+            rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws)
+            assert rc == 0 and proof_rows == proof
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws)
+        torch.cuda.synchronize()
+        ms_rows = (time.perf_counter() - t0) * 1e3 / args.steps
     phases = {}
     for name in ("total", "count", "inverse", "round_data", "round_table"):
         rc, recs, total_ms = zk.zkmi_profile_query(name)
