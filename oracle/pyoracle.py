@@ -38,6 +38,7 @@ def lib():
         _lib = ctypes.CDLL(_LIB_PATH)
         _lib.oracle_tlookup_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_product_proof_bytes.restype = ctypes.c_uint64
+        _lib.oracle_tlookup_batch_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_matmul_proof_bytes.restype = ctypes.c_uint64
     return _lib
 
@@ -290,6 +291,48 @@ def tlookup_verify(seed, proof, T, D, S=None, m=None, A=None, B=None, threads=No
                                      _p(None if B is None else _c(B).reshape(-1, 32)),
                                      _p(claims), _p(v), ctypes.byref(stage), threads or default_threads())
     return rc, {"claims": claims, "v": v[:n], "stage": stage.value}
+
+
+def _ptr_array(arrays):
+    arr = (ctypes.c_void_p * len(arrays))()
+    for i, a in enumerate(arrays):
+        arr[i] = None if a is None else a.ctypes.data
+    return arr
+
+
+def tlookup_batch_prove(seed, S_list, T_list, threads=None):
+    """Several instances of one shape, one sumcheck.  Returns (rc, proof, info)."""
+    S_list = [_c(s).reshape(-1, 32) for s in S_list]
+    T_list = [_c(t).reshape(-1, 32) for t in T_list]
+    K, D, N = len(S_list), S_list[0].shape[0], T_list[0].shape[0]
+    n = max(D.bit_length() - 1, 0)
+    cap = int(lib().oracle_tlookup_batch_proof_bytes(_u64(D), _u64(K))) if D and (D & (D - 1)) == 0 else 64
+    proof = np.zeros(cap, dtype=np.uint8)
+    ln = ctypes.c_uint64(0)
+    aux = np.zeros((3 + 2 * K, 32), dtype=np.uint8)
+    v = np.zeros((max(n, 1), 32), dtype=np.uint8)
+    bad_i, bad_x = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    rc = lib().oracle_tlookup_batch_prove(_p(seedb), _ptr_array(S_list), _ptr_array(T_list), _u64(K), _u64(D), _u64(N),
+                                          _p(proof), _u64(cap), ctypes.byref(ln), _p(aux), _p(v), ctypes.byref(bad_i),
+                                          ctypes.byref(bad_x), threads or default_threads())
+    info = {"beta": aux[0], "alpha": aux[1], "lambda": aux[2], "sum_A": aux[3::2], "sum_mB": aux[4::2], "v": v[:n],
+            "bad_instance": bad_i.value, "bad_index": bad_x.value}
+    return rc, proof[:ln.value].tobytes() if rc == OK else b"", info
+
+
+def tlookup_batch_verify(seed, proof, T_list, D, S_list=None, m_list=None, threads=None):
+    T_list = [_c(t).reshape(-1, 32) for t in T_list]
+    K, N = len(T_list), T_list[0].shape[0]
+    pb = np.frombuffer(bytes(proof), dtype=np.uint8).copy() if len(proof) else np.zeros(1, dtype=np.uint8)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    S_arr = None if S_list is None else _ptr_array([_c(s).reshape(-1, 32) for s in S_list])
+    keep_m = None if m_list is None else [np.ascontiguousarray(m, dtype=np.uint64) for m in m_list]
+    m_arr = None if keep_m is None else _ptr_array(keep_m)
+    keep_s = None if S_list is None else [_c(s).reshape(-1, 32) for s in S_list]
+    S_arr = None if keep_s is None else _ptr_array(keep_s)
+    return lib().oracle_tlookup_batch_verify(_p(seedb), _p(pb), _u64(len(proof)), _ptr_array(T_list), _u64(K), _u64(D),
+                                             _u64(N), S_arr, m_arr, None, threads or default_threads())
 
 
 # ---- product sumcheck / matmul ----------------------------------------------

@@ -163,3 +163,59 @@ def matmul_proof(seed, X, W):
     head = b"ZKMM" + (1).to_bytes(4, "little") + b"".join(d.to_bytes(8, "little") for d in (D0, D1, D2))
     return head + fr_bytes(claim) + body, {"u": u, "v": v, "r": r, "claim": claim, "Y": Y,
                                            "Xr": mle(Xp, u + r), "Wr": mle(Wp, r + v)}
+
+
+def tlookup_batch_proof(seed, S_list, T_list):
+    """K tlookup instances of one shape under one sumcheck of f = sum_k lambda^k f_k,
+    everything from the definitions."""
+    K, D, N = len(S_list), len(S_list[0]), len(T_list[0])
+    n, l = D.bit_length() - 1, N.bit_length() - 1
+    h = n - l
+    tr = Transcript(b"zkmi/tlookup-batch/v1" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little") + K.to_bytes(8, "little"))
+    out = b"ZKTB" + (1).to_bytes(4, "little") + D.to_bytes(8, "little") + N.to_bytes(8, "little") + K.to_bytes(8, "little")
+    ms = []
+    for S, T in zip(S_list, T_list):
+        first = {}
+        for j, t in enumerate(T):
+            first.setdefault(t, j)
+        m = [0] * N
+        for s in S:
+            m[first[s]] += 1
+        ms.append(m)
+        md = m_digest(m)
+        tr.absorb("m", md)
+        out += md
+    beta = tr.challenge("beta")
+    As = [[pow(beta + s, -1, R) for s in S] for S in S_list]
+    Bs = [[pow(beta + t, -1, R) for t in T] for T in T_list]
+    alpha = tr.challenge("alpha")
+    u = [tr.challenge("u") for _ in range(n)]
+    lam = tr.challenge("lambda")
+    scale = pow(pow(2, h, R), -1, R)
+
+    def f(w):
+        wt = w[h:]
+        total = 0
+        for k in range(K):
+            A, S, B, T, m = As[k], S_list[k], Bs[k], T_list[k], ms[k]
+            left = mle(A, w) * ((alpha * eq(u, w) % R) * ((mle(S, w) + beta) % R) + 1) % R
+            right = scale * mle(B, wt) % R * ((alpha * alpha % R) * eq(u[h:], wt) % R * ((mle(T, wt) + beta) % R) - mle(m, wt)) % R
+            total += pow(lam, k, R) * (left + right)
+        return total % R
+
+    v = []
+    first_claim = None
+    for k in range(n):
+        g = [round_poly(f, v, n, X) for X in range(4)]
+        if first_claim is None:
+            first_claim = (g[0] + g[1]) % R
+        msg = b"".join(fr_bytes(y) for y in g)
+        out += msg
+        tr.absorb("g", msg)
+        v.append(tr.challenge("r"))
+    vt = v[h:]
+    fin = b""
+    for k in range(K):
+        fin += b"".join(fr_bytes(y) for y in [mle(As[k], v), mle(S_list[k], v), mle(Bs[k], vt), mle(ms[k], vt), mle(T_list[k], vt)])
+    out += fin
+    return out, {"beta": beta, "alpha": alpha, "lambda": lam, "v": v, "first_claim": first_claim, "m": ms}
