@@ -205,6 +205,57 @@ size_t tlookup_verify_workspace_bytes(size_t D, size_t N);
 int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
                    const tlookup_witness* witness, tlookup_claims* claims, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- several tlookup instances under one sumcheck ---------------------------- */
+
+/* The paper proves each lookup of an attention layer on its own (Section 5.2,
+ * Protocol 2) and does not describe batching; this is the standard random
+ * linear combination applied to Protocol 1.  K instances (S_i, T_i) of one shape
+ * (D, N) share beta, alpha, u and all round challenges, and ONE sumcheck runs on
+ *   f = sum_i lambda^i f_i,   claim = (sum_i lambda^i)(alpha + alpha^2),
+ * f_i being the summand of tlookup_prove for instance i and lambda one more
+ * challenge.  It ends in 5 K claims: A_i~(v), S_i~(v), B_i~(v'), m_i~(v'), T_i~(v').
+ *
+ * Transcript: SHA256("zkmi/tlookup-batch/v1" || seed || LE64 D || LE64 N || LE64 K);
+ * absorb("m", digest(m_i)) for i = 0..K-1; beta, alpha, u_0..u_{n-1} as in
+ * tlookup_prove; lambda = challenge("lambda"); per round absorb("g", 4 values),
+ * r = challenge("r"); absorb("final", 5 K claims).
+ *
+ * Proof (host, tlookup_batch_proof_bytes(D, K) bytes):
+ *   "ZKTB" | u32 1 | LE64 D | LE64 N | LE64 K | K digests | n x 4 elements | K x 5 elements. */
+#define TLOOKUP_BATCH_MAX 8
+
+typedef struct {
+    fr_t beta, alpha, lambda;
+    fr_t sum_A[TLOOKUP_BATCH_MAX], sum_mB[TLOOKUP_BATCH_MAX]; /* per instance, as in tlookup_aux */
+    uint64_t bad_instance, bad_index; /* on ZK_E_NOT_IN_TABLE: first offending instance, smallest i in it */
+} tlookup_batch_aux;
+
+typedef struct {
+    fr_t value[TLOOKUP_BATCH_MAX][5]; /* per instance: A~(v), S~(v), B~(v'), m~(v'), T~(v') */
+    fr_t v[32];
+    fr_t lambda;
+    int nvars, count;
+} tlookup_batch_claims;
+
+/* S, T: host arrays of K descriptors of device vectors (all S_i of D elements,
+ * all T_i of N).  idx: NULL, or a host array of K device pointers, each NULL or
+ * the rows of that instance as in tlookup_multiplicities.  1 <= K <=
+ * TLOOKUP_BATCH_MAX.  ws: device, tlookup_batch_workspace_bytes(D, N, K) (K times
+ * the single-instance buffers; the weight tables are shared).  Other arguments
+ * and error behaviour as tlookup_prove.  Synchronises the stream. */
+size_t tlookup_batch_proof_bytes(size_t D, size_t K);
+size_t tlookup_batch_workspace_bytes(size_t D, size_t N, size_t K);
+int tlookup_prove_batch(const uint8_t seed[32], const fr_vec* S, const uint32_t* const* idx, const fr_vec* T, size_t K,
+                        uint8_t* proof, size_t cap, size_t* len, tlookup_batch_aux* aux, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/* Verifier of the batched proof.  witness: NULL or a host array of K entries
+ * (members may be empty, as in tlookup_verify).  ws: device,
+ * tlookup_verify_workspace_bytes(D, N). */
+int tlookup_verify_batch(const uint8_t seed[32], const uint8_t* proof, size_t len, const fr_vec* T, size_t K, size_t D,
+                         const tlookup_witness* witness, tlookup_batch_claims* claims, void* ws, size_t ws_bytes,
+                         void* stream);
+
 /* ---- product sumcheck and matrix multiplication (Sections 3.3, 6.1.1) -------- */
 
 /* Sumcheck of sum_{x in {0,1}^d} a(x) b(x) = claim over vectors of 2^d elements

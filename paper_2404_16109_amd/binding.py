@@ -36,6 +36,19 @@ class tlookup_claims(ctypes.Structure):
                 ("nvars", ctypes.c_int)]
 
 
+TLOOKUP_BATCH_MAX = 8
+
+
+class tlookup_batch_aux(ctypes.Structure):
+    _fields_ = [("beta", fr_t), ("alpha", fr_t), ("lambda_", fr_t), ("sum_A", fr_t * TLOOKUP_BATCH_MAX),
+                ("sum_mB", fr_t * TLOOKUP_BATCH_MAX), ("bad_instance", ctypes.c_uint64), ("bad_index", ctypes.c_uint64)]
+
+
+class tlookup_batch_claims(ctypes.Structure):
+    _fields_ = [("value", (fr_t * 5) * TLOOKUP_BATCH_MAX), ("v", fr_t * 32), ("lambda_", fr_t),
+                ("nvars", ctypes.c_int), ("count", ctypes.c_int)]
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -74,6 +87,12 @@ def _load():
         "tlookup_prove_with_beta": (i32, [vp, fr_vec, vp, fr_vec, P(fr_t), vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_verify_workspace_bytes": (sz, [sz, sz]),
         "tlookup_verify": (i32, [vp, vp, sz, fr_vec, sz, P(tlookup_witness), P(tlookup_claims), vp, sz, vp]),
+        "tlookup_batch_proof_bytes": (sz, [sz, sz]),
+        "tlookup_batch_workspace_bytes": (sz, [sz, sz, sz]),
+        "tlookup_prove_batch": (i32, [vp, P(fr_vec), P(vp), P(fr_vec), sz, vp, sz, P(sz), P(tlookup_batch_aux), vp, sz,
+                                      vp]),
+        "tlookup_verify_batch": (i32, [vp, vp, sz, P(fr_vec), sz, sz, P(tlookup_witness), P(tlookup_batch_claims), vp,
+                                       sz, vp]),
         "sumcheck_product_proof_bytes": (sz, [sz]),
         "sumcheck_product_workspace_bytes": (sz, [sz]),
         "sumcheck_prove_product": (i32, [vp, fr_vec, fr_vec, P(fr_t), vp, sz, P(sz), vp, sz, vp]),
@@ -97,6 +116,7 @@ EXPORTS = ["zkmi_version", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_pr
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
            "tlookup_prove_by_rows", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
+           "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
            "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove",
            "matmul_verify_workspace_bytes", "matmul_sumcheck_verify"]
@@ -329,6 +349,63 @@ def tlookup_verify(seed, proof, T, D, S=None, A=None, B=None, m=None, ws=None):
         out = {"A_v": _fr_int(claims.A_v), "S_v": _fr_int(claims.S_v), "B_vp": _fr_int(claims.B_vp),
                "m_vp": _fr_int(claims.m_vp), "T_vp": _fr_int(claims.T_vp),
                "v": [_fr_int(claims.v[t]) for t in range(claims.nvars)]}
+    return rc, out
+
+
+def tlookup_batch_proof_bytes(D, K):
+    return _lib.tlookup_batch_proof_bytes(D, K)
+
+
+def tlookup_batch_workspace_bytes(D, N, K):
+    return _lib.tlookup_batch_workspace_bytes(D, N, K)
+
+
+def tlookup_prove_batch(seed, S, idx, T, ws=None, cap=None):
+    """S, T: lists of K Vec; idx: None or a list of K (tensor or None).
+    Returns (rc, proof bytes, aux dict with 'len')."""
+    K = len(S)
+    assert len(T) == K and (idx is None or len(idx) == K)
+    D, N = S[0].n, T[0].n
+    ws = ws if ws is not None else _ws(tlookup_batch_workspace_bytes(D, N, K))
+    cap = tlookup_batch_proof_bytes(D, K) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    aux = tlookup_batch_aux()
+    Sv = (fr_vec * K)(*[s.c for s in S])
+    Tv = (fr_vec * K)(*[t.c for t in T])
+    Iv = None
+    if idx is not None:
+        Iv = (ctypes.c_void_p * K)(*[_idx_ptr(i) for i in idx])
+    rc = _lib.tlookup_prove_batch(_seed(seed), Sv, Iv, Tv, K, proof, cap, ctypes.byref(ln), ctypes.byref(aux),
+                                  ws.data_ptr(), ws.numel(), _stream())
+    info = {"beta": _fr_int(aux.beta), "alpha": _fr_int(aux.alpha), "lambda": _fr_int(aux.lambda_),
+            "sum_A": [_fr_int(aux.sum_A[i]) for i in range(min(K, TLOOKUP_BATCH_MAX))],
+            "sum_mB": [_fr_int(aux.sum_mB[i]) for i in range(min(K, TLOOKUP_BATCH_MAX))],
+            "bad_instance": int(aux.bad_instance), "bad_index": int(aux.bad_index), "len": ln.value}
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b"", info
+
+
+def tlookup_verify_batch(seed, proof, T, D, S=None, A=None, B=None, m=None, ws=None):
+    """T: list of K Vec; S, A, B, m: None or lists of K (entries may be None).
+    Returns (rc, claims dict)."""
+    K = len(T)
+    ws = ws if ws is not None else _ws(_lib.tlookup_verify_workspace_bytes(D, T[0].n))
+    Tv = (fr_vec * K)(*[t.c for t in T])
+    wit = None
+    if any(x is not None for x in (S, A, B, m)):
+        def member(lst, i):
+            return lst[i].c if lst is not None and lst[i] is not None else _EMPTY
+        wit = (tlookup_witness * K)(*[
+            tlookup_witness(member(S, i), member(A, i), member(B, i),
+                            m[i].data_ptr() if m is not None and m[i] is not None else None) for i in range(K)])
+    claims = tlookup_batch_claims()
+    pb = ctypes.create_string_buffer(bytes(proof), max(len(proof), 1))
+    rc = _lib.tlookup_verify_batch(_seed(seed), pb, len(proof), Tv, K, D, wit, ctypes.byref(claims), ws.data_ptr(),
+                                   ws.numel(), _stream())
+    out = {}
+    if rc == ZK_OK:
+        out = {"lambda": _fr_int(claims.lambda_), "v": [_fr_int(claims.v[t]) for t in range(claims.nvars)],
+               "value": [[_fr_int(claims.value[i][q]) for q in range(5)] for i in range(K)]}
     return rc, out
 
 

@@ -84,11 +84,15 @@ struct Mailbox {
         return seq;
     }
 };
-static const size_t kMailboxWords = 1024;
-static const size_t kMailboxFlag = 1016;    // the flag word
-static const size_t kMailboxInvB = 960;     // grand total of the table-side inversion
-static const size_t kMailboxInvA = 968;     // grand total of the data-side inversion
-static const size_t kMailboxTableC = 976;   // the two table-side constants
+static const size_t kMailboxWords = 2048;
+static const size_t kMailboxFlag = 2040;    // the flag word
+// A tlookup instance's round sums (eleven values) and final claims start at
+// kMailboxSlot * instance; up to eight instances share the mailbox.
+static const size_t kMailboxSlot = 96;
+static const size_t kMailboxMaxInstances = 8;
+static const size_t kMailboxInvB = 1024;    // grand total of the table-side inversion (+16 per instance)
+static const size_t kMailboxInvA = 1032;    // grand total of the data-side inversion (+16 per instance)
+static const size_t kMailboxTableC = 1280;  // the two table-side constants (+16 per instance)
 
 int mailbox_get(Mailbox** out);
 int mailbox_bulk(Mailbox* mb, size_t bytes);

@@ -106,7 +106,7 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
     f.p[0] = a; f.stride[0] = as; f.fold[0] = d >= 1;
     f.p[1] = b; f.stride[1] = bs; f.fold[1] = d >= 1;
     const uint32_t seq = mb->next_seq();
-    hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words, seq);
+    hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words, mb->words, seq);
     ZK_HIP_TRY(hipGetLastError());
     ZK_TRY(mailbox_wait(mb, seq, stream));
     ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device

@@ -180,12 +180,16 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     return ZK_OK;
 }
 
-static size_t prove_ws_bytes(size_t D, size_t N) {
+// K instances of one shape: their buffers, the shared weight tables, and the
+// scratch of the 2K inversions that are in flight together.
+static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
     Carver cv(nullptr, 0);
-    ProveWs w;
-    carve_prove(w, cv, D, N);
+    for (size_t i = 0; i < K; ++i) {
+        ProveWs w;
+        carve_prove(w, cv, D, N);
+    }
     cv.limbs(EqPool::entries(log2_floor(D)));
-    cv.take(batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N));
+    for (size_t i = 0; i < K; ++i) cv.take(batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N));
     return cv.used();
 }
 
@@ -245,98 +249,187 @@ static void digest_of_leaves(uint8_t out[32], const uint8_t* leaves, uint32_t nl
     h.finish(out);
 }
 
-// by_rows: form A as B[idx_i] instead of inverting beta + S_i (idx required).
-static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
-                      bool by_rows,
-                      uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
-                      void* stream_v) {
+// ---- prover --------------------------------------------------------------------------------------
+//
+// One routine proves K instances of a common shape with a single sumcheck over
+//   f = sum_i lambda^i f_i,   claim_0 = (sum_i lambda^i)(alpha + alpha^2),
+// f_i the tlookup summand of instance i; beta, alpha, u and the round challenges
+// are shared.  tlookup_prove is K = 1 without lambda and with its own transcript
+// label and proof header.  Per instance the device work is exactly that of a
+// single proof: every round launches the instance's kernels one after the other
+// on the stream, each instance's sums land in its own part of the mailbox, only
+// the last launch of a round publishes, and the host adds the instances' round
+// polynomials weighted by lambda^i.
+
+struct Instance {
+    ProveWs w;
+    fr_vec S, T;
+    const uint32_t* idx = nullptr;
+    uint32_t* b_cur = nullptr;  // where B lives at the moment (it ping-pongs while folding)
+    size_t b_cur_stride = 0;
+    uint32_t* words = nullptr;  // this instance's round sums in the mailbox
+    uint32_t* inv_words = nullptr;    // totals of its two inversions (B, then A)
+    uint32_t* const_words = nullptr;  // its two table-side constants
+    host::F c1, c2, cB, sum_A, lam;
+    uint8_t md[32];
+    BatchInverseJob job_a, job_b;
+};
+
+struct ProveCall {
+    const uint8_t* seed = nullptr;
+    size_t K = 1;
+    const fr_vec* S = nullptr;
+    const uint32_t* const* idx = nullptr;  // may be null, entries may be null
+    const fr_vec* T = nullptr;
+    bool batch = false;                    // batched transcript and proof layout
+    const fr_t* forced_beta = nullptr;
+    bool by_rows = false;                  // A as B[idx_i] instead of inverting beta + S_i
+    uint8_t* proof = nullptr;
+    size_t cap = 0;
+    size_t* len = nullptr;
+    tlookup_aux* aux = nullptr;            // single proof
+    tlookup_batch_aux* baux = nullptr;     // batched proof
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    void* stream = nullptr;
+};
+
+static size_t batch_proof_bytes(size_t D, size_t K) {
+    return 32 + 32 * K + (size_t)log2_floor(D ? D : 1) * 128 + 160 * K;
+}
+
+static int prove_core(const ProveCall& c) {
     using namespace host;
-    const size_t D = S.n, N = T.n;
-    if (!seed || !is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
-    if (!vec_ok(S, D) || !vec_ok(T, N)) return ZK_E_BADARG;
-    if (forced_beta && !canonical_in_range(*forced_beta)) return ZK_E_BADARG;
-    if (by_rows && !idx) return ZK_E_BADARG;
+    const size_t K = c.K;
+    if (!c.seed || !c.S || !c.T || K == 0 || K > kMailboxMaxInstances) return ZK_E_BADARG;
+    if (!c.batch && K != 1) return ZK_E_BADARG;
+    const size_t D = c.S[0].n, N = c.T[0].n;
+    if (!is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
+    for (size_t i = 0; i < K; ++i) {
+        if (c.S[i].n != D || c.T[i].n != N || !vec_ok(c.S[i], D) || !vec_ok(c.T[i], N)) return ZK_E_BADARG;
+        if (c.by_rows && !(c.idx && c.idx[i])) return ZK_E_BADARG;
+    }
+    if (c.forced_beta && !canonical_in_range(*c.forced_beta)) return ZK_E_BADARG;
     const int n = log2_floor(D), l = log2_floor(N), h = n - l;
-    const size_t need = tlookup_proof_bytes(D);
-    if (len) *len = need;
-    if (!proof || cap < need) return ZK_E_BUFSZ;
-    if (!ws || ws_bytes < prove_ws_bytes(D, N)) return ZK_E_BUFSZ;
-    hipStream_t stream = as_stream(stream_v);
+    const size_t need = c.batch ? batch_proof_bytes(D, K) : tlookup_proof_bytes(D);
+    if (c.len) *c.len = need;
+    if (!c.proof || c.cap < need) return ZK_E_BUFSZ;
+    if (!c.ws || c.ws_bytes < prove_ws_bytes(D, N, K)) return ZK_E_BUFSZ;
+    hipStream_t stream = as_stream(c.stream);
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
-    Carver cv(ws, ws_bytes);
-    ProveWs w;
-    carve_prove(w, cv, D, N);
+    Carver cv(c.ws, c.ws_bytes);
+    Instance inst[kMailboxMaxInstances];
+    for (size_t i = 0; i < K; ++i) {
+        Instance& I = inst[i];
+        carve_prove(I.w, cv, D, N);
+        I.S = c.S[i];
+        I.T = c.T[i];
+        I.idx = c.idx ? c.idx[i] : nullptr;
+        I.b_cur = I.w.B;
+        I.b_cur_stride = N;
+        I.words = mb->words + kMailboxSlot * i;
+        I.inv_words = mb->words + kMailboxInvB + 16 * i;
+        I.const_words = mb->words + kMailboxTableC + 16 * i;
+        I.c1 = I.c2 = I.cB = I.sum_A = zero();
+    }
     if (cv.overflow()) return ZK_E_BUFSZ;
 
     ProfileScope prof_total(kProfTotal, stream);
 
-    // -- Prep: multiplicities and their digest ------------------------------------
-    uint64_t bad = 0;
-    int rc;
-    {
-        ProfileScope prof(kProfCount, stream);
-        rc = count_rows(w, S, idx, T, D, N, &bad, mb, stream);
+    // -- Prep: multiplicities and their digests -------------------------------------------------
+    for (size_t i = 0; i < K; ++i) {
+        uint64_t bad = 0;
+        int rc;
+        {
+            ProfileScope prof(kProfCount, stream);
+            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, D, N, &bad, mb, stream);
+        }
+        if (rc == ZK_E_NOT_IN_TABLE) {
+            if (c.aux) c.aux->bad_index = bad;
+            if (c.baux) {
+                c.baux->bad_instance = i;
+                c.baux->bad_index = bad;
+            }
+        }
+        ZK_TRY(rc);
+        digest_of_leaves(inst[i].md, mb->bulk + 16, inst[i].w.nleaves);
     }
-    if (rc == ZK_E_NOT_IN_TABLE && aux) aux->bad_index = bad;
-    ZK_TRY(rc);
-    uint8_t md[32];
-    digest_of_leaves(md, mb->bulk + 16, w.nleaves);
 
-    uint64_t dims[2] = {D, N};
-    Transcript tr("zkmi/tlookup/v1", seed, dims, 2);
-    tr.absorb("m", md, 32);
+    uint64_t dims[3] = {D, N, K};
+    Transcript tr(c.batch ? "zkmi/tlookup-batch/v1" : "zkmi/tlookup/v1", c.seed, dims, c.batch ? 3 : 2);
+    for (size_t i = 0; i < K; ++i) tr.absorb("m", inst[i].md, 32);
 
-    // -- Prove: beta, inverse vectors ------------------------------------------------
+    // -- Prove: beta, inverse vectors ---------------------------------------------------------------
     F beta = tr.challenge("beta");
-    if (forced_beta) beta = from_canonical(*forced_beta);
-    hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.M, N, w.m, N);
-    if (!by_rows) {
-        // both inversions share one wait: down passes of B and A, one round trip,
-        // one host inversion (of the product of the two grand totals), up passes
+    if (c.forced_beta) beta = from_canonical(*c.forced_beta);
+    for (size_t i = 0; i < K; ++i)
+        hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, inst[i].w.M, N, inst[i].w.m, N);
+    if (!c.by_rows) {
+        // all inversions share one wait: the down passes of every B and A, one round
+        // trip, one host inversion (of the product of all grand totals), the up passes
         ProfileScope prof(kProfInverse, stream);
         Carver inv_cv = cv;
-        BatchInverseJob job_b, job_a;
-        uint32_t seq = mb->next_seq();
-        ZK_TRY(batch_inverse_begin(job_b, w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb->words + kMailboxInvB, mb->words,
-                                   0, stream));
-        ZK_TRY(batch_inverse_begin(job_a, w.A, D, S.limbs, S.stride, D, beta, inv_cv, mb->words + kMailboxInvA, mb->words,
-                                   seq, stream));
+        const uint32_t seq = mb->next_seq();
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            ZK_TRY(batch_inverse_begin(I.job_b, I.w.B, N, I.T.limbs, I.T.stride, N, beta, inv_cv, I.inv_words, mb->words, 0,
+                                       stream));
+            ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
+                                       mb->words, i + 1 == K ? seq : 0, stream));
+        }
         ZK_TRY(mailbox_wait(mb, seq, stream));
-        F total_b = from_dev(mb->words + kMailboxInvB), total_a = from_dev(mb->words + kMailboxInvA);
-        if (is_zero(total_b) || is_zero(total_a)) return ZK_E_ZERO_DENOM;
-        F inv_both = inv(mul(total_a, total_b));
-        ZK_TRY(batch_inverse_end(job_b, mul(inv_both, total_a), stream));
-        ZK_TRY(batch_inverse_end(job_a, mul(inv_both, total_b), stream));
+        // inverse of each total from one inversion of their product
+        F tot[2 * kMailboxMaxInstances], pre[2 * kMailboxMaxInstances + 1];
+        pre[0] = one();
+        for (size_t q = 0; q < 2 * K; ++q) {
+            tot[q] = from_dev(inst[q / 2].inv_words + 8 * (q & 1));
+            if (is_zero(tot[q])) return ZK_E_ZERO_DENOM;
+            pre[q + 1] = mul(pre[q], tot[q]);
+        }
+        F suffix_inv = inv(pre[2 * K]);  // 1 / (tot_0 ... tot_q) while walking down
+        for (size_t q = 2 * K; q-- > 0;) {
+            F inv_q = mul(suffix_inv, pre[q]);
+            suffix_inv = mul(suffix_inv, tot[q]);
+            ZK_TRY(batch_inverse_end((q & 1) ? inst[q / 2].job_a : inst[q / 2].job_b, inv_q, stream));
+        }
     } else {
         // every S_i has been checked to equal T[idx_i]: invert the table side only
         // and read A off it (a zero beta + S_i is a zero beta + T[idx_i])
         ProfileScope prof(kProfInverse, stream);
-        Carver inv_cv = cv;
-        ZK_TRY(batch_inverse_run(w.B, N, T.limbs, T.stride, N, beta, inv_cv, mb, stream));
-        hipLaunchKernelGGL(k_rows_of, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.rows, w.B, N, (uint32_t)N);
-        hipLaunchKernelGGL(k_gather_rows, dim3(grid_for(D, kBlock, 16384)), dim3(kBlock), 0, stream, w.A, D, D, idx, w.rows);
-        ZK_HIP_TRY(hipGetLastError());
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            Carver inv_cv = cv;
+            ZK_TRY(batch_inverse_run(I.w.B, N, I.T.limbs, I.T.stride, N, beta, inv_cv, mb, stream));
+            hipLaunchKernelGGL(k_rows_of, dim3(grid_for(N)), dim3(kBlock), 0, stream, I.w.rows, I.w.B, N, (uint32_t)N);
+            hipLaunchKernelGGL(k_gather_rows, dim3(grid_for(D, kBlock, 16384)), dim3(kBlock), 0, stream, I.w.A, D, D, I.idx,
+                               I.w.rows);
+            ZK_HIP_TRY(hipGetLastError());
+        }
     }
 
     F alpha = tr.challenge("alpha");
     F alpha2 = sqr(alpha);
     F u[32];
     for (int t = 0; t < n; ++t) u[t] = tr.challenge("u");
+    F lambda = one();
+    if (c.batch) lambda = tr.challenge("lambda");
+    inst[0].lam = one();
+    for (size_t i = 1; i < K; ++i) inst[i].lam = mul(inst[i - 1].lam, lambda);
 
     EqPool ep;
     ZK_TRY(eq_pool_build(ep, u, n, cv, stream));
 
-    // -- table-side constants -----------------------------------------------------------
+    // -- table-side constants ---------------------------------------------------------------------
     // c1 = sum_j e'_j B_j (T_j+beta), c2 = sum_j m_j B_j.  e' = e~(u_[h:], .) is the
     // weight table of "round h-1" (remaining variables h .. n-1); with h = 0 no
     // round needs the constant, only c2 is reported.
-    F c1 = zero(), c2 = zero();
-    {
+    for (size_t i = 0; i < K; ++i) {
+        Instance& I = inst[i];
         TableConstArgs a;
-        a.B = w.B; a.bs = N;
-        a.T = T.limbs; a.ts = T.stride;
-        a.M = w.M; a.ms = N;
+        a.B = I.w.B; a.bs = N;
+        a.T = I.T.limbs; a.ts = I.T.stride;
+        a.M = I.w.M; a.ms = N;
         a.N = N;
         a.beta = to_dev(beta);
         if (h >= 1) {
@@ -345,33 +438,42 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
             // weights unused for the reported sum; point at the one-entry table
             a.eq = EqSplit{ep.pool, ep.stride, ep.suffix_off[0], 0, 0, 0};
         }
-        a.partials = w.partT;
-        a.pstride = w.part_blocks * 6;
+        a.partials = I.w.partT;
+        a.pstride = I.w.part_blocks * 6;
         unsigned blocks = grid_for(N, kBlock * 4, kMaxPartialBlocks);
         hipLaunchKernelGGL(k_table_const, dim3(blocks), dim3(kBlock), 0, stream, a);
         // read back together with the first round's sums (or the final values)
-        launch_final_sum(w.partT, a.pstride, blocks, 2, mb->words + kMailboxTableC, mb->words, 0, w.flags + 1, stream);
+        launch_final_sum(I.w.partT, a.pstride, blocks, 2, I.const_words, mb->words, 0, I.w.flags + 1, stream);
         ZK_HIP_TRY(hipGetLastError());
     }
     bool table_consts_read = false;
     auto read_table_consts = [&]() {
         if (table_consts_read) return;
-        c1 = from_dev(mb->words + kMailboxTableC);
-        c2 = from_dev(mb->words + kMailboxTableC + 8);
+        for (size_t i = 0; i < K; ++i) {
+            inst[i].c1 = from_dev(inst[i].const_words);
+            inst[i].c2 = from_dev(inst[i].const_words + 8);
+            inst[i].cB = sub(mul(alpha2, inst[i].c1), inst[i].c2);
+        }
         table_consts_read = true;
     };
-    F cB = zero();
 
-    // -- header ------------------------------------------------------------------------------
-    uint8_t* out = proof;
-    memcpy(out, "ZKTL", 4);
+    // -- header -----------------------------------------------------------------------------------------
+    uint8_t* out = c.proof;
+    memcpy(out, c.batch ? "ZKTB" : "ZKTL", 4);
     out[4] = 1; out[5] = out[6] = out[7] = 0;
     put_le64(out + 8, D);
     put_le64(out + 16, N);
-    memcpy(out + 24, md, 32);
-    out += 56;
+    out += 24;
+    if (c.batch) {
+        put_le64(out, K);
+        out += 8;
+    }
+    for (size_t i = 0; i < K; ++i) {
+        memcpy(out, inst[i].md, 32);
+        out += 32;
+    }
 
-    // -- rounds ------------------------------------------------------------------------------
+    // -- rounds -----------------------------------------------------------------------------------------
     F scale = one();  // 2^-h
     {
         F half = inv(from_u64(2));
@@ -381,9 +483,6 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
     F half_pow = one();       // 2^-(k+1) in round k
     F cD = one(), cT = one();  // products of e~(u_t, r_t) over bound variables
     F r_prev = zero();
-    F sum_A = zero();
-    uint32_t* b_cur = w.B;
-    size_t b_cur_stride = N;
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
         const EqSplit eq = ep.round(k);
@@ -396,103 +495,115 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         if (eq.has_hi && span > ((size_t)1 << eq.lbits)) span = (size_t)1 << eq.lbits;
         if (span > half) span = half;
         const unsigned blocks = (unsigned)(half / span);
-        if (blocks > w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
-
-        DataRoundArgs d;
-        d.A = PairArray{w.A, D, w.A, D};
-        if (k <= 1) d.S = PairArray{S.limbs, S.stride, w.Sf, D / 2};
-        else d.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
-        d.half = half;
-        d.block_span = span;
-        d.r_prev = to_dev(r_prev);
-        d.beta = to_dev(beta);
-        d.eq = eq;
-        d.partials = w.partD;
-        d.pstride = w.part_blocks * 5;
-        TableRoundArgs t;
-        // B alternates between its two buffers on every fold (it has two readers)
-        if (k > h) {
-            uint32_t* other = b_cur == w.B ? w.Bf : w.B;
-            size_t other_stride = b_cur == w.B ? N / 2 : N;
-            t.B = PairArray{b_cur, b_cur_stride, other, other_stride};
-        } else {
-            t.B = PairArray{b_cur, b_cur_stride, b_cur, b_cur_stride};
-        }
-        if (k <= h + 1) t.T = PairArray{T.limbs, T.stride, w.Tf, N / 2};
-        else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
-        t.M = PairArray{w.M, N, w.M, N};
-        t.half = half;
-        t.block_span = span;
-        t.r_prev = d.r_prev;
-        t.beta = d.beta;
-        t.eq = eq;
-        t.partials = w.partT;
-        t.pstride = w.part_blocks * 6;
+        if (blocks > inst[0].w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
 
         const uint32_t seq = mb->next_seq();
-        if (small) {
-            // one workgroup, one launch, sums straight to the host
-            ProfileScope prof(kProfRoundData, stream);
-            if (!table_round)
-                hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words, seq);
-            else if (k == h)
-                hipLaunchKernelGGL(k_round_small<1>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words, seq);
-            else
-                hipLaunchKernelGGL(k_round_small<2>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, mb->words, seq);
-        } else if (table_round && k > 0) {
-            {
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            ProveWs& w = I.w;
+            const uint32_t my_seq = i + 1 == K ? seq : 0;  // the last instance's last launch publishes the round
+            DataRoundArgs d;
+            d.A = PairArray{w.A, D, w.A, D};
+            if (k <= 1) d.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
+            else d.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
+            d.half = half;
+            d.block_span = span;
+            d.r_prev = to_dev(r_prev);
+            d.beta = to_dev(beta);
+            d.eq = eq;
+            d.partials = w.partD;
+            d.pstride = w.part_blocks * 5;
+            TableRoundArgs t;
+            // B alternates between its two buffers on every fold (it has two readers)
+            if (k > h) {
+                uint32_t* other = I.b_cur == w.B ? w.Bf : w.B;
+                size_t other_stride = I.b_cur == w.B ? N / 2 : N;
+                t.B = PairArray{I.b_cur, I.b_cur_stride, other, other_stride};
+            } else {
+                t.B = PairArray{I.b_cur, I.b_cur_stride, I.b_cur, I.b_cur_stride};
+            }
+            if (k <= h + 1) t.T = PairArray{I.T.limbs, I.T.stride, w.Tf, N / 2};
+            else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
+            t.M = PairArray{w.M, N, w.M, N};
+            t.half = half;
+            t.block_span = span;
+            t.r_prev = d.r_prev;
+            t.beta = d.beta;
+            t.eq = eq;
+            t.partials = w.partT;
+            t.pstride = w.part_blocks * 6;
+
+            if (small) {
+                // one workgroup, one launch, sums straight to the host
                 ProfileScope prof(kProfRoundData, stream);
-                if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
-                else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
+                if (!table_round)
+                    hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
+                                       my_seq);
+                else if (k == h)
+                    hipLaunchKernelGGL(k_round_small<1>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
+                                       my_seq);
+                else
+                    hipLaunchKernelGGL(k_round_small<2>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
+                                       my_seq);
+            } else if (table_round && k > 0) {
+                {
+                    ProfileScope prof(kProfRoundData, stream);
+                    if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
+                    else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
+                }
+                launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, I.words, mb->words, my_seq,
+                                  w.flags + 1, stream);
+            } else {
+                {
+                    ProfileScope prof(kProfRoundData, stream);
+                    if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
+                    else hipLaunchKernelGGL(k_round_data<false>, dim3(blocks), dim3(kBlock), 0, stream, d);
+                }
+                if (table_round) {  // only with k == 0, i.e. D == N
+                    ProfileScope prof(kProfRoundTable, stream);
+                    hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
+                }
+                launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, table_round ? 6 : 0, blocks, I.words,
+                                  mb->words, my_seq, w.flags + 1, stream);
             }
-            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, mb->words, mb->words, seq, w.flags + 1,
-                              stream);
-        } else {
-            {
-                ProfileScope prof(kProfRoundData, stream);
-                if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
-                else hipLaunchKernelGGL(k_round_data<false>, dim3(blocks), dim3(kBlock), 0, stream, d);
+            ZK_HIP_TRY(hipGetLastError());
+            if (k > h) {
+                I.b_cur = t.B.dst;
+                I.b_cur_stride = t.B.ds;
             }
-            if (table_round) {  // only with k == 0, i.e. D == N
-                ProfileScope prof(kProfRoundTable, stream);
-                hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
-            }
-            launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, table_round ? 6 : 0, blocks, mb->words,
-                              mb->words, seq, w.flags + 1, stream);
-        }
-        ZK_HIP_TRY(hipGetLastError());
-        if (k > h) {
-            b_cur = t.B.dst;
-            b_cur_stride = t.B.ds;
         }
         ZK_TRY(mailbox_wait(mb, seq, stream));
         read_table_consts();
-        cB = sub(mul(alpha2, c1), c2);
 
-        F q0 = from_dev(mb->words), q1 = from_dev(mb->words + 8), qi = from_dev(mb->words + 16);
-        if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
-        F sA0 = from_dev(mb->words + 24), sA1 = from_dev(mb->words + 32);
-        if (k == 0) sum_A = add(sA0, sA1);
-        F e[4], q[4], sa[4], g[4];
+        F e[4], g[4];
         line_values(e, sub(one(), u[k]), u[k]);
-        quad_values(q, q0, q1, qi);
-        line_values(sa, sA0, sA1);
-        F wD = mul(alpha, cD);
+        const F wD = mul(alpha, cD);
+        const F wT = table_round ? mul(alpha2, cT) : zero();
         half_pow = mul(half_pow, inv2);
-        F tq[4], tm[4];
-        F wT = zero();
-        if (table_round) {
-            quad_values(tq, from_dev(mb->words + 40), from_dev(mb->words + 48), from_dev(mb->words + 56));
-            quad_values(tm, from_dev(mb->words + 64), from_dev(mb->words + 72), from_dev(mb->words + 80));
-            wT = mul(alpha2, cT);
+        for (int X = 0; X < 4; ++X) g[X] = zero();
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            const uint32_t* sums = I.words;
+            F q0 = from_dev(sums), q1 = from_dev(sums + 8), qi = from_dev(sums + 16);
+            if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
+            F sA0 = from_dev(sums + 24), sA1 = from_dev(sums + 32);
+            if (k == 0) I.sum_A = add(sA0, sA1);
+            F q[4], sa[4], tq[4], tm[4];
+            quad_values(q, q0, q1, qi);
+            line_values(sa, sA0, sA1);
+            if (table_round) {
+                quad_values(tq, from_dev(sums + 40), from_dev(sums + 48), from_dev(sums + 56));
+                quad_values(tm, from_dev(sums + 64), from_dev(sums + 72), from_dev(sums + 80));
+            }
+            const F table_const = mul(I.cB, half_pow);
+            for (int X = 0; X < 4; ++X) {
+                F data = add(mul(mul(wD, e[X]), q[X]), sa[X]);
+                F table = table_round ? mul(scale, sub(mul(mul(wT, e[X]), tq[X]), tm[X])) : table_const;
+                F f = add(data, table);
+                g[X] = add(g[X], K == 1 ? f : mul(I.lam, f));
+            }
         }
-        F table_const = mul(cB, half_pow);
-        for (int X = 0; X < 4; ++X) {
-            F data = add(mul(mul(wD, e[X]), q[X]), sa[X]);
-            F table = table_round ? mul(scale, sub(mul(mul(wT, e[X]), tq[X]), tm[X])) : table_const;
-            g[X] = add(data, table);
-            to_bytes(out + 32 * X, g[X]);
-        }
+        for (int X = 0; X < 4; ++X) to_bytes(out + 32 * X, g[X]);
         tr.absorb("g", out, 128);
         out += 128;
         F r = tr.challenge("r");
@@ -502,42 +613,59 @@ static int prove_impl(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_
         r_prev = r;
     }
 
-    // -- final claims --------------------------------------------------------------------------
+    // -- final claims -------------------------------------------------------------------------------------
     {
-        FinalArgs f;
-        f.count = 5;
-        f.r = to_dev(r_prev);
-        const bool d_fold = n >= 1, t_fold = l >= 1;
-        // A, S, B, m, T in the order of the proof
-        f.p[0] = w.A; f.stride[0] = D; f.fold[0] = d_fold;
-        if (n <= 1) { f.p[1] = S.limbs; f.stride[1] = S.stride; }
-        else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
-        f.fold[1] = d_fold;
-        f.p[2] = b_cur; f.stride[2] = b_cur_stride; f.fold[2] = t_fold;
-        f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
-        if (l <= 1) { f.p[4] = T.limbs; f.stride[4] = T.stride; }
-        else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
-        f.fold[4] = t_fold;
         const uint32_t seq = mb->next_seq();
-        hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, mb->words, seq);
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            ProveWs& w = I.w;
+            FinalArgs f;
+            f.count = 5;
+            f.r = to_dev(r_prev);
+            const bool d_fold = n >= 1, t_fold = l >= 1;
+            // A, S, B, m, T in the order of the proof
+            f.p[0] = w.A; f.stride[0] = D; f.fold[0] = d_fold;
+            if (n <= 1) { f.p[1] = I.S.limbs; f.stride[1] = I.S.stride; }
+            else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
+            f.fold[1] = d_fold;
+            f.p[2] = I.b_cur; f.stride[2] = I.b_cur_stride; f.fold[2] = t_fold;
+            f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
+            if (l <= 1) { f.p[4] = I.T.limbs; f.stride[4] = I.T.stride; }
+            else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
+            f.fold[4] = t_fold;
+            hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, I.words, mb->words, i + 1 == K ? seq : 0);
+        }
         ZK_HIP_TRY(hipGetLastError());
         ZK_TRY(mailbox_wait(mb, seq, stream));
         ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device
         read_table_consts();
-        F fin[5];
-        for (int i = 0; i < 5; ++i) {
-            fin[i] = from_dev(mb->words + 8 * i);
-            to_bytes(out + 32 * i, fin[i]);
+        uint8_t* first = out;
+        for (size_t i = 0; i < K; ++i) {
+            for (int q = 0; q < 5; ++q) {
+                F v = from_dev(inst[i].words + 8 * q);
+                if (q == 0 && n == 0) inst[i].sum_A = v;
+                to_bytes(out, v);
+                out += 32;
+            }
         }
-        tr.absorb("final", out, 160);
-        if (n == 0) sum_A = fin[0];
+        tr.absorb("final", first, 160 * K);
     }
-    if (aux) {
-        aux->beta = to_canonical(beta);
-        aux->alpha = to_canonical(alpha);
-        aux->sum_A = to_canonical(sum_A);
-        aux->sum_mB = to_canonical(c2);
-        aux->bad_index = 0;
+    if (c.aux) {
+        c.aux->beta = to_canonical(beta);
+        c.aux->alpha = to_canonical(alpha);
+        c.aux->sum_A = to_canonical(inst[0].sum_A);
+        c.aux->sum_mB = to_canonical(inst[0].c2);
+        c.aux->bad_index = 0;
+    }
+    if (c.baux) {
+        memset(c.baux, 0, sizeof *c.baux);
+        c.baux->beta = to_canonical(beta);
+        c.baux->alpha = to_canonical(alpha);
+        c.baux->lambda = to_canonical(lambda);
+        for (size_t i = 0; i < K; ++i) {
+            c.baux->sum_A[i] = to_canonical(inst[i].sum_A);
+            c.baux->sum_mB[i] = to_canonical(inst[i].c2);
+        }
     }
     return ZK_OK;
 }
@@ -552,32 +680,67 @@ static size_t verify_ws_bytes(size_t D, size_t N) {
     return cv.used();
 }
 
-static int verify_impl(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
-                       const tlookup_witness* wit, tlookup_claims* claims, void* ws, size_t ws_bytes, void* stream_v) {
+struct VerifyCall {
+    const uint8_t* seed = nullptr;
+    const uint8_t* proof = nullptr;
+    size_t len = 0;
+    size_t K = 1;
+    const fr_vec* T = nullptr;
+    size_t D = 0;
+    bool batch = false;
+    const tlookup_witness* wit = nullptr;  // K entries, or null
+    tlookup_claims* claims = nullptr;      // single proof
+    tlookup_batch_claims* bclaims = nullptr;
+    void* ws = nullptr;
+    size_t ws_bytes = 0;
+    void* stream = nullptr;
+};
+
+static int verify_core(const VerifyCall& c) {
     using namespace host;
-    const size_t N = T.n;
-    if (!seed || !proof || !is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31) || !vec_ok(T, N))
-        return ZK_E_BADARG;
-    if (!ws || ws_bytes < verify_ws_bytes(D, N)) return ZK_E_BUFSZ;
+    const size_t K = c.K, D = c.D;
+    if (!c.seed || !c.proof || !c.T || K == 0 || K > kMailboxMaxInstances || (!c.batch && K != 1)) return ZK_E_BADARG;
+    const size_t N = c.T[0].n;
+    if (!is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
+    for (size_t i = 0; i < K; ++i)
+        if (c.T[i].n != N || !vec_ok(c.T[i], N)) return ZK_E_BADARG;
+    if (!c.ws || c.ws_bytes < verify_ws_bytes(D, N)) return ZK_E_BUFSZ;
     const int n = log2_floor(D), l = log2_floor(N), h = n - l;
-    if (len != tlookup_proof_bytes(D)) return ZK_E_REJECT;
-    if (memcmp(proof, "ZKTL\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
-    if (get_le64(proof + 8) != D || get_le64(proof + 16) != N) return ZK_E_REJECT;
-    const uint8_t* body = proof + 56;
-    F el[4 * 32 + 5];
-    const int nel = 4 * n + 5;
+    const uint8_t* proof = c.proof;
+    const uint8_t* digests;
+    if (c.batch) {
+        if (c.len != batch_proof_bytes(D, K)) return ZK_E_REJECT;
+        if (memcmp(proof, "ZKTB\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
+        if (get_le64(proof + 8) != D || get_le64(proof + 16) != N || get_le64(proof + 24) != K) return ZK_E_REJECT;
+        digests = proof + 32;
+    } else {
+        if (c.len != tlookup_proof_bytes(D)) return ZK_E_REJECT;
+        if (memcmp(proof, "ZKTL\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
+        if (get_le64(proof + 8) != D || get_le64(proof + 16) != N) return ZK_E_REJECT;
+        digests = proof + 24;
+    }
+    const uint8_t* body = digests + 32 * K;
+    F el[4 * 32 + 5 * kMailboxMaxInstances];
+    const int nel = 4 * n + 5 * (int)K;
     for (int i = 0; i < nel; ++i)
         if (!from_bytes(&el[i], body + 32 * i)) return ZK_E_REJECT;
 
-    uint64_t dims[2] = {D, N};
-    Transcript tr("zkmi/tlookup/v1", seed, dims, 2);
-    tr.absorb("m", proof + 24, 32);
+    uint64_t dims[3] = {D, N, K};
+    Transcript tr(c.batch ? "zkmi/tlookup-batch/v1" : "zkmi/tlookup/v1", c.seed, dims, c.batch ? 3 : 2);
+    for (size_t i = 0; i < K; ++i) tr.absorb("m", digests + 32 * i, 32);
     F beta = tr.challenge("beta");
     F alpha = tr.challenge("alpha");
     F alpha2 = sqr(alpha);
     F u[32], v[32];
     for (int t = 0; t < n; ++t) u[t] = tr.challenge("u");
-    F claim = add(alpha, alpha2);
+    F lambda = one();
+    if (c.batch) lambda = tr.challenge("lambda");
+    F lam[kMailboxMaxInstances], lam_sum = zero();
+    for (size_t i = 0; i < K; ++i) {
+        lam[i] = i == 0 ? one() : mul(lam[i - 1], lambda);
+        lam_sum = add(lam_sum, lam[i]);
+    }
+    F claim = mul(lam_sum, add(alpha, alpha2));
     for (int k = 0; k < n; ++k) {
         const F* g = &el[4 * k];
         if (!equal(add(g[0], g[1]), claim)) return ZK_E_REJECT;
@@ -586,22 +749,27 @@ static int verify_impl(const uint8_t seed[32], const uint8_t* proof, size_t len,
         claim = interpolate_at(g, 4, v[k]);
     }
     const F* fin = &el[4 * n];
-    tr.absorb("final", body + 128 * n, 160);
+    tr.absorb("final", body + 128 * n, 160 * K);
     F scale = one();
     {
         F half = inv(from_u64(2));
         for (int i = 0; i < h; ++i) scale = mul(scale, half);
     }
     F e_full = eq_point(u, v, n), e_tab = eq_point(u + h, v + h, l);
-    F lhs = mul(fin[0], add(mul(mul(alpha, e_full), add(fin[1], beta)), one()));
-    F rhs = mul(scale, mul(fin[2], sub(mul(mul(alpha2, e_tab), add(fin[4], beta)), fin[3])));
-    if (!equal(add(lhs, rhs), claim)) return ZK_E_REJECT;
+    F total = zero();
+    for (size_t i = 0; i < K; ++i) {
+        const F* f = fin + 5 * i;
+        F lhs = mul(f[0], add(mul(mul(alpha, e_full), add(f[1], beta)), one()));
+        F rhs = mul(scale, mul(f[2], sub(mul(mul(alpha2, e_tab), add(f[4], beta)), f[3])));
+        total = add(total, mul(lam[i], add(lhs, rhs)));
+    }
+    if (!equal(total, claim)) return ZK_E_REJECT;
 
     // claims against tensors
-    hipStream_t stream = as_stream(stream_v);
+    hipStream_t stream = as_stream(c.stream);
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
-    Carver cv(ws, ws_bytes);
+    Carver cv(c.ws, c.ws_bytes);
     uint32_t* Mfr = cv.limbs(N);
     uint32_t nleaves = (uint32_t)div_up(N, kLeafCounts);
     uint32_t* leaves = (uint32_t*)cv.take((size_t)nleaves * 32);
@@ -614,23 +782,26 @@ static int verify_impl(const uint8_t seed[32], const uint8_t* proof, size_t len,
         *ok = equal(from_dev(mb->words), want) ? 1 : 0;
         return ZK_OK;
     };
-    int ok = 0;
-    ZK_TRY(check(T.limbs, T.stride, l, v + h, fin[4], &ok));
-    if (!ok) return ZK_E_REJECT;
-    if (wit) {
+    for (size_t i = 0; i < K; ++i) {
+        const F* f = fin + 5 * i;
+        int ok = 0;
+        ZK_TRY(check(c.T[i].limbs, c.T[i].stride, l, v + h, f[4], &ok));
+        if (!ok) return ZK_E_REJECT;
+        if (!c.wit) continue;
+        const tlookup_witness* wit = c.wit + i;
         if (wit->S.limbs) {
             if (!vec_ok(wit->S, D)) return ZK_E_BADARG;
-            ZK_TRY(check(wit->S.limbs, wit->S.stride, n, v, fin[1], &ok));
+            ZK_TRY(check(wit->S.limbs, wit->S.stride, n, v, f[1], &ok));
             if (!ok) return ZK_E_REJECT;
         }
         if (wit->A.limbs) {
             if (!vec_ok(wit->A, D)) return ZK_E_BADARG;
-            ZK_TRY(check(wit->A.limbs, wit->A.stride, n, v, fin[0], &ok));
+            ZK_TRY(check(wit->A.limbs, wit->A.stride, n, v, f[0], &ok));
             if (!ok) return ZK_E_REJECT;
         }
         if (wit->B.limbs) {
             if (!vec_ok(wit->B, N)) return ZK_E_BADARG;
-            ZK_TRY(check(wit->B.limbs, wit->B.stride, l, v + h, fin[2], &ok));
+            ZK_TRY(check(wit->B.limbs, wit->B.stride, l, v + h, f[2], &ok));
             if (!ok) return ZK_E_REJECT;
         }
         if (wit->m) {
@@ -639,22 +810,31 @@ static int verify_impl(const uint8_t seed[32], const uint8_t* proof, size_t len,
                                (uint32_t)N, nleaves);
             ZK_TRY(mailbox_bulk(mb, (size_t)nleaves * 32));
             ZK_HIP_TRY(hipMemcpyAsync(mb->bulk, leaves, (size_t)nleaves * 32, hipMemcpyDeviceToHost, stream));
-            ZK_TRY(check(Mfr, N, l, v + h, fin[3], &ok));
+            ZK_TRY(check(Mfr, N, l, v + h, f[3], &ok));
             if (!ok) return ZK_E_REJECT;
             uint8_t md[32];
             digest_of_leaves(md, mb->bulk, nleaves);
-            if (memcmp(md, proof + 24, 32) != 0) return ZK_E_REJECT;
+            if (memcmp(md, digests + 32 * i, 32) != 0) return ZK_E_REJECT;
         }
     }
-    if (claims) {
-        memset(claims, 0, sizeof *claims);
-        claims->A_v = to_canonical(fin[0]);
-        claims->S_v = to_canonical(fin[1]);
-        claims->B_vp = to_canonical(fin[2]);
-        claims->m_vp = to_canonical(fin[3]);
-        claims->T_vp = to_canonical(fin[4]);
-        claims->nvars = n;
-        for (int t = 0; t < n; ++t) claims->v[t] = to_canonical(v[t]);
+    if (c.claims) {
+        memset(c.claims, 0, sizeof *c.claims);
+        c.claims->A_v = to_canonical(fin[0]);
+        c.claims->S_v = to_canonical(fin[1]);
+        c.claims->B_vp = to_canonical(fin[2]);
+        c.claims->m_vp = to_canonical(fin[3]);
+        c.claims->T_vp = to_canonical(fin[4]);
+        c.claims->nvars = n;
+        for (int t = 0; t < n; ++t) c.claims->v[t] = to_canonical(v[t]);
+    }
+    if (c.bclaims) {
+        memset(c.bclaims, 0, sizeof *c.bclaims);
+        c.bclaims->nvars = n;
+        c.bclaims->count = (int)K;
+        c.bclaims->lambda = to_canonical(lambda);
+        for (int t = 0; t < n; ++t) c.bclaims->v[t] = to_canonical(v[t]);
+        for (size_t i = 0; i < K; ++i)
+            for (int q = 0; q < 5; ++q) c.bclaims->value[i][q] = to_canonical(fin[5 * i + q]);
     }
     return ZK_OK;
 }
@@ -689,22 +869,43 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
     return ZK_OK;
 }
 
+static int prove_single(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
+                        bool by_rows, uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws,
+                        size_t ws_bytes, void* stream) {
+    ProveCall c;
+    c.seed = seed;
+    c.K = 1;
+    c.S = &S;
+    c.idx = &idx;
+    c.T = &T;
+    c.forced_beta = forced_beta;
+    c.by_rows = by_rows;
+    c.proof = proof;
+    c.cap = cap;
+    c.len = len;
+    c.aux = aux;
+    c.ws = ws;
+    c.ws_bytes = ws_bytes;
+    c.stream = stream;
+    return prove_core(c);
+}
+
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
-    return prove_impl(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, ws_bytes, stream);
+    return prove_single(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, ws_bytes, stream);
 }
 
 int tlookup_prove_by_rows(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                           size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
     if (!idx) return ZK_E_BADARG;
-    return prove_impl(seed, S, idx, T, nullptr, true, proof, cap, len, aux, ws, ws_bytes, stream);
+    return prove_single(seed, S, idx, T, nullptr, true, proof, cap, len, aux, ws, ws_bytes, stream);
 }
 
 int tlookup_prove_with_beta(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
                             uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes,
                             void* stream) {
     if (!forced_beta) return ZK_E_BADARG;
-    return prove_impl(seed, S, idx, T, forced_beta, false, proof, cap, len, aux, ws, ws_bytes, stream);
+    return prove_single(seed, S, idx, T, forced_beta, false, proof, cap, len, aux, ws, ws_bytes, stream);
 }
 
 size_t tlookup_verify_workspace_bytes(size_t D, size_t N) {
@@ -714,7 +915,65 @@ size_t tlookup_verify_workspace_bytes(size_t D, size_t N) {
 
 int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
                    const tlookup_witness* witness, tlookup_claims* claims, void* ws, size_t ws_bytes, void* stream) {
-    return verify_impl(seed, proof, len, T, D, witness, claims, ws, ws_bytes, stream);
+    VerifyCall c;
+    c.seed = seed;
+    c.proof = proof;
+    c.len = len;
+    c.K = 1;
+    c.T = &T;
+    c.D = D;
+    c.wit = witness;
+    c.claims = claims;
+    c.ws = ws;
+    c.ws_bytes = ws_bytes;
+    c.stream = stream;
+    return verify_core(c);
+}
+
+size_t tlookup_batch_proof_bytes(size_t D, size_t K) { return batch_proof_bytes(D, K); }
+
+size_t tlookup_batch_workspace_bytes(size_t D, size_t N, size_t K) {
+    if (!is_pow2(D) || !is_pow2(N) || N > D || K == 0 || K > TLOOKUP_BATCH_MAX) return 0;
+    return prove_ws_bytes(D, N, K);
+}
+
+int tlookup_prove_batch(const uint8_t seed[32], const fr_vec* S, const uint32_t* const* idx, const fr_vec* T, size_t K,
+                        uint8_t* proof, size_t cap, size_t* len, tlookup_batch_aux* aux, void* ws, size_t ws_bytes,
+                        void* stream) {
+    ProveCall c;
+    c.seed = seed;
+    c.K = K;
+    c.S = S;
+    c.idx = idx;
+    c.T = T;
+    c.batch = true;
+    c.proof = proof;
+    c.cap = cap;
+    c.len = len;
+    c.baux = aux;
+    c.ws = ws;
+    c.ws_bytes = ws_bytes;
+    c.stream = stream;
+    return prove_core(c);
+}
+
+int tlookup_verify_batch(const uint8_t seed[32], const uint8_t* proof, size_t len, const fr_vec* T, size_t K, size_t D,
+                         const tlookup_witness* witness, tlookup_batch_claims* claims, void* ws, size_t ws_bytes,
+                         void* stream) {
+    VerifyCall c;
+    c.seed = seed;
+    c.proof = proof;
+    c.len = len;
+    c.K = K;
+    c.T = T;
+    c.D = D;
+    c.batch = true;
+    c.wit = witness;
+    c.bclaims = claims;
+    c.ws = ws;
+    c.ws_bytes = ws_bytes;
+    c.stream = stream;
+    return verify_core(c);
 }
 
 }  // extern "C"

@@ -658,15 +658,16 @@ static __global__ void __launch_bounds__(kBlock) k_round_both(DataRoundArgs d, T
 // The last rounds (at most 256 pairs): one workgroup does the whole round, data
 // pairs on threads 0..255, the T sums of the table side on threads 256..511 and
 // its m sums on threads 512..767, and writes the eleven sums straight to
-// out_words (value q at words 8q..8q+7, data sums first), so the round costs a
-// single launch.  TABLE: 0 = the table is not being bound yet, 1 = first table
+// out_words (value q at words 8q..8q+7, data sums first; `words` is the mailbox
+// the flag lives in), so the round costs a single launch.  TABLE: 0 = the table is not being bound yet, 1 = first table
 // round (nothing to fold), 2 = fold.
 static const int kSmallThreads = 768;
 static const size_t kSmallPairs = 256;
 
 template <int TABLE>
 static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundArgs d, TableRoundArgs t,
-                                                                     uint32_t* out_words, uint32_t seq) {
+                                                                     uint32_t* out_words, uint32_t* words,
+                                                                     uint32_t seq) {
     __shared__ uint32_t lds[12 * 6 * 8];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int group = threadIdx.x >> 8;  // 0 data, 1 table T sums, 2 table m sums
@@ -716,7 +717,7 @@ static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundA
         mailbox_written();
     }
     __syncthreads();
-    if (threadIdx.x == 0) mailbox_publish(out_words, seq);
+    if (threadIdx.x == 0) mailbox_publish(words, seq);
 }
 
 // Sums over the whole table, before any of its variables is bound:
@@ -752,7 +753,8 @@ static __global__ void __launch_bounds__(kBlock) k_table_const(TableConstArgs g)
 }
 
 // Final values: each of up to five arrays is either a single entry or a pair
-// still to be bound to the last challenge.  Value q goes to out_words[8q..8q+8).
+// still to be bound to the last challenge.  Value q goes to out_words[8q..8q+8);
+// `words` is the mailbox the flag lives in.
 struct FinalArgs {
     const uint32_t* p[5];
     size_t stride[5];
@@ -761,7 +763,7 @@ struct FinalArgs {
     Fr r;
 };
 
-static __global__ void k_final_values(FinalArgs g, uint32_t* out_words, uint32_t seq) {
+static __global__ void k_final_values(FinalArgs g, uint32_t* out_words, uint32_t* words, uint32_t seq) {
     int q = threadIdx.x;
     if (q < g.count) {
         Fr v = fr_load(g.p[q], g.stride[q], 0);
@@ -771,7 +773,7 @@ static __global__ void k_final_values(FinalArgs g, uint32_t* out_words, uint32_t
         mailbox_written();
     }
     __syncthreads();
-    if (threadIdx.x == 0) mailbox_publish(out_words, seq);
+    if (threadIdx.x == 0) mailbox_publish(words, seq);
 }
 
 }  // namespace zkmi

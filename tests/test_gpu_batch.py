@@ -1,0 +1,228 @@
+"""GPU parity: several tlookup instances under one sumcheck (the two digit
+lookups of an attention layer, Section 5.2, proved together) through the C
+boundary against the CPU oracle.  Integer work throughout: the bar is equality
+of bytes."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_16109_amd import synth
+from tests.gpu_common import device_table_and_tensor, first_difference, oracle_table_and_tensor
+from tests.pyref import R
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def zk():
+    import paper_2404_16109_amd as zk
+    assert torch.cuda.is_available()
+    return zk
+
+
+def _instances(orc, zk, rng, K, D, N, dup=False):
+    Sb, Tb, Sv, Tv, idx = [], [], [], [], []
+    for _ in range(K):
+        T, seen = [], set()
+        while len(T) < N:
+            t = rng.randrange(R)
+            if t not in seen:
+                seen.add(t)
+                T.append(t)
+        if dup and N >= 4:
+            T[N - 1] = T[1]
+        rows = [rng.randrange(N) for _ in range(D)]
+        tb = orc.to_bytes(T)
+        sb = tb[np.array(rows)]
+        Tb.append(tb)
+        Sb.append(sb)
+        Sv.append(zk.vec_from_bytes(sb))
+        Tv.append(zk.vec_from_bytes(tb))
+        idx.append(torch.tensor(rows, dtype=torch.int32).cuda())
+    return Sb, Tb, Sv, Tv, idx
+
+
+def _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx):
+    K = len(Sb)
+    rc_o, want, info_o = orc.tlookup_batch_prove(seed, Sb, Tb)
+    rc_g, got, info_g = zk.tlookup_prove_batch(seed, Sv, idx, Tv)
+    assert rc_o == 0 and rc_g == 0
+    assert len(got) == zk.tlookup_batch_proof_bytes(Sv[0].n, K) == info_g["len"]
+    assert first_difference(got, want) == -1
+    for key in ("beta", "alpha", "lambda"):
+        assert [info_g[key]] == orc.to_ints(info_o[key])
+    assert info_g["sum_A"] == orc.to_ints(info_o["sum_A"]) and info_g["sum_mB"] == orc.to_ints(info_o["sum_mB"])
+    assert info_g["sum_A"] == info_g["sum_mB"]
+    return got, info_o
+
+
+@pytest.mark.parametrize("K,D,N,dup", [(1, 1, 1, False), (2, 1, 1, False), (2, 2, 1, False), (3, 2, 2, False),
+                                       (2, 8, 8, True), (8, 16, 4, False), (2, 64, 2, False),
+                                       (3, 1 << 10, 1 << 4, True), (2, 1 << 13, 1 << 13, False),
+                                       (2, 1 << 15, 1 << 8, False), (5, 1 << 14, 1 << 9, False),
+                                       (2, 1 << 17, 1 << 14, True)])
+def test_batch_proof_bytes_equal_oracle(zk, orc, K, D, N, dup):
+    rng = random.Random(7000 + 31 * K + D + N)
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, K, D, N, dup)
+    seed = rng.randbytes(32)
+    got, info_o = _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx)   # rows given
+    rc, again, _ = zk.tlookup_prove_batch(seed, Sv, None, Tv)     # rows found by the library
+    assert rc == 0 and again == got
+    mixed = [idx[i] if i % 2 == 0 else None for i in range(K)]    # rows given for some instances only
+    rc, again, _ = zk.tlookup_prove_batch(seed, Sv, mixed, Tv)
+    assert rc == 0 and again == got
+    for i in range(K):  # inputs are not modified
+        assert np.array_equal(zk.vec_to_bytes(Sv[i]), Sb[i]) and np.array_equal(zk.vec_to_bytes(Tv[i]), Tb[i])
+    # both verifiers accept, and agree on the point and the claims
+    rc, claims = zk.tlookup_verify_batch(seed, got, Tv, D, S=Sv)
+    assert rc == 0
+    assert orc.tlookup_batch_verify(seed, got, Tb, D, S_list=Sb) == 0
+    assert claims["v"] == orc.to_ints(info_o["v"])
+    n = max(D.bit_length() - 1, 0)
+    body = got[32 + 32 * K + 128 * n:]
+    for i in range(K):
+        for q in range(5):
+            off = 32 * (5 * i + q)
+            assert claims["value"][i][q] == int.from_bytes(body[off:off + 32], "little")
+
+
+def test_one_instance_batch_is_not_the_single_proof(zk, orc):
+    """K = 1 goes through the batched transcript (own label, lambda drawn): its
+    rounds differ from tlookup_prove's, and each verifier rejects the other's proof."""
+    rng = random.Random(5)
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, 1, 1 << 8, 1 << 4)
+    seed = rng.randbytes(32)
+    got, _ = _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx)
+    rc, single, _ = zk.tlookup_prove(seed, Sv[0], idx[0], Tv[0])
+    assert rc == 0 and single[56:] != got[64:]
+    assert zk.tlookup_verify_batch(seed, single, Tv, 1 << 8)[0] == zk.ZK_E_REJECT
+    assert zk.tlookup_verify(seed, got, Tv[0], 1 << 8)[0] == zk.ZK_E_REJECT
+
+
+def test_config5_scaled_two_digit_segments(zk, orc):
+    """The attention workload at a size the oracle finishes in seconds: two pair
+    tables of 2^10 rows, 2^17 lookups each, padded tail included."""
+    segs = synth.attention_segments(heads=3, rows=160, cols=256, logD=17, logN=10, sigma=300.0)
+    assert segs[0]["real"] < segs[0]["D"]
+    Sb, Tb, Sv, Tv, idx = [], [], [], [], []
+    for cfg in segs:
+        sb, tb = oracle_table_and_tensor(orc, cfg)
+        sv, tv, ix = device_table_and_tensor(cfg)
+        Sb.append(sb); Tb.append(tb); Sv.append(sv); Tv.append(tv); idx.append(ix)
+    seed = segs[0]["seed"]
+    got, _ = _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx)
+    ms = []
+    for i in range(2):
+        rc, m, _ = zk.tlookup_multiplicities(Sv[i], idx[i], Tv[i])
+        assert rc == 0
+        ms.append(m)
+    assert zk.tlookup_verify_batch(seed, got, Tv, segs[0]["D"], S=Sv, m=ms)[0] == 0
+    counts = [m.cpu().numpy().astype(np.uint64) for m in ms]
+    assert orc.tlookup_batch_verify(seed, got, Tb, segs[0]["D"], S_list=Sb, m_list=counts) == 0
+
+
+def test_not_in_table_names_the_instance(zk, orc):
+    rng = random.Random(11)
+    K, D, N = 3, 1 << 9, 1 << 5
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, K, D, N)
+    bad_value = next(x for x in range(1, 1 << 20) if orc.to_bytes([x])[0].tobytes() not in
+                     {row.tobytes() for row in Tb[1]})
+    sb = Sb[1].copy()
+    sb[77] = orc.to_bytes([bad_value])[0]
+    sb[300] = orc.to_bytes([bad_value])[0]
+    Sb[1] = sb
+    Sv[1] = zk.vec_from_bytes(sb)
+    seed = rng.randbytes(32)
+    rc_o, _, info_o = orc.tlookup_batch_prove(seed, Sb, Tb)
+    rc_g, proof, info_g = zk.tlookup_prove_batch(seed, Sv, None, Tv)
+    assert rc_o == -2 and rc_g == zk.ZK_E_NOT_IN_TABLE and proof == b""
+    assert (info_g["bad_instance"], info_g["bad_index"]) == (1, 77) == (info_o["bad_instance"], info_o["bad_index"])
+
+
+def test_bad_arguments(zk, orc):
+    rng = random.Random(12)
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, 2, 1 << 6, 1 << 3)
+    seed = rng.randbytes(32)
+    assert zk.tlookup_batch_workspace_bytes(1 << 6, 1 << 3, 0) == 0
+    assert zk.tlookup_batch_workspace_bytes(1 << 6, 1 << 3, 9) == 0
+    assert zk.tlookup_batch_workspace_bytes(1 << 6, 1 << 3, 2) > zk.tlookup_workspace_bytes(1 << 6, 1 << 3)
+    # instances of different shapes
+    other = zk.vec_from_bytes(Tb[1][:4])
+    assert zk.tlookup_prove_batch(seed, Sv, None, [Tv[0], other])[0] == zk.ZK_E_BADARG
+    # nine instances
+    ws = torch.empty(zk.tlookup_batch_workspace_bytes(1 << 6, 1 << 3, 8), dtype=torch.uint8, device="cuda")
+    assert zk.tlookup_prove_batch(seed, [Sv[0]] * 9, None, [Tv[0]] * 9, ws=ws, cap=1 << 16)[0] == zk.ZK_E_BADARG
+    # short proof buffer reports the size; short workspace is refused
+    rc, _, info = zk.tlookup_prove_batch(seed, Sv, None, Tv, cap=100)
+    assert rc == zk.ZK_E_BUFSZ and info["len"] == zk.tlookup_batch_proof_bytes(1 << 6, 2)
+    small = torch.empty(zk.tlookup_workspace_bytes(1 << 6, 1 << 3), dtype=torch.uint8, device="cuda")
+    assert zk.tlookup_prove_batch(seed, Sv, None, Tv, ws=small)[0] == zk.ZK_E_BUFSZ
+
+
+def test_verify_rejects_tampering_and_wrong_witness(zk, orc):
+    rng = random.Random(13)
+    K, D, N = 2, 1 << 8, 1 << 4
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, K, D, N)
+    seed = rng.randbytes(32)
+    rc, proof, _ = zk.tlookup_prove_batch(seed, Sv, idx, Tv)
+    assert rc == 0 and zk.tlookup_verify_batch(seed, proof, Tv, D, S=Sv)[0] == 0
+    n = 8
+    body = 32 + 32 * K
+    for off in (0, 4, 8, 16, 24, 40, 70, body + 3, body + 128 * 3 + 40, body + 128 * n + 5, body + 128 * n + 160 + 33,
+                len(proof) - 1):
+        bad = bytearray(proof)
+        bad[off] ^= 1
+        assert zk.tlookup_verify_batch(seed, bytes(bad), Tv, D)[0] == zk.ZK_E_REJECT, off
+        assert orc.tlookup_batch_verify(seed, bytes(bad), Tb, D) == -4, off
+    assert zk.tlookup_verify_batch(seed, proof[:-1], Tv, D)[0] == zk.ZK_E_REJECT
+    assert zk.tlookup_verify_batch(bytes(32), proof, Tv, D)[0] == zk.ZK_E_REJECT
+    # instances swapped: tables no longer match their claims
+    assert zk.tlookup_verify_batch(seed, proof, [Tv[1], Tv[0]], D)[0] == zk.ZK_E_REJECT
+    assert zk.tlookup_verify_batch(seed, proof, Tv, D, S=[Sv[1], Sv[0]])[0] == zk.ZK_E_REJECT
+    # a witness given for the second instance only
+    assert zk.tlookup_verify_batch(seed, proof, Tv, D, S=[None, Sv[1]])[0] == 0
+    assert zk.tlookup_verify_batch(seed, proof, Tv, D, S=[None, Sv[0]])[0] == zk.ZK_E_REJECT
+
+
+def test_config5_fullsize_batch(zk, orc):
+    """Both digit lookups of the attention workload at full size (2 x 2^28
+    lookups, tables of 2^16 pairs) under one sumcheck.  The oracle cannot hold
+    this prover in memory, so: the oracle's verifier replays every round and the
+    final identity and recomputes both T~(v'); the device verifier recomputes the
+    S, A and m claims from tensors obtained independently of the prover (A by the
+    library's batch inversion at the reported beta, checked on a sample by the
+    oracle; m checked against a count of the row numbers)."""
+    segs = synth.attention_segments()
+    D, N = segs[0]["D"], segs[0]["N"]
+    Sv, Tv, idx = [], [], []
+    for cfg in segs:
+        sv, tv, ix = device_table_and_tensor(cfg)
+        Sv.append(sv); Tv.append(tv); idx.append(ix)
+    seed = segs[0]["seed"]
+    rc, proof, info = zk.tlookup_prove_batch(seed, Sv, idx, Tv)
+    assert rc == 0 and info["sum_A"] == info["sum_mB"]
+    rc, again, _ = zk.tlookup_prove_batch(seed, Sv, idx, Tv)
+    assert rc == 0 and again == proof
+    Tb = [zk.vec_to_bytes(t) for t in Tv]
+    assert orc.tlookup_batch_verify(seed, proof, Tb, D) == 0
+    rng = np.random.default_rng(2)
+    for i in range(2):
+        rc, m, _ = zk.tlookup_multiplicities(Sv[i], idx[i], Tv[i])
+        counts = m.cpu().numpy().astype(np.int64)
+        assert rc == 0 and np.array_equal(counts, np.bincount(segs[i]["idx"], minlength=N))
+        shifted, A = zk.Vec(D), zk.Vec(D)
+        assert zk.fr_add_scalar(shifted, Sv[i], info["beta"]) == 0 and zk.fr_batch_inverse(A, shifted) == 0
+        sample = np.concatenate([[0, D // 2, D - 1], rng.integers(0, D, 100)])
+        pick = torch.from_numpy(sample).cuda()
+        sub_x, sub_a = zk.Vec(len(sample)), zk.Vec(len(sample))
+        sub_x.data.copy_(shifted.data.index_select(1, pick))
+        sub_a.data.copy_(A.data.index_select(1, pick))
+        rc_o, inv = orc.fr_inv(zk.vec_to_bytes(sub_x))
+        assert rc_o == 0 and np.array_equal(inv, zk.vec_to_bytes(sub_a))
+        del shifted
+        wit_S, wit_A, wit_m = [None, None], [None, None], [None, None]
+        wit_S[i], wit_A[i], wit_m[i] = Sv[i], A, m
+        assert zk.tlookup_verify_batch(seed, proof, Tv, D, S=wit_S, A=wit_A, m=wit_m)[0] == 0
+        del A
