@@ -129,6 +129,71 @@ def bench_matmul(args, zk, synth, torch, np):
                    "fr_mul_model": muls, "bytes_read": 32 * muls, "GBps": 32 * muls / (ms * 1e-3) / 1e9}}))
 
 
+def pair_table_inputs(zk, synth, torch, np, cfg):
+    """Inputs into HBM: T = T_X + rho T_Y, S = T[idx] (the looked-up values)."""
+    D, N = cfg["D"], cfg["N"]
+    T = zk.Vec(N)
+    assert zk.fr_from_i32(T, torch.from_numpy(cfg["tx"].astype(np.int32)).cuda()) == 0
+    Y = zk.Vec(N)
+    assert zk.fr_from_i32(Y, torch.from_numpy(cfg["ty"].astype(np.int32)).cuda()) == 0
+    assert zk.fr_axpy(T, T, synth.pair_combiner(cfg["seed"]), Y) == 0
+    idx = torch.from_numpy(cfg["idx"].astype(np.int32)).cuda()
+    S = zk.Vec(D)
+    chunk = 1 << 22
+    for s in range(0, D, chunk):
+        S.data[:, s:s + chunk] = T.data[:, :N].index_select(1, idx[s:s + chunk].long())
+    return S, T, idx
+
+
+def bench_attention(args, zk, synth, torch, np):
+    """Secondary timing: the two digit lookups of the attention workload (2 x 2^28
+    lookups, tables of 2^16 pairs) proved with one batched sumcheck, beside the two
+    separate proofs."""
+    segs = synth.attention_segments()
+    D, N = segs[0]["D"], segs[0]["N"]
+    Sv, Tv, idx = [], [], []
+    for cfg in segs:
+        sv, tv, ix = pair_table_inputs(zk, synth, torch, np, cfg)
+        Sv.append(sv); Tv.append(tv); idx.append(ix)
+    ws = torch.empty(zk.tlookup_batch_workspace_bytes(D, N, 2), dtype=torch.uint8, device="cuda")
+
+    def timed(fn):
+        first = None
+        for _ in range(args.warmup):
+            first = fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            out = fn()
+        torch.cuda.synchronize()
+        assert first is None or out == first
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    def batch():
+        rc, proof, _ = zk.tlookup_prove_batch(segs[0]["seed"], Sv, idx, Tv, ws=ws)
+        assert rc == 0
+        return proof
+
+    def separate():
+        out = b""
+        for i in range(2):
+            rc, proof, _ = zk.tlookup_prove(segs[i]["seed"], Sv[i], idx[i], Tv[i], ws=ws)
+            assert rc == 0
+            out += proof
+        return out
+
+    ms_batch, ms_sep = timed(batch), timed(separate)
+    muls = 2 * fr_mul_model(D, N)
+    print(json.dumps({
+        "metric": "tlookup_prove_batch Fr-mul/s, 2 instances of D=2^28, N=2^16 (secondary timing)",
+        "value": muls / (ms_batch * 1e-3), "unit": "Fr-mul/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_batch, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32x8 (255-bit Montgomery integers)", "data": "synthetic",
+        "config": {"workload": "config 5: attention scores 40 x 2048 x 2048 padded to 2^28, two 16-bit digit lookups, "
+                               "each in its own table of 2^16 pairs, one batched sumcheck",
+                   "fr_mul_model": muls, "two_separate_proofs_ms": ms_sep}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,9 +203,9 @@ def main():
     ap.add_argument("--logN", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-logD", type=int, default=19)
-    ap.add_argument("--workload", choices=["c3", "c4"], default="c3",
-                    help="c3: tlookup at D=2^25, N=2^16 (the headline metric); c4: matmul sumcheck 2048x5120x5120 "
-                         "(secondary timing)")
+    ap.add_argument("--workload", choices=["c3", "c4", "c5"], default="c3",
+                    help="c3: tlookup at D=2^25, N=2^16 (the headline metric); c4: matmul sumcheck 2048x5120x5120; "
+                         "c5: batched two-segment attention lookup at D=2^28 (c4, c5: secondary timings)")
     ap.add_argument("--no-by-rows", action="store_true", help="skip the tlookup_prove_by_rows timing beside the headline")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 2^30 B, writes 2^30 B) so that rocprofv3 "
@@ -160,22 +225,14 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "c4":
         return bench_matmul(args, zk, synth, torch, np)
+    if args.workload == "c5":
+        return bench_attention(args, zk, synth, torch, np)
     D, N = 1 << args.logD, 1 << args.logN
     rows = 2048 if args.logD >= 25 else max(1, (D * 11) // (16 * 2048))
     cols = 11008 if args.logD >= 25 else 2048
     cfg = synth.activation_table(rows=rows, cols=cols, logD=args.logD, logN=args.logN)
 
-    # inputs into HBM: T = T_X + rho T_Y, S = T[idx] (the looked-up activations)
-    T = zk.Vec(N)
-    assert zk.fr_from_i32(T, torch.from_numpy(cfg["tx"].astype(np.int32)).cuda()) == 0
-    Y = zk.Vec(N)
-    assert zk.fr_from_i32(Y, torch.from_numpy(cfg["ty"].astype(np.int32)).cuda()) == 0
-    assert zk.fr_axpy(T, T, synth.pair_combiner(cfg["seed"]), Y) == 0
-    idx = torch.from_numpy(cfg["idx"].astype(np.int32)).cuda()
-    S = zk.Vec(D)
-    chunk = 1 << 22
-    for s in range(0, D, chunk):
-        S.data[:, s:s + chunk] = T.data[:, :N].index_select(1, idx[s:s + chunk].long())
+    S, T, idx = pair_table_inputs(zk, synth, torch, np, cfg)
     ws = torch.empty(zk.tlookup_workspace_bytes(D, N), dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
 
