@@ -130,178 +130,225 @@ __device__ __forceinline__ Fr fr_double(const Fr& a) { return fr_add(a, a); }
 // full-rate instructions per limb product.  A whole column goes into one asm
 // statement so that the compiler's hazard padding between statements is paid
 // once per column, not once per product.  The K variants take wave-uniform
-// second factors (limbs of r) from scalar registers.
+// second factors (limbs of r) from scalar registers.  With FIRST the statement
+// opens a column: ex is written, not updated (its first carry fold adds to zero),
+// so that it needs no clearing and can be allocated straight into the register
+// it has to end up in.
 #define ZK_MAC(x, y) "v_mad_u64_u32 %0, vcc, %" #x ", %" #y ", %0\n\tv_addc_co_u32 %1, vcc, 0, %1, vcc\n\t"
+#define ZK_MAC0(x, y) "v_mad_u64_u32 %0, vcc, %" #x ", %" #y ", %0\n\tv_addc_co_u32 %1, vcc, 0, 0, vcc\n\t"
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac1(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0) {
-    asm(ZK_MAC(2, 3) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0) : "vcc");
+    else asm(ZK_MAC(2, 3) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack1(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0) {
-    asm(ZK_MAC(2, 3) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0) : "vcc");
+    else asm(ZK_MAC(2, 3) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac2(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack2(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac3(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack3(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac4(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack4(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac5(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack5(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac6(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack6(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac7(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack7(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mac8(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6, uint32_t x7, uint32_t y7) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6), "v"(x7), "v"(y7) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "=&v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6), "v"(x7), "v"(y7) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "+v"(ex) : "v"(x0), "v"(y0), "v"(x1), "v"(y1), "v"(x2), "v"(y2), "v"(x3), "v"(y3), "v"(x4), "v"(y4), "v"(x5), "v"(y5), "v"(x6), "v"(y6), "v"(x7), "v"(y7) : "vcc");
 }
+template <bool FIRST = false>
 __device__ __forceinline__ void fr_mack8(uint64_t& acc, uint32_t& ex, uint32_t x0, uint32_t y0, uint32_t x1, uint32_t y1, uint32_t x2, uint32_t y2, uint32_t x3, uint32_t y3, uint32_t x4, uint32_t y4, uint32_t x5, uint32_t y5, uint32_t x6, uint32_t y6, uint32_t x7, uint32_t y7) {
-    asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6), "v"(x7), "s"(y7) : "vcc");
+    if constexpr (FIRST) asm(ZK_MAC0(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "=&v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6), "v"(x7), "s"(y7) : "vcc");
+    else asm(ZK_MAC(2, 3) ZK_MAC(4, 5) ZK_MAC(6, 7) ZK_MAC(8, 9) ZK_MAC(10, 11) ZK_MAC(12, 13) ZK_MAC(14, 15) ZK_MAC(16, 17) : "+v"(acc), "+v"(ex) : "v"(x0), "s"(y0), "v"(x1), "s"(y1), "v"(x2), "s"(y2), "v"(x3), "s"(y3), "v"(x4), "s"(y4), "v"(x5), "s"(y5), "v"(x6), "s"(y6), "v"(x7), "s"(y7) : "vcc");
 }
 
 // Adds a_lo..a_hi times the matching b limbs of column c (indices j, c-j).
-template <int C, int LO, int N>
+template <int C, int LO, int N, bool FIRST = false>
 __device__ __forceinline__ void fr_col_products(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* b) {
-    if constexpr (N == 1) fr_mac1(acc, ex, a[LO], b[C - LO]);
-    if constexpr (N == 2) fr_mac2(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1]);
-    if constexpr (N == 3) fr_mac3(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2]);
-    if constexpr (N == 4)
-        fr_mac4(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3]);
-    if constexpr (N == 5)
-        fr_mac5(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
-                a[LO + 4], b[C - LO - 4]);
-    if constexpr (N == 6)
-        fr_mac6(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
-                a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5]);
-    if constexpr (N == 7)
-        fr_mac7(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
-                a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5], a[LO + 6], b[C - LO - 6]);
-    if constexpr (N == 8)
-        fr_mac8(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3],
-                a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5], a[LO + 6], b[C - LO - 6], a[LO + 7], b[C - LO - 7]);
+    if constexpr (N == 1) fr_mac1<FIRST>(acc, ex, a[LO], b[C - LO]);
+    if constexpr (N == 2) fr_mac2<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1]);
+    if constexpr (N == 3) fr_mac3<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2]);
+    if constexpr (N == 4) fr_mac4<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3]);
+    if constexpr (N == 5) fr_mac5<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3], a[LO + 4], b[C - LO - 4]);
+    if constexpr (N == 6) fr_mac6<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3], a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5]);
+    if constexpr (N == 7) fr_mac7<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3], a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5], a[LO + 6], b[C - LO - 6]);
+    if constexpr (N == 8) fr_mac8<FIRST>(acc, ex, a[LO], b[C - LO], a[LO + 1], b[C - LO - 1], a[LO + 2], b[C - LO - 2], a[LO + 3], b[C - LO - 3], a[LO + 4], b[C - LO - 4], a[LO + 5], b[C - LO - 5], a[LO + 6], b[C - LO - 6], a[LO + 7], b[C - LO - 7]);
 }
 
 // Adds m_lo..m_hi times the matching limbs of r of column c (indices i, c-i).
-template <int C, int LO, int N>
+template <int C, int LO, int N, bool FIRST = false>
 __device__ __forceinline__ void fr_col_reductions(uint64_t& acc, uint32_t& ex, const uint32_t* m) {
     constexpr uint32_t r[8] = {ZK_R0, ZK_R1, ZK_R2, ZK_R3, ZK_R4, ZK_R5, ZK_R6, ZK_R7};
-    if constexpr (N == 1) fr_mack1(acc, ex, m[LO], r[C - LO]);
-    if constexpr (N == 2) fr_mack2(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1]);
-    if constexpr (N == 3) fr_mack3(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2]);
-    if constexpr (N == 4)
-        fr_mack4(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3]);
-    if constexpr (N == 5)
-        fr_mack5(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
-                 m[LO + 4], r[C - LO - 4]);
-    if constexpr (N == 6)
-        fr_mack6(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
-                 m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5]);
-    if constexpr (N == 7)
-        fr_mack7(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
-                 m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5], m[LO + 6], r[C - LO - 6]);
-    if constexpr (N == 8)
-        fr_mack8(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3],
-                 m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5], m[LO + 6], r[C - LO - 6], m[LO + 7], r[C - LO - 7]);
-}
-
-// Next column: drop the finished low word.
-__device__ __forceinline__ void fr_col_shift(uint64_t& acc, uint32_t& ex) {
-    acc = (acc >> 32) | ((uint64_t)ex << 32);
-    ex = 0;
+    if constexpr (N == 1) fr_mack1<FIRST>(acc, ex, m[LO], r[C - LO]);
+    if constexpr (N == 2) fr_mack2<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1]);
+    if constexpr (N == 3) fr_mack3<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2]);
+    if constexpr (N == 4) fr_mack4<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3]);
+    if constexpr (N == 5) fr_mack5<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3], m[LO + 4], r[C - LO - 4]);
+    if constexpr (N == 6) fr_mack6<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3], m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5]);
+    if constexpr (N == 7) fr_mack7<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3], m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5], m[LO + 6], r[C - LO - 6]);
+    if constexpr (N == 8) fr_mack8<FIRST>(acc, ex, m[LO], r[C - LO], m[LO + 1], r[C - LO - 1], m[LO + 2], r[C - LO - 2], m[LO + 3], r[C - LO - 3], m[LO + 4], r[C - LO - 4], m[LO + 5], r[C - LO - 5], m[LO + 6], r[C - LO - 6], m[LO + 7], r[C - LO - 7]);
 }
 
 // Same as fr_col_products with the b limbs wave-uniform (scalar registers).
-template <int C, int LO, int N>
+template <int C, int LO, int N, bool FIRST = false>
 __device__ __forceinline__ void fr_col_products_k(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* k) {
-    if constexpr (N == 1) fr_mack1(acc, ex, a[LO], k[C - LO]);
-    if constexpr (N == 2) fr_mack2(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1]);
-    if constexpr (N == 3) fr_mack3(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2]);
-    if constexpr (N == 4)
-        fr_mack4(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3]);
-    if constexpr (N == 5)
-        fr_mack5(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
-                 a[LO + 4], k[C - LO - 4]);
-    if constexpr (N == 6)
-        fr_mack6(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
-                 a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5]);
-    if constexpr (N == 7)
-        fr_mack7(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
-                 a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5], a[LO + 6], k[C - LO - 6]);
-    if constexpr (N == 8)
-        fr_mack8(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3],
-                 a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5], a[LO + 6], k[C - LO - 6], a[LO + 7], k[C - LO - 7]);
+    if constexpr (N == 1) fr_mack1<FIRST>(acc, ex, a[LO], k[C - LO]);
+    if constexpr (N == 2) fr_mack2<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1]);
+    if constexpr (N == 3) fr_mack3<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2]);
+    if constexpr (N == 4) fr_mack4<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3]);
+    if constexpr (N == 5) fr_mack5<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3], a[LO + 4], k[C - LO - 4]);
+    if constexpr (N == 6) fr_mack6<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3], a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5]);
+    if constexpr (N == 7) fr_mack7<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3], a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5], a[LO + 6], k[C - LO - 6]);
+    if constexpr (N == 8) fr_mack8<FIRST>(acc, ex, a[LO], k[C - LO], a[LO + 1], k[C - LO - 1], a[LO + 2], k[C - LO - 2], a[LO + 3], k[C - LO - 3], a[LO + 4], k[C - LO - 4], a[LO + 5], k[C - LO - 5], a[LO + 6], k[C - LO - 6], a[LO + 7], k[C - LO - 7]);
+}
+
+// ---- from one column to the next ------------------------------------------------
+//
+// After a column, the accumulator's upper word and the overflow count become the
+// next column's accumulator.  The upper word of a 64-bit register pair can only
+// become a lower word by being written again, so these steps make that write do
+// some work: it takes in what the next column starts from (the carry of a word
+// that has just been cleared, a limb of a wide accumulator).
+
+// next = (acc >> 32) + (ex << 32)
+__device__ __forceinline__ uint64_t fr_col_next(uint64_t acc, uint32_t ex) {
+    return (acc >> 32) | ((uint64_t)ex << 32);
+}
+
+// The same plus a 32-bit addend for the next column.
+__device__ __forceinline__ uint64_t fr_col_next_plus(uint64_t acc, uint32_t ex, uint32_t addend) {
+    uint32_t hi = (uint32_t)(acc >> 32), nlo, nhi;
+    asm("v_add_co_u32 %0, vcc, %2, %3\n\tv_addc_co_u32 %1, vcc, 0, %4, vcc"
+        : "=&v"(nlo), "=v"(nhi)
+        : "v"(hi), "v"(addend), "v"(ex)
+        : "vcc");
+    return nlo | ((uint64_t)nhi << 32);
+}
+
+// After the Montgomery digit m = -lo of a column has been chosen: adding
+// m * r_0 = m clears the column's low word and carries one unless that word was
+// zero already, so next = hi + (lo != 0) + (ex << 32) and the product m * r_0 is
+// never formed.
+__device__ __forceinline__ uint64_t fr_col_next_cleared(uint64_t acc, uint32_t ex) {
+    uint32_t lo = (uint32_t)acc, hi = (uint32_t)(acc >> 32), nlo, nhi;
+    asm("v_cmp_ne_u32 vcc, 0, %2\n\tv_addc_co_u32 %0, vcc, 0, %3, vcc\n\tv_addc_co_u32 %1, vcc, 0, %4, vcc"
+        : "=&v"(nlo), "=v"(nhi)
+        : "v"(lo), "v"(hi), "v"(ex)
+        : "vcc");
+    return nlo | ((uint64_t)nhi << 32);
+}
+
+// Both: next = hi + (lo != 0) + addend + (ex << 32).
+__device__ __forceinline__ uint64_t fr_col_next_cleared_plus(uint64_t acc, uint32_t ex, uint32_t addend) {
+    uint32_t lo = (uint32_t)acc, hi = (uint32_t)(acc >> 32), nlo, nhi;
+    asm("v_cmp_ne_u32 vcc, 0, %2\n\tv_addc_co_u32 %0, vcc, %3, %5, vcc\n\tv_addc_co_u32 %1, vcc, 0, %4, vcc"
+        : "=&v"(nlo), "=v"(nhi)
+        : "v"(lo), "v"(hi), "v"(ex), "v"(addend)
+        : "vcc");
+    return nlo | ((uint64_t)nhi << 32);
 }
 
 template <bool UNIFORM_B, int C>
-__device__ __forceinline__ void fr_mul_low_column(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* b,
-                                                  uint32_t* m) {
-    if constexpr (C > 0) {
-        if constexpr (UNIFORM_B) fr_col_products_k<C, 0, C + 1>(acc, ex, a, b);
-        else fr_col_products<C, 0, C + 1>(acc, ex, a, b);
-        fr_col_reductions<C, 0, C>(acc, ex, m);
-    }
+__device__ __forceinline__ uint64_t fr_mul_low_column(uint64_t acc, const uint32_t* a, const uint32_t* b, uint32_t* m) {
+    uint32_t ex;
+    if constexpr (UNIFORM_B) fr_col_products_k<C, 0, C + 1, true>(acc, ex, a, b);
+    else fr_col_products<C, 0, C + 1, true>(acc, ex, a, b);
+    fr_col_reductions<C, 0, C>(acc, ex, m);
     m[C] = 0u - (uint32_t)acc;
-    fr_mack1(acc, ex, m[C], 1u);
-    fr_col_shift(acc, ex);
+    return fr_col_next_cleared(acc, ex);
 }
 
 template <bool UNIFORM_B, int C>
-__device__ __forceinline__ void fr_mul_high_column(uint64_t& acc, uint32_t& ex, const uint32_t* a, const uint32_t* b,
-                                                   const uint32_t* m, uint32_t* t) {
-    if constexpr (UNIFORM_B) fr_col_products_k<C, C - 7, 15 - C>(acc, ex, a, b);
-    else fr_col_products<C, C - 7, 15 - C>(acc, ex, a, b);
+__device__ __forceinline__ uint64_t fr_mul_high_column(uint64_t acc, const uint32_t* a, const uint32_t* b,
+                                                       const uint32_t* m, uint32_t* t) {
+    uint32_t ex;
+    if constexpr (UNIFORM_B) fr_col_products_k<C, C - 7, 15 - C, true>(acc, ex, a, b);
+    else fr_col_products<C, C - 7, 15 - C, true>(acc, ex, a, b);
     fr_col_reductions<C, C - 7, 15 - C>(acc, ex, m);
     t[C - 8] = (uint32_t)acc;
-    fr_col_shift(acc, ex);
+    return fr_col_next(acc, ex);
 }
 
 // Montgomery product a * b / 2^256 mod r, column by column (product scanning with
 // the reduction interleaved): column c collects a_j b_(c-j) and m_i r_(c-i); for
-// c < 8 the digit m_c = -column (r = 1 mod 2^32) is chosen so that its r_0 term
-// clears the column's low word.  128 multiply-adds, each with one carry fold.
+// c < 8 the digit m_c = -column (r = 1 mod 2^32) is the one whose r_0 term clears
+// the column's low word.  120 multiply-adds, each with one carry fold.
 template <bool UNIFORM_B>
 __device__ __forceinline__ Fr fr_mul_impl(const Fr& a, const Fr& b) {
     uint32_t m[8];
     uint32_t t[8];
     uint64_t acc = (uint64_t)a.l[0] * b.l[0];  // column 0 has a single product
-    uint32_t ex = 0;
-    fr_mul_low_column<UNIFORM_B, 0>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 1>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 2>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 3>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 4>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 5>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 6>(acc, ex, a.l, b.l, m);
-    fr_mul_low_column<UNIFORM_B, 7>(acc, ex, a.l, b.l, m);
-    fr_mul_high_column<UNIFORM_B, 8>(acc, ex, a.l, b.l, m, t);
-    fr_mul_high_column<UNIFORM_B, 9>(acc, ex, a.l, b.l, m, t);
-    fr_mul_high_column<UNIFORM_B, 10>(acc, ex, a.l, b.l, m, t);
-    fr_mul_high_column<UNIFORM_B, 11>(acc, ex, a.l, b.l, m, t);
-    fr_mul_high_column<UNIFORM_B, 12>(acc, ex, a.l, b.l, m, t);
-    fr_mul_high_column<UNIFORM_B, 13>(acc, ex, a.l, b.l, m, t);
-    fr_mul_high_column<UNIFORM_B, 14>(acc, ex, a.l, b.l, m, t);
+    m[0] = 0u - (uint32_t)acc;
+    acc = fr_col_next_cleared(acc, 0u);
+    acc = fr_mul_low_column<UNIFORM_B, 1>(acc, a.l, b.l, m);
+    acc = fr_mul_low_column<UNIFORM_B, 2>(acc, a.l, b.l, m);
+    acc = fr_mul_low_column<UNIFORM_B, 3>(acc, a.l, b.l, m);
+    acc = fr_mul_low_column<UNIFORM_B, 4>(acc, a.l, b.l, m);
+    acc = fr_mul_low_column<UNIFORM_B, 5>(acc, a.l, b.l, m);
+    acc = fr_mul_low_column<UNIFORM_B, 6>(acc, a.l, b.l, m);
+    acc = fr_mul_low_column<UNIFORM_B, 7>(acc, a.l, b.l, m);
+    acc = fr_mul_high_column<UNIFORM_B, 8>(acc, a.l, b.l, m, t);
+    acc = fr_mul_high_column<UNIFORM_B, 9>(acc, a.l, b.l, m, t);
+    acc = fr_mul_high_column<UNIFORM_B, 10>(acc, a.l, b.l, m, t);
+    acc = fr_mul_high_column<UNIFORM_B, 11>(acc, a.l, b.l, m, t);
+    acc = fr_mul_high_column<UNIFORM_B, 12>(acc, a.l, b.l, m, t);
+    acc = fr_mul_high_column<UNIFORM_B, 13>(acc, a.l, b.l, m, t);
+    acc = fr_mul_high_column<UNIFORM_B, 14>(acc, a.l, b.l, m, t);
     // column 15 holds only what was carried up; the result is < 2r < 2^256
     t[7] = (uint32_t)acc;
     return fr_reduce_once(t);
@@ -332,64 +379,70 @@ __device__ __forceinline__ FrWide fr_wide_zero() {
     return w;
 }
 
+// Column C of w += a * b.  The accumulator comes in holding the carry of the
+// column below plus w's own limb C, and leaves holding the same for column C + 1.
 template <int C>
-__device__ __forceinline__ void fr_wide_column(uint64_t& acc, uint32_t& ex, FrWide& w, const uint32_t* a,
-                                               const uint32_t* b) {
-    if constexpr (C < 8) fr_col_products<C, 0, C + 1>(acc, ex, a, b);
-    else fr_col_products<C, C - 7, 15 - C>(acc, ex, a, b);
-    fr_mack1(acc, ex, w.l[C], 1u);
+__device__ __forceinline__ uint64_t fr_wide_column(uint64_t acc, FrWide& w, const uint32_t* a, const uint32_t* b) {
+    uint32_t ex;
+    if constexpr (C < 8) fr_col_products<C, 0, C + 1, true>(acc, ex, a, b);
+    else fr_col_products<C, C - 7, 15 - C, true>(acc, ex, a, b);
     w.l[C] = (uint32_t)acc;
-    fr_col_shift(acc, ex);
+    return fr_col_next_plus(acc, ex, w.l[C + 1]);
 }
 
 // w += a * b (as integers), keeping the invariant.
 __device__ __forceinline__ void fr_wide_mac(FrWide& w, const Fr& a, const Fr& b) {
-    uint64_t acc = 0;
-    uint32_t ex = 0;
-    fr_wide_column<0>(acc, ex, w, a.l, b.l);
-    fr_wide_column<1>(acc, ex, w, a.l, b.l);
-    fr_wide_column<2>(acc, ex, w, a.l, b.l);
-    fr_wide_column<3>(acc, ex, w, a.l, b.l);
-    fr_wide_column<4>(acc, ex, w, a.l, b.l);
-    fr_wide_column<5>(acc, ex, w, a.l, b.l);
-    fr_wide_column<6>(acc, ex, w, a.l, b.l);
-    fr_wide_column<7>(acc, ex, w, a.l, b.l);
-    fr_wide_column<8>(acc, ex, w, a.l, b.l);
-    fr_wide_column<9>(acc, ex, w, a.l, b.l);
-    fr_wide_column<10>(acc, ex, w, a.l, b.l);
-    fr_wide_column<11>(acc, ex, w, a.l, b.l);
-    fr_wide_column<12>(acc, ex, w, a.l, b.l);
-    fr_wide_column<13>(acc, ex, w, a.l, b.l);
-    fr_wide_column<14>(acc, ex, w, a.l, b.l);
-    w.l[15] += (uint32_t)acc;  // upper half stays below 1.46 r < 2^256: no carry out
+    uint64_t acc = w.l[0];
+    acc = fr_wide_column<0>(acc, w, a.l, b.l);
+    acc = fr_wide_column<1>(acc, w, a.l, b.l);
+    acc = fr_wide_column<2>(acc, w, a.l, b.l);
+    acc = fr_wide_column<3>(acc, w, a.l, b.l);
+    acc = fr_wide_column<4>(acc, w, a.l, b.l);
+    acc = fr_wide_column<5>(acc, w, a.l, b.l);
+    acc = fr_wide_column<6>(acc, w, a.l, b.l);
+    acc = fr_wide_column<7>(acc, w, a.l, b.l);
+    acc = fr_wide_column<8>(acc, w, a.l, b.l);
+    acc = fr_wide_column<9>(acc, w, a.l, b.l);
+    acc = fr_wide_column<10>(acc, w, a.l, b.l);
+    acc = fr_wide_column<11>(acc, w, a.l, b.l);
+    acc = fr_wide_column<12>(acc, w, a.l, b.l);
+    acc = fr_wide_column<13>(acc, w, a.l, b.l);
+    acc = fr_wide_column<14>(acc, w, a.l, b.l);
+    w.l[15] = (uint32_t)acc;  // upper half stays below 1.46 r < 2^256: nothing above this word
     Fr hi = fr_reduce_once(&w.l[8]);
 #pragma unroll
     for (int k = 0; k < 8; ++k) w.l[8 + k] = hi.l[k];
 }
 
 // w / 2^256 mod r, fully reduced: the reduction half of a Montgomery product.
+// Column c < 8: w_c + sum_{i<c} m_i r_(c-i), then m_c clears it; columns 8..14
+// give the result.  As in fr_wide_mac the accumulator enters a column already
+// holding w's limb of that column.
 __device__ __forceinline__ Fr fr_wide_reduce(const FrWide& w) {
     uint32_t m[8];
     uint32_t t[8];
-    uint64_t acc = 0;
-    uint32_t ex = 0;
-    // column c < 8: w_c + sum_{i<c} m_i r_(c-i), then m_c clears it
-#define ZK_WIDE_LOW(C)                                              \
-    fr_mack1(acc, ex, w.l[C], 1u);                                  \
-    if constexpr (C > 0) fr_col_reductions<C, 0, C>(acc, ex, m);    \
-    m[C] = 0u - (uint32_t)acc;                                      \
-    fr_mack1(acc, ex, m[C], 1u);                                    \
-    fr_col_shift(acc, ex);
-    ZK_WIDE_LOW(0) ZK_WIDE_LOW(1) ZK_WIDE_LOW(2) ZK_WIDE_LOW(3) ZK_WIDE_LOW(4) ZK_WIDE_LOW(5) ZK_WIDE_LOW(6) ZK_WIDE_LOW(7)
+    uint64_t acc = w.l[0];
+    m[0] = 0u - (uint32_t)acc;
+    acc = fr_col_next_cleared_plus(acc, 0u, w.l[1]);
+#define ZK_WIDE_LOW(C)                                         \
+    {                                                          \
+        uint32_t ex;                                           \
+        fr_col_reductions<C, 0, C, true>(acc, ex, m);          \
+        m[C] = 0u - (uint32_t)acc;                             \
+        acc = fr_col_next_cleared_plus(acc, ex, w.l[C + 1]);   \
+    }
+    ZK_WIDE_LOW(1) ZK_WIDE_LOW(2) ZK_WIDE_LOW(3) ZK_WIDE_LOW(4) ZK_WIDE_LOW(5) ZK_WIDE_LOW(6) ZK_WIDE_LOW(7)
 #undef ZK_WIDE_LOW
-#define ZK_WIDE_HIGH(C)                                             \
-    fr_mack1(acc, ex, w.l[C], 1u);                                  \
-    fr_col_reductions<C, C - 7, 15 - C>(acc, ex, m);                \
-    t[C - 8] = (uint32_t)acc;                                       \
-    fr_col_shift(acc, ex);
+#define ZK_WIDE_HIGH(C)                                        \
+    {                                                          \
+        uint32_t ex;                                           \
+        fr_col_reductions<C, C - 7, 15 - C, true>(acc, ex, m); \
+        t[C - 8] = (uint32_t)acc;                              \
+        acc = fr_col_next_plus(acc, ex, w.l[C + 1]);           \
+    }
     ZK_WIDE_HIGH(8) ZK_WIDE_HIGH(9) ZK_WIDE_HIGH(10) ZK_WIDE_HIGH(11) ZK_WIDE_HIGH(12) ZK_WIDE_HIGH(13) ZK_WIDE_HIGH(14)
 #undef ZK_WIDE_HIGH
-    t[7] = (uint32_t)acc + w.l[15];  // result < 2r < 2^256
+    t[7] = (uint32_t)acc;  // result < 2r < 2^256
     return fr_reduce_once(t);
 }
 
