@@ -298,7 +298,7 @@ def main():
                    "D": D, "N": N, "proof_bytes": len(proof), "fr_mul_model": fr_mul_model(D, N)},
         "phases_ms": {k: round(v["ms_per_step"], 4) for k, v in phases.items()},
         "by_rows_ms_per_step": ms_rows,
-        "roofline": {"bound": "alu", "kernel": "k_round_data",
+        "roofline": {"bound": "alu", "kernel": "round kernels (k_round_data0, k_round_data29, k_round_both, k_round_small)",
                      "achieved": achieved / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
                      "frac": achieved / PEAK_MAD_PER_S, "traffic": measured_traffic(),
                      "launches_per_step": launches, "avg_launch_ms": avg_launch_s * 1e3,

@@ -15,6 +15,7 @@
 // 2^-h (alpha^2 c'_k e~(u_k,X) qT(X) - bm(X)) afterwards.
 #include "internal.h"
 #include "tlookup_kernels.h"
+#include "tlookup_round29.h"
 #include "transcript.h"
 
 namespace zkmi {
@@ -23,18 +24,22 @@ static const int kLoBits = 12;  // low eq table covers up to this many variables
 
 // Pool of eq tables for a point u of n variables.
 //   suffix[s], s = 0..min(kLoBits, n-1): e~ over the last s variables;
+//   suffix29[s]: the same times 2^10, for the rounds on 29-bit limbs, whose
+//                multiplication divides by 2^261 instead of 2^256 (twice on the way
+//                into a sum of products);
 //   high[k], for rounds k with n-k-1 > kLoBits: e~ over variables k+1 .. n-kLoBits-1.
 struct EqPool {
     uint32_t* pool = nullptr;
     size_t stride = 0;
     uint32_t suffix_off[kLoBits + 1];
+    uint32_t suffix29_off[kLoBits + 1];
     uint32_t high_off[32];
     int n = 0;
 
     static size_t entries(int n) {
         size_t total = 0;
         int smax = n - 1 < kLoBits ? n - 1 : kLoBits;
-        for (int s = 0; s <= smax; ++s) total += (size_t)1 << s;
+        for (int s = 0; s <= smax; ++s) total += (size_t)2 << s;
         for (int k = 0; k < n; ++k) {
             int rest = n - k - 1;
             if (rest > kLoBits) total += (size_t)1 << (rest - kLoBits);
@@ -52,6 +57,11 @@ struct EqPool {
         e.lo_off = suffix_off[e.lbits];
         e.has_hi = rest > kLoBits;
         e.hi_off = e.has_hi ? high_off[k] : 0;
+        return e;
+    }
+    EqSplit round29(int k) const {
+        EqSplit e = round(k);
+        e.lo_off = suffix29_off[e.lbits];
         return e;
     }
 };
@@ -76,6 +86,16 @@ static int eq_pool_build(EqPool& ep, const host::F* u, int n, Carver& cv, hipStr
         ++q;
     }
     if (n == 0) ep.suffix_off[0] = 0;
+    args.scale = to_dev(host::from_u64(1024));
+    for (int s = 0; s <= smax; ++s) {
+        ep.suffix29_off[s] = off;
+        args.offset[q] = off;
+        args.var0[q] = (uint8_t)(n - s);
+        args.nvars[q] = (uint8_t)s;
+        args.scaled[q] = 1;
+        off += 1u << s;
+        ++q;
+    }
     for (int k = 0; k < n; ++k) {
         int rest = n - k - 1;
         if (rest <= kLoBits) continue;
@@ -121,6 +141,8 @@ static void line_values(host::F out[4], const host::F& v0, const host::F& v1) {
 struct ProveWs {
     uint32_t* A;        // D
     uint32_t* Sf;       // D/2
+    uint4* A29;         // folded A and S while they are held in 29-bit limbs: D/2 elements of 36 bytes each
+    uint4* S29;
     uint32_t* B;        // N
     uint32_t* Bf;       // N/2: B is folded back and forth between B and Bf
     uint32_t* Tf;       // N/2
@@ -159,6 +181,8 @@ static uint32_t hash_capacity(size_t N) {
 static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.A = cv.limbs(D);
     w.Sf = cv.limbs(D / 2 ? D / 2 : 1);
+    w.A29 = (uint4*)cv.take((D / 2 ? D / 2 : 1) * 36);
+    w.S29 = (uint4*)cv.take((D / 2 ? D / 2 : 1) * 36);
     w.B = cv.limbs(N);
     w.Bf = cv.limbs(N / 2 ? N / 2 : 1);
     w.Tf = cv.limbs(N / 2 ? N / 2 : 1);
@@ -483,16 +507,28 @@ static int prove_core(const ProveCall& c) {
     F half_pow = one();       // 2^-(k+1) in round k
     F cD = one(), cT = one();  // products of e~(u_t, r_t) over bound variables
     F r_prev = zero();
+    // Rounds that fold the data arrays only and are large run on 29-bit limbs
+    // (tlookup_round29.h).  Between two of them the arrays stay in 29-bit planes,
+    // unreduced, for at most kMaxLazyRounds rounds in a row.
+    auto on_29_bits = [&](int k) { return k >= 1 && k < h && ((size_t)1 << (n - k - 1)) > kSmallPairs; };
+    int lazy_rounds = 0;  // how many rounds in a row have left the data arrays in 29-bit planes
+    const F29 beta29 = f29_unpack(to_dev(beta).l);
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
         const EqSplit eq = ep.round(k);
         const bool table_round = k >= h;
         const bool small = k > 0 && half <= kSmallPairs;
+        const bool use29 = on_29_bits(k);
+        const bool in32 = lazy_rounds == 0;
+        const bool out32 = use29 && (!on_29_bits(k + 1) || lazy_rounds + 1 == kMaxLazyRounds);
         // pairs per workgroup: a workgroup's pairs must share the high factor of
-        // their weights; small rounds get one pair per thread
-        size_t span = half / 2048;  // about 2048 workgroups where the round is large enough
+        // their weights (at most 2^kLoBits pairs, 16 per thread).  As many as that
+        // allows, since a thread's closing reduction costs about as much as two
+        // pairs, but at least 512 workgroups while the round is large enough;
+        // small rounds get one pair per thread
+        size_t span = half / 512;
         if (span < (size_t)kBlock) span = (size_t)kBlock;
-        if (eq.has_hi && span > ((size_t)1 << eq.lbits)) span = (size_t)1 << eq.lbits;
+        if (span > ((size_t)1 << kLoBits)) span = (size_t)1 << kLoBits;
         if (span > half) span = half;
         const unsigned blocks = (unsigned)(half / span);
         if (blocks > inst[0].w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
@@ -553,11 +589,33 @@ static int prove_core(const ProveCall& c) {
                 }
                 launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, I.words, mb->words, my_seq,
                                   w.flags + 1, stream);
-            } else {
+            } else if (use29) {
+                DataRound29Args d29;
+                // 32-bit words: A in place (stride D), S from the caller's vector or Sf; 29-bit limbs: A29, S29
+                d29.A = PairArray29{w.A, D, w.A29, w.A29 + D / 2, (const uint32_t*)(w.A29 + D) , w.A29, w.A29 + D / 2,
+                                    (uint32_t*)(w.A29 + D), w.A, D};
+                d29.S = PairArray29{d.S.src, d.S.ss, w.S29, w.S29 + D / 2, (const uint32_t*)(w.S29 + D), w.S29, w.S29 + D / 2,
+                                    (uint32_t*)(w.S29 + D), w.Sf, D / 2};
+                d29.half = half;
+                d29.block_span = span;
+                d29.r_prev = f29_unpack(to_dev(mul(r_prev, from_u64(32))).l);
+                d29.beta = beta29;
+                d29.eq = ep.round29(k);
+                d29.partials = d.partials;
+                d29.pstride = d.pstride;
                 {
                     ProfileScope prof(kProfRoundData, stream);
-                    if (k > 0) hipLaunchKernelGGL(k_round_data<true>, dim3(blocks), dim3(kBlock), 0, stream, d);
-                    else hipLaunchKernelGGL(k_round_data<false>, dim3(blocks), dim3(kBlock), 0, stream, d);
+                    if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else if (in32) hipLaunchKernelGGL((k_round_data29<true, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else if (out32) hipLaunchKernelGGL((k_round_data29<false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else hipLaunchKernelGGL((k_round_data29<false, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                }
+                launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 0, blocks, I.words, mb->words, my_seq,
+                                  w.flags + 1, stream);
+            } else {
+                {  // the first round (every later one is small, binds a table variable, or runs on 29-bit limbs)
+                    ProfileScope prof(kProfRoundData, stream);
+                    hipLaunchKernelGGL(k_round_data0, dim3(blocks), dim3(kBlock), 0, stream, d);
                 }
                 if (table_round) {  // only with k == 0, i.e. D == N
                     ProfileScope prof(kProfRoundTable, stream);
@@ -572,6 +630,7 @@ static int prove_core(const ProveCall& c) {
                 I.b_cur_stride = t.B.ds;
             }
         }
+        lazy_rounds = use29 && !out32 ? lazy_rounds + 1 : 0;
         ZK_TRY(mailbox_wait(mb, seq, stream));
         read_table_consts();
 

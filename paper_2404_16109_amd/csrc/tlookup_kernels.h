@@ -377,6 +377,8 @@ struct EqPoolArgs {
     uint32_t offset[64];
     uint8_t var0[64];
     uint8_t nvars[64];
+    uint8_t scaled[64];  // entries of this table are multiplied by `scale`
+    Fr scale;
     int ntables;
     uint32_t total;
 };
@@ -394,6 +396,7 @@ static __global__ void __launch_bounds__(kBlock) k_eq_pool(uint32_t* __restrict_
             Fr f = bit ? args.u[v0 + t] : fr_sub(one, args.u[v0 + t]);
             acc = t == 0 ? f : fr_mul(acc, f);
         }
+        if (args.scaled[q]) acc = fr_mul(acc, args.scale);
         fr_store(pool, stride, g, acc);
     }
 }
@@ -554,23 +557,12 @@ __device__ __forceinline__ void round_data_block(const DataRoundArgs& g, unsigne
     }
 }
 
-// The first round streams 128 bytes per pair for two multiplications and wants
-// many wavefronts in flight; the folding rounds are bound by instruction issue
-// and carry three 16-limb accumulators, for which three wavefronts per SIMD is
-// the register budget asked of the compiler.
-template <bool FOLD>
-static __global__ void __launch_bounds__(kBlock) k_round_data(DataRoundArgs g);
-
-template <>
-__global__ void __launch_bounds__(kBlock) k_round_data<false>(DataRoundArgs g) {
+// The first round: 128 bytes per pair for two multiplications, bound by HBM.  (The
+// large folding rounds after it are in tlookup_round29.h; round_data_block<true>
+// serves the rounds that also bind a table variable.)
+static __global__ void __launch_bounds__(kBlock) k_round_data0(DataRoundArgs g) {
     __shared__ uint32_t lds[4 * 6 * 8];
     round_data_block<false>(g, blockIdx.x, lds, nullptr);
-}
-
-template <>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 3))) k_round_data<true>(DataRoundArgs g) {
-    __shared__ uint32_t lds[4 * 6 * 8];
-    round_data_block<true>(g, blockIdx.x, lds, nullptr);
 }
 
 struct TableRoundArgs {
