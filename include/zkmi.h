@@ -174,7 +174,17 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
  * Proof (host buffer, tlookup_proof_bytes(D) bytes):
  *   "ZKTL" | u32 1 | LE64 D | LE64 N | digest(m) | n x 4 elements | 5 elements.
  * *len (host) receives the size, also on ZK_E_BUFSZ.  aux: host, may be NULL.
- * ws: device, at least tlookup_workspace_bytes(D, N).  Synchronises the stream. */
+ * ws: device, at least tlookup_workspace_bytes(D, N).  Synchronises the stream.
+ *
+ * S not in T is ZK_E_NOT_IN_TABLE with aux->bad_index the smallest such i, as in
+ * tlookup_multiplicities.  With idx given (and D > 256, N <= 2^16) the prover does
+ * not compare every S_i with T[idx_i] up front: it counts from idx alone and then
+ * applies the identity the protocol itself rests on, sum_i 1/(beta+S_i) =
+ * sum_j m_j/(beta+T_j) (Section 4), to the sums it has after the first round;
+ * only if they differ are all S_i compared with their rows to find bad_index.  A
+ * tensor with S_i != T[idx_i] slips through with probability at most (D+N)/|F|
+ * over beta (Appendix C's bound for the same identity), and then yields a proof
+ * that the verifier accepts with that same probability. */
 size_t tlookup_proof_bytes(size_t D);
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);

@@ -219,8 +219,13 @@ static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
 
 // Multiplicities into w.m (and the digest leaves into w.leaves).  Returns
 // ZK_E_NOT_IN_TABLE with *bad_index set if some S_i is not in T.
+// With defer_check (hints given, workgroup histograms in use) the hints are
+// only range-checked here; S_i = T[idx_i] is then checked by the caller.
+static bool can_defer_check(const ProveWs& w, const uint32_t* idx, size_t D) { return w.hist && idx && D > (size_t)kBlock; }
+
 static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_t D, size_t N, uint64_t* bad_index,
-                      Mailbox* mb, hipStream_t stream) {
+                      Mailbox* mb, hipStream_t stream, bool defer_check = false) {
+    if (defer_check && !can_defer_check(w, idx, D)) return ZK_E_BADARG;
     uint32_t cap = w.cap_mask + 1;
     hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(cap)), dim3(kBlock), 0, stream, w.slots, (size_t)cap, kEmptySlot);
     hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.m, N, 0u);
@@ -235,14 +240,21 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
         static thread_local bool lds_limit_raised = false;
         const size_t lds_bytes = ((N + 1) / 2) * 4;
         if (!lds_limit_raised) {
-            ZK_HIP_TRY(hipFuncSetAttribute((const void*)k_count_lds, hipFuncAttributeMaxDynamicSharedMemorySize,
+            ZK_HIP_TRY(hipFuncSetAttribute((const void*)k_count_lds<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)(((kLdsHistMaxRows + 1) / 2) * 4)));
+            ZK_HIP_TRY(hipFuncSetAttribute((const void*)k_count_lds<false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)(((kLdsHistMaxRows + 1) / 2) * 4)));
             lds_limit_raised = true;
         }
         size_t per_block = align_up(div_up(D, w.hist_parts), kHistThreads);
-        hipLaunchKernelGGL(k_count_lds, dim3(w.hist_parts), dim3(kHistThreads), lds_bytes, stream, w.m, w.hist, S.limbs,
-                           S.stride, D, per_block, idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots, w.cap_mask,
-                           w.canon, w.flags, (unsigned long long*)(w.flags + 2));
+        if (defer_check)
+            hipLaunchKernelGGL(k_count_lds<false>, dim3(w.hist_parts), dim3(kHistThreads), lds_bytes, stream, w.m, w.hist,
+                               S.limbs, S.stride, D, per_block, idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots,
+                               w.cap_mask, w.canon, w.flags, (unsigned long long*)(w.flags + 2));
+        else
+            hipLaunchKernelGGL(k_count_lds<true>, dim3(w.hist_parts), dim3(kHistThreads), lds_bytes, stream, w.m, w.hist,
+                               S.limbs, S.stride, D, per_block, idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots,
+                               w.cap_mask, w.canon, w.flags, (unsigned long long*)(w.flags + 2));
         const uint32_t group = 16;
         hipLaunchKernelGGL(k_hist_reduce, dim3((unsigned)div_up(N, kBlock), (unsigned)div_up(w.hist_parts, group)),
                            dim3(kBlock), 0, stream, w.m, w.hist, w.hist_parts, group, (uint32_t)N);
@@ -264,6 +276,17 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
         if (bad_index) *bad_index = bad;
         return ZK_E_NOT_IN_TABLE;
     }
+    return ZK_OK;
+}
+
+// Smallest i with S_i != row idx_i of the table (w.rows), or all ones.
+static int find_bad_row(ProveWs& w, fr_vec S, const uint32_t* idx, size_t D, size_t N, uint64_t* bad, hipStream_t stream) {
+    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags + 2, (size_t)2, 0xffffffffu);
+    hipLaunchKernelGGL(k_check_rows, dim3(grid_for(D, kBlock, 16384)), dim3(kBlock), 0, stream, S.limbs, S.stride, D, idx,
+                       w.rows, (uint32_t)N, (unsigned long long*)(w.flags + 2));
+    ZK_HIP_TRY(hipGetLastError());
+    ZK_HIP_TRY(hipMemcpyAsync(bad, w.flags + 2, 8, hipMemcpyDeviceToHost, stream));
+    ZK_HIP_TRY(hipStreamSynchronize(stream));
     return ZK_OK;
 }
 
@@ -297,6 +320,7 @@ struct Instance {
     host::F c1, c2, cB, sum_A, lam;
     uint8_t md[32];
     BatchInverseJob job_a, job_b;
+    bool deferred = false;  // S_i = T[idx_i] is checked through sum A = sum m B after the first round, not while counting
 };
 
 struct ProveCall {
@@ -362,12 +386,17 @@ static int prove_core(const ProveCall& c) {
     ProfileScope prof_total(kProfTotal, stream);
 
     // -- Prep: multiplicities and their digests -------------------------------------------------
+    bool defer_all = !c.by_rows;
+    for (size_t i = 0; i < K; ++i) defer_all = defer_all && can_defer_check(inst[i].w, inst[i].idx, D);
     for (size_t i = 0; i < K; ++i) {
         uint64_t bad = 0;
         int rc;
         {
             ProfileScope prof(kProfCount, stream);
-            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, D, N, &bad, mb, stream);
+            // with hints, the inverse vectors themselves tell whether S_i = T[idx_i] everywhere (see the first round);
+            // all instances or none, so that the first instance at fault is the one reported
+            inst[i].deferred = defer_all;
+            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, D, N, &bad, mb, stream, inst[i].deferred);
         }
         if (rc == ZK_E_NOT_IN_TABLE) {
             if (c.aux) c.aux->bad_index = bad;
@@ -647,6 +676,21 @@ static int prove_core(const ProveCall& c) {
             if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
             F sA0 = from_dev(sums + 24), sA1 = from_dev(sums + 32);
             if (k == 0) I.sum_A = add(sA0, sA1);
+            if (k == 0 && I.deferred && !equal(I.sum_A, I.c2)) {
+                // The counts were taken from the hints without looking at S.  Had every
+                // S_i been the hinted row, sum_i 1/(beta+S_i) = sum_j m_j/(beta+T_j) would hold
+                // (Section 4, first form of the identity); it does not, so some S_i differs
+                // from its row: find the smallest such i by comparing them all.
+                uint64_t bad = UINT64_MAX;
+                ZK_TRY(find_bad_row(I.w, I.S, I.idx, D, N, &bad, stream));
+                if (bad == UINT64_MAX) return ZK_E_HIP;  // the sums disagree although every row matches
+                if (c.aux) c.aux->bad_index = bad;
+                if (c.baux) {
+                    c.baux->bad_instance = i;
+                    c.baux->bad_index = bad;
+                }
+                return ZK_E_NOT_IN_TABLE;
+            }
             F q[4], sa[4], tq[4], tm[4];
             quad_values(q, q0, q1, qi);
             line_values(sa, sA0, sA1);

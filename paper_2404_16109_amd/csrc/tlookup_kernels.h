@@ -172,6 +172,10 @@ static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint
 static const int kHistThreads = 1024;
 static const uint32_t kHistPass = 60 * 1024;  // elements per pass, < 2^16
 
+// CHECK_S = false: rows are taken from the hints unchecked (an out-of-range hint
+// still counts as a failure); the comparison of every S_i with its row is then
+// the caller's business (it rides on the inversion's first pass over S).
+template <bool CHECK_S>
 static __global__ void __launch_bounds__(kHistThreads)
 k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict__ S, size_t ss, size_t D,
             size_t per_block, const uint32_t* __restrict__ idx, const uint32_t* __restrict__ T, size_t ts,
@@ -200,7 +204,7 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
             for (int e = 0; e < 2; ++e) {
                 if (in_range[e]) {
                     if (idx) row[e] = idx[i[e]];
-                    v[e] = fr_load(S, ss, i[e]);
+                    if constexpr (CHECK_S) v[e] = fr_load(S, ss, i[e]);
                 }
             }
 #pragma unroll
@@ -209,9 +213,12 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
                 if (idx) {
                     uint32_t r = row[e];
                     if (r < N) {
-                        uint4 lo = rows[2 * (size_t)r], hi = rows[2 * (size_t)r + 1];
-                        uint32_t diff = (lo.x ^ v[e].l[0]) | (lo.y ^ v[e].l[1]) | (lo.z ^ v[e].l[2]) | (lo.w ^ v[e].l[3]) |
-                                        (hi.x ^ v[e].l[4]) | (hi.y ^ v[e].l[5]) | (hi.z ^ v[e].l[6]) | (hi.w ^ v[e].l[7]);
+                        uint32_t diff = 0;
+                        if constexpr (CHECK_S) {
+                            uint4 lo = rows[2 * (size_t)r], hi = rows[2 * (size_t)r + 1];
+                            diff = (lo.x ^ v[e].l[0]) | (lo.y ^ v[e].l[1]) | (lo.z ^ v[e].l[2]) | (lo.w ^ v[e].l[3]) |
+                                   (hi.x ^ v[e].l[4]) | (hi.y ^ v[e].l[5]) | (hi.z ^ v[e].l[6]) | (hi.w ^ v[e].l[7]);
+                        }
                         if (diff) r = kEmptySlot;
                         else if (dups) r = canon[r];
                     } else {
@@ -221,7 +228,8 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
                 } else {
                     row[e] = hash_find(slots, cap_mask, T, ts, v[e]);
                 }
-                if (row[e] == kEmptySlot) atomicMin(bad, (unsigned long long)i[e]);
+                // without the comparison a hint out of range is left for the caller's check to report
+                if (CHECK_S && row[e] == kEmptySlot) atomicMin(bad, (unsigned long long)i[e]);
             }
 #pragma unroll
             for (int e = 0; e < 2; ++e) {
@@ -271,6 +279,25 @@ static __global__ void __launch_bounds__(kBlock) k_hist_reduce(uint32_t* __restr
     uint32_t acc = 0;
     for (uint32_t b = b0; b < b1; ++b) acc += part[(size_t)b * N + j];
     if (acc) atomicAdd(&m[j], acc);
+}
+
+// Smallest index i whose S_i is not row idx_i of the table (or whose hint is out
+// of range) into *bad.  Only runs after the prover's sums have shown that there
+// is such an index.
+static __global__ void __launch_bounds__(kBlock) k_check_rows(const uint32_t* __restrict__ S, size_t ss, size_t D,
+                                                       const uint32_t* __restrict__ idx, const uint4* __restrict__ rows,
+                                                       uint32_t N, unsigned long long* bad) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < D; i += (size_t)gridDim.x * kBlock) {
+        const uint32_t r = idx[i];
+        bool ok = r < N;
+        if (ok) {
+            const Fr x = fr_load(S, ss, i);
+            const uint4 lo = rows[2 * (size_t)r], hi = rows[2 * (size_t)r + 1];
+            ok = ((lo.x ^ x.l[0]) | (lo.y ^ x.l[1]) | (lo.z ^ x.l[2]) | (lo.w ^ x.l[3]) | (hi.x ^ x.l[4]) | (hi.y ^ x.l[5]) |
+                  (hi.z ^ x.l[6]) | (hi.w ^ x.l[7])) == 0;
+        }
+        if (!ok) atomicMin(bad, (unsigned long long)i);
+    }
 }
 
 // A_i = B[row_i]: with the row of every S_i known and checked, 1/(beta + S_i) is

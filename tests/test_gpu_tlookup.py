@@ -130,6 +130,16 @@ def test_not_in_table_reports_smallest_index(zk, orc):
     wrong[5] = (wrong[5] + 1) % 64
     good = zk.vec_from_bytes(Tb[idx.cpu().numpy()])
     assert zk.tlookup_multiplicities(good, wrong, Tv)[0] == zk.ZK_E_NOT_IN_TABLE
+    # the prover compares S with the hinted rows while it inverts; hints out of range fail the same way
+    rc, _, info = zk.tlookup_prove(b"\x01" * 32, good, wrong, Tv)
+    assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 5
+    wrong[3] = 64
+    wrong[2000] = 0xFFFFFFF
+    rc, _, info = zk.tlookup_prove(b"\x01" * 32, good, wrong, Tv)
+    assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 3
+    assert zk.tlookup_multiplicities(good, wrong, Tv)[2] == 3
+    rc, proof, _ = zk.tlookup_prove(b"\x01" * 32, good, idx, Tv)
+    assert rc == 0 and zk.tlookup_verify(b"\x01" * 32, proof, Tv, 1 << 12)[0] == 0
 
 
 def test_zero_denominator(zk, orc):
