@@ -183,8 +183,9 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
  * sum_j m_j/(beta+T_j) (Section 4), to the sums it has after the first round;
  * only if they differ are all S_i compared with their rows to find bad_index.  A
  * tensor with S_i != T[idx_i] slips through with probability at most (D+N)/|F|
- * over beta (Appendix C's bound for the same identity), and then yields a proof
- * that the verifier accepts with that same probability. */
+ * over beta (the identity cleared of its denominators is a polynomial identity of
+ * degree below D+N; this is the step the soundness proof of Appendix C takes),
+ * and the proof it then yields is one the verifier accepts for the same reason. */
 size_t tlookup_proof_bytes(size_t D);
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
