@@ -246,7 +246,9 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
                                            (int)(((kLdsHistMaxRows + 1) / 2) * 4)));
             lds_limit_raised = true;
         }
-        size_t per_block = align_up(div_up(D, w.hist_parts), kHistThreads);
+        // equal chunks, as few passes per workgroup as the 16-bit counters allow
+        const size_t passes = div_up(div_up(D, w.hist_parts), (size_t)kHistPass);
+        const size_t per_block = align_up(div_up(D, w.hist_parts * passes), kHistThreads);
         if (defer_check)
             hipLaunchKernelGGL(k_count_lds<false>, dim3(w.hist_parts), dim3(kHistThreads), lds_bytes, stream, w.m, w.hist,
                                S.limbs, S.stride, D, per_block, idx, T.limbs, T.stride, w.rows, (uint32_t)N, w.slots,

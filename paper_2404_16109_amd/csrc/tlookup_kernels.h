@@ -163,7 +163,8 @@ static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint
 // For tables of up to 2^16 rows the counters of a workgroup fit in LDS as packed
 // 16-bit pairs (128 KiB at 2^16 rows, of the 160 KiB a gfx950 compute unit has),
 // which takes the counting off the device-wide atomics.  A workgroup walks its
-// share of S in passes short enough that no 16-bit counter can overflow, and
+// share of S in passes (chunks of at most kHistPass elements, handed out round
+// robin) short enough that no 16-bit counter can overflow, and
 // after each pass adds its counters into a 32-bit histogram of its own in HBM
 // (plain loads and stores, nobody else touches it); a second kernel adds the
 // workgroups' histograms up.  Runs of one row that fill half a wavefront or more
@@ -178,37 +179,42 @@ static const uint32_t kHistPass = 60 * 1024;  // elements per pass, < 2^16
 template <bool CHECK_S>
 static __global__ void __launch_bounds__(kHistThreads)
 k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict__ S, size_t ss, size_t D,
-            size_t per_block, const uint32_t* __restrict__ idx, const uint32_t* __restrict__ T, size_t ts,
+            size_t chunk, const uint32_t* __restrict__ idx, const uint32_t* __restrict__ T, size_t ts,
             const uint4* __restrict__ rows, uint32_t N, const uint32_t* __restrict__ slots, uint32_t cap_mask,
             const uint32_t* __restrict__ canon, const uint32_t* __restrict__ dup_flag, unsigned long long* bad) {
     extern __shared__ uint32_t hist[];  // (N+1)/2 words, two 16-bit counters each
     const uint32_t words = (N + 1) / 2;
     const bool dups = *dup_flag != 0;
     uint32_t* mine_part = part + (size_t)blockIdx.x * N;
-    const size_t begin = blockIdx.x * per_block;
-    const size_t end = begin + per_block < D ? begin + per_block : D;
     bool first = true;
     HotRun hot;
-    for (size_t pass_begin = begin; pass_begin < end || first; pass_begin += kHistPass) {
+    // pass p of this workgroup covers chunk p * gridDim.x + blockIdx.x of S: stretches
+    // that are cheap to count (padding) are spread over all workgroups that way
+    for (size_t pass_begin = blockIdx.x * chunk; pass_begin < D || first; pass_begin += (size_t)gridDim.x * chunk) {
         for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) hist[w] = 0;
         __syncthreads();
-        const size_t pass_end = pass_begin + kHistPass < end ? pass_begin + kHistPass : end;
+        const size_t pass_end = pass_begin + chunk < D ? pass_begin + chunk : D;
         // whole wavefronts iterate together so that the cross-lane merge sees all 64
-        // lanes; two elements per thread per trip keep more loads in flight
-        for (size_t base = pass_begin; base < pass_end; base += 2 * kHistThreads) {
-            size_t i[2] = {base + threadIdx.x, base + kHistThreads + threadIdx.x};
-            bool in_range[2] = {i[0] < pass_end, i[1] < pass_end};
-            uint32_t row[2] = {kEmptySlot, kEmptySlot};
-            Fr v[2];
+        // lanes; several elements per thread per trip keep more loads in flight
+        // (two when S is read as well, eight when only the hints are)
+        constexpr int E = CHECK_S ? 2 : 8;
+        for (size_t base = pass_begin; base < pass_end; base += E * kHistThreads) {
+            size_t i[E];
+            bool in_range[E];
+            uint32_t row[E];
+            Fr v[CHECK_S ? E : 1];
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
+            for (int e = 0; e < E; ++e) {
+                i[e] = base + (size_t)e * kHistThreads + threadIdx.x;
+                in_range[e] = i[e] < pass_end;
+                row[e] = kEmptySlot;
                 if (in_range[e]) {
                     if (idx) row[e] = idx[i[e]];
                     if constexpr (CHECK_S) v[e] = fr_load(S, ss, i[e]);
                 }
             }
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
+            for (int e = 0; e < E; ++e) {
                 if (!in_range[e]) continue;
                 if (idx) {
                     uint32_t r = row[e];
@@ -226,13 +232,13 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
                     }
                     row[e] = r;
                 } else {
-                    row[e] = hash_find(slots, cap_mask, T, ts, v[e]);
+                    if constexpr (CHECK_S) row[e] = hash_find(slots, cap_mask, T, ts, v[e]);
                 }
                 // without the comparison a hint out of range is left for the caller's check to report
                 if (CHECK_S && row[e] == kEmptySlot) atomicMin(bad, (unsigned long long)i[e]);
             }
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
+            for (int e = 0; e < E; ++e) {
                 bool pending = in_range[e] && row[e] != kEmptySlot;
 #pragma unroll 1
                 for (int round = 0; round < 4; ++round) {
@@ -242,7 +248,15 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
                     uint32_t lead_row = __shfl(row[e], leader, 64);
                     bool same_row = pending && row[e] == lead_row;
                     uint32_t run = (uint32_t)__popcll(__ballot(same_row));
+                    // A long run goes to the wavefront's running total and a run of a few
+                    // lanes is added once by its first lane (lanes on one address are
+                    // served one after the other).  A run of one to three lanes says that
+                    // the wavefront's rows are mostly different: the remaining lanes then
+                    // go in one instruction, because the LDS pipeline, which every
+                    // instruction occupies for about as long whatever it carries, is what
+                    // bounds this kernel.
                     if (run >= 32) hot.add(m, lead_row, run);
+                    else if (run < 4) break;
                     else if ((int)(threadIdx.x & 63) == leader)
                         atomicAdd(&hist[lead_row >> 1], run << (16 * (lead_row & 1)));
                     pending = pending && !same_row;
@@ -251,15 +265,38 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
             }
         }
         __syncthreads();
-        for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) {
-            uint32_t v = hist[w];
-            uint32_t c0 = v & 0xffffu, c1 = v >> 16;
-            if (first) {
-                mine_part[2 * w] = c0;
-                if (2 * w + 1 < N) mine_part[2 * w + 1] = c1;
-            } else if (v) {
-                mine_part[2 * w] += c0;
-                if (2 * w + 1 < N) mine_part[2 * w + 1] += c1;
+        // Flush into this workgroup's 32-bit histogram, eight words per thread at a
+        // time so that the loads of a group are in flight together (one word after
+        // the other this flush cost more than the counting).
+        if ((N & 1u) == 0) {
+            uint2* mine2 = reinterpret_cast<uint2*>(mine_part);
+            for (uint32_t w0 = threadIdx.x; w0 < words; w0 += 8 * kHistThreads) {
+                uint32_t v[8];
+                uint2 old[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t w = w0 + k * kHistThreads;
+                    v[k] = w < words ? hist[w] : 0;
+                    old[k] = make_uint2(0, 0);
+                    if (!first && v[k]) old[k] = mine2[w];
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t w = w0 + k * kHistThreads;
+                    if (w < words && (first || v[k])) mine2[w] = make_uint2(old[k].x + (v[k] & 0xffffu), old[k].y + (v[k] >> 16));
+                }
+            }
+        } else {  // a table of one row
+            for (uint32_t w = threadIdx.x; w < words; w += kHistThreads) {
+                uint32_t v = hist[w];
+                uint32_t c0 = v & 0xffffu, c1 = v >> 16;
+                if (first) {
+                    mine_part[2 * w] = c0;
+                    if (2 * w + 1 < N) mine_part[2 * w + 1] = c1;
+                } else if (v) {
+                    mine_part[2 * w] += c0;
+                    if (2 * w + 1 < N) mine_part[2 * w + 1] += c1;
+                }
             }
         }
         __syncthreads();
