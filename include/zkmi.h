@@ -323,6 +323,14 @@ int zkmi_profile_enable(int on);
 int zkmi_profile_reset(void);
 int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms);
 
+/* SHA-256 of `len` bytes at `data` (host) into out (host, 32 bytes): the hash
+ * the transcript is built on, exported so that it can be checked on its own.
+ * use_sha_instructions: 0 = the portable compression function, 1 = the x86 SHA
+ * extensions if the processor has them (what the library uses by default),
+ * else the portable one.  Returns 1 if the instruction path was used, 0 if not,
+ * ZK_E_BADARG on null pointers. */
+int zkmi_sha256(const uint8_t* data, size_t len, uint8_t out[32], int use_sha_instructions);
+
 /* Library version (major * 100 + minor). */
 int zkmi_version(void);
 

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "common.h"
+#include "transcript.h"
 
 namespace zkmi {
 
@@ -201,6 +202,19 @@ using namespace zkmi;
 extern "C" {
 
 int zkmi_version(void) { return 100; }
+
+int zkmi_sha256(const uint8_t* data, size_t len, uint8_t out[32], int use_sha_instructions) {
+    if ((!data && len) || !out) return ZK_E_BADARG;
+    bool& flag = host::Sha256::use_sha_instructions();
+    const bool available = flag;
+    flag = available && use_sha_instructions != 0;
+    const int used = flag ? 1 : 0;
+    host::Sha256 h;
+    h.update(data, len);
+    h.finish(out);
+    flag = available;
+    return used;
+}
 
 int zkmi_profile_enable(int on) {
     profile_state().on = on != 0;

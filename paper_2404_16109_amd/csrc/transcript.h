@@ -10,6 +10,10 @@
 
 #include <string>
 
+#if defined(__x86_64__)
+#include <immintrin.h>
+#endif
+
 #include "host_fr.h"
 
 namespace zkmi {
@@ -45,14 +49,17 @@ public:
     }
 
     void finish(uint8_t out[32]) {
-        uint64_t bits = total_ * 8;
-        uint8_t pad = 0x80;
-        update(&pad, 1);
-        uint8_t z = 0;
-        while (fill_ != 56) update(&z, 1);
-        uint8_t lenb[8];
-        for (int i = 0; i < 8; ++i) lenb[i] = (uint8_t)(bits >> (56 - 8 * i));
-        update(lenb, 8);
+        const uint64_t bits = total_ * 8;
+        buf_[fill_++] = 0x80;
+        if (fill_ > 56) {
+            memset(buf_ + fill_, 0, 64 - fill_);
+            block(buf_);
+            fill_ = 0;
+        }
+        memset(buf_ + fill_, 0, 56 - fill_);
+        for (int i = 0; i < 8; ++i) buf_[56 + i] = (uint8_t)(bits >> (56 - 8 * i));
+        block(buf_);
+        fill_ = 0;
         for (int i = 0; i < 8; ++i) {
             out[4 * i] = (uint8_t)(h_[i] >> 24);
             out[4 * i + 1] = (uint8_t)(h_[i] >> 16);
@@ -61,10 +68,20 @@ public:
         }
     }
 
+    // Tests can switch the instruction-set path off to compare the two.
+    static bool& use_sha_instructions() {
+#if defined(__x86_64__)
+        static bool on = __builtin_cpu_supports("sha") && __builtin_cpu_supports("sse4.1") && __builtin_cpu_supports("ssse3");
+#else
+        static bool on = false;
+#endif
+        return on;
+    }
+
 private:
     static uint32_t ror(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
 
-    void block(const uint8_t* b) {
+    static const uint32_t* round_constants() {
         static const uint32_t k[64] = {
             0x428a2f98u, 0x71374491u, 0xb5c0fbcfu, 0xe9b5dba5u, 0x3956c25bu, 0x59f111f1u, 0x923f82a4u, 0xab1c5ed5u,
             0xd807aa98u, 0x12835b01u, 0x243185beu, 0x550c7dc3u, 0x72be5d74u, 0x80deb1feu, 0x9bdc06a7u, 0xc19bf174u,
@@ -74,6 +91,60 @@ private:
             0xa2bfe8a1u, 0xa81a664bu, 0xc24b8b70u, 0xc76c51a3u, 0xd192e819u, 0xd6990624u, 0xf40e3585u, 0x106aa070u,
             0x19a4c116u, 0x1e376c08u, 0x2748774cu, 0x34b0bcb5u, 0x391c0cb3u, 0x4ed8aa4au, 0x5b9cca4fu, 0x682e6ff3u,
             0x748f82eeu, 0x78a5636fu, 0x84c87814u, 0x8cc70208u, 0x90befffau, 0xa4506cebu, 0xbef9a3f7u, 0xc67178f2u};
+        return k;
+    }
+
+#if defined(__x86_64__)
+    // One block with the x86 SHA extensions.  sha256rnds2 does two rounds on the
+    // state split as (A,B,E,F) and (C,D,G,H), taking W+K of those rounds from the
+    // low half of its third operand; sha256msg1/msg2 produce four schedule words
+    // from the sixteen before them.
+    __attribute__((target("sha,sse4.1,ssse3"))) void block_shani(const uint8_t* b) {
+        const __m128i* kk = (const __m128i*)round_constants();
+        const __m128i bswap = _mm_set_epi64x(0x0c0d0e0f08090a0bULL, 0x0405060700010203ULL);
+        __m128i abcd = _mm_loadu_si128((const __m128i*)&h_[0]);  // lanes: a b c d (a lowest)
+        __m128i efgh = _mm_loadu_si128((const __m128i*)&h_[4]);
+        // -> (F,E,B,A) and (H,G,D,C), highest lane first, as the instruction expects
+        __m128i t = _mm_shuffle_epi32(abcd, 0xB1);        // b a d c
+        __m128i u = _mm_shuffle_epi32(efgh, 0x1B);        // h g f e
+        __m128i abef = _mm_alignr_epi8(t, u, 8);          // f e b a   (lane0 = f)
+        __m128i cdgh = _mm_blend_epi16(u, t, 0xF0);       // h g d c   (lane0 = h)
+        const __m128i abef0 = abef, cdgh0 = cdgh;
+        __m128i w[4];
+        for (int i = 0; i < 4; ++i) w[i] = _mm_shuffle_epi8(_mm_loadu_si128((const __m128i*)(b + 16 * i)), bswap);
+        for (int g = 0; g < 16; ++g) {  // four rounds per step
+            __m128i cur;
+            if (g < 4) {
+                cur = w[g];
+            } else {
+                // W[4g..4g+3] from the four vectors before it
+                __m128i x = _mm_sha256msg1_epu32(w[g & 3], w[(g + 1) & 3]);
+                x = _mm_add_epi32(x, _mm_alignr_epi8(w[(g + 3) & 3], w[(g + 2) & 3], 4));
+                cur = _mm_sha256msg2_epu32(x, w[(g + 3) & 3]);
+                w[g & 3] = cur;
+            }
+            __m128i wk = _mm_add_epi32(cur, _mm_loadu_si128(kk + g));
+            cdgh = _mm_sha256rnds2_epu32(cdgh, abef, wk);
+            abef = _mm_sha256rnds2_epu32(abef, cdgh, _mm_shuffle_epi32(wk, 0x0E));
+        }
+        abef = _mm_add_epi32(abef, abef0);
+        cdgh = _mm_add_epi32(cdgh, cdgh0);
+        // back to a b c d / e f g h
+        t = _mm_shuffle_epi32(abef, 0x1B);                // a b e f  (lane0 = a)
+        u = _mm_shuffle_epi32(cdgh, 0xB1);                // g h c d  (lane0 = g)
+        _mm_storeu_si128((__m128i*)&h_[0], _mm_blend_epi16(t, u, 0xF0));       // a b c d
+        _mm_storeu_si128((__m128i*)&h_[4], _mm_alignr_epi8(u, t, 8));          // e f g h
+    }
+#endif
+
+    void block(const uint8_t* b) {
+#if defined(__x86_64__)
+        if (use_sha_instructions()) {
+            block_shani(b);
+            return;
+        }
+#endif
+        const uint32_t* k = round_constants();
         uint32_t w[16];
         for (int i = 0; i < 16; ++i)
             w[i] = ((uint32_t)b[4 * i] << 24) | ((uint32_t)b[4 * i + 1] << 16) | ((uint32_t)b[4 * i + 2] << 8) |

@@ -63,3 +63,30 @@ def test_host_verifier_accepts_oracle_product_proofs(orc):
                 bad[pos] ^= 1 << rng.randrange(8)
                 assert zk.sumcheck_verify_product(seed, bytes(bad), 1 << d)[0] == zk.ZK_E_REJECT
         assert zk.sumcheck_verify_product(seed, proof, 3)[0] == zk.ZK_E_BADARG
+
+
+def test_library_sha256_both_paths_match_hashlib():
+    """The transcript's hash, through the portable compression function and through
+    the x86 SHA extensions (when the processor has them), against hashlib at every
+    length around the block and padding boundaries, and on long inputs."""
+    import hashlib
+    import random
+    import paper_2404_16109_amd as zk
+    rng = random.Random(9)
+    lengths = list(range(0, 200)) + [255, 256, 257, 1000, 4096, 16384, 16385]
+    used_any = False
+    for n in lengths:
+        data = rng.randbytes(n)
+        want = hashlib.sha256(data).digest()
+        used, got = zk.zkmi_sha256(data, use_sha_instructions=False)
+        assert used == 0 and got == want, n
+        used, got = zk.zkmi_sha256(data, use_sha_instructions=True)
+        assert used in (0, 1) and got == want, n
+        used_any = used_any or used == 1
+    golden = [l.split() for l in open("tests/golden/sha256_vectors.txt") if l.strip() and not l.startswith("#")]
+    assert golden
+    for message, digest in golden:
+        for flag in (False, True):
+            assert zk.zkmi_sha256(message.encode(), use_sha_instructions=flag)[1].hex() == digest
+    cpu_has_sha = "sha_ni" in open("/proc/cpuinfo").read()
+    assert used_any == cpu_has_sha
