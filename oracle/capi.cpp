@@ -8,6 +8,7 @@
 
 #include "product.hpp"
 #include "tlookup_batch.hpp"
+#include "zkattn_link.hpp"
 
 #if !defined(__BYTE_ORDER__) || __BYTE_ORDER__ != __ORDER_LITTLE_ENDIAN__
 #error "the oracle's C boundary assumes a little-endian host"
@@ -213,6 +214,29 @@ int oracle_matmul_sumcheck_verify(const uint8_t seed[32], const uint8_t* proof, 
                                   uint64_t D1, uint64_t D2, const uint8_t* Y, const int64_t* X, const int64_t* W,
                                   int threads) {
     return matmul_sumcheck_verify(seed, proof, len, D0, D1, D2, Y ? as_fr(Y) : nullptr, X, W, threads);
+}
+
+uint64_t oracle_link_proof_bytes(uint64_t rows, uint64_t cols, uint64_t K) {
+    return link_proof_bytes(log2_exact(rows) + log2_exact(cols), (int)K);
+}
+// X, Yk: arrays of K pointers; bases: K elements.
+int oracle_zkattn_link_prove(const uint8_t seed[32], const uint8_t* Zp, const uint8_t* const* X, const uint8_t* Y,
+                             const uint8_t* const* Yk, const uint8_t* yhat, const uint8_t* bases, uint64_t rows,
+                             uint64_t cols, uint64_t K, uint8_t* proof, uint64_t cap, uint64_t* len, uint8_t* point_out,
+                             int threads) {
+    return zkattn_link_prove(seed, as_fr(Zp), reinterpret_cast<const Fr* const*>(X), as_fr(Y),
+                             reinterpret_cast<const Fr* const*>(Yk), as_fr(yhat), as_fr(bases), rows, cols, (int)K, proof,
+                             cap, len, point_out ? as_fr(point_out) : nullptr, threads);
+}
+// Any of Zp, X (or its entries), Y, Yk (or its entries), yhat may be null.
+int oracle_zkattn_link_verify(const uint8_t seed[32], const uint8_t* proof, uint64_t len, uint64_t rows, uint64_t cols,
+                              uint64_t K, const uint8_t* bases, const uint8_t* Zp, const uint8_t* const* X,
+                              const uint8_t* Y, const uint8_t* const* Yk, const uint8_t* yhat, uint8_t* point_out,
+                              int threads) {
+    return zkattn_link_verify(seed, proof, len, rows, cols, (int)K, as_fr(bases), Zp ? as_fr(Zp) : nullptr,
+                              reinterpret_cast<const Fr* const*>(X), Y ? as_fr(Y) : nullptr,
+                              reinterpret_cast<const Fr* const*>(Yk), yhat ? as_fr(yhat) : nullptr,
+                              point_out ? as_fr(point_out) : nullptr, threads);
 }
 
 }  // extern "C"

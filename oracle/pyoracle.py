@@ -40,6 +40,7 @@ def lib():
         _lib.oracle_product_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_tlookup_batch_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_matmul_proof_bytes.restype = ctypes.c_uint64
+        _lib.oracle_link_proof_bytes.restype = ctypes.c_uint64
     return _lib
 
 
@@ -391,3 +392,39 @@ def matmul_sumcheck_verify(seed, proof, D0, D1, D2, Y=None, X=None, W=None, thre
         _p(None if Y is None else _c(Y).reshape(-1, 32)),
         None if Xc is None else Xc.ctypes.data_as(ctypes.c_void_p),
         None if Wc is None else Wc.ctypes.data_as(ctypes.c_void_p), threads or default_threads())
+
+
+# ---- the sumcheck that links zkAttn's tensors --------------------------------
+
+def zkattn_link_prove(seed, Zp, X_list, Y, Yk_list, yhat, bases, rows, cols, threads=None):
+    """Zp, Y: (rows*cols, 32) bytes; X_list, Yk_list: K such arrays; yhat: (rows, 32);
+    bases: (K, 32).  Returns (rc, proof, point)."""
+    Zp, Y, yhat, bases = [_c(a).reshape(-1, 32) for a in (Zp, Y, yhat, bases)]
+    X_list = [_c(a).reshape(-1, 32) for a in X_list]
+    Yk_list = [_c(a).reshape(-1, 32) for a in Yk_list]
+    K = len(X_list)
+    n = max(int(rows * cols).bit_length() - 1, 0)
+    cap = int(lib().oracle_link_proof_bytes(_u64(rows), _u64(cols), _u64(K)))
+    proof = np.zeros(cap, dtype=np.uint8)
+    ln = ctypes.c_uint64(0)
+    point = np.zeros((max(n, 1), 32), dtype=np.uint8)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    rc = lib().oracle_zkattn_link_prove(_p(seedb), _p(Zp), _ptr_array(X_list), _p(Y), _ptr_array(Yk_list), _p(yhat),
+                                        _p(bases), _u64(rows), _u64(cols), _u64(K), _p(proof), _u64(cap),
+                                        ctypes.byref(ln), _p(point), threads or default_threads())
+    return rc, proof[:ln.value].tobytes() if rc == OK else b"", point[:n]
+
+
+def zkattn_link_verify(seed, proof, rows, cols, bases, Zp=None, X_list=None, Y=None, Yk_list=None, yhat=None,
+                       threads=None):
+    bases = _c(bases).reshape(-1, 32)
+    K = bases.shape[0]
+    pb = np.frombuffer(bytes(proof), dtype=np.uint8).copy() if len(proof) else np.zeros(1, dtype=np.uint8)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    keep_x = [None] * K if X_list is None else [None if a is None else _c(a).reshape(-1, 32) for a in X_list]
+    keep_y = [None] * K if Yk_list is None else [None if a is None else _c(a).reshape(-1, 32) for a in Yk_list]
+    return lib().oracle_zkattn_link_verify(
+        _p(seedb), _p(pb), _u64(len(proof)), _u64(rows), _u64(cols), _u64(K), _p(bases),
+        _p(None if Zp is None else _c(Zp).reshape(-1, 32)), _ptr_array(keep_x),
+        _p(None if Y is None else _c(Y).reshape(-1, 32)), _ptr_array(keep_y),
+        _p(None if yhat is None else _c(yhat).reshape(-1, 32)), None, threads or default_threads())

@@ -219,3 +219,42 @@ def tlookup_batch_proof(seed, S_list, T_list):
         fin += b"".join(fr_bytes(y) for y in [mle(As[k], v), mle(S_list[k], v), mle(Bs[k], vt), mle(ms[k], vt), mle(T_list[k], vt)])
     out += fin
     return out, {"beta": beta, "alpha": alpha, "lambda": lam, "v": v, "first_claim": first_claim, "m": ms}
+
+
+def zkattn_link_proof(seed, Zp, X, Y, Yk, yhat, bases, rows, cols):
+    """The sumcheck linking zkAttn's tensors (Protocol 2, last step) from the
+    definitions: every round polynomial is the sum of the summand, built from
+    brute-force multilinear extensions, over the remaining cube.  Lists of ints."""
+    K = len(X)
+    nr, nc = rows.bit_length() - 1, cols.bit_length() - 1
+    n = nr + nc
+    init = b"zkmi/zkattn-link/v1" + seed + rows.to_bytes(8, "little") + cols.to_bytes(8, "little") + K.to_bytes(8, "little")
+    init += b"".join(fr_bytes(b) for b in bases)
+    tr = Transcript(init)
+    u = [tr.challenge("u") for _ in range(n)]
+    cy = mle(yhat, u[:nr])
+    tr.absorb("yhat", fr_bytes(cy))
+    alpha = tr.challenge("alpha")
+
+    def f(w):
+        lin = mle(Zp, w)
+        prod = 1
+        for k in range(K):
+            lin += bases[k] * mle(X[k], w)
+            prod = prod * mle(Yk[k], w) % R
+        y = mle(Y, w)
+        return (eq(u, w) * ((lin + alpha * (y - prod)) % R) + alpha * alpha % R * eq(u[:nr], w[:nr]) % R * y) % R
+
+    out = b"ZKAL" + (1).to_bytes(4, "little") + rows.to_bytes(8, "little") + cols.to_bytes(8, "little") + K.to_bytes(8, "little")
+    out += fr_bytes(cy)
+    v, polys = [], []
+    for k in range(n):
+        g = [round_poly(f, v, n, Xp) for Xp in range(K + 4)]
+        polys.append(g)
+        msg = b"".join(fr_bytes(y) for y in g[:K + 2])
+        out += msg
+        tr.absorb("g", msg)
+        v.append(tr.challenge("r"))
+    fin = [mle(Zp, v)] + [mle(X[k], v) for k in range(K)] + [mle(Y, v)] + [mle(Yk[k], v) for k in range(K)]
+    out += b"".join(fr_bytes(y) for y in fin)
+    return out, {"u": u, "alpha": alpha, "cy": cy, "v": v, "polys": polys, "f": f, "fin": fin}
