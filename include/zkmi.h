@@ -309,6 +309,68 @@ size_t matmul_verify_workspace_bytes(size_t D0, size_t D1, size_t D2);
 int matmul_sumcheck_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, size_t D0, size_t D1, size_t D2,
                            fr_vec Y, fr_vec X, fr_vec W, void* ws, size_t ws_bytes, void* stream);
 
+/* ---- zkAttn: the sumcheck linking the tensors of an attention layer ------------
+ *
+ * Last step of zkAttn-Prove (Protocol 2): after the lookups of the K segments
+ * have been proved, one sumcheck shows the arithmetic relations between the
+ * tensors (Section 5.1): for a rows x cols matrix of shifted scores Z' (row-major,
+ * rows and cols powers of two, rows * cols <= 2^31), digits X^(k) of -Z' to the
+ * public bases B^(k), segment outputs Y^(k), their product Y and its row sums yhat,
+ *     Z'_x + sum_k B^(k) X^(k)_x = 0,   Y_x = prod_k Y^(k)_x,   yhat_i = sum_j Y_(i,j).
+ * (Z' = Z - zhat 1^T, also part of that step, is linear in committed tensors and
+ * left to the caller: Z'~(v) = Z~(v) - zhat~(v_rows).  Segments without an output
+ * table are the case Y^(k) = 1.)  The paper leaves the batching of the relations
+ * open; with u in F^n, n = log2(rows cols), and alpha from the transcript the
+ * identity proved is
+ *   alpha^2 yhat~(u_rows) = sum_x [ e~(u,x) (Z'(x) + sum_k B^(k) X^(k)(x))
+ *                                  + alpha e~(u,x) (Y(x) - prod_k Y^(k)(x))
+ *                                  + alpha^2 e~(u_rows, x_rows) Y(x) ],
+ * degree K+1 per variable, round polynomials sent as values at X = 0..K+1, row
+ * variables bound first.  1 <= K <= ZKATTN_LINK_MAX_K.
+ *
+ * Transcript: SHA256("zkmi/zkattn-link/v1" || seed || LE64 rows || LE64 cols ||
+ * LE64 K || B^(0..K-1)); u_t = challenge("u"); absorb("yhat", yhat~(u_rows));
+ * alpha = challenge("alpha"); per round absorb("g", K+2 values), r =
+ * challenge("r"); absorb("final", 2K+2 claims).
+ * Proof: "ZKAL" | u32 1 | LE64 rows | LE64 cols | LE64 K | yhat~(u_rows)
+ *        | n x (K+2) elements | Z'~(v) X^(0..K-1)~(v) Y~(v) Y^(0..K-1)~(v).
+ *
+ * X, Yk: host arrays of K device vectors of rows*cols elements; yhat: rows
+ * elements; bases: host, K canonical non-zero elements.  Inputs are not
+ * modified.  ZK_E_REJECT if the tensors do not satisfy the relations (seen in the
+ * first round, where the sum differs from the claim).  ws: device,
+ * zkattn_link_workspace_bytes.  Synchronises the stream. */
+#define ZKATTN_LINK_MAX_K 3
+
+typedef struct {
+    fr_vec Zp, Y, yhat;
+    fr_vec X[ZKATTN_LINK_MAX_K], Yk[ZKATTN_LINK_MAX_K];
+} zkattn_link_witness; /* device tensors; a member with limbs == NULL is skipped */
+
+typedef struct {
+    fr_t yhat_u;                     /* yhat~(u_rows) */
+    fr_t Zp_v, Y_v;                  /* claimed values at v */
+    fr_t X_v[ZKATTN_LINK_MAX_K], Yk_v[ZKATTN_LINK_MAX_K];
+    fr_t u[32], v[32];               /* the random point and the sumcheck point, nvars entries used */
+    int nvars, K;
+} zkattn_link_claims;
+
+size_t zkattn_link_proof_bytes(size_t rows, size_t cols, size_t K);
+size_t zkattn_link_workspace_bytes(size_t rows, size_t cols, size_t K);
+int zkattn_link_prove(const uint8_t seed[32], fr_vec Zp, const fr_vec* X, fr_vec Y, const fr_vec* Yk, fr_vec yhat,
+                      const fr_t* bases, size_t rows, size_t cols, size_t K, uint8_t* proof, size_t cap, size_t* len,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* Verifier: replays the transcript, checks every round and the last claim against
+ * the summand at the final point built from the stated values, and recomputes
+ * from each tensor given in *witness (may be NULL) the value stated for it.
+ * claims: host, may be NULL.  ws: device, zkattn_link_verify_workspace_bytes
+ * (only needed with a witness). */
+size_t zkattn_link_verify_workspace_bytes(size_t rows, size_t cols);
+int zkattn_link_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, size_t rows, size_t cols, size_t K,
+                       const fr_t* bases, const zkattn_link_witness* witness, zkattn_link_claims* claims, void* ws,
+                       size_t ws_bytes, void* stream);
+
 /* ---- measurement support ------------------------------------------------------
  * For benchmarks: the library can time its own phases with HIP events recorded
  * on the caller's stream (so that kernels are timed where they are launched).

@@ -37,6 +37,7 @@ class tlookup_claims(ctypes.Structure):
 
 
 TLOOKUP_BATCH_MAX = 8
+ZKATTN_LINK_MAX_K = 3
 
 
 class tlookup_batch_aux(ctypes.Structure):
@@ -47,6 +48,17 @@ class tlookup_batch_aux(ctypes.Structure):
 class tlookup_batch_claims(ctypes.Structure):
     _fields_ = [("value", (fr_t * 5) * TLOOKUP_BATCH_MAX), ("v", fr_t * 32), ("lambda_", fr_t),
                 ("nvars", ctypes.c_int), ("count", ctypes.c_int)]
+
+
+class zkattn_link_witness(ctypes.Structure):
+    _fields_ = [("Zp", fr_vec), ("Y", fr_vec), ("yhat", fr_vec), ("X", fr_vec * ZKATTN_LINK_MAX_K),
+                ("Yk", fr_vec * ZKATTN_LINK_MAX_K)]
+
+
+class zkattn_link_claims(ctypes.Structure):
+    _fields_ = [("yhat_u", fr_t), ("Zp_v", fr_t), ("Y_v", fr_t), ("X_v", fr_t * ZKATTN_LINK_MAX_K),
+                ("Yk_v", fr_t * ZKATTN_LINK_MAX_K), ("u", fr_t * 32), ("v", fr_t * 32), ("nvars", ctypes.c_int),
+                ("K", ctypes.c_int)]
 
 
 def _load():
@@ -103,6 +115,13 @@ def _load():
         "matmul_sumcheck_prove": (i32, [vp, fr_vec, sz, sz, fr_vec, sz, vp, sz, P(sz), vp, sz, vp]),
         "matmul_verify_workspace_bytes": (sz, [sz, sz, sz]),
         "matmul_sumcheck_verify": (i32, [vp, vp, sz, sz, sz, sz, fr_vec, fr_vec, fr_vec, vp, sz, vp]),
+        "zkattn_link_proof_bytes": (sz, [sz, sz, sz]),
+        "zkattn_link_workspace_bytes": (sz, [sz, sz, sz]),
+        "zkattn_link_prove": (i32, [vp, fr_vec, P(fr_vec), fr_vec, P(fr_vec), fr_vec, P(fr_t), sz, sz, sz, vp, sz, P(sz),
+                                    vp, sz, vp]),
+        "zkattn_link_verify_workspace_bytes": (sz, [sz, sz]),
+        "zkattn_link_verify": (i32, [vp, vp, sz, sz, sz, sz, P(fr_t), P(zkattn_link_witness), P(zkattn_link_claims), vp,
+                                     sz, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -120,7 +139,9 @@ EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_profile_enable", "zkmi_profile_r
            "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
            "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove",
-           "matmul_verify_workspace_bytes", "matmul_sumcheck_verify"]
+           "matmul_verify_workspace_bytes", "matmul_sumcheck_verify", "zkattn_link_proof_bytes",
+           "zkattn_link_workspace_bytes", "zkattn_link_prove", "zkattn_link_verify_workspace_bytes",
+           "zkattn_link_verify"]
 
 
 def raw():
@@ -484,3 +505,58 @@ def vec_to_bytes(v):
     assert rc == ZK_OK, rc
     torch.cuda.synchronize()
     return t.cpu().numpy()[:v.n].view(np.uint8).reshape(-1, 32)
+
+
+# ---- zkAttn: the sumcheck linking an attention layer's tensors ---------------------------------------
+
+def zkattn_link_proof_bytes(rows, cols, K):
+    return _lib.zkattn_link_proof_bytes(rows, cols, K)
+
+
+def zkattn_link_workspace_bytes(rows, cols, K):
+    return _lib.zkattn_link_workspace_bytes(rows, cols, K)
+
+
+def zkattn_link_prove(seed, Zp, X, Y, Yk, yhat, bases, rows, cols, ws=None, cap=None):
+    """Zp, Y, yhat: Vec; X, Yk: lists of K Vec; bases: K integers.  Returns (rc, proof bytes)."""
+    K = len(X)
+    assert len(Yk) == K and len(bases) == K
+    ws = ws if ws is not None else _ws(zkattn_link_workspace_bytes(rows, cols, K))
+    cap = zkattn_link_proof_bytes(rows, cols, K) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    Xv = (fr_vec * K)(*[x.c for x in X])
+    Yv = (fr_vec * K)(*[y.c for y in Yk])
+    Bv = (fr_t * K)(*[_fr(b) for b in bases])
+    rc = _lib.zkattn_link_prove(_seed(seed), Zp.c, Xv, Y.c, Yv, yhat.c, Bv, rows, cols, K, proof, cap, ctypes.byref(ln),
+                                ws.data_ptr(), ws.numel(), _stream())
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b""
+
+
+def zkattn_link_verify(seed, proof, rows, cols, bases, Zp=None, X=None, Y=None, Yk=None, yhat=None, ws=None):
+    """Tensors (Vec, or lists of K Vec / None) stand in for the openings.  Returns (rc, claims dict)."""
+    K = len(bases)
+    Bv = (fr_t * K)(*[_fr(b) for b in bases])
+    wit = None
+    if any(t is not None for t in (Zp, X, Y, Yk, yhat)):
+        wit = zkattn_link_witness()
+        wit.Zp = Zp.c if Zp is not None else _EMPTY
+        wit.Y = Y.c if Y is not None else _EMPTY
+        wit.yhat = yhat.c if yhat is not None else _EMPTY
+        for k in range(ZKATTN_LINK_MAX_K):
+            wit.X[k] = X[k].c if X is not None and k < K and X[k] is not None else _EMPTY
+            wit.Yk[k] = Yk[k].c if Yk is not None and k < K and Yk[k] is not None else _EMPTY
+        ws = ws if ws is not None else _ws(_lib.zkattn_link_verify_workspace_bytes(rows, cols))
+    claims = zkattn_link_claims()
+    pb = ctypes.create_string_buffer(bytes(proof), max(len(proof), 1))
+    rc = _lib.zkattn_link_verify(_seed(seed), pb, len(proof), rows, cols, K, Bv,
+                                 ctypes.byref(wit) if wit is not None else None, ctypes.byref(claims),
+                                 ws.data_ptr() if ws is not None else None, ws.numel() if ws is not None else 0,
+                                 _stream() if wit is not None else None)
+    out = {}
+    if rc == ZK_OK:
+        n = claims.nvars
+        out = {"yhat_u": _fr_int(claims.yhat_u), "Zp_v": _fr_int(claims.Zp_v), "Y_v": _fr_int(claims.Y_v),
+               "X_v": [_fr_int(claims.X_v[k]) for k in range(K)], "Yk_v": [_fr_int(claims.Yk_v[k]) for k in range(K)],
+               "u": [_fr_int(claims.u[t]) for t in range(n)], "v": [_fr_int(claims.v[t]) for t in range(n)]}
+    return rc, out

@@ -812,9 +812,9 @@ static __global__ void __launch_bounds__(kBlock) k_table_const(TableConstArgs g)
 // still to be bound to the last challenge.  Value q goes to out_words[8q..8q+8);
 // `words` is the mailbox the flag lives in.
 struct FinalArgs {
-    const uint32_t* p[5];
-    size_t stride[5];
-    int fold[5];
+    const uint32_t* p[8];
+    size_t stride[8];
+    int fold[8];
     int count;
     Fr r;
 };

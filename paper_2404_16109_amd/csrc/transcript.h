@@ -185,7 +185,9 @@ inline uint64_t get_le64(const uint8_t in[8]) {
 class Transcript {
 public:
     // state = SHA256(label || seed || LE64(dims[0]) || ...)
-    Transcript(const char* label, const uint8_t seed[32], const uint64_t* dims, int ndims) {
+    // (more public parameters may follow the dimensions as raw bytes)
+    Transcript(const char* label, const uint8_t seed[32], const uint64_t* dims, int ndims, const uint8_t* extra = nullptr,
+               size_t extra_len = 0) {
         Sha256 h;
         h.update(label, strlen(label));
         h.update(seed, 32);
@@ -194,6 +196,7 @@ public:
             put_le64(le, dims[i]);
             h.update(le, 8);
         }
+        if (extra_len) h.update(extra, extra_len);
         h.finish(state_);
     }
 

@@ -90,3 +90,27 @@ def test_library_sha256_both_paths_match_hashlib():
             assert zk.zkmi_sha256(message.encode(), use_sha_instructions=flag)[1].hex() == digest
     cpu_has_sha = "sha_ni" in open("/proc/cpuinfo").read()
     assert used_any == cpu_has_sha
+
+
+def test_host_verifier_accepts_oracle_link_proofs(orc):
+    """The library's verifier of the zkAttn linking sumcheck, without tensors (no
+    GPU involved), replays proofs written by the oracle and rejects corrupted ones."""
+    import random
+    import paper_2404_16109_amd as zk
+    from tests.test_oracle_link import make_witness, prove
+    rng = random.Random(78)
+    for rows, cols, K in [(1, 1, 1), (2, 4, 2), (8, 4, 3), (4, 16, 2)]:
+        w = make_witness(rng, rows, cols, K)
+        seed = rng.randbytes(32)
+        rc, proof, point = prove(orc, seed, w, rows, cols)
+        assert rc == 0
+        rc, claims = zk.zkattn_link_verify(seed, proof, rows, cols, w[5])
+        assert rc == zk.ZK_OK and claims["v"] == orc.to_ints(point)
+        n = (rows * cols).bit_length() - 1
+        fin = [int.from_bytes(proof[64 + n * (K + 2) * 32 + 32 * q:][:32], "little") for q in range(2 * K + 2)]
+        assert [claims["Zp_v"]] + claims["X_v"] + [claims["Y_v"]] + claims["Yk_v"] == fin
+        for pos in rng.sample(range(len(proof)), min(40, len(proof))):
+            bad = bytearray(proof)
+            bad[pos] ^= 1 << rng.randrange(8)
+            assert zk.zkattn_link_verify(seed, bytes(bad), rows, cols, w[5])[0] == zk.ZK_E_REJECT
+        assert zk.zkattn_link_verify(seed, proof, rows, cols, [b + 1 for b in w[5]])[0] == zk.ZK_E_REJECT
