@@ -194,6 +194,92 @@ def bench_attention(args, zk, synth, torch, np):
                    "fr_mul_model": muls, "two_separate_proofs_ms": ms_sep}}))
 
 
+def link_inputs(zk, synth, torch, np, cfg):
+    """The tensors of the closing sumcheck of an attention layer, in HBM: digits
+    X^(k), segment outputs Y^(k) = table_k[X^(k)], Y = Y^(0) Y^(1), Z' = -(X^(0) +
+    2^16 X^(1)), row sums yhat.  Embedding and products by the library's own
+    elementwise calls; only the row sums are added up as integers here."""
+    rows, cols = cfg["rows"], cfg["cols"]
+    D = rows * cols
+    X, Yk = [], []
+    ysum = None
+    yprod = None
+    for k in range(2):
+        xi = torch.from_numpy(cfg["x"][k].astype(np.int32)).cuda()
+        xv = zk.Vec(D)
+        assert zk.fr_from_i32(xv, xi) == 0
+        X.append(xv)
+        yi = torch.from_numpy(cfg["ty"][k].astype(np.int32)).cuda()[xi.long()]
+        yv = zk.Vec(D)
+        assert zk.fr_from_i32(yv, yi) == 0
+        Yk.append(yv)
+        yprod = yi.long() if yprod is None else yprod * yi.long()
+        del xi, yi
+    yhat_int = yprod.reshape(rows, cols).sum(dim=1).cpu().numpy().astype(np.uint64)
+    del yprod
+    Y = zk.Vec(D)
+    assert zk.fr_mul(Y, Yk[0], Yk[1]) == 0
+    Zp = zk.Vec(D)
+    assert zk.fr_axpy(Zp, X[0], cfg["bases"][1], X[1]) == 0
+    assert zk.fr_mul_scalar(Zp, Zp, synth.BLS12_381_R - 1) == 0
+    canon = np.zeros((rows, 32), dtype=np.uint8)
+    canon[:, :8] = yhat_int.astype("<u8").view(np.uint8).reshape(rows, 8)
+    yhat = zk.vec_from_bytes(canon)
+    return Zp, X, Y, Yk, yhat
+
+
+def link_fr_mul_model(D):
+    """Multiplications of zkattn_link_prove with two segments, as built: per pair 11
+    in the first round (scaling on the fly, two weights, weighted first factor,
+    three products), 23 in the second (12 folds more), 19 afterwards."""
+    return 11 * (D // 2) + 23 * (D // 4) + 19 * (D // 4 - 1)
+
+
+def bench_link(args, zk, synth, torch, np):
+    """Secondary timing: the sumcheck that closes zkAttn-Prove (Protocol 2, last
+    step) on the attention workload's tensors."""
+    if args.link_rows:
+        cfg = synth.attention_link(heads=1, rows=args.link_rows)
+    else:
+        cfg = synth.attention_link()
+    rows, cols = cfg["rows"], cfg["cols"]
+    D = rows * cols
+    Zp, X, Y, Yk, yhat = link_inputs(zk, synth, torch, np, cfg)
+    ws = torch.empty(zk.zkattn_link_workspace_bytes(rows, cols, 2), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        rc, proof = zk.zkattn_link_prove(cfg["seed"], Zp, X, Y, Yk, yhat, cfg["bases"], rows, cols, ws=ws)
+        assert rc == 0, rc
+        return proof
+
+    first = None
+    for _ in range(args.warmup):
+        first = step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        proof = step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    assert first is None or proof == first
+    # the proof opens to the tensors it was made from
+    rc, _ = zk.zkattn_link_verify(cfg["seed"], proof, rows, cols, cfg["bases"], Zp=Zp, X=X, Y=Y, Yk=Yk, yhat=yhat)
+    assert rc == 0, rc
+    muls = link_fr_mul_model(D)
+    # every array: read once at full size, then read at size s and written at s/2 for s = D, D/2, ...
+    hbm = 6 * 32 * (D + 2 * D + D)
+    print(json.dumps({
+        "metric": "zkattn_link_prove Fr-mul/s at %d x %d, 2 segments (secondary timing)" % (rows, cols),
+        "value": muls / (ms * 1e-3), "unit": "Fr-mul/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u32x8 (255-bit Montgomery integers)", "data": "synthetic",
+        "config": {"workload": "config 5: the sumcheck linking Z', two 16-bit digits, their table outputs, the product "
+                               "and its row sums, attention scores %d x %d" % (rows, cols),
+                   "fr_mul_model": muls, "proof_bytes": len(proof), "algorithmic_hbm_bytes": hbm,
+                   "hbm_GBps_algorithmic": hbm / (ms * 1e-3) / 1e9}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -203,9 +289,12 @@ def main():
     ap.add_argument("--logN", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-logD", type=int, default=19)
-    ap.add_argument("--workload", choices=["c3", "c4", "c5"], default="c3",
+    ap.add_argument("--workload", choices=["c3", "c4", "c5", "link"], default="c3",
                     help="c3: tlookup at D=2^25, N=2^16 (the headline metric); c4: matmul sumcheck 2048x5120x5120; "
-                         "c5: batched two-segment attention lookup at D=2^28 (c4, c5: secondary timings)")
+                         "c5: batched two-segment attention lookup at D=2^28; link: the sumcheck linking the attention "
+                         "workload's tensors, 2^17 x 2048 (c4, c5, link: secondary timings)")
+    ap.add_argument("--link-rows", type=int, default=0, help="with --workload link: this many rows of 2048 scores "
+                    "instead of the full 40 x 2048 (a power of two)")
     ap.add_argument("--no-by-rows", action="store_true", help="skip the tlookup_prove_by_rows timing beside the headline")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 2^30 B, writes 2^30 B) so that rocprofv3 "
@@ -227,6 +316,8 @@ def main():
         return bench_matmul(args, zk, synth, torch, np)
     if args.workload == "c5":
         return bench_attention(args, zk, synth, torch, np)
+    if args.workload == "link":
+        return bench_link(args, zk, synth, torch, np)
     D, N = 1 << args.logD, 1 << args.logN
     rows = 2048 if args.logD >= 25 else max(1, (D * 11) // (16 * 2048))
     cols = 11008 if args.logD >= 25 else 2048

@@ -119,6 +119,30 @@ def attention_segments(heads=40, rows=2048, cols=2048, logD=28, logN=16, sigma=6
     return out
 
 
+def attention_link(heads=40, rows=2048, cols=2048, logN=16, sigma=65536.0, seed=5):
+    """Config 5, the tensors that zkAttn's closing sumcheck links: the same scores
+    and digit tables as attention_segments, as a (heads*rows padded to a power of
+    two) x cols matrix.  Returns the digits x[k] and the table columns ty[k] (the
+    segment outputs are ty[k][x[k]], their product and its row sums follow from
+    them); padded rows hold the digit 0."""
+    N = 1 << logN
+    real_rows = heads * rows
+    prows = 1
+    while prows < real_rows:
+        prows <<= 1
+    z = rounded_normal(seed, real_rows * cols, sigma, -(1 << 31), 1 << 31).reshape(real_rows, cols)
+    z = (z.max(axis=1, keepdims=True) - z).reshape(-1)
+    z = np.minimum(z, N * N - 1)
+    x, ty = [], []
+    for k in range(2):
+        digit = np.zeros(prows * cols, dtype=np.uint32)
+        digit[:real_rows * cols] = ((z >> (logN * k)) & (N - 1)).astype(np.uint32)
+        x.append(digit)
+        ty.append(uniform_ints(seed + 1000 * (k + 1), N, 0, 1 << 16))
+    return {"name": "c5-attn-link", "rows": prows, "cols": cols, "x": x, "ty": ty, "bases": [1, N],
+            "seed": seed_bytes("c5link")}
+
+
 BLS12_381_R = 0x73eda753299d7d483339d80809a1d80553bda402fffe5bfeffffffff00000001
 
 
