@@ -302,6 +302,16 @@ size_t matmul_workspace_bytes(size_t D0, size_t D1, size_t D2);
 int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1, fr_vec W, size_t D2, uint8_t* proof,
                           size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream);
 
+/* The same proof, byte for byte, from matrices of 16-bit integers (device,
+ * row-major, D0*D1 and D1*D2 entries; an entry x stands for the field element x,
+ * negative x for r - |x|): quantised activations and weights need not be expanded
+ * to field vectors, and the partial evaluations a_k, b_k cost eight 32-bit
+ * multiply-adds and two bytes of traffic per matrix entry instead of a field
+ * multiplication and 32 bytes.  D0 <= 2^21 and D2 <= 2^15 (the unreduced sums
+ * must fit their accumulators), else ZK_E_BADARG. */
+int matmul_sumcheck_prove_i16(const uint8_t seed[32], const int16_t* X, size_t D0, size_t D1, const int16_t* W, size_t D2,
+                              uint8_t* proof, size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream);
+
 /* Verifier of the above: rounds and last claim as in sumcheck_verify_product;
  * for each of Y (D0 x D2), X, W given (device, may be empty) the corresponding
  * claim Y~(u,v), X~(u,r), W~(r,v) is recomputed from the tensor. */

@@ -113,6 +113,7 @@ def _load():
         "matmul_proof_bytes": (sz, [sz]),
         "matmul_workspace_bytes": (sz, [sz, sz, sz]),
         "matmul_sumcheck_prove": (i32, [vp, fr_vec, sz, sz, fr_vec, sz, vp, sz, P(sz), vp, sz, vp]),
+        "matmul_sumcheck_prove_i16": (i32, [vp, vp, sz, sz, vp, sz, vp, sz, P(sz), vp, sz, vp]),
         "matmul_verify_workspace_bytes": (sz, [sz, sz, sz]),
         "matmul_sumcheck_verify": (i32, [vp, vp, sz, sz, sz, sz, fr_vec, fr_vec, fr_vec, vp, sz, vp]),
         "zkattn_link_proof_bytes": (sz, [sz, sz, sz]),
@@ -138,7 +139,7 @@ EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_profile_enable", "zkmi_profile_r
            "tlookup_prove_by_rows", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
            "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
-           "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove",
+           "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove", "matmul_sumcheck_prove_i16",
            "matmul_verify_workspace_bytes", "matmul_sumcheck_verify", "zkattn_link_proof_bytes",
            "zkattn_link_workspace_bytes", "zkattn_link_prove", "zkattn_link_verify_workspace_bytes",
            "zkattn_link_verify"]
@@ -473,6 +474,21 @@ def matmul_sumcheck_prove(seed, X, D0, D1, W, D2, ws=None, cap=None):
     ln = ctypes.c_size_t(0)
     rc = _lib.matmul_sumcheck_prove(_seed(seed), X.c, D0, D1, W.c, D2, proof, cap, ctypes.byref(ln), ws.data_ptr(),
                                     ws.numel(), _stream())
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b""
+
+
+def matmul_sumcheck_prove_i16(seed, X, W, ws=None, cap=None):
+    """X: (D0, D1) int16 device tensor, W: (D1, D2) int16 device tensor.  Returns (rc, proof bytes)."""
+    assert X.dtype == torch.int16 and W.dtype == torch.int16 and X.is_contiguous() and W.is_contiguous()
+    D0, D1 = X.shape
+    D2 = W.shape[1]
+    assert W.shape[0] == D1
+    ws = ws if ws is not None else _ws(matmul_workspace_bytes(D0, D1, D2))
+    cap = _lib.matmul_proof_bytes(D1) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    rc = _lib.matmul_sumcheck_prove_i16(_seed(seed), X.data_ptr(), D0, D1, W.data_ptr(), D2, proof, cap, ctypes.byref(ln),
+                                        ws.data_ptr(), ws.numel(), _stream())
     return rc, proof.raw[:ln.value] if rc == ZK_OK else b""
 
 

@@ -192,6 +192,193 @@ __global__ void __launch_bounds__(kBlock) k_dot_partial(const uint32_t* __restri
     if (threadIdx.x == 0) fr_store(partials, pstride, blockIdx.x, acc[0]);
 }
 
+// ---- the same for matrices of small integers -----------------------------------------------
+//
+// Quantised activations and weights are 16-bit integers.  With x' = x + 2^15 (so
+// 0 <= x' < 2^16) a sum  sum_i e_i x_i  of field elements times matrix entries is
+// sum_i e_i x'_i - 2^15 sum_i e_i.  A product e_i x'_i is eight 32x32-bit products
+// of at most 48 bits, added limb by limb into 64-bit accumulators with no carries
+// and no reduction (2^16 terms fit); the sums leave the kernels as plain 288-bit
+// integers ("raw", nine 32-bit limbs, limb-major) and one small kernel reduces
+// them mod r and subtracts the constant.  Per matrix entry that is eight
+// multiply-adds and two bytes of traffic instead of a field multiplication and 32.
+static const int kRawLimbs = 9;
+static const size_t kSmallTermsMax = 1 << 15;  // terms per accumulator: 2^48 * 2^15 = 2^63
+
+__device__ __forceinline__ void small_mac(uint64_t (&acc)[8], const Fr& e, int16_t x) {
+    const uint32_t xp = (uint32_t)((int)x + 32768);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += (uint64_t)e.l[j] * xp;
+}
+
+// sum_j acc[j] 2^(32 j) as nine 32-bit limbs (acc[j] < 2^63).
+__device__ __forceinline__ void small_normalize(uint32_t (&out)[kRawLimbs], const uint64_t (&acc)[8]) {
+    uint64_t carry = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint64_t s = (acc[j] & 0xffffffffu) + (carry & 0xffffffffu);
+        out[j] = (uint32_t)s;
+        carry = (acc[j] >> 32) + (carry >> 32) + (s >> 32);
+    }
+    out[8] = (uint32_t)carry;  // the sum is below 2^288
+}
+
+// raw part[c][limb][k] = sum over rows i of chunk c of e[i] * (X[i][k] + 2^15); thread per column.
+__global__ void __launch_bounds__(kBlock) k_colsum_partial_i16(const int16_t* __restrict__ X, size_t D0, size_t D1,
+                                                               const uint32_t* __restrict__ e, size_t es,
+                                                               size_t rows_per_chunk, uint32_t* __restrict__ part,
+                                                               size_t P1) {
+    size_t k = blockIdx.x * (size_t)kBlock + threadIdx.x;
+    if (k >= D1) return;
+    size_t i0 = blockIdx.y * rows_per_chunk, i1 = i0 + rows_per_chunk;
+    if (i1 > D0) i1 = D0;
+    uint64_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0;
+    size_t i = i0;
+    for (; i + 4 <= i1; i += 4) {  // four rows at a time: their loads are in flight together
+        int16_t x[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) x[q] = X[(i + q) * D1 + k];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) small_mac(acc, fr_load(e, es, i + q), x[q]);
+    }
+    for (; i < i1; ++i) small_mac(acc, fr_load(e, es, i), X[i * D1 + k]);
+    uint32_t raw[kRawLimbs];
+    small_normalize(raw, acc);
+#pragma unroll
+    for (int j = 0; j < kRawLimbs; ++j) part[((size_t)blockIdx.y * kRawLimbs + j) * P1 + k] = raw[j];
+}
+
+// raw rows[limb][k] = sum_j (W[k][j] + 2^15) e[j]; one wavefront per four rows, lanes over j.
+static const int kRowsPerWave = 4;
+__global__ void __launch_bounds__(64) k_rowdot_i16(uint32_t* __restrict__ raw_out, size_t P1, const int16_t* __restrict__ W,
+                                                   size_t D1, size_t D2, const uint32_t* __restrict__ e, size_t es) {
+    const size_t k0 = (size_t)blockIdx.x * kRowsPerWave;
+    if (k0 >= D1) return;
+    uint64_t acc[kRowsPerWave][8];
+#pragma unroll
+    for (int r = 0; r < kRowsPerWave; ++r)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[r][j] = 0;
+    const int rows = D1 - k0 < (size_t)kRowsPerWave ? (int)(D1 - k0) : kRowsPerWave;
+    size_t j = 0;
+    if ((D2 & 3) == 0 && (es & 3) == 0 && (reinterpret_cast<uintptr_t>(W) & 7) == 0 && (reinterpret_cast<uintptr_t>(e) & 15) == 0) {
+        // four consecutive columns per lane: eight 16-byte loads bring four elements of e
+        // (limb-major: limb k of columns j..j+3 is one uint4) and one 8-byte load per row four entries of W
+        for (j = 4 * (size_t)threadIdx.x; j + 3 < D2; j += 4 * 64) {
+            uint4 el[8];
+            uint2 xw[kRowsPerWave];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) el[k] = *reinterpret_cast<const uint4*>(e + k * es + j);
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r)
+                xw[r] = r < rows ? *reinterpret_cast<const uint2*>(W + (k0 + r) * D2 + j) : make_uint2(0x80008000u, 0x80008000u);
+            Fr ej[4];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                ej[0].l[k] = el[k].x;
+                ej[1].l[k] = el[k].y;
+                ej[2].l[k] = el[k].z;
+                ej[3].l[k] = el[k].w;
+            }
+#pragma unroll
+            for (int r = 0; r < kRowsPerWave; ++r) {
+                small_mac(acc[r], ej[0], (int16_t)(xw[r].x & 0xffffu));
+                small_mac(acc[r], ej[1], (int16_t)(xw[r].x >> 16));
+                small_mac(acc[r], ej[2], (int16_t)(xw[r].y & 0xffffu));
+                small_mac(acc[r], ej[3], (int16_t)(xw[r].y >> 16));
+            }
+        }
+        j = D2;  // D2 is a multiple of four: the loop above has covered every column
+    }
+    for (j += threadIdx.x; j < D2; j += 64) {
+        const Fr ej = fr_load(e, es, j);
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r)
+            if (r < rows) small_mac(acc[r], ej, W[(k0 + r) * D2 + j]);
+    }
+    // the wavefront's sum of a limb is below 2^48 * D2 <= 2^63 (the caller keeps D2 <= 2^15)
+#pragma unroll
+    for (int r = 0; r < kRowsPerWave; ++r) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint64_t v = acc[r][j];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+            acc[r][j] = v;
+        }
+    }
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int r = 0; r < kRowsPerWave; ++r) {
+            if (k0 + r >= D1) break;
+            uint32_t raw[kRawLimbs];
+            small_normalize(raw, acc[r]);
+#pragma unroll
+            for (int j = 0; j < kRawLimbs; ++j) raw_out[(size_t)j * P1 + k0 + r] = raw[j];
+        }
+    }
+}
+
+// dst[k] = (sum over `chunks` raw values of entry k) mod r - 2^15 * (*esum), zero for k >= count.
+__global__ void __launch_bounds__(kBlock) k_small_finish(uint32_t* __restrict__ dst, size_t ds, const uint32_t* __restrict__ raw,
+                                                         size_t P, size_t chunks, size_t count, const uint32_t* __restrict__ esum) {
+    size_t k = blockIdx.x * (size_t)kBlock + threadIdx.x;
+    if (k >= P) return;
+    if (k >= count) {
+        fr_store(dst, ds, k, fr_zero());
+        return;
+    }
+    uint64_t limb[kRawLimbs];
+#pragma unroll
+    for (int j = 0; j < kRawLimbs; ++j) limb[j] = 0;
+    size_t c = 0;
+    for (; c + 8 <= chunks; c += 8) {  // eight chunks per trip: 72 loads in flight
+        uint32_t v[8][kRawLimbs];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+            for (int j = 0; j < kRawLimbs; ++j) v[q][j] = raw[((c + q) * kRawLimbs + j) * P + k];
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+#pragma unroll
+            for (int j = 0; j < kRawLimbs; ++j) limb[j] += v[q][j];
+    }
+    for (; c < chunks; ++c)
+#pragma unroll
+        for (int j = 0; j < kRawLimbs; ++j) limb[j] += raw[(c * kRawLimbs + j) * P + k];
+    // carry: the total is below 2^288 * chunks, chunks <= 2^16
+    Fr lo, hi = fr_zero();
+    uint64_t carry = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint64_t s = limb[j] + carry;
+        lo.l[j] = (uint32_t)s;
+        carry = s >> 32;
+    }
+    uint64_t top = limb[8] + carry;
+    hi.l[0] = (uint32_t)top;
+    hi.l[1] = (uint32_t)(top >> 32);
+    // lo (any value below 2^256) mod r = lo * 2^512 / 2^256 / 2^256; hi * 2^256 mod r = hi * 2^512 / 2^256
+    Fr one_raw = fr_zero();
+    one_raw.l[0] = 1;
+    Fr sum = fr_add(fr_mul(fr_mul(lo, fr_rr()), one_raw), fr_mul(hi, fr_rr()));
+    Fr shift = fr_zero();
+    shift.l[0] = 32768;
+    shift = fr_mul(shift, fr_rr());  // 2^15 in Montgomery form
+    fr_store(dst, ds, k, fr_sub(sum, fr_mul(shift, fr_load(esum, 1, 0))));
+}
+
+// out (eight words, Montgomery limbs of one element) = sum_{i < n} e[i]; one workgroup.
+__global__ void __launch_bounds__(1024) k_sum_one(uint32_t* __restrict__ out, const uint32_t* __restrict__ e, size_t es, size_t n) {
+    __shared__ uint32_t lds[16 * 8];
+    Fr acc[1] = {fr_zero()};
+    for (size_t i = threadIdx.x; i < n; i += 1024) acc[0] = fr_add(acc[0], fr_load(e, es, i));
+    block_sum<1, 16>(acc, lds);
+    if (threadIdx.x == 0) fr_store(out, 1, 0, acc[0]);
+}
+
 static const size_t kColChunks = 64;
 
 struct MatmulWs {
@@ -208,7 +395,8 @@ static void carve_matmul(MatmulWs& w, Carver& cv, size_t D0, size_t D1, size_t D
     w.a = cv.limbs(w.P1);
     w.b = cv.limbs(w.P1);
     size_t widest = w.P1 > w.P2 ? w.P1 : w.P2;
-    w.part = cv.limbs(kColChunks * widest);
+    // chunk sums as field elements (8 words each) or raw (9 words each, plus one element)
+    w.part = cv.limbs(2 * kColChunks * widest + 8);
     w.dot = cv.limbs(kMaxPartialBlocks);
 }
 
@@ -221,6 +409,29 @@ static void colsum_run(uint32_t* a, size_t PC, const uint32_t* M, size_t ms, siz
                        ms, R, C, e0, e0s, rows_per_chunk, part, kColChunks * PC, PC);
     hipLaunchKernelGGL(k_colsum_reduce, dim3((unsigned)div_up(PC, kBlock)), dim3(kBlock), 0, stream, a, PC, part,
                        kColChunks * PC, chunks, C, PC);
+}
+
+static void colsum_i16_run(uint32_t* a, size_t PC, const int16_t* M, size_t R, size_t C, const uint32_t* e0, size_t e0s,
+                           uint32_t* scratch, hipStream_t stream) {
+    size_t rows_per_chunk = div_up(R, kColChunks);
+    size_t chunks = div_up(R, rows_per_chunk);
+    uint32_t* raw = scratch;
+    uint32_t* esum = scratch + kColChunks * kRawLimbs * PC;
+    hipLaunchKernelGGL(k_sum_one, dim3(1), dim3(1024), 0, stream, esum, e0, e0s, R);
+    hipLaunchKernelGGL(k_colsum_partial_i16, dim3((unsigned)div_up(C, kBlock), (unsigned)chunks), dim3(kBlock), 0, stream, M,
+                       R, C, e0, e0s, rows_per_chunk, raw, PC);
+    hipLaunchKernelGGL(k_small_finish, dim3((unsigned)div_up(PC, kBlock)), dim3(kBlock), 0, stream, a, PC, raw, PC, chunks,
+                       C, esum);
+}
+
+static void rowdot_i16_run(uint32_t* b, size_t PR, const int16_t* M, size_t R, size_t C, const uint32_t* e1, size_t e1s,
+                           uint32_t* scratch, hipStream_t stream) {
+    uint32_t* raw = scratch;
+    uint32_t* esum = scratch + kColChunks * kRawLimbs * PR;
+    hipLaunchKernelGGL(k_sum_one, dim3(1), dim3(1024), 0, stream, esum, e1, e1s, C);
+    hipLaunchKernelGGL(k_rowdot_i16, dim3((unsigned)div_up(R, kRowsPerWave)), dim3(64), 0, stream, raw, PR, M, R, C, e1, e1s);
+    hipLaunchKernelGGL(k_small_finish, dim3((unsigned)div_up(PR, kBlock)), dim3(kBlock), 0, stream, b, PR, raw, PR,
+                       (size_t)1, R, esum);
 }
 
 static void rowdot_run(uint32_t* b, size_t PR, const uint32_t* M, size_t ms, size_t R, size_t C, const uint32_t* e1,
@@ -310,9 +521,13 @@ static bool matmul_dims_ok(size_t D0, size_t D1, size_t D2) {
     return D0 && D1 && D2 && D0 <= lim && D1 <= lim && D2 <= lim && D0 * D1 / D1 == D0 && D1 * D2 / D2 == D1;
 }
 
-int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1, fr_vec W, size_t D2, uint8_t* proof,
-                          size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream_v) {
-    if (!seed || !matmul_dims_ok(D0, D1, D2) || !vec_ok(X, D0 * D1) || !vec_ok(W, D1 * D2)) return ZK_E_BADARG;
+// X, W as field vectors, or (X16, W16 non-null) as row-major 16-bit integers.
+static int matmul_prove_any(const uint8_t seed[32], fr_vec X, const int16_t* X16, size_t D0, size_t D1, fr_vec W,
+                            const int16_t* W16, size_t D2, uint8_t* proof, size_t cap, size_t* len, void* ws,
+                            size_t ws_bytes, void* stream_v) {
+    const bool small = X16 != nullptr;
+    if (!seed || !matmul_dims_ok(D0, D1, D2)) return ZK_E_BADARG;
+    if (small ? !W16 : (!vec_ok(X, D0 * D1) || !vec_ok(W, D1 * D2))) return ZK_E_BADARG;
     const int n0 = log2_ceil(D0), n1 = log2_ceil(D1), n2 = log2_ceil(D2);
     const size_t need = matmul_proof_bytes(D1);
     if (len) *len = need;
@@ -331,14 +546,33 @@ int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1
     for (int t = 0; t < n2; ++t) v[t] = tr.challenge("v");
     ZK_TRY(eq_table_run(w.eu, w.P0, u, n0, stream));
     ZK_TRY(eq_table_run(w.ev, w.P2, v, n2, stream));
-    colsum_run(w.a, w.P1, X.limbs, X.stride, D0, D1, w.eu, w.P0, w.part, stream);
-    rowdot_run(w.b, w.P1, W.limbs, W.stride, D1, D2, w.ev, w.P2, stream);
+    if (small) {
+        // entries per accumulator: rows of X per chunk, columns of W per lane
+        if (D0 > kColChunks * kSmallTermsMax || D2 > kSmallTermsMax) return ZK_E_BADARG;
+        colsum_i16_run(w.a, w.P1, X16, D0, D1, w.eu, w.P0, w.part, stream);
+        rowdot_i16_run(w.b, w.P1, W16, D1, D2, w.ev, w.P2, w.part, stream);
+    } else {
+        colsum_run(w.a, w.P1, X.limbs, X.stride, D0, D1, w.eu, w.P0, w.part, stream);
+        rowdot_run(w.b, w.P1, W.limbs, W.stride, D1, D2, w.ev, w.P2, stream);
+    }
     ZK_HIP_TRY(hipGetLastError());
     memcpy(proof, "ZKMM\x01\0\0\0", 8);
     host::put_le64(proof + 8, D0);
     host::put_le64(proof + 16, D1);
     host::put_le64(proof + 24, D2);
     return product_rounds_run(tr, w.a, w.P1, w.b, w.P1, n1, nullptr, proof + 32, proof + 64, cv, mb, stream);
+}
+
+int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1, fr_vec W, size_t D2, uint8_t* proof,
+                          size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream) {
+    return matmul_prove_any(seed, X, nullptr, D0, D1, W, nullptr, D2, proof, cap, len, ws, ws_bytes, stream);
+}
+
+int matmul_sumcheck_prove_i16(const uint8_t seed[32], const int16_t* X, size_t D0, size_t D1, const int16_t* W, size_t D2,
+                              uint8_t* proof, size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream) {
+    if (!X || !W) return ZK_E_BADARG;
+    fr_vec none = {nullptr, 0, 0};
+    return matmul_prove_any(seed, none, X, D0, D1, none, W, D2, proof, cap, len, ws, ws_bytes, stream);
 }
 
 size_t matmul_verify_workspace_bytes(size_t D0, size_t D1, size_t D2) { return matmul_workspace_bytes(D0, D1, D2); }

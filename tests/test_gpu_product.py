@@ -48,6 +48,11 @@ def _matmul_case(zk, orc, X, W, seed):
     rc, got = zk.matmul_sumcheck_prove(seed, vx, D0, D1, vw, D2)
     assert rc == 0 == rc_o
     assert got == want
+    # the same bytes straight from the 16-bit matrices
+    if np.abs(X).max() < 1 << 15 and np.abs(W).max() < 1 << 15:
+        rc, got16 = zk.matmul_sumcheck_prove_i16(seed, torch.from_numpy(X.astype(np.int16)).cuda(),
+                                                 torch.from_numpy(W.astype(np.int16)).cuda())
+        assert rc == 0 and got16 == want
     return got, vx, vw
 
 
@@ -79,3 +84,20 @@ def test_matmul_proof(zk, orc, shape):
 def test_config4_matmul_13b_layer_shape(zk, orc):
     cfg = synth.matmul_operands()
     _matmul_case(zk, orc, cfg["X"], cfg["W"], cfg["seed"])
+
+
+def test_matmul_i16_extreme_values(zk, orc):
+    """Entries at both ends of the 16-bit range, all of one sign, and columns of
+    zeros: the unreduced accumulators take their largest values."""
+    rng = np.random.default_rng(77)
+    D0, D1, D2 = 300, 40, 129
+    for fill in (-32768, 32767):
+        X = np.full((D0, D1), fill, dtype=np.int64)
+        W = np.full((D1, D2), fill, dtype=np.int64)
+        X[:, 3] = 0
+        W[5, :] = -fill - 1 if fill < 0 else -fill
+        seed = bytes(rng.integers(0, 256, 32, dtype=np.uint8))
+        rc_o, want, _ = orc.matmul_sumcheck_prove(seed, X, W)
+        rc, got = zk.matmul_sumcheck_prove_i16(seed, torch.from_numpy(X.astype(np.int16)).cuda(),
+                                               torch.from_numpy(W.astype(np.int16)).cuda())
+        assert rc == 0 == rc_o and got == want
