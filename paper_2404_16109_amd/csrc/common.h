@@ -83,7 +83,33 @@ struct Mailbox {
         seq = seq == 0xfffffffeu ? 1 : seq + 1;
         return seq;
     }
+    // The other direction: a kernel that stays resident over several sumcheck
+    // rounds reads each round's challenge from here.  Word 0 is the sequence
+    // number of the challenge in words 1..8 (the host writes it last); kCmdAbort
+    // tells a waiting kernel to give up.
+    uint32_t* cmd = nullptr;    // kCmdWords uint32_t, coherent pinned memory
+    uint32_t cmd_seq = 0;
+    uint32_t next_cmd_seq() {
+        cmd_seq = cmd_seq >= 0xfffffff0u ? 1 : cmd_seq + 1;
+        return cmd_seq;
+    }
 };
+static const size_t kCmdWords = 16;
+static const uint32_t kCmdAbort = 0xffffffffu;
+
+// Host side of the command channel: the challenge, then (release) its number.
+inline void mailbox_send_challenge(Mailbox* mb, uint32_t seq, const uint32_t limbs[8]) {
+    volatile uint32_t* c = mb->cmd;
+    for (int k = 0; k < 8; ++k) c[1 + k] = limbs[k];
+    __atomic_store_n(&mb->cmd[0], seq, __ATOMIC_RELEASE);
+}
+inline void mailbox_send_abort(Mailbox* mb) { __atomic_store_n(&mb->cmd[0], kCmdAbort, __ATOMIC_RELEASE); }
+
+// How many times a resident kernel polls for a challenge before it gives up
+// (every poll crosses PCIe, about a microsecond): bounded so that a kernel can
+// never outlive a host that has stopped talking to it by more than a fraction
+// of a second.
+uint32_t device_spin_limit();
 static const size_t kMailboxWords = 2048;
 static const size_t kMailboxFlag = 2040;    // the flag word
 // A tlookup instance's round sums (eleven values) and final claims start at
@@ -130,6 +156,23 @@ __device__ __forceinline__ void mailbox_publish(uint32_t* words, uint32_t seq) {
     if (seq == 0) return;
     __threadfence_system();
     __hip_atomic_store(&words[kMailboxFlag], seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// Device side of the command channel, for one thread: waits until the host has
+// published challenge number `want` and reads it.  False on abort or when the
+// bound on polls is reached; the caller then winds the kernel down.
+__device__ __forceinline__ bool mailbox_receive_challenge(const uint32_t* cmd, uint32_t want, uint32_t spin_limit,
+                                                          uint32_t (&limbs)[8]) {
+    uint32_t polls = 0;
+    for (;;) {
+        uint32_t v = __hip_atomic_load(&cmd[0], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (v == want) break;
+        if (v == kCmdAbort || ++polls >= spin_limit) return false;
+        __builtin_amdgcn_s_sleep(4);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) limbs[k] = __hip_atomic_load(&cmd[1 + k], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return true;
 }
 
 // Launch geometry for an elementwise pass over n items.

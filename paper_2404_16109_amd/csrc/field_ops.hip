@@ -19,10 +19,17 @@ int mailbox_get(Mailbox** out) {
         ZK_HIP_TRY(hipHostMalloc(&p, kMailboxWords * sizeof(uint32_t), hipHostMallocDefault));
         mb.words = (uint32_t*)p;
         memset(mb.words, 0, kMailboxWords * sizeof(uint32_t));
+        void* q = nullptr;
+        ZK_HIP_TRY(hipHostMalloc(&q, kCmdWords * sizeof(uint32_t), hipHostMallocCoherent));
+        mb.cmd = (uint32_t*)q;
+        memset(mb.cmd, 0, kCmdWords * sizeof(uint32_t));
     }
     *out = &mb;
     return ZK_OK;
 }
+
+static std::atomic<uint32_t> g_spin_limit{1u << 20};  // about two seconds
+uint32_t device_spin_limit() { return g_spin_limit.load(); }
 
 int mailbox_wait(Mailbox* mb, uint32_t seq, hipStream_t stream) {
     volatile uint32_t* flag = mb->words + kMailboxFlag;

@@ -38,6 +38,108 @@ __global__ void __launch_bounds__(kBlock) k_round_product(ProductRoundArgs g) {
     }
 }
 
+// ---- the last rounds in one resident kernel ----------------------------------------------------
+//
+// A round over a few hundred pairs is a few microseconds of arithmetic; launched on
+// its own it costs a kernel launch, a second one for the totals and two trips
+// through the runtime's queue, about 40 us.  Once the arrays have shrunk to
+// kTailPairs pairs one workgroup stays resident for all remaining rounds: it
+// writes a round's three sums to the host's mailbox, waits (bounded) for the
+// challenge on the command channel, folds and goes on; at the end it writes the
+// two final values.  Every thread takes every barrier, and a wait that fails
+// ends the kernel for all of them.
+static const int kTailThreads = 1024;
+static const size_t kTailPairs = 1024;
+
+struct ProductTailArgs {
+    uint32_t* a;
+    size_t as;
+    uint32_t* b;
+    size_t bs;
+    size_t half0;       // pairs in the first of these rounds
+    int nrounds;        // rounds run here (>= 1)
+    int fold_first;     // the first of them binds the previous variable to r_prev
+    Fr r_prev;
+    uint32_t* words;    // mailbox: sums at words[0..24), final values at words[0..16)
+    const uint32_t* cmd;
+    uint32_t out_seq[33];  // [i]: the sums of round i are there; [nrounds]: the final values are
+    uint32_t cmd_seq[32];  // [i]: the challenge of round i
+    uint32_t spin_limit;
+};
+
+static __global__ void __launch_bounds__(kTailThreads) k_product_tail(ProductTailArgs g) {
+    __shared__ uint32_t lds[16 * 3 * 8];
+    __shared__ uint32_t sh_r[8];
+    __shared__ int sh_ok;
+    Fr r = g.r_prev;
+    bool fold = g.fold_first != 0;
+    size_t half = g.half0;
+    bool ok = true;
+    for (int i = 0; i < g.nrounds; ++i, half >>= 1) {
+        Fr tot[3] = {fr_zero(), fr_zero(), fr_zero()};
+        const size_t p = threadIdx.x;
+        if (p < half) {
+            const PairArray A{g.a, g.as, g.a, g.as}, B{g.b, g.bs, g.b, g.bs};
+            Fr a0, a1, b0, b1;
+            if (fold) {
+                load_pair<true>(A, p, half, r, a0, a1);
+                load_pair<true>(B, p, half, r, b0, b1);
+            } else {
+                load_pair<false>(A, p, half, r, a0, a1);
+                load_pair<false>(B, p, half, r, b0, b1);
+            }
+            tot[0] = fr_mul(a0, b0);
+            tot[1] = fr_mul(a1, b1);
+            tot[2] = fr_mul(fr_sub(a1, a0), fr_sub(b1, b0));
+        }
+        block_sum<3, 16>(tot, lds);
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int q = 0; q < 3; ++q)
+#pragma unroll
+                for (int k = 0; k < 8; ++k) g.words[8 * q + k] = tot[q].l[k];
+            mailbox_written();
+            mailbox_publish(g.words, g.out_seq[i]);
+            uint32_t limbs[8];
+            const bool got = mailbox_receive_challenge(g.cmd, g.cmd_seq[i], g.spin_limit, limbs);
+            if (got) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sh_r[k] = limbs[k];
+            }
+            sh_ok = got ? 1 : 0;
+        }
+        __syncthreads();  // the folded entries written in this round are visible to the workgroup from here on
+        ok = sh_ok != 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r.l[k] = __builtin_amdgcn_readfirstlane(sh_r[k]);
+        __syncthreads();  // sh_ok and sh_r are free to be written again
+        if (!ok) break;   // the same for every thread
+        fold = true;
+    }
+    if (ok && threadIdx.x < 2) {
+        const uint32_t* arr = threadIdx.x == 0 ? g.a : g.b;
+        const size_t stride = threadIdx.x == 0 ? g.as : g.bs;
+        Fr v = fr_fold(fr_load(arr, stride, 0), fr_load(arr, stride, 1), r);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) g.words[8 * threadIdx.x + k] = v.l[k];
+        mailbox_written();
+    }
+    __syncthreads();
+    if (ok && threadIdx.x == 0) mailbox_publish(g.words, g.out_seq[g.nrounds]);
+}
+
+// Ends a resident kernel that is still waiting when the host leaves early.
+struct TailGuard {
+    Mailbox* mb;
+    hipStream_t stream;
+    bool armed = false;
+    ~TailGuard() {
+        if (!armed) return;
+        mailbox_send_abort(mb);
+        (void)hipStreamSynchronize(stream);
+    }
+};
+
 static size_t product_scratch_bytes() {
     Carver cv(nullptr, 0);
     cv.limbs((size_t)kMaxPartialBlocks * 3);
@@ -65,7 +167,28 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         tr.absorb("claim", claim_bytes, 32);
         claim_done = true;
     }
-    for (int k = 0; k < d; ++k) {
+    // rounds with at most kTailPairs pairs run in one resident kernel (see k_product_tail)
+    int tail_first = d;
+    for (int k = 0; k < d; ++k)
+        if (((size_t)1 << (d - k - 1)) <= kTailPairs) {
+            tail_first = k;
+            break;
+        }
+    auto emit_round = [&](const F& g0, const F& g1, const F& lead) {
+        if (!claim_done) {
+            to_bytes(claim_bytes, add(g0, g1));
+            tr.absorb("claim", claim_bytes, 32);
+            claim_done = true;
+        }
+        F g2 = add(sub(add(g1, g1), g0), add(lead, lead));
+        to_bytes(out, g0);
+        to_bytes(out + 32, g1);
+        to_bytes(out + 64, g2);
+        tr.absorb("g", out, 96);
+        out += 96;
+        r_prev = tr.challenge("r");
+    };
+    for (int k = 0; k < tail_first; ++k) {
         const size_t half = (size_t)1 << (d - k - 1);
         size_t span = half / kMaxPartialBlocks;
         if (span < (size_t)kBlock * 4) span = (size_t)kBlock * 4;
@@ -85,19 +208,38 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         launch_final_sum(partials, pstride, blocks, 3, mb->words, mb->words, seq, ticket, stream);
         ZK_HIP_TRY(hipGetLastError());
         ZK_TRY(mailbox_wait(mb, seq, stream));
-        F g0 = from_dev(mb->words), g1 = from_dev(mb->words + 8), lead = from_dev(mb->words + 16);
-        if (!claim_done) {
-            to_bytes(claim_bytes, add(g0, g1));
-            tr.absorb("claim", claim_bytes, 32);
-            claim_done = true;
+        emit_round(from_dev(mb->words), from_dev(mb->words + 8), from_dev(mb->words + 16));
+    }
+    if (tail_first < d) {
+        ProductTailArgs g;
+        memset(&g, 0, sizeof g);
+        g.a = a; g.as = as; g.b = b; g.bs = bs;
+        g.half0 = (size_t)1 << (d - tail_first - 1);
+        g.nrounds = d - tail_first;
+        g.fold_first = tail_first > 0;
+        g.r_prev = to_dev(r_prev);
+        g.words = mb->words;
+        g.cmd = mb->cmd;
+        for (int i = 0; i <= g.nrounds; ++i) g.out_seq[i] = mb->next_seq();
+        for (int i = 0; i < g.nrounds; ++i) g.cmd_seq[i] = mb->next_cmd_seq();
+        g.spin_limit = device_spin_limit();
+        TailGuard guard{mb, stream};
+        hipLaunchKernelGGL(k_product_tail, dim3(1), dim3(kTailThreads), 0, stream, g);
+        ZK_HIP_TRY(hipGetLastError());
+        guard.armed = true;
+        for (int i = 0; i < g.nrounds; ++i) {
+            ZK_TRY(mailbox_wait(mb, g.out_seq[i], stream));
+            emit_round(from_dev(mb->words), from_dev(mb->words + 8), from_dev(mb->words + 16));
+            mailbox_send_challenge(mb, g.cmd_seq[i], to_dev(r_prev).l);
         }
-        F g2 = add(sub(add(g1, g1), g0), add(lead, lead));
-        to_bytes(out, g0);
-        to_bytes(out + 32, g1);
-        to_bytes(out + 64, g2);
-        tr.absorb("g", out, 96);
-        out += 96;
-        r_prev = tr.challenge("r");
+        ZK_TRY(mailbox_wait(mb, g.out_seq[g.nrounds], stream));
+        guard.armed = false;
+        ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device
+        F fa = from_dev(mb->words), fb = from_dev(mb->words + 8);
+        to_bytes(out, fa);
+        to_bytes(out + 32, fb);
+        tr.absorb("final", out, 64);
+        return ZK_OK;
     }
     FinalArgs f;
     memset(&f, 0, sizeof f);
