@@ -105,6 +105,18 @@ inline void mailbox_send_challenge(Mailbox* mb, uint32_t seq, const uint32_t lim
 }
 inline void mailbox_send_abort(Mailbox* mb) { __atomic_store_n(&mb->cmd[0], kCmdAbort, __ATOMIC_RELEASE); }
 
+// Ends a resident kernel that is still waiting when the host leaves early.
+struct TailGuard {
+    Mailbox* mb;
+    hipStream_t stream;
+    bool armed = false;
+    ~TailGuard() {
+        if (!armed) return;
+        mailbox_send_abort(mb);
+        (void)hipStreamSynchronize(stream);
+    }
+};
+
 // How many times a resident kernel polls for a challenge before it gives up
 // (every poll crosses PCIe, about a microsecond): bounded so that a kernel can
 // never outlive a host that has stopped talking to it by more than a fraction

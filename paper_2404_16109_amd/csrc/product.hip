@@ -128,18 +128,6 @@ static __global__ void __launch_bounds__(kTailThreads) k_product_tail(ProductTai
     if (ok && threadIdx.x == 0) mailbox_publish(g.words, g.out_seq[g.nrounds]);
 }
 
-// Ends a resident kernel that is still waiting when the host leaves early.
-struct TailGuard {
-    Mailbox* mb;
-    hipStream_t stream;
-    bool armed = false;
-    ~TailGuard() {
-        if (!armed) return;
-        mailbox_send_abort(mb);
-        (void)hipStreamSynchronize(stream);
-    }
-};
-
 static size_t product_scratch_bytes() {
     Carver cv(nullptr, 0);
     cv.limbs((size_t)kMaxPartialBlocks * 3);

@@ -544,6 +544,53 @@ static int prove_core(const ProveCall& c) {
     auto on_29_bits = [&](int k) { return k >= 1 && k < h && ((size_t)1 << (n - k - 1)) > kSmallPairs; };
     int lazy_rounds = 0;  // how many rounds in a row have left the data arrays in 29-bit planes
     const F29 beta29 = f29_unpack(to_dev(beta).l);
+    // Where round k reads and writes the arrays that change place: S comes from the
+    // caller's vector until it has been folded once, T likewise, and B alternates
+    // between its two buffers on every fold (it has two readers).  b_cur: where B is
+    // before the round; returns where it is afterwards.
+    struct Moving {
+        PairArray S, B, T;
+    };
+    auto moving_arrays = [&](int k, const Instance& I, uint32_t*& b_cur, size_t& b_stride) {
+        const ProveWs& w = I.w;
+        Moving m;
+        if (k <= 1) m.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
+        else m.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
+        if (k > h) {
+            uint32_t* other = b_cur == w.B ? w.Bf : w.B;
+            size_t other_stride = b_cur == w.B ? N / 2 : N;
+            m.B = PairArray{b_cur, b_stride, other, other_stride};
+            b_cur = other;
+            b_stride = other_stride;
+        } else {
+            m.B = PairArray{b_cur, b_stride, b_cur, b_stride};
+        }
+        if (k <= h + 1) m.T = PairArray{I.T.limbs, I.T.stride, w.Tf, N / 2};
+        else m.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
+        return m;
+    };
+    auto final_arrays = [&](const Instance& I, const uint32_t* b_cur, size_t b_stride) {
+        const ProveWs& w = I.w;
+        FinalArgs f;
+        memset(&f, 0, sizeof f);
+        f.count = 5;
+        const bool d_fold = n >= 1, t_fold = l >= 1;
+        // A, S, B, m, T in the order of the proof
+        f.p[0] = w.A; f.stride[0] = D; f.fold[0] = d_fold;
+        if (n <= 1) { f.p[1] = I.S.limbs; f.stride[1] = I.S.stride; }
+        else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
+        f.fold[1] = d_fold;
+        f.p[2] = b_cur; f.stride[2] = b_stride; f.fold[2] = t_fold;
+        f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
+        if (l <= 1) { f.p[4] = I.T.limbs; f.stride[4] = I.T.stride; }
+        else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
+        f.fold[4] = t_fold;
+        return f;
+    };
+    // A single proof runs all its small rounds in one resident kernel (k_tlookup_tail).
+    TlookupTailArgs tail;
+    int tail_first = -1;  // the round the resident kernel was launched for, if it is running
+    TailGuard tail_guard{mb, stream};
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
         const EqSplit eq = ep.round(k);
@@ -564,15 +611,51 @@ static int prove_core(const ProveCall& c) {
         const unsigned blocks = (unsigned)(half / span);
         if (blocks > inst[0].w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
 
-        const uint32_t seq = mb->next_seq();
-        for (size_t i = 0; i < K; ++i) {
+        if (small && K == 1 && tail_first < 0 && n - k <= kTailRoundsMax) {
+            // this and every later round in one launch
+            Instance& I = inst[0];
+            memset(&tail, 0, sizeof tail);
+            tail.A = PairArray{I.w.A, D, I.w.A, D};
+            tail.M = PairArray{I.w.M, N, I.w.M, N};
+            tail.beta = to_dev(beta);
+            tail.r_prev = to_dev(r_prev);
+            tail.nrounds = n - k;
+            uint32_t* b_at = I.b_cur;
+            size_t b_at_stride = I.b_cur_stride;
+            for (int j = k; j < n; ++j) {
+                TailRound& rd = tail.round[j - k];
+                Moving m = moving_arrays(j, I, b_at, b_at_stride);
+                rd.S = m.S;
+                rd.B = m.B;
+                rd.T = m.T;
+                rd.eq = ep.round(j);
+                rd.half = (size_t)1 << (n - j - 1);
+                rd.table = j < h ? 0 : j == h ? 1 : 2;
+            }
+            tail.fin = final_arrays(I, b_at, b_at_stride);
+            tail.out_words = I.words;
+            tail.words = mb->words;
+            tail.cmd = mb->cmd;
+            for (int j = 0; j <= tail.nrounds; ++j) tail.out_seq[j] = mb->next_seq();
+            for (int j = 0; j < tail.nrounds; ++j) tail.cmd_seq[j] = mb->next_cmd_seq();
+            tail.spin_limit = device_spin_limit();
+            {
+                ProfileScope prof(kProfRoundData, stream);
+                hipLaunchKernelGGL(k_tlookup_tail, dim3(1), dim3(kSmallThreads), 0, stream, tail);
+            }
+            ZK_HIP_TRY(hipGetLastError());
+            tail_guard.armed = true;
+            tail_first = k;
+        }
+        const uint32_t seq = tail_first >= 0 ? tail.out_seq[k - tail_first] : mb->next_seq();
+        for (size_t i = 0; i < K && tail_first < 0; ++i) {
             Instance& I = inst[i];
             ProveWs& w = I.w;
             const uint32_t my_seq = i + 1 == K ? seq : 0;  // the last instance's last launch publishes the round
+            const Moving mv = moving_arrays(k, I, I.b_cur, I.b_cur_stride);
             DataRoundArgs d;
             d.A = PairArray{w.A, D, w.A, D};
-            if (k <= 1) d.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
-            else d.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
+            d.S = mv.S;
             d.half = half;
             d.block_span = span;
             d.r_prev = to_dev(r_prev);
@@ -581,16 +664,8 @@ static int prove_core(const ProveCall& c) {
             d.partials = w.partD;
             d.pstride = w.part_blocks * 5;
             TableRoundArgs t;
-            // B alternates between its two buffers on every fold (it has two readers)
-            if (k > h) {
-                uint32_t* other = I.b_cur == w.B ? w.Bf : w.B;
-                size_t other_stride = I.b_cur == w.B ? N / 2 : N;
-                t.B = PairArray{I.b_cur, I.b_cur_stride, other, other_stride};
-            } else {
-                t.B = PairArray{I.b_cur, I.b_cur_stride, I.b_cur, I.b_cur_stride};
-            }
-            if (k <= h + 1) t.T = PairArray{I.T.limbs, I.T.stride, w.Tf, N / 2};
-            else t.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
+            t.B = mv.B;
+            t.T = mv.T;
             t.M = PairArray{w.M, N, w.M, N};
             t.half = half;
             t.block_span = span;
@@ -656,10 +731,6 @@ static int prove_core(const ProveCall& c) {
                                   mb->words, my_seq, w.flags + 1, stream);
             }
             ZK_HIP_TRY(hipGetLastError());
-            if (k > h) {
-                I.b_cur = t.B.dst;
-                I.b_cur_stride = t.B.ds;
-            }
         }
         lazy_rounds = use29 && !out32 ? lazy_rounds + 1 : 0;
         ZK_TRY(mailbox_wait(mb, seq, stream));
@@ -716,32 +787,26 @@ static int prove_core(const ProveCall& c) {
         cD = mul(cD, er);
         if (table_round) cT = mul(cT, er);
         r_prev = r;
+        if (tail_first >= 0) mailbox_send_challenge(mb, tail.cmd_seq[k - tail_first], to_dev(r).l);
     }
 
     // -- final claims -------------------------------------------------------------------------------------
     {
-        const uint32_t seq = mb->next_seq();
-        for (size_t i = 0; i < K; ++i) {
-            Instance& I = inst[i];
-            ProveWs& w = I.w;
-            FinalArgs f;
-            f.count = 5;
-            f.r = to_dev(r_prev);
-            const bool d_fold = n >= 1, t_fold = l >= 1;
-            // A, S, B, m, T in the order of the proof
-            f.p[0] = w.A; f.stride[0] = D; f.fold[0] = d_fold;
-            if (n <= 1) { f.p[1] = I.S.limbs; f.stride[1] = I.S.stride; }
-            else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
-            f.fold[1] = d_fold;
-            f.p[2] = I.b_cur; f.stride[2] = I.b_cur_stride; f.fold[2] = t_fold;
-            f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
-            if (l <= 1) { f.p[4] = I.T.limbs; f.stride[4] = I.T.stride; }
-            else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
-            f.fold[4] = t_fold;
-            hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, I.words, mb->words, i + 1 == K ? seq : 0);
+        if (tail_first >= 0) {
+            // the resident kernel writes them after the last challenge
+            ZK_TRY(mailbox_wait(mb, tail.out_seq[tail.nrounds], stream));
+            tail_guard.armed = false;
+        } else {
+            const uint32_t seq = mb->next_seq();
+            for (size_t i = 0; i < K; ++i) {
+                Instance& I = inst[i];
+                FinalArgs f = final_arrays(I, I.b_cur, I.b_cur_stride);
+                f.r = to_dev(r_prev);
+                hipLaunchKernelGGL(k_final_values, dim3(1), dim3(64), 0, stream, f, I.words, mb->words, i + 1 == K ? seq : 0);
+            }
+            ZK_HIP_TRY(hipGetLastError());
+            ZK_TRY(mailbox_wait(mb, seq, stream));
         }
-        ZK_HIP_TRY(hipGetLastError());
-        ZK_TRY(mailbox_wait(mb, seq, stream));
         ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device
         read_table_consts();
         uint8_t* first = out;

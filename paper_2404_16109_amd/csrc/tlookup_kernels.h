@@ -776,6 +776,156 @@ static __global__ void __launch_bounds__(kSmallThreads) k_round_small(DataRoundA
     if (threadIdx.x == 0) mailbox_publish(words, seq);
 }
 
+// Final values: each of up to five arrays is either a single entry or a pair
+// still to be bound to the last challenge.  Value q goes to out_words[8q..8q+8);
+// `words` is the mailbox the flag lives in.
+struct FinalArgs {
+    const uint32_t* p[8];
+    size_t stride[8];
+    int fold[8];
+    int count;
+    Fr r;
+};
+
+// All the last rounds of one proof in one resident kernel: what k_round_small
+// does for one round, repeated, with each round's challenge received over the
+// host's command channel (a bounded wait) instead of as a launch argument, and
+// the five final values at the end.  What changes from round to round comes in
+// a small record per round.  Every thread takes every barrier; a wait that
+// fails ends the kernel for all of them.
+static const int kTailRoundsMax = 9;  // pairs go 256, 128, .., 1
+
+struct TailRound {
+    PairArray S, B, T;  // this round's sources and destinations (A and M fold in place)
+    EqSplit eq;
+    size_t half;
+    int table;          // as k_round_small's TABLE
+};
+
+struct TlookupTailArgs {
+    PairArray A, M;
+    Fr beta, r_prev;
+    TailRound round[kTailRoundsMax];
+    int nrounds;
+    FinalArgs fin;      // where the five arrays end up (fin.r is not used)
+    uint32_t* out_words;   // this proof's slot in the mailbox
+    uint32_t* words;       // the mailbox (flag)
+    const uint32_t* cmd;
+    uint32_t out_seq[kTailRoundsMax + 1];
+    uint32_t cmd_seq[kTailRoundsMax];
+    uint32_t spin_limit;
+};
+
+static __global__ void __launch_bounds__(kSmallThreads) k_tlookup_tail(TlookupTailArgs g) {
+    __shared__ uint32_t lds[12 * 6 * 8];
+    __shared__ uint32_t sh_r[8];
+    __shared__ int sh_ok;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int group = threadIdx.x >> 8;  // 0 data, 1 table T sums, 2 table m sums
+    const size_t p = threadIdx.x & 255;
+    Fr r = g.r_prev;
+    bool ok = true;
+    for (int i = 0; i < g.nrounds; ++i) {
+        const TailRound& rd = g.round[i];
+        const size_t lo_mask = ((size_t)1 << rd.eq.lbits) - 1;
+        Fr tot[6];
+#pragma unroll
+        for (int q = 0; q < 6; ++q) tot[q] = fr_zero();
+        if (group == 0) {
+            if (p < rd.half) {
+                DataRoundArgs d;
+                d.A = g.A;
+                d.S = rd.S;
+                d.half = rd.half;
+                d.block_span = 0;
+                d.r_prev = r;
+                d.beta = g.beta;
+                d.eq = rd.eq;
+                d.partials = nullptr;
+                d.pstride = 0;
+                WideInRegs wide;
+                wide.clear();
+                data_pair<true>(d, p, lo_mask, wide, tot[3], tot[4]);
+                tot[0] = wide.finish(0);
+                tot[1] = wide.finish(1);
+                tot[2] = wide.finish(2);
+            }
+        } else if (rd.table != 0 && p < rd.half) {
+            TableRoundArgs t;
+            t.B = rd.B;
+            t.T = rd.T;
+            t.M = g.M;
+            t.half = rd.half;
+            t.block_span = 0;
+            t.r_prev = r;
+            t.beta = g.beta;
+            t.eq = rd.eq;
+            t.partials = nullptr;
+            t.pstride = 0;
+            if (rd.table == 2) {
+                if (group == 1) table_pair<true, 1>(t, p, lo_mask, tot);
+                else table_pair<true, 2>(t, p, lo_mask, tot);
+            } else {
+                if (group == 1) table_pair<false, 1>(t, p, lo_mask, tot);
+                else table_pair<false, 2>(t, p, lo_mask, tot);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            tot[q] = wave_sum(tot[q]);
+            if (lane == 0) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) lds[(wave * 6 + q) * 8 + k] = tot[q].l[k];
+            }
+        }
+        __syncthreads();
+        // thread `slot` adds up output value `slot` over the four wavefronts of its group
+        // (see k_round_small)
+        const int slot = threadIdx.x;
+        if (slot < (rd.table != 0 ? 11 : 5)) {
+            const int gq = slot < 5 ? 0 : slot < 8 ? 1 : 2;
+            const int q = slot < 5 ? slot : slot - 5;
+            Fr acc = fr_zero();
+            for (int w = 4 * gq; w < 4 * gq + 4; ++w) {
+                Fr o;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) o.l[k] = lds[(w * 6 + q) * 8 + k];
+                acc = fr_add(acc, o);
+            }
+#pragma unroll
+            for (int k = 0; k < 8; ++k) g.out_words[8 * slot + k] = acc.l[k];
+            mailbox_written();
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            mailbox_publish(g.words, g.out_seq[i]);
+            uint32_t limbs[8];
+            const bool got = mailbox_receive_challenge(g.cmd, g.cmd_seq[i], g.spin_limit, limbs);
+            if (got) {
+#pragma unroll
+                for (int k = 0; k < 8; ++k) sh_r[k] = limbs[k];
+            }
+            sh_ok = got ? 1 : 0;
+        }
+        __syncthreads();  // the folded entries written in this round are visible to the workgroup from here on
+        ok = sh_ok != 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) r.l[k] = __builtin_amdgcn_readfirstlane(sh_r[k]);
+        __syncthreads();
+        if (!ok) break;  // the same for every thread
+    }
+    if (ok && threadIdx.x < (unsigned)g.fin.count) {
+        const int q = threadIdx.x;
+        Fr v = fr_load(g.fin.p[q], g.fin.stride[q], 0);
+        if (g.fin.fold[q]) v = fr_fold(v, fr_load(g.fin.p[q], g.fin.stride[q], 1), r);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) g.out_words[8 * q + k] = v.l[k];
+        mailbox_written();
+    }
+    __syncthreads();
+    if (ok && threadIdx.x == 0) mailbox_publish(g.words, g.out_seq[g.nrounds]);
+}
+
 // Sums over the whole table, before any of its variables is bound:
 //   c1 = sum_j e'_j B_j (T_j + beta),  c2 = sum_j B_j M_j,
 // with e'_j = lo[j & mask] * hi[j >> lbits].
@@ -807,17 +957,6 @@ static __global__ void __launch_bounds__(kBlock) k_table_const(TableConstArgs g)
         fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 2 + 1, tot[1]);
     }
 }
-
-// Final values: each of up to five arrays is either a single entry or a pair
-// still to be bound to the last challenge.  Value q goes to out_words[8q..8q+8);
-// `words` is the mailbox the flag lives in.
-struct FinalArgs {
-    const uint32_t* p[8];
-    size_t stride[8];
-    int fold[8];
-    int count;
-    Fr r;
-};
 
 static __global__ void k_final_values(FinalArgs g, uint32_t* out_words, uint32_t* words, uint32_t seq) {
     int q = threadIdx.x;
