@@ -395,6 +395,13 @@ int zkmi_profile_enable(int on);
 int zkmi_profile_reset(void);
 int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms);
 
+/* Self-test of the bounded wait in the kernels that stay resident over the last
+ * sumcheck rounds and receive each round's challenge from the host: such a kernel
+ * is started on a tiny input with a bound of a few polls and never answered.  ZK_OK
+ * if it published its first round, then gave up by itself and published nothing
+ * more; ZK_E_HIP otherwise.  ws: device, at least 1 KiB. */
+int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream);
+
 /* SHA-256 of `len` bytes at `data` (host) into out (host, 32 bytes): the hash
  * the transcript is built on, exported so that it can be checked on its own.
  * use_sha_instructions: 0 = the portable compression function, 1 = the x86 SHA

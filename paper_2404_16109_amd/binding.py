@@ -72,6 +72,7 @@ def _load():
     sigs = {
         "zkmi_version": (i32, []),
         "zkmi_sha256": (i32, [ctypes.c_char_p, sz, ctypes.c_char_p, i32]),
+        "zkmi_selftest_resident_wait": (i32, [vp, sz, vp]),
         "zkmi_profile_enable": (i32, [i32]),
         "zkmi_profile_reset": (i32, []),
         "zkmi_profile_query": (i32, [ctypes.c_char_p, P(ctypes.c_uint64), P(ctypes.c_double)]),
@@ -132,7 +133,7 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
+EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
@@ -206,6 +207,11 @@ def zkmi_sha256(data, use_sha_instructions=True):
     buf = bytes(data)
     rc = _lib.zkmi_sha256(buf, len(buf), out, 1 if use_sha_instructions else 0)
     return rc, out.raw
+
+
+def zkmi_selftest_resident_wait():
+    ws = _ws(4096)
+    return _lib.zkmi_selftest_resident_wait(ws.data_ptr(), ws.numel(), _stream())
 
 
 def zkmi_profile_enable(on):

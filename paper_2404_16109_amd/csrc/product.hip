@@ -693,6 +693,39 @@ static int matmul_prove_any(const uint8_t seed[32], fr_vec X, const int16_t* X16
     return product_rounds_run(tr, w.a, w.P1, w.b, w.P1, n1, nullptr, proof + 32, proof + 64, cv, mb, stream);
 }
 
+int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream_v) {
+    // The last rounds run in a kernel that waits for the host between rounds.  Here
+    // the host never answers: with a bound of a few polls the kernel must give up by
+    // itself, having published its first round's sums and nothing after them.
+    if (!ws || ws_bytes < 4 * 32 * 4 + 512) return ZK_E_BUFSZ;
+    hipStream_t stream = as_stream(stream_v);
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    Carver cv(ws, ws_bytes);
+    uint32_t* a = cv.limbs(4);
+    uint32_t* b = cv.limbs(4);
+    launch_fill_u32(a, 32, 1u, stream);
+    launch_fill_u32(b, 32, 1u, stream);
+    ProductTailArgs g;
+    memset(&g, 0, sizeof g);
+    g.a = a; g.as = 4; g.b = b; g.bs = 4;
+    g.half0 = 2;
+    g.nrounds = 2;
+    g.fold_first = 0;
+    g.r_prev = to_dev(host::zero());
+    g.words = mb->words;
+    g.cmd = mb->cmd;
+    for (int i = 0; i <= g.nrounds; ++i) g.out_seq[i] = mb->next_seq();
+    for (int i = 0; i < g.nrounds; ++i) g.cmd_seq[i] = mb->next_cmd_seq();
+    g.spin_limit = 8;
+    hipLaunchKernelGGL(k_product_tail, dim3(1), dim3(kTailThreads), 0, stream, g);
+    ZK_HIP_TRY(hipGetLastError());
+    ZK_TRY(mailbox_wait(mb, g.out_seq[0], stream));          // the first round's sums arrive
+    ZK_HIP_TRY(hipStreamSynchronize(stream));                 // and the kernel ends without an answer
+    const uint32_t flag = mb->words[kMailboxFlag];
+    return flag == g.out_seq[0] ? ZK_OK : ZK_E_HIP;           // nothing was published after them
+}
+
 int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1, fr_vec W, size_t D2, uint8_t* proof,
                           size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream) {
     return matmul_prove_any(seed, X, nullptr, D0, D1, W, nullptr, D2, proof, cap, len, ws, ws_bytes, stream);

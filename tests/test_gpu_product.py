@@ -101,3 +101,17 @@ def test_matmul_i16_extreme_values(zk, orc):
         rc, got = zk.matmul_sumcheck_prove_i16(seed, torch.from_numpy(X.astype(np.int16)).cuda(),
                                                torch.from_numpy(W.astype(np.int16)).cuda())
         assert rc == 0 == rc_o and got == want
+
+
+def test_resident_kernel_gives_up_when_the_host_is_silent(zk, orc):
+    """The bounded wait of the kernels that receive challenges from the host, forced
+    from the host side: a tiny bound, no answer; the kernel ends by itself.  A proof
+    made right after it is unaffected."""
+    assert zk.zkmi_selftest_resident_wait() == zk.ZK_OK
+    rng = random.Random(99)
+    a = [rng.randrange(R) for _ in range(64)]
+    b = [rng.randrange(R) for _ in range(64)]
+    claim = sum(x * y for x, y in zip(a, b)) % R
+    va, vb = zk.vec_from_bytes(orc.to_bytes(a)), zk.vec_from_bytes(orc.to_bytes(b))
+    rc, proof = zk.sumcheck_prove_product(b"\x03" * 32, va, vb, claim)
+    assert rc == 0 and zk.sumcheck_verify_product(b"\x03" * 32, proof, 64)[0] == 0
