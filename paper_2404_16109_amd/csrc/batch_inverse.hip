@@ -16,6 +16,18 @@ namespace zkmi {
 
 static const int kBiK = 16;  // elements per thread per level
 
+// A level can be the concatenation of two vectors (the tensor and the table of a
+// lookup, inverted in one go): elements from n1 on belong to the second, which
+// has its own source and its own prefix/result buffer.  n1 is a multiple of the
+// elements one workgroup covers, so a workgroup lies in one of them.
+struct BiSecond {
+    const uint32_t* src;
+    size_t ss;
+    uint32_t* p;
+    size_t ps;
+    size_t n1;  // SIZE_MAX: no second vector
+};
+
 __device__ __forceinline__ Fr bi_load(const uint32_t* __restrict__ src, size_t ss, size_t i, bool shifted,
                                       const Fr& shift) {
     Fr x = fr_load(src, ss, i);
@@ -26,9 +38,19 @@ __device__ __forceinline__ Fr bi_load(const uint32_t* __restrict__ src, size_t s
 // thread's total goes to next[tid].
 __global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__ src, size_t ss, size_t n, int shifted,
                                                     Fr shift, uint32_t* __restrict__ prefix, size_t ps,
-                                                    uint32_t* __restrict__ next, size_t ns) {
+                                                    uint32_t* __restrict__ next, size_t ns, BiSecond second) {
     size_t tid = blockIdx.x * (size_t)kBlock + threadIdx.x;
     size_t base = blockIdx.x * (size_t)kBlock * kBiK + threadIdx.x;
+    if (blockIdx.x * (size_t)kBlock * kBiK >= second.n1) {  // the whole workgroup is in the second vector
+        src = second.src;
+        ss = second.ss;
+        prefix = second.p;
+        ps = second.ps;
+        base -= second.n1;
+        n -= second.n1;
+    } else if (n > second.n1) {
+        n = second.n1;
+    }
     Fr acc = fr_one();
     bool first = true;
     for (int j = 0; j < kBiK; ++j) {
@@ -47,9 +69,21 @@ __global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__
 __global__ void __launch_bounds__(kBlock) k_bi_up(const uint32_t* __restrict__ src, size_t ss, size_t n, int shifted,
                                                   Fr shift, const uint32_t* prefix, size_t ps,
                                                   const uint32_t* __restrict__ inv_next, size_t is, uint32_t* out,
-                                                  size_t os) {
+                                                  size_t os, BiSecond second) {
     size_t tid = blockIdx.x * (size_t)kBlock + threadIdx.x;
     size_t base = blockIdx.x * (size_t)kBlock * kBiK + threadIdx.x;
+    if (blockIdx.x * (size_t)kBlock * kBiK >= second.n1) {  // prefix and out are the same buffer (see batch_inverse_end)
+        src = second.src;
+        ss = second.ss;
+        prefix = second.p;
+        ps = second.ps;
+        out = second.p;
+        os = second.ps;
+        base -= second.n1;
+        n -= second.n1;
+    } else if (n > second.n1) {
+        n = second.n1;
+    }
     Fr inv = fr_load(inv_next, is, tid);
     for (int j = kBiK - 1; j >= 0; --j) {
         size_t i = base + (size_t)j * kBlock;
@@ -143,14 +177,28 @@ size_t batch_inverse_scratch_bytes(size_t n) {
     return cv.used();
 }
 
+static BiSecond bi_second_of(const BatchInverseJob& job, int depth) {
+    if (depth == 0 && job.n2) return BiSecond{job.src2, job.src2_stride, job.dst2, job.dst2_stride, job.lv[0].n - job.n2};
+    return BiSecond{nullptr, 0, nullptr, 0, SIZE_MAX};
+}
+
+bool batch_inverse_can_join(size_t n1) { return n1 % ((size_t)kBlock * kBiK) == 0; }
+
 int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride,
                         size_t n, const host::F& shift, Carver& cv, uint32_t* total_words, uint32_t* flag_words,
-                        uint32_t seq, hipStream_t stream) {
+                        uint32_t seq, hipStream_t stream, uint32_t* dst2, size_t dst2_stride, const uint32_t* src2,
+                        size_t src2_stride, size_t n2) {
     typedef BatchInverseJob::Level Level;
+    if (n2 && !batch_inverse_can_join(n)) return ZK_E_BADARG;
     job.depth = 0;
     job.shift = to_dev(shift);
+    job.n2 = n2;
+    job.src2 = src2;
+    job.src2_stride = src2_stride;
+    job.dst2 = dst2;
+    job.dst2_stride = dst2_stride;
     int shifted0 = host::is_zero(shift) ? 0 : 1;
-    job.lv[0] = Level{src, src_stride, dst, dst_stride, n, shifted0};
+    job.lv[0] = Level{src, src_stride, dst, dst_stride, n + n2, shifted0};
     while (job.lv[job.depth].n > (size_t)kBlock) {
         size_t m = bi_next_size(job.lv[job.depth].n);
         uint32_t* x = cv.limbs(m);
@@ -158,10 +206,11 @@ int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, 
         if (!x || !p) return ZK_E_BUFSZ;
         const Level& cur = job.lv[job.depth];
         hipLaunchKernelGGL(k_bi_down, dim3((unsigned)(m / kBlock)), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n,
-                           cur.shifted, job.shift, cur.p, cur.ps, x, m);
+                           cur.shifted, job.shift, cur.p, cur.ps, x, m, bi_second_of(job, job.depth));
         ++job.depth;
         job.lv[job.depth] = Level{x, m, p, m, m, 0};
     }
+    if (n2 && job.depth == 0) return ZK_E_BADARG;  // a joined vector is longer than one workgroup's share
     const Level& top = job.lv[job.depth];
     hipLaunchKernelGGL(k_bi_top_total, dim3(1), dim3(kBlock), 0, stream, top.x, top.xs, top.n, top.shifted, job.shift,
                        total_words, flag_words, seq);
@@ -178,7 +227,7 @@ int batch_inverse_end(const BatchInverseJob& job, const host::F& inv_total, hipS
         const Level& cur = job.lv[d];
         const Level& up = job.lv[d + 1];
         hipLaunchKernelGGL(k_bi_up, dim3((unsigned)(up.n / kBlock)), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n,
-                           cur.shifted, job.shift, cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps);
+                           cur.shifted, job.shift, cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps, bi_second_of(job, d));
     }
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
@@ -190,7 +239,7 @@ int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, siz
     BatchInverseJob job;
     uint32_t seq = mb->next_seq();
     ZK_TRY(batch_inverse_begin(job, dst, dst_stride, src, src_stride, n, shift, cv, mb->words + kMailboxInvA, mb->words,
-                               seq, stream));
+                               seq, stream, nullptr, 0, nullptr, 0, 0));
     ZK_TRY(mailbox_wait(mb, seq, stream));
     host::F total = from_dev(mb->words + kMailboxInvA);
     if (host::is_zero(total)) return ZK_E_ZERO_DENOM;

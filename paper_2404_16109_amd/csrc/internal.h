@@ -28,10 +28,20 @@ struct BatchInverseJob {
     Level lv[16];
     int depth = 0;
     Fr shift;
+    // a second vector inverted together with the first (its elements follow the first's)
+    size_t n2 = 0;
+    const uint32_t* src2 = nullptr;
+    size_t src2_stride = 0;
+    uint32_t* dst2 = nullptr;
+    size_t dst2_stride = 0;
 };
+// src2 (n2 elements, may be none: n2 = 0) is inverted into dst2 by the same passes,
+// shifted like src; needs batch_inverse_can_join(n) and scratch for n + n2 elements.
+bool batch_inverse_can_join(size_t n);
 int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride,
                         size_t n, const host::F& shift, Carver& cv, uint32_t* total_words, uint32_t* flag_words,
-                        uint32_t seq, hipStream_t stream);
+                        uint32_t seq, hipStream_t stream, uint32_t* dst2, size_t dst2_stride, const uint32_t* src2,
+                        size_t src2_stride, size_t n2);
 int batch_inverse_end(const BatchInverseJob& job, const host::F& inv_total, hipStream_t stream);
 
 // ---- sums -----------------------------------------------------------------

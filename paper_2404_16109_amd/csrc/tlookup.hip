@@ -213,7 +213,10 @@ static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
         carve_prove(w, cv, D, N);
     }
     cv.limbs(EqPool::entries(log2_floor(D)));
-    for (size_t i = 0; i < K; ++i) cv.take(batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N));
+    for (size_t i = 0; i < K; ++i) {
+        size_t apart = batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N), joined = batch_inverse_scratch_bytes(D + N);
+        cv.take(apart > joined ? apart : joined);
+    }
     return cv.used();
 }
 
@@ -421,32 +424,48 @@ static int prove_core(const ProveCall& c) {
     for (size_t i = 0; i < K; ++i)
         hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, inst[i].w.M, N, inst[i].w.m, N);
     if (!c.by_rows) {
-        // all inversions share one wait: the down passes of every B and A, one round
-        // trip, one host inversion (of the product of all grand totals), the up passes
+        // all inversions share one wait: the down passes, one round trip, one host
+        // inversion (of the product of all grand totals), the up passes.  The table
+        // is inverted together with the tensor, as one vector, whenever the tensor's
+        // length allows (its small passes then cost nothing of their own).
         ProfileScope prof(kProfInverse, stream);
         Carver inv_cv = cv;
         const uint32_t seq = mb->next_seq();
+        const bool joined = batch_inverse_can_join(D) && D > (size_t)kBlock;
+        BatchInverseJob* jobs[2 * kMailboxMaxInstances];
+        const uint32_t* totals[2 * kMailboxMaxInstances];
+        size_t njobs = 0;
         for (size_t i = 0; i < K; ++i) {
             Instance& I = inst[i];
-            ZK_TRY(batch_inverse_begin(I.job_b, I.w.B, N, I.T.limbs, I.T.stride, N, beta, inv_cv, I.inv_words, mb->words, 0,
-                                       stream));
-            ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
-                                       mb->words, i + 1 == K ? seq : 0, stream));
+            const uint32_t last = i + 1 == K ? seq : 0;
+            if (joined) {
+                ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
+                                           mb->words, last, stream, I.w.B, N, I.T.limbs, I.T.stride, N));
+            } else {
+                ZK_TRY(batch_inverse_begin(I.job_b, I.w.B, N, I.T.limbs, I.T.stride, N, beta, inv_cv, I.inv_words, mb->words,
+                                           0, stream, nullptr, 0, nullptr, 0, 0));
+                jobs[njobs] = &I.job_b;
+                totals[njobs++] = I.inv_words;
+                ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
+                                           mb->words, last, stream, nullptr, 0, nullptr, 0, 0));
+            }
+            jobs[njobs] = &I.job_a;
+            totals[njobs++] = I.inv_words + 8;
         }
         ZK_TRY(mailbox_wait(mb, seq, stream));
         // inverse of each total from one inversion of their product
         F tot[2 * kMailboxMaxInstances], pre[2 * kMailboxMaxInstances + 1];
         pre[0] = one();
-        for (size_t q = 0; q < 2 * K; ++q) {
-            tot[q] = from_dev(inst[q / 2].inv_words + 8 * (q & 1));
+        for (size_t q = 0; q < njobs; ++q) {
+            tot[q] = from_dev(totals[q]);
             if (is_zero(tot[q])) return ZK_E_ZERO_DENOM;
             pre[q + 1] = mul(pre[q], tot[q]);
         }
-        F suffix_inv = inv(pre[2 * K]);  // 1 / (tot_0 ... tot_q) while walking down
-        for (size_t q = 2 * K; q-- > 0;) {
+        F suffix_inv = inv(pre[njobs]);  // 1 / (tot_0 ... tot_q) while walking down
+        for (size_t q = njobs; q-- > 0;) {
             F inv_q = mul(suffix_inv, pre[q]);
             suffix_inv = mul(suffix_inv, tot[q]);
-            ZK_TRY(batch_inverse_end((q & 1) ? inst[q / 2].job_a : inst[q / 2].job_b, inv_q, stream));
+            ZK_TRY(batch_inverse_end(*jobs[q], inv_q, stream));
         }
     } else {
         // every S_i has been checked to equal T[idx_i]: invert the table side only
