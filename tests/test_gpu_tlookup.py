@@ -65,6 +65,24 @@ def test_proof_bytes_equal_oracle(zk, orc, D, N, dup):
     assert np.array_equal(zk.vec_to_bytes(Sv), Sb) and np.array_equal(zk.vec_to_bytes(Tv), Tb)
 
 
+def test_every_shape_up_to_2_pow_12(zk, orc):
+    """All pairs (D, N) of powers of two with N <= D <= 2^12 and a few larger ones with
+    tiny tables: every place where the path changes (which rounds run on 29-bit limbs
+    and where such a run of rounds starts and ends, where the resident kernel takes
+    over, whether table and tensor are inverted as one vector, which rounds bind table
+    variables) moves with the shape."""
+    rng = random.Random(4242)
+    shapes = [(1 << n, 1 << l) for n in range(13) for l in range(n + 1)]
+    shapes += [(1 << 18, 1), (1 << 18, 2), (1 << 19, 1 << 3), (1 << 16, 1 << 16), (1 << 14, 1 << 13)]
+    for D, N in shapes:
+        Sb, Tb, Sv, Tv, idx = _random_instance(orc, zk, rng, D, N, dup=(D + N) % 3 == 0)
+        seed = rng.randbytes(32)
+        rc_o, want, _ = orc.tlookup_prove(seed, Sb, Tb)
+        hints = idx if (D // N) % 2 == 0 else None
+        rc, got, _ = zk.tlookup_prove(seed, Sv, hints, Tv)
+        assert rc == 0 == rc_o and got == want, (D, N)
+
+
 def test_config1_range_check_prove_and_verify(zk, orc):
     cfg = synth.range_check_unsigned()
     Sb, Tb = oracle_table_and_tensor(orc, cfg)
