@@ -1,0 +1,159 @@
+"""The non-arithmetic part of LayerNorm (Section 6.1.3 of the paper) composed from
+the library's pieces, on the GPU: the per-row statistic V (the row's variance at
+full scale) goes through two lookups one after the other,
+  * downscaling:     V = gamma V' + R1,   R1  in  T_R = [-gamma/2, gamma/2),
+  * compound step:   (V', Y)  in  T_X + rho T_Y,   T_Y(x) = round(s / sqrt(x + 1)),
+the first keeping the second's table small, as in Example 4.2.  There is one
+value per row, so the tensors are far shorter than the tables: each is padded to
+its table's length with a value the table holds (Section 4 pads D to a multiple
+of N), the two lookups have different shapes and are proved one by one, and the
+downscaling is tied to them by the linear relation between the multilinear
+extensions at the first proof's point.  Each proof must equal the oracle's."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_16109_amd import synth
+
+pytestmark = pytest.mark.gpu
+R = synth.BLS12_381_R
+
+ROWS = 200          # not a power of two, and fewer than either table has rows
+LOG_GAMMA = 10      # the downscaling factor: T_R has 2^10 rows
+LOG_B = 12          # range of the downscaled statistic: the compound table has 2^12 rows
+SCALE = 1 << 12     # fixed-point scale of 1/sqrt
+
+
+@pytest.fixture(scope="module")
+def zk():
+    import paper_2404_16109_amd as zk
+    assert torch.cuda.is_available()
+    return zk
+
+
+def fr_of(zk, values):
+    v = zk.Vec(len(values))
+    assert zk.fr_from_i32(v, torch.from_numpy(np.asarray(values).astype(np.int32)).cuda()) == 0
+    return v
+
+
+def inv_sqrt_table():
+    x = np.arange(1 << LOG_B)
+    return np.floor(SCALE / np.sqrt(x + 1.0) + 0.5).astype(np.int64)
+
+
+def statistics(seed=7):
+    """Per-row variances at full scale (a chi-square-like spread), their downscaled
+    value, the remainder, and the looked-up 1/sqrt."""
+    gamma, B = 1 << LOG_GAMMA, 1 << LOG_B
+    g = synth.rounded_normal(seed, ROWS, 1 << 10, -(1 << 11), 1 << 11)
+    V = np.minimum(g * g, gamma * B - gamma)            # in [0, gamma B)
+    Vq = (V + gamma // 2) // gamma
+    R1 = V - gamma * Vq
+    assert Vq.min() >= 0 and Vq.max() < B and R1.min() >= -gamma // 2 and R1.max() < gamma // 2
+    return {"V": V, "Vq": Vq, "R1": R1, "Y": inv_sqrt_table()[Vq], "seed": synth.seed_bytes("lnorm")}
+
+
+def padded(values, n, fill):
+    out = np.full(n, fill, dtype=np.int64)
+    out[:len(values)] = values
+    return out
+
+
+def build(zk, t):
+    gamma, B = 1 << LOG_GAMMA, 1 << LOG_B
+    rho = synth.pair_combiner(t["seed"])
+    ty = inv_sqrt_table()
+    d = {"rho": rho}
+    # lookup 1: the remainders, padded with 0 (a row of T_R) to the table's length
+    d["D1"] = gamma
+    d["T1"] = fr_of(zk, np.arange(-gamma // 2, gamma // 2))
+    d["R1"] = fr_of(zk, padded(t["R1"], d["D1"], 0))
+    d["idx1"] = torch.from_numpy((padded(t["R1"], d["D1"], 0) + gamma // 2).astype(np.int32)).cuda()
+    d["V"] = fr_of(zk, padded(t["V"], d["D1"], 0))
+    d["Vq1"] = fr_of(zk, padded(t["Vq"], d["D1"], 0))
+    # lookup 2: the pairs (V', Y), padded with the table's first row (0, T_Y(0))
+    d["D2"] = B
+    d["T2"] = fr_of(zk, np.arange(B))
+    assert zk.fr_axpy(d["T2"], d["T2"], rho, fr_of(zk, ty)) == 0
+    d["Vq2"] = fr_of(zk, padded(t["Vq"], d["D2"], 0))
+    d["Y"] = fr_of(zk, padded(t["Y"], d["D2"], ty[0]))
+    d["S2"] = zk.Vec(d["D2"])
+    assert zk.fr_axpy(d["S2"], d["Vq2"], rho, d["Y"]) == 0
+    d["idx2"] = torch.from_numpy(padded(t["Vq"], d["D2"], 0).astype(np.int32)).cuda()
+    return d
+
+
+def prove_both(zk, orc, t, d, against_oracle=True):
+    out = []
+    for S, idx, T, D, tag in ((d["R1"], d["idx1"], d["T1"], d["D1"], b"/downscale"),
+                              (d["S2"], d["idx2"], d["T2"], d["D2"], b"/inv-sqrt")):
+        seed = bytes(a ^ b for a, b in zip(t["seed"], tag.ljust(32, b"\0")))
+        rc, proof, info = zk.tlookup_prove(seed, S, idx, T)
+        if rc != 0:
+            return rc, info, None
+        if against_oracle:
+            rc_o, want, _ = orc.tlookup_prove(seed, zk.vec_to_bytes(S), zk.vec_to_bytes(T))
+            assert rc_o == 0 and proof == want
+        rc, claims = zk.tlookup_verify(seed, proof, T, D, S=S)
+        assert rc == 0
+        out.append(claims)
+    return 0, None, out
+
+
+def openings_consistent(zk, d, claims):
+    gamma = 1 << LOG_GAMMA
+    c1, c2 = claims
+    ev = lambda vec, v: zk.fr_mle_eval(vec, v)[1]
+    downscaled = ev(d["V"], c1["v"]) == (gamma * ev(d["Vq1"], c1["v"]) + c1["S_v"]) % R
+    remainder = c1["S_v"] == ev(d["R1"], c1["v"])
+    paired = c2["S_v"] == (ev(d["Vq2"], c2["v"]) + d["rho"] * ev(d["Y"], c2["v"])) % R
+    return downscaled, remainder, paired
+
+
+def test_layernorm_lookups(zk, orc):
+    t = statistics()
+    d = build(zk, t)
+    # the two lookups have different shapes, the first with as many rows as entries
+    assert (d["D1"], d["T1"].n) == (1 << LOG_GAMMA, 1 << LOG_GAMMA) and (d["D2"], d["T2"].n) == (1 << LOG_B, 1 << LOG_B)
+    rc, _, claims = prove_both(zk, orc, t, d)
+    assert rc == 0
+    assert openings_consistent(zk, d, claims) == (True, True, True)
+
+
+def test_a_tensor_shorter_than_its_table_is_refused(zk):
+    """Without the padding the first lookup has 256 entries against 1024 rows."""
+    t = statistics()
+    gamma = 1 << LOG_GAMMA
+    short = fr_of(zk, padded(t["R1"], 256, 0))
+    T1 = fr_of(zk, np.arange(-gamma // 2, gamma // 2))
+    rc, proof, _ = zk.tlookup_prove(t["seed"], short, None, T1)
+    assert rc == zk.ZK_E_BADARG and proof == b""
+
+
+def test_layernorm_violations_are_caught(zk, orc):
+    t = statistics()
+    gamma = 1 << LOG_GAMMA
+    # (1) a wrong inverse square root: the pair is not a row of the compound table
+    bad = dict(t, Y=t["Y"].copy())
+    bad["Y"][3] += 1
+    d = build(zk, bad)
+    rc, info, _ = prove_both(zk, orc, bad, d, against_oracle=False)
+    assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 3
+    # (2) a remainder out of range, compensated in V' so that V = gamma V' + R1 still holds
+    j = int(np.argmax(t["Vq"] > 0))
+    bad = dict(t, R1=t["R1"].copy(), Vq=t["Vq"].copy())
+    bad["R1"][j] += gamma
+    bad["Vq"][j] -= 1
+    bad["Y"] = inv_sqrt_table()[bad["Vq"]]
+    d = build(zk, bad)
+    d["idx1"] = None                                   # no honest hint exists for it
+    rc, info, _ = prove_both(zk, orc, bad, d, against_oracle=False)
+    assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == j
+    # (3) both lookups fine but the downscaling wrong: only the linear check on the openings sees it
+    bad = dict(t, V=t["V"].copy())
+    bad["V"][5] += gamma
+    d = build(zk, bad)
+    rc, _, claims = prove_both(zk, orc, bad, d)
+    assert rc == 0
+    assert openings_consistent(zk, d, claims) == (False, True, True)
