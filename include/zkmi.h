@@ -397,9 +397,11 @@ int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms);
 
 /* Self-test of the bounded wait in the kernels that stay resident over the last
  * sumcheck rounds and receive each round's challenge from the host: such a kernel
- * is started on a tiny input with a bound of a few polls and never answered.  ZK_OK
- * if it published its first round, then gave up by itself and published nothing
- * more; ZK_E_HIP otherwise.  ws: device, at least 1 KiB. */
+ * is started on a tiny input with a bound of a few polls and never answered.  It
+ * must publish its first round, then give up by itself and publish nothing more.
+ * Then an abort is left in the channel, as a call that ends early leaves one, and
+ * the kernel is started again and answered: it must run to its end.  ZK_OK if
+ * both hold, ZK_E_HIP otherwise.  ws: device, at least 1 KiB. */
 int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream);
 
 /* SHA-256 of `len` bytes at `data` (host) into out (host, 32 bytes): the hash

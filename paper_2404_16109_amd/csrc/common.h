@@ -104,6 +104,10 @@ inline void mailbox_send_challenge(Mailbox* mb, uint32_t seq, const uint32_t lim
     __atomic_store_n(&mb->cmd[0], seq, __ATOMIC_RELEASE);
 }
 inline void mailbox_send_abort(Mailbox* mb) { __atomic_store_n(&mb->cmd[0], kCmdAbort, __ATOMIC_RELEASE); }
+// Before a resident kernel is launched: an abort left behind by an earlier call
+// that ended early must not reach it.  (No kernel of this thread's is listening
+// then: a call that aborts waits for its stream before it returns.)
+inline void mailbox_channel_reset(Mailbox* mb) { __atomic_store_n(&mb->cmd[0], 0u, __ATOMIC_RELEASE); }
 
 // Ends a resident kernel that is still waiting when the host leaves early.
 struct TailGuard {

@@ -211,6 +211,7 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         for (int i = 0; i <= g.nrounds; ++i) g.out_seq[i] = mb->next_seq();
         for (int i = 0; i < g.nrounds; ++i) g.cmd_seq[i] = mb->next_cmd_seq();
         g.spin_limit = device_spin_limit();
+        mailbox_channel_reset(mb);
         TailGuard guard{mb, stream};
         hipLaunchKernelGGL(k_product_tail, dim3(1), dim3(kTailThreads), 0, stream, g);
         ZK_HIP_TRY(hipGetLastError());
@@ -718,12 +719,32 @@ int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream_v) {
     for (int i = 0; i <= g.nrounds; ++i) g.out_seq[i] = mb->next_seq();
     for (int i = 0; i < g.nrounds; ++i) g.cmd_seq[i] = mb->next_cmd_seq();
     g.spin_limit = 8;
+    mailbox_channel_reset(mb);
     hipLaunchKernelGGL(k_product_tail, dim3(1), dim3(kTailThreads), 0, stream, g);
     ZK_HIP_TRY(hipGetLastError());
     ZK_TRY(mailbox_wait(mb, g.out_seq[0], stream));          // the first round's sums arrive
     ZK_HIP_TRY(hipStreamSynchronize(stream));                 // and the kernel ends without an answer
     const uint32_t flag = mb->words[kMailboxFlag];
-    return flag == g.out_seq[0] ? ZK_OK : ZK_E_HIP;           // nothing was published after them
+    if (flag != g.out_seq[0]) return ZK_E_HIP;                // nothing was published after them
+    // A call that ends early leaves an abort in the channel.  The next kernel must
+    // not see it: this one is answered and has to run to its end.
+    mailbox_send_abort(mb);
+    for (int i = 0; i <= g.nrounds; ++i) g.out_seq[i] = mb->next_seq();
+    for (int i = 0; i < g.nrounds; ++i) g.cmd_seq[i] = mb->next_cmd_seq();
+    g.spin_limit = device_spin_limit();
+    mailbox_channel_reset(mb);
+    TailGuard guard{mb, stream};
+    hipLaunchKernelGGL(k_product_tail, dim3(1), dim3(kTailThreads), 0, stream, g);
+    ZK_HIP_TRY(hipGetLastError());
+    guard.armed = true;
+    for (int i = 0; i < g.nrounds; ++i) {
+        ZK_TRY(mailbox_wait(mb, g.out_seq[i], stream));
+        mailbox_send_challenge(mb, g.cmd_seq[i], to_dev(host::one()).l);
+    }
+    ZK_TRY(mailbox_wait(mb, g.out_seq[g.nrounds], stream));
+    guard.armed = false;
+    ZK_HIP_TRY(hipStreamSynchronize(stream));
+    return ZK_OK;
 }
 
 int matmul_sumcheck_prove(const uint8_t seed[32], fr_vec X, size_t D0, size_t D1, fr_vec W, size_t D2, uint8_t* proof,

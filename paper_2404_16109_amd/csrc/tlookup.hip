@@ -658,6 +658,7 @@ static int prove_core(const ProveCall& c) {
             for (int j = 0; j <= tail.nrounds; ++j) tail.out_seq[j] = mb->next_seq();
             for (int j = 0; j < tail.nrounds; ++j) tail.cmd_seq[j] = mb->next_cmd_seq();
             tail.spin_limit = device_spin_limit();
+            mailbox_channel_reset(mb);
             {
                 ProfileScope prof(kProfRoundData, stream);
                 hipLaunchKernelGGL(k_tlookup_tail, dim3(1), dim3(kSmallThreads), 0, stream, tail);
