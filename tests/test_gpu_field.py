@@ -90,7 +90,7 @@ def test_empty_and_bad_arguments(zk):
     assert zk.fr_add(a, a, b) == zk.ZK_E_BADARG
 
 
-@pytest.mark.parametrize("n", [1, 2, 63, 256, 257, 4096, 4097, 70001])
+@pytest.mark.parametrize("n", [1, 2, 63, 256, 257, 1000, 1024, 1025, 4096, 4097, 16385, 70001, 300001])
 def test_batch_inverse(zk, orc, n):
     rng = random.Random(10 + n)
     x = [rng.randrange(1, R) for _ in range(n)]
@@ -104,6 +104,51 @@ def test_batch_inverse(zk, orc, n):
     assert np.array_equal(got, want)
     # a * a^-1 = 1 on every output
     assert orc.to_ints(orc.fr_mul(got, X)) == [1] * n
+
+
+@pytest.mark.parametrize("n", [(1 << 22) + 4097, 5 * (1 << 20) + 3, (1 << 24) + 1])
+def test_batch_inverse_long(zk, orc, n):
+    """Lengths whose reduction takes one, two and three levels below the first, the
+    last of them by whole workgroups with a ragged end.  Checked by the defining
+    property x * x^-1 = 1 on every element (the product is the library's, pinned
+    elsewhere against the oracle), and against the oracle on a sample."""
+    rng = random.Random(n)
+    raw = np.random.default_rng(n).integers(0, 256, size=(n, 32), dtype=np.uint8) & np.array([255] * 31 + [63], dtype=np.uint8)
+    X = zk.vec_from_bytes(raw)
+    out, prod = zk.Vec(n), zk.Vec(n)
+    assert zk.fr_batch_inverse(out, X) == 0
+    assert zk.fr_mul(prod, out, X) == 0
+    got = zk.vec_to_bytes(prod)
+    one = np.zeros(32, dtype=np.uint8)
+    one[0] = 1
+    assert np.array_equal(got, np.broadcast_to(one, (n, 32)))
+    pick = sorted({0, 1, 255, 256, 4095, 4096, n - 1, n - 2, n - 4097} | {rng.randrange(n) for _ in range(200)})
+    rc_o, want = orc.fr_inv(np.ascontiguousarray(raw[pick]))
+    assert rc_o == 0 and np.array_equal(zk.vec_to_bytes(out)[pick], want)
+
+
+def test_batch_inverse_two_levels_of_threads(zk, orc):
+    """2^26 + 4097 elements: the level below the first is still too long for whole
+    workgroups.  Inputs are small integers made on the device; every product
+    x * x^-1 must be the field's one, compared on the device, and a sample of the
+    inverses must equal the oracle's."""
+    import torch
+    n = (1 << 26) + 4097
+    g = torch.Generator(device="cuda")
+    g.manual_seed(26)
+    ints = torch.randint(1, 2 ** 31 - 1, (n,), dtype=torch.int32, device="cuda", generator=g)
+    X, out = zk.Vec(n), zk.Vec(n)
+    assert zk.fr_from_i32(X, ints) == 0
+    assert zk.fr_batch_inverse(out, X) == 0
+    assert zk.fr_mul(X, out, X) == 0
+    one = zk.Vec(1)
+    assert zk.fr_from_i32(one, torch.ones(1, dtype=torch.int32, device="cuda")) == 0
+    assert bool((X.data[:, :n] == one.data[:, :1]).all())
+    pick = torch.tensor(sorted({0, 4095, 4096, n - 1, n - 4098} | {(i * 7919 * 4099) % n for i in range(100)}), device="cuda")
+    sample = zk.Vec(len(pick))
+    sample.data.copy_(out.data[:, pick])
+    rc_o, want = orc.fr_inv(orc.to_bytes([int(v) for v in ints[pick].cpu()]))
+    assert rc_o == 0 and np.array_equal(zk.vec_to_bytes(sample), want)
 
 
 def test_batch_inverse_reports_zero(zk, orc):
