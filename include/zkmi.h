@@ -336,7 +336,10 @@ int matmul_sumcheck_verify(const uint8_t seed[32], const uint8_t* proof, size_t 
  *                                  + alpha e~(u,x) (Y(x) - prod_k Y^(k)(x))
  *                                  + alpha^2 e~(u_rows, x_rows) Y(x) ],
  * degree K+1 per variable, round polynomials sent as values at X = 0..K+1, row
- * variables bound first.  1 <= K <= ZKATTN_LINK_MAX_K.
+ * variables bound first.  1 <= K <= ZKATTN_LINK_MAX_K.  (Z' and the X^(k) are read
+ * by the first round and once more at the end: their combination is the zero
+ * polynomial once the first round has passed, so the later rounds do without them
+ * and their values at the final point are evaluated from the tensors directly.)
  *
  * Transcript: SHA256("zkmi/zkattn-link/v1" || seed || LE64 rows || LE64 cols ||
  * LE64 K || B^(0..K-1)); u_t = challenge("u"); absorb("yhat", yhat~(u_rows));
@@ -370,6 +373,23 @@ size_t zkattn_link_workspace_bytes(size_t rows, size_t cols, size_t K);
 int zkattn_link_prove(const uint8_t seed[32], fr_vec Zp, const fr_vec* X, fr_vec Y, const fr_vec* Yk, fr_vec yhat,
                       const fr_t* bases, size_t rows, size_t cols, size_t K, uint8_t* proof, size_t cap, size_t* len,
                       void* ws, size_t ws_bytes, void* stream);
+
+/* The same proof, byte for byte, from the tensors as the integers they are
+ * quantised to (Section 3.3: tensors enter the field by scaling and rounding;
+ * until the first challenge binds a variable they are still small): Zp int64,
+ * X^(k) and Y^(k) uint32, Y uint64, row-major device arrays of rows*cols entries;
+ * X, Yk: host arrays of K device pointers; bases: host, K integers in [1, 2^32).
+ * The first round checks the relations entry by entry as integers and multiplies
+ * weights by integers (16 multiply-adds, no reduction until the end of a sum);
+ * the second folds integers straight into reduced field elements; from the third
+ * round on the path is zkattn_link_prove's.  Ranges: |Zp|, Y < 2^62; Y^(k) below
+ * 2^32 - 1, 2^30, 2^18 for K = 1, 2, 3 (so that products of K extrapolated
+ * factors fit 63 bits); rows*cols >= 4.  ZK_E_BADARG if an entry is out of range,
+ * ZK_E_REJECT if one breaks a relation or yhat is not the row sums.  Workspace
+ * and proof size as for zkattn_link_prove.  Synchronises the stream. */
+int zkattn_link_prove_small(const uint8_t seed[32], const int64_t* Zp, const uint32_t* const* X, const uint64_t* Y,
+                            const uint32_t* const* Yk, fr_vec yhat, const uint64_t* bases, size_t rows, size_t cols,
+                            size_t K, uint8_t* proof, size_t cap, size_t* len, void* ws, size_t ws_bytes, void* stream);
 
 /* Verifier: replays the transcript, checks every round and the last claim against
  * the summand at the final point built from the stated values, and recomputes

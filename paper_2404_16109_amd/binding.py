@@ -119,6 +119,8 @@ def _load():
         "matmul_sumcheck_verify": (i32, [vp, vp, sz, sz, sz, sz, fr_vec, fr_vec, fr_vec, vp, sz, vp]),
         "zkattn_link_proof_bytes": (sz, [sz, sz, sz]),
         "zkattn_link_workspace_bytes": (sz, [sz, sz, sz]),
+        "zkattn_link_prove_small": (i32, [vp, vp, P(vp), vp, P(vp), fr_vec, P(ctypes.c_uint64), sz, sz, sz, vp, sz, P(sz),
+                                          vp, sz, vp]),
         "zkattn_link_prove": (i32, [vp, fr_vec, P(fr_vec), fr_vec, P(fr_vec), fr_vec, P(fr_t), sz, sz, sz, vp, sz, P(sz),
                                     vp, sz, vp]),
         "zkattn_link_verify_workspace_bytes": (sz, [sz, sz]),
@@ -142,7 +144,8 @@ EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_p
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
            "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove", "matmul_sumcheck_prove_i16",
            "matmul_verify_workspace_bytes", "matmul_sumcheck_verify", "zkattn_link_proof_bytes",
-           "zkattn_link_workspace_bytes", "zkattn_link_prove", "zkattn_link_verify_workspace_bytes",
+           "zkattn_link_workspace_bytes", "zkattn_link_prove", "zkattn_link_prove_small",
+           "zkattn_link_verify_workspace_bytes",
            "zkattn_link_verify"]
 
 
@@ -552,6 +555,26 @@ def zkattn_link_prove(seed, Zp, X, Y, Yk, yhat, bases, rows, cols, ws=None, cap=
     Bv = (fr_t * K)(*[_fr(b) for b in bases])
     rc = _lib.zkattn_link_prove(_seed(seed), Zp.c, Xv, Y.c, Yv, yhat.c, Bv, rows, cols, K, proof, cap, ctypes.byref(ln),
                                 ws.data_ptr(), ws.numel(), _stream())
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b""
+
+
+def zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, bases, rows, cols, ws=None, cap=None):
+    """The tensors as integers on the device: Zp int64, Y int64 (read as unsigned),
+    X and Yk lists of K int32 tensors (read as unsigned); yhat: Vec; bases: K
+    integers below 2^32.  Returns (rc, proof bytes)."""
+    K = len(X)
+    assert len(Yk) == K and len(bases) == K
+    assert Zp.dtype == torch.int64 and Y.dtype == torch.int64 and all(t.dtype == torch.int32 for t in list(X) + list(Yk))
+    assert all(t.is_contiguous() and t.numel() >= rows * cols for t in [Zp, Y] + list(X) + list(Yk))
+    ws = ws if ws is not None else _ws(zkattn_link_workspace_bytes(rows, cols, K))
+    cap = zkattn_link_proof_bytes(rows, cols, K) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    Xv = (ctypes.c_void_p * K)(*[x.data_ptr() for x in X])
+    Yv = (ctypes.c_void_p * K)(*[y.data_ptr() for y in Yk])
+    Bv = (ctypes.c_uint64 * K)(*[int(b) for b in bases])
+    rc = _lib.zkattn_link_prove_small(_seed(seed), Zp.data_ptr(), Xv, Y.data_ptr(), Yv, yhat.c, Bv, rows, cols, K, proof,
+                                      cap, ctypes.byref(ln), ws.data_ptr(), ws.numel(), _stream())
     return rc, proof.raw[:ln.value] if rc == ZK_OK else b""
 
 

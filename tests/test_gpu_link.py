@@ -82,6 +82,120 @@ def test_attention_shaped_instance(zk, orc):
     assert rc == zk.ZK_OK and got == want
 
 
+def small_witness(gen, rows, cols, K, digit_bits, out_bits):
+    """The relations' tensors as integers: digits, per-segment tables of out_bits-bit outputs,
+    their product, the negated recomposed score and the row sums."""
+    D = rows * cols
+    bases = [1 << (digit_bits * k) for k in range(K)]
+    X = [gen.integers(0, 1 << digit_bits, D) for _ in range(K)]
+    tables = [gen.integers(0, 1 << out_bits, 1 << digit_bits) for _ in range(K)]
+    Yk = [tables[k][X[k]] for k in range(K)]
+    Y = np.ones(D, dtype=np.int64)
+    for k in range(K):
+        Y = Y * Yk[k]
+    Zp = -sum(bases[k] * X[k] for k in range(K))
+    yhat = [sum(int(v) for v in row) for row in Y.reshape(rows, cols)]  # may pass 2^63
+    return Zp.astype(np.int64), X, Y, Yk, yhat, bases
+
+
+def small_on_device(zk, orc, w):
+    Zp, X, Y, Yk, yhat, bases = w
+    i64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int64)).cuda()
+    u32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).cuda()
+    yh = zk.vec_from_bytes(orc.to_bytes(yhat))
+    return i64(Zp), [u32(a) for a in X], i64(Y), [u32(a) for a in Yk], yh, bases
+
+
+def small_oracle_proof(orc, seed, w, rows, cols):
+    Zp, X, Y, Yk, yhat, bases = w
+    to = lambda a: orc.fr_from_i64(np.asarray(a, dtype=np.int64))
+    return orc.zkattn_link_prove(seed, to(Zp), [to(a) for a in X], to(Y), [to(a) for a in Yk], orc.to_bytes(yhat),
+                                 orc.to_bytes(bases), rows, cols)
+
+
+@pytest.mark.parametrize("rows,cols,K,digit_bits,out_bits", [
+    (2, 2, 2, 4, 8), (1, 4, 1, 8, 31), (4, 1, 2, 8, 16), (1, 1024, 2, 8, 16), (1024, 1, 2, 8, 16), (8, 512, 2, 16, 16),
+    (64, 64, 1, 8, 20), (32, 128, 3, 5, 17), (512, 2, 3, 4, 9), (16, 4096, 2, 16, 29), (4, 16384, 2, 12, 16)])
+def test_integer_tensors_give_the_same_proof(zk, orc, rows, cols, K, digit_bits, out_bits):
+    gen = np.random.default_rng(rows * 131 + cols * 7 + K)
+    w = small_witness(gen, rows, cols, K, digit_bits, out_bits)
+    seed = bytes(gen.integers(0, 256, 32, dtype=np.uint8))
+    rc_o, want, _ = small_oracle_proof(orc, seed, w, rows, cols)
+    assert rc_o == 0
+    Zp, X, Y, Yk, yhat, bases = small_on_device(zk, orc, w)
+    rc, got = zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, bases, rows, cols)
+    assert rc == zk.ZK_OK and got == want
+    # the same bytes as from the tensors as field elements
+    to = lambda a: zk.vec_from_bytes(orc.fr_from_i64(np.asarray(a, dtype=np.int64)))
+    rc, again = zk.zkattn_link_prove(seed, to(w[0]), [to(a) for a in w[1]], to(w[2]), [to(a) for a in w[3]], yhat, bases,
+                                     rows, cols)
+    assert rc == zk.ZK_OK and again == got
+
+
+def test_integer_tensors_extreme_values(zk, orc):
+    """Entries at the ends of the ranges the integer path is written for: scores near
+    -2^61 (a base of 2^32 - 1 against digits up to 2^29), segment outputs of 2^30 - 1
+    against zero (the extrapolated factors change sign)."""
+    rows, cols, K = 8, 64, 2
+    D = rows * cols
+    gen = np.random.default_rng(99)
+    bases = [1, (1 << 32) - 1]
+    X = [gen.integers(0, 1 << 32, D), gen.integers(0, 1 << 29, D)]
+    Yk = [gen.choice([0, 1, (1 << 30) - 1], D), gen.choice([0, 1, (1 << 30) - 1], D)]
+    Y = Yk[0] * Yk[1]
+    Zp = -(X[0] + bases[1] * X[1])
+    assert Zp.min() > -(1 << 62) and Y.max() < (1 << 62)
+    yhat_int = [sum(int(v) for v in row) for row in Y.reshape(rows, cols)]
+    w = (Zp, X, Y, Yk, None, bases)
+    seed = b"\x42" * 32
+    to = lambda a: orc.fr_from_i64(np.asarray(a, dtype=np.int64))
+    rc_o, want, _ = orc.zkattn_link_prove(seed, to(Zp), [to(a) for a in X], to(Y), [to(a) for a in Yk],
+                                          orc.to_bytes(yhat_int), orc.to_bytes(bases), rows, cols)
+    assert rc_o == 0
+    i64 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int64)).cuda()
+    u32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint32).view(np.int32)).cuda()
+    yh = zk.vec_from_bytes(orc.to_bytes(yhat_int))
+    rc, got = zk.zkattn_link_prove_small(seed, i64(Zp), [u32(a) for a in X], i64(Y), [u32(a) for a in Yk], yh, bases,
+                                         rows, cols)
+    assert rc == zk.ZK_OK and got == want
+
+
+def test_integer_tensors_refusals(zk, orc):
+    gen = np.random.default_rng(7)
+    rows, cols, K = 16, 256, 2
+    w = small_witness(gen, rows, cols, K, 8, 16)
+    seed = b"\x11" * 32
+    Zp, X, Y, Yk, yhat, bases = small_on_device(zk, orc, w)
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, bases, rows, cols)[0] == zk.ZK_OK
+    D = rows * cols
+
+    def altered(t, pos, delta):
+        c = t.clone()
+        c[pos] += delta
+        return c
+    # each relation broken in one entry, anywhere in the tensor (both halves of the first round's pairs)
+    for pos in (0, D // 2 - 1, D // 2, D - 1):
+        assert zk.zkattn_link_prove_small(seed, altered(Zp, pos, 1), X, Y, Yk, yhat, bases, rows, cols)[0] == zk.ZK_E_REJECT
+        assert zk.zkattn_link_prove_small(seed, Zp, [X[0], altered(X[1], pos, 1)], Y, Yk, yhat, bases, rows, cols)[0] == zk.ZK_E_REJECT
+        assert zk.zkattn_link_prove_small(seed, Zp, X, altered(Y, pos, 1), Yk, yhat, bases, rows, cols)[0] == zk.ZK_E_REJECT
+        assert zk.zkattn_link_prove_small(seed, Zp, X, Y, [altered(Yk[0], pos, 1), Yk[1]], yhat, bases, rows, cols)[0] == zk.ZK_E_REJECT
+    # wrong row sums: seen where the first round's polynomial is compared with the claim
+    bad_sums = list(w[4])
+    bad_sums[3] += 1
+    yh = zk.vec_from_bytes(orc.to_bytes(bad_sums))
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yh, bases, rows, cols)[0] == zk.ZK_E_REJECT
+    # out of range: a segment output of 2^30 with two segments, a score beyond 2^62
+    big = Yk[0].clone()
+    big[5] = 1 << 30
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, [big, Yk[1]], yhat, bases, rows, cols)[0] == zk.ZK_E_BADARG
+    assert zk.zkattn_link_prove_small(seed, altered(Zp, 9, -(1 << 62)), X, Y, Yk, yhat, bases, rows, cols)[0] == zk.ZK_E_BADARG
+    # arguments
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, [1, 0], rows, cols)[0] == zk.ZK_E_BADARG
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, [1, 1 << 32], rows, cols)[0] == zk.ZK_E_BADARG
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, bases, 1, 2)[0] == zk.ZK_E_BADARG   # fewer than four entries
+    assert zk.zkattn_link_prove_small(seed, Zp, X, Y, Yk, yhat, bases, rows, cols, cap=10)[0] == zk.ZK_E_BUFSZ
+
+
 def test_broken_relations_are_refused(zk, orc):
     rng = random.Random(21)
     rows, cols, K = 16, 256, 2
