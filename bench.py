@@ -23,7 +23,6 @@ sys.path.insert(0, ROOT)
 
 PEAK_MAD_PER_S = 256 * 64 * 2.4e9      # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit multiply-add per lane per clock
 MADS_PER_FR_MUL = 112                   # 64 for the 8x8-limb product + 48 for the reduction (two of r's limbs need no multiplier)
-ROUND_DATA_FR_MUL_FIRST = 2             # first round: only the leading coefficient, A (S+beta) = 1 gives the rest
 ROUND_DATA_FR_MUL_PER_PAIR_EVAL = 5     # two to weight A0, A1, three products
 ROUND_DATA_FR_MUL_PER_PAIR_FOLD = 4     # two arrays, two folded entries per pair
 
@@ -32,31 +31,15 @@ def fr_mul_model(D, N):
     return 10 * D + 10 * N
 
 
-def round_data_fr_mul(D):
-    """Field multiplications the data-side round kernel needs over one prove:
-    round k has D/2^(k+1) pairs; the first round needs 2 per pair, every later
-    round 5 to evaluate and 4 to fold."""
-    n = D.bit_length() - 1
-    total = 0
-    for k in range(n):
-        pairs = D >> (k + 1)
-        if k == 0:
-            total += ROUND_DATA_FR_MUL_FIRST * pairs
-        else:
-            total += (ROUND_DATA_FR_MUL_PER_PAIR_EVAL + ROUND_DATA_FR_MUL_PER_PAIR_FOLD) * pairs
-    return total
+def rounds_on_29_bits(D, N):
+    """The rounds the dominant kernel (k_round_data29) runs: after the first, before
+    the table's variables, while more than 256 pairs remain."""
+    n, h = D.bit_length() - 1, (D // N).bit_length() - 1
+    return [k for k in range(1, h) if (D >> (k + 1)) > 256]
 
 
-def round_data_bytes(D):
-    """HBM bytes the data-side round kernel has to move over one prove: round 0
-    reads A and S (2 x 32 B x D); round k >= 1 reads 2^(n-k+1) entries of each
-    and writes half as many."""
-    n = D.bit_length() - 1
-    total = 2 * 32 * D
-    for k in range(1, n):
-        entries = D >> (k - 1)
-        total += 2 * 32 * entries + 2 * 32 * (entries // 2)
-    return total
+def round29_pairs(D, N):
+    return sum(D >> (k + 1) for k in rounds_on_29_bits(D, N))
 
 
 def measured_traffic():
@@ -403,13 +386,19 @@ def main():
         torch.cuda.synchronize()
         ms_rows = (time.perf_counter() - t0) * 1e3 / args.steps
     phases = {}
-    for name in ("total", "count", "inverse", "round_data", "round_table"):
+    for name in ("total", "count", "inverse", "round_data", "round_table", "round_data29"):
         rc, recs, total_ms = zk.zkmi_profile_query(name)
         phases[name] = {"records": recs, "ms_per_step": total_ms / args.steps}
-    rd = phases["round_data"]
+    # round_data: every round kernel with a data side, the dominant one (round_data29) included
+    phases["round_data"] = {"records": phases["round_data"]["records"] + phases["round_data29"]["records"],
+                            "ms_per_step": phases["round_data"]["ms_per_step"] + phases["round_data29"]["ms_per_step"]}
+    # the dominant kernel: k_round_data29, one launch per large folding round
+    rd = phases["round_data29"]
     launches = rd["records"] / args.steps
     avg_launch_s = rd["ms_per_step"] * 1e-3 / max(launches, 1)
-    mads_per_launch = round_data_fr_mul(D) * MADS_PER_FR_MUL / max(launches, 1)
+    pairs29 = round29_pairs(D, N)
+    mads_per_launch = pairs29 * (ROUND_DATA_FR_MUL_PER_PAIR_EVAL + ROUND_DATA_FR_MUL_PER_PAIR_FOLD) * MADS_PER_FR_MUL / max(launches, 1)
+    bytes_per_launch = pairs29 * 12 * 32 / max(launches, 1)  # per pair: four entries of A and of S read, two of each written
     achieved = mads_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
     out = {
         "metric": "tlookup_prove Fr-mul/s at D=2^%d, N=2^%d (wall ms in ms_per_step)" % (args.logD, args.logN),
@@ -423,12 +412,12 @@ def main():
                    "D": D, "N": N, "proof_bytes": len(proof), "fr_mul_model": fr_mul_model(D, N)},
         "phases_ms": {k: round(v["ms_per_step"], 4) for k, v in phases.items()},
         "by_rows_ms_per_step": ms_rows,
-        "roofline": {"bound": "alu", "kernel": "round kernels (k_round_data0, k_round_data29, k_round_both, k_round_small)",
+        "roofline": {"bound": "alu", "kernel": "k_round_data29 (the large folding rounds, %d launches per prove)" % len(rounds_on_29_bits(D, N)),
                      "achieved": achieved / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
                      "frac": achieved / PEAK_MAD_PER_S, "traffic": measured_traffic(),
                      "launches_per_step": launches, "avg_launch_ms": avg_launch_s * 1e3,
-                     "algorithmic_bytes_per_launch": round_data_bytes(D) / max(launches, 1),
-                     "hbm_GBps_algorithmic": round_data_bytes(D) / (rd["ms_per_step"] * 1e-3) / 1e9 if rd["ms_per_step"] else 0.0},
+                     "algorithmic_bytes_per_launch": bytes_per_launch,
+                     "hbm_GBps_algorithmic": bytes_per_launch / avg_launch_s / 1e9 if avg_launch_s > 0 else 0.0},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_logD, min(args.logN, args.cpu_logD))

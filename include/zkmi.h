@@ -406,8 +406,10 @@ int zkattn_link_verify(const uint8_t seed[32], const uint8_t* proof, size_t len,
  * on the caller's stream (so that kernels are timed where they are launched).
  * State is per host thread.  Phases: "total" (a whole tlookup_prove call),
  * "count" (multiplicities and digest leaves), "inverse" (both batch inversions),
- * "round_data" (the data-side round kernel alone, one record per launch),
- * "round_table" (the table-side round kernel alone).
+ * "round_data29" (the large folding rounds, which run on 29-bit limbs: one
+ * record per launch of that kernel), "round_data" (every other round kernel
+ * launch with a data side, one record each), "round_table" (the table-side
+ * round kernel alone).
  * zkmi_profile_query returns the number of records and their summed duration in
  * milliseconds; call it after the stream has been synchronised.  Unknown phase:
  * ZK_E_BADARG. */

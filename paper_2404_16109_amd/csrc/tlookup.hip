@@ -730,7 +730,7 @@ static int prove_core(const ProveCall& c) {
                 d29.partials = d.partials;
                 d29.pstride = d.pstride;
                 {
-                    ProfileScope prof(kProfRoundData, stream);
+                    ProfileScope prof(kProfRound29, stream);
                     if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (in32) hipLaunchKernelGGL((k_round_data29<true, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (out32) hipLaunchKernelGGL((k_round_data29<false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
