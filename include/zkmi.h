@@ -55,7 +55,7 @@ enum {
     ZK_E_BADARG = -1,       /* null pointer, bad size, D or N not a power of two, N > D */
     ZK_E_NOT_IN_TABLE = -2, /* some S_i is not an entry of T */
     ZK_E_ZERO_DENOM = -3,   /* an element to invert is zero (beta + S_i = 0 or beta + T_j = 0) */
-    ZK_E_REJECT = -4,       /* verifiers only: the proof does not verify */
+    ZK_E_REJECT = -4,       /* verifiers: the proof does not verify; zkattn_link_prove*: the tensors break a relation */
     ZK_E_BUFSZ = -5,        /* proof buffer or workspace too small */
     ZK_E_HIP = -6           /* a HIP runtime call failed */
 };
