@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libzkmi.so")
 SOURCES = ["field_ops.hip", "poly.hip", "batch_inverse.hip", "tlookup.hip", "product.hip", "zkattn_link.hip"]
-FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall",
+FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wshadow", "-Werror=shadow",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -433,11 +433,11 @@ __global__ void __launch_bounds__(64) k_rowdot_i16(uint32_t* __restrict__ raw_ou
 #pragma unroll
     for (int r = 0; r < kRowsPerWave; ++r) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint64_t v = acc[r][j];
+        for (int limb = 0; limb < 8; ++limb) {
+            uint64_t v = acc[r][limb];
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
-            acc[r][j] = v;
+            acc[r][limb] = v;
         }
     }
     if (threadIdx.x == 0) {
@@ -447,7 +447,7 @@ __global__ void __launch_bounds__(64) k_rowdot_i16(uint32_t* __restrict__ raw_ou
             uint32_t raw[kRawLimbs];
             small_normalize(raw, acc[r]);
 #pragma unroll
-            for (int j = 0; j < kRawLimbs; ++j) raw_out[(size_t)j * P1 + k0 + r] = raw[j];
+            for (int limb = 0; limb < kRawLimbs; ++limb) raw_out[(size_t)limb * P1 + k0 + r] = raw[limb];
         }
     }
 }

@@ -663,16 +663,16 @@ static int link_prove_k(const uint8_t seed[32], fr_vec Zp, const fr_vec* X, fr_v
 
         F L0 = from_dev(mb->words), L1 = from_dev(mb->words + 8);
         F Q[NPTS];
-        for (int X = 0; X <= K; ++X) Q[X] = from_dev(mb->words + 8 * (2 + X));
+        for (int pt = 0; pt <= K; ++pt) Q[pt] = from_dev(mb->words + 8 * (2 + pt));
         Q[K + 1] = extrapolate_next(Q, K + 1);
         F s0 = from_dev(mb->words + 8 * (K + 3)), s1 = from_dev(mb->words + 8 * (K + 4));
         F gX[NPTS];
         F e = sub(one(), u[t]), de = sub(u[t], e);  // e~(u_t, X) = (1-u_t) + X (2 u_t - 1)
         F L = L0, dL = sub(L1, L0), s = s0, ds = sub(s1, s0);
-        for (int X = 0; X < NPTS; ++X) {
+        for (int pt = 0; pt < NPTS; ++pt) {
             F ce = mul(c, e);
             F wy = t < nr ? ce : c_rows;
-            gX[X] = add(mul(ce, sub(L, mul(alpha, Q[X]))), mul(alpha, mul(wy, s)));
+            gX[pt] = add(mul(ce, sub(L, mul(alpha, Q[pt]))), mul(alpha, mul(wy, s)));
             e = add(e, de);
             L = add(L, dL);
             s = add(s, ds);
@@ -681,7 +681,7 @@ static int link_prove_k(const uint8_t seed[32], fr_vec Zp, const fr_vec* X, fr_v
             ZK_HIP_TRY(hipStreamSynchronize(stream));
             return ZK_E_REJECT;  // the tensors do not satisfy the relations
         }
-        for (int X = 0; X < NPTS; ++X) to_bytes(out + 32 * X, gX[X]);
+        for (int pt = 0; pt < NPTS; ++pt) to_bytes(out + 32 * pt, gX[pt]);
         tr.absorb("g", out, 32 * NPTS);
         out += 32 * NPTS;
         const F r = tr.challenge("r");
