@@ -109,6 +109,21 @@ int fr_batch_inverse(fr_vec dst, fr_vec src, void* ws, size_t ws_bytes, void* st
 size_t fr_sum_workspace_bytes(size_t n);
 int fr_sum(fr_t* out, fr_vec a, void* ws, size_t ws_bytes, void* stream);
 
+/* fr_sum for callers that cannot allocate or wait: code under HIP graph capture,
+ * serving loops that must not call hipMalloc, harnesses that forbid it.  Takes
+ * no workspace and allocates nothing, on the device or on the host, in any call:
+ * the per-workgroup partial sums live in an array of 32 KiB that is part of the
+ * library's image on every GPU it runs on (held until the process ends).  It only
+ * enqueues two kernels on `stream` and returns; the sum arrives in out (DEVICE
+ * memory, 8 uint32_t: the canonical integer, least significant word first) when
+ * the stream reaches that point.  a.n may be 0 (the sum is zero) and at most
+ * FR_SUM_NOALLOC_MAX, else ZK_E_BADARG.  All calls on one GPU share the one
+ * array (nothing in it needs clearing between calls: a call only reads what it
+ * has written), so calls that overlap on one GPU, on different streams or from
+ * different threads, race; calls on one stream are ordered and safe. */
+#define FR_SUM_NOALLOC_MAX ((size_t)1 << 28)
+int fr_sum_noalloc(uint32_t* out, fr_vec a, void* stream);
+
 /* dst_x = e~(u, x) = prod_t (u_t x_t + (1-u_t)(1-x_t)) for all x in
  * {0,1}^nvars (Section 3.3; the product, which restricts to the equality
  * indicator on bits).  u: host, nvars elements; dst.n = 2^nvars. */

@@ -90,6 +90,7 @@ def _load():
         "fr_batch_inverse": (i32, [fr_vec, fr_vec, vp, sz, vp]),
         "fr_sum_workspace_bytes": (sz, [sz]),
         "fr_sum": (i32, [P(fr_t), fr_vec, vp, sz, vp]),
+        "fr_sum_noalloc": (i32, [vp, fr_vec, vp]),
         "fr_eq_table": (i32, [fr_vec, P(fr_t), i32, vp]),
         "fr_mle_eval_workspace_bytes": (sz, [i32]),
         "fr_mle_eval": (i32, [P(fr_t), fr_vec, P(fr_t), i32, vp, sz, vp]),
@@ -137,7 +138,7 @@ def _load():
 _lib = _load()
 EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
-           "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_eq_table", "fr_mle_eval_workspace_bytes",
+           "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_sum_noalloc", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
            "tlookup_prove_by_rows", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
            "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
@@ -292,6 +293,12 @@ def fr_sum(a, ws=None):
     out = fr_t()
     rc = _lib.fr_sum(ctypes.byref(out), a.c, ws.data_ptr(), ws.numel(), _stream())
     return rc, _fr_int(out)
+
+
+def fr_sum_noalloc(out, a):
+    """out: int32 cuda tensor of 8 words, written when the current stream gets there."""
+    assert out.is_cuda and out.is_contiguous() and out.numel() * out.element_size() == 32
+    return _lib.fr_sum_noalloc(out.data_ptr(), a.c, _stream())
 
 
 def fr_eq_table(dst, u):

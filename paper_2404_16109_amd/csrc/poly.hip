@@ -1,5 +1,7 @@
 // Sums, eq tables, folding and multilinear evaluation (Section 3.3 of the paper:
 // tensors as functions on the Boolean cube and their multilinear extensions).
+#include <mutex>
+
 #include "internal.h"
 #include "reduce_dev.h"
 
@@ -92,6 +94,50 @@ int sum_run(const uint32_t* a, size_t stride, size_t n, Carver& cv, Mailbox* mb,
     launch_final_sum(partials, kMaxPartialBlocks, blocks, 1, mb->words, mb->words, seq, ticket, stream);
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
+}
+
+// ---- the sum for callers that cannot allocate ---------------------------------------
+//
+// fr_sum_noalloc keeps its per-workgroup partial sums in an array that is part of
+// the library's image on every GPU instead of in a workspace.  The array's name
+// is only a handle on the host: the address kernels can use is asked for once per
+// device (hipGetSymbolAddress with that device current) and kept.
+
+static const unsigned kStaticSumBlocks = 1024;
+static __device__ __align__(256) uint32_t scratch[kStaticSumBlocks * 8];  // 32 KiB on every GPU the library runs on
+
+static const int kStaticMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static uint32_t* g_scratch_ptr[kStaticMaxDevices];  // device address of `scratch`, per device
+
+static int scratch_of_current_device(uint32_t** out) {
+    int dev = -1;
+    ZK_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kStaticMaxDevices) return ZK_E_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return ZK_E_HIP;
+        g_scratch_ptr[dev] = (uint32_t*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ZK_OK;
+}
+
+// Adds up nblocks partial sums (limb-major, stride pstride) and writes the total
+// as the canonical integer, eight little-endian words, to out (device memory).
+__global__ void __launch_bounds__(kFinalThreads) k_sum_finish_canonical(const uint32_t* __restrict__ partials,
+                                                                        size_t pstride, unsigned nblocks,
+                                                                        uint32_t* __restrict__ out) {
+    __shared__ uint32_t lds[16 * 8];
+    Fr acc[1] = {fr_zero()};
+    for (unsigned b = threadIdx.x; b < nblocks; b += kFinalThreads) acc[0] = fr_add(acc[0], fr_load(partials, pstride, b));
+    block_sum<1, 16>(acc, lds);
+    if (threadIdx.x == 0) {
+        const Fr c = fr_from_mont(acc[0]);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) out[k] = c.l[k];
+    }
 }
 
 // ---- eq tables ----------------------------------------------------------------
@@ -231,6 +277,24 @@ int fr_sum(fr_t* out, fr_vec a, void* ws, size_t ws_bytes, void* stream) {
     ZK_TRY(mailbox_wait(mb, seq, as_stream(stream)));
     ZK_HIP_TRY(hipStreamSynchronize(as_stream(stream)));
     *out = host::to_canonical(from_dev(mb->words));
+    return ZK_OK;
+}
+
+int fr_sum_noalloc(uint32_t* out, fr_vec a, void* stream) {
+    if (!out || a.n > FR_SUM_NOALLOC_MAX || (a.n && !vec_ok(a, a.n))) return ZK_E_BADARG;
+    uint32_t* partials = nullptr;
+    ZK_TRY(scratch_of_current_device(&partials));
+    // every workgroup writes its partial sum before the closing kernel reads exactly
+    // that many: nothing in the array has to start at zero
+    unsigned blocks = 0;
+    if (a.n) {
+        blocks = grid_for(a.n, kBlock * 8, kStaticSumBlocks);
+        hipLaunchKernelGGL(k_sum_partial, dim3(blocks), dim3(kBlock), 0, as_stream(stream), a.limbs, a.stride, a.n, partials,
+                           (size_t)kStaticSumBlocks);
+    }
+    hipLaunchKernelGGL(k_sum_finish_canonical, dim3(1), dim3(kFinalThreads), 0, as_stream(stream), partials,
+                       (size_t)kStaticSumBlocks, blocks, out);
+    ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
 }
 
