@@ -141,6 +141,8 @@ void oracle_m_digest(uint8_t out[32], const uint64_t* m, uint64_t N) {
     m_digest(out, mv);
 }
 
+void oracle_vec_digest(uint8_t out[32], const uint8_t* v, uint64_t n, int threads) { vec_digest(out, as_fr(v), n, threads); }
+
 uint64_t oracle_tlookup_proof_bytes(uint64_t D) { return tlookup_proof_bytes(log2_exact(D)); }
 
 // aux: beta | alpha | sum_A | sum_mB (4 x 32 bytes); u_out, v_out: log2(D) elements each.

@@ -247,6 +247,14 @@ def m_digest(m):
     return out.tobytes()
 
 
+def vec_digest(v, threads=None):
+    """Digest of a vector of field elements (canonical bytes, n a power of two)."""
+    v = _c(v).reshape(-1, 32)
+    out = np.zeros(32, dtype=np.uint8)
+    lib().oracle_vec_digest(_p(out), _p(v), _u64(v.shape[0]), threads or default_threads())
+    return out.tobytes()
+
+
 def tlookup_proof_bytes(D):
     return int(lib().oracle_tlookup_proof_bytes(_u64(D)))
 

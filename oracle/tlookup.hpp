@@ -20,11 +20,16 @@
 //   * a round polynomial (degree <= 3) is sent as its values at X = 0,1,2,3;
 //   * the commitments of Protocol 1 are outside this build: the seed stands in
 //     for the commitments of T and S, a digest of m for the commitment of m,
-//     nothing stands in for the commitments of A and B;
+//     digests of A and B for theirs.  Message order is Protocol 1's: m is sent
+//     before beta is drawn, A and B after beta and before the sumcheck, so that
+//     alpha, u and every round challenge depend on them;
 //   * digest of m: counts as 32-bit little-endian words, cut into leaves of
-//     128 counts, leaf digests concatenated and hashed once more.
+//     128 counts, leaf digests concatenated and hashed once more;
+//   * digest of a vector of field elements (vec_digest below): a hash tree over
+//     the elements' canonical bytes.
 //
-// Proof bytes: "ZKTL" | u32 version=1 | LE64 D | LE64 N | digest(m) (32)
+// Proof bytes: "ZKTL" | u32 version=2 | LE64 D | LE64 N | digest(m) (32)
+//              | digest(A) (32) | digest(B) (32)
 //              | n x [g(0) g(1) g(2) g(3)] | A~(v) S~(v) B~(v') m~(v') T~(v')
 // with every field element as 32 little-endian bytes of its canonical integer,
 // n = log2 D and v' = v_[h:].
@@ -48,7 +53,10 @@ enum {
 
 static const size_t M_LEAF = 128;
 
-inline size_t tlookup_proof_bytes(int n) { return 56 + (size_t)n * 128 + 160; }
+static const size_t VEC_LEAF = 128;     // elements per leaf of vec_digest
+static const size_t TLOOKUP_HEADER = 120;  // magic, version, D, N and the three digests
+
+inline size_t tlookup_proof_bytes(int n) { return TLOOKUP_HEADER + (size_t)n * 128 + 160; }
 
 // m_j by counting.  Returns OK or E_NOT_IN_TABLE (then *bad_index is the
 // smallest i with S_i outside T).
@@ -105,9 +113,40 @@ inline void m_digest(uint8_t out[32], const std::vector<uint64_t>& m) {
     leaves.digest(out);
 }
 
+// Digest of a vector of n field elements (n a power of two), the stand-in for
+// its commitment.  With L = max(1, n / 128) leaves, leaf i is the SHA-256 of the
+// canonical bytes of elements i, i + L, i + 2L, ... in that order (128 of them,
+// or all n when n < 128).  The leaf digests are then hashed upward: consecutive
+// digests in groups of four (the two that are left, if only two are) give the
+// next row, until one digest remains.
+inline void vec_digest(uint8_t out[32], const Fr* v, size_t n, int threads = 1) {
+    const size_t L = n / VEC_LEAF ? n / VEC_LEAF : 1;
+    std::vector<uint8_t> row(32 * L);
+    parallel_ranges(L, std::max(1, threads), [&](size_t lo, size_t hi, int) {
+        for (size_t i = lo; i < hi; ++i) {
+            Bytes leaf;
+            for (size_t x = i; x < n; x += L) {
+                uint8_t b[32];
+                fr_to_bytes(b, v[x]);
+                leaf.raw(b, 32);
+            }
+            leaf.digest(&row[32 * i]);
+        }
+    });
+    size_t count = L;
+    while (count > 1) {
+        const size_t group = count >= 4 ? 4 : 2;
+        std::vector<uint8_t> next(32 * (count / group));
+        for (size_t i = 0; i < count / group; ++i) sha256(&next[32 * i], &row[32 * group * i], 32 * group);
+        row.swap(next);
+        count /= group;
+    }
+    memcpy(out, row.data(), 32);
+}
+
 inline Transcript tlookup_transcript(const uint8_t seed[32], uint64_t D, uint64_t N) {
     Bytes init;
-    init.str("zkmi/tlookup/v1").raw(seed, 32).le64(D).le64(N);
+    init.str("zkmi/tlookup/v2").raw(seed, 32).le64(D).le64(N);
     return Transcript(init);
 }
 
@@ -175,6 +214,13 @@ inline int tlookup_prove(const uint8_t seed[32], const Fr* S_in, uint64_t D, con
     for (uint64_t i = 0; i < D; ++i) sum_A = fr_add(sum_A, A[i]);
     for (uint64_t j = 0; j < N; ++j) sum_mB = fr_add(sum_mB, fr_mul(M[j], B[j]));
 
+    // The prover sends A and B (their digests here) before the sumcheck starts.
+    uint8_t dA[32], dB[32];
+    vec_digest(dA, A.data(), D, threads);
+    vec_digest(dB, B.data(), N, threads);
+    tr.absorb("A", dA, 32);
+    tr.absorb("B", dB, 32);
+
     Fr alpha = tr.challenge("alpha");
     Fr alpha2 = fr_mul(alpha, alpha);
     std::vector<Fr> u(n);
@@ -189,11 +235,13 @@ inline int tlookup_prove(const uint8_t seed[32], const Fr* S_in, uint64_t D, con
     // Header.
     uint8_t* out = proof;
     memcpy(out, "ZKTL", 4);
-    out[4] = 1; out[5] = out[6] = out[7] = 0;
+    out[4] = 2; out[5] = out[6] = out[7] = 0;
     for (int i = 0; i < 8; ++i) out[8 + i] = (uint8_t)(D >> (8 * i));
     for (int i = 0; i < 8; ++i) out[16 + i] = (uint8_t)(N >> (8 * i));
     memcpy(out + 24, md, 32);
-    out += 56;
+    memcpy(out + 56, dA, 32);
+    memcpy(out + 88, dB, 32);
+    out += TLOOKUP_HEADER;
 
     // Rounds.
     int workers = std::max(1, threads);
@@ -276,7 +324,7 @@ inline int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, uint64_t
     int h = n - l;
     auto fail = [&](int s) { if (stage) *stage = s; return (int)E_REJECT; };
     if (len != tlookup_proof_bytes(n)) return fail(1);
-    if (memcmp(proof, "ZKTL", 4) != 0 || proof[4] != 1 || proof[5] || proof[6] || proof[7]) return fail(1);
+    if (memcmp(proof, "ZKTL", 4) != 0 || proof[4] != 2 || proof[5] || proof[6] || proof[7]) return fail(1);
     uint64_t Dp = 0, Np = 0;
     for (int i = 0; i < 8; ++i) { Dp |= (uint64_t)proof[8 + i] << (8 * i); Np |= (uint64_t)proof[16 + i] << (8 * i); }
     if (Dp != D || Np != N) return fail(1);
@@ -285,13 +333,15 @@ inline int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, uint64_t
     size_t nfr = (size_t)4 * n + 5;
     std::vector<Fr> el(nfr);
     for (size_t i = 0; i < nfr; ++i) {
-        el[i] = fr_from_bytes(proof + 56 + 32 * i);
+        el[i] = fr_from_bytes(proof + TLOOKUP_HEADER + 32 * i);
         if (!fr_is_canonical(el[i])) return fail(1);
     }
 
     Transcript tr = tlookup_transcript(seed, D, N);
     tr.absorb("m", proof + 24, 32);
     Fr beta = tr.challenge("beta");
+    tr.absorb("A", proof + 56, 32);
+    tr.absorb("B", proof + 88, 32);
     Fr alpha = tr.challenge("alpha");
     Fr alpha2 = fr_mul(alpha, alpha);
     std::vector<Fr> u(n), v(n);
@@ -317,8 +367,18 @@ inline int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, uint64_t
 
     if (!fr_eq(mle_eval(T, l, v.data() + h, threads), c.T_vp)) return fail(4);
     if (S && !fr_eq(mle_eval(S, n, v.data(), threads), c.S_v)) return fail(4);
-    if (A && !fr_eq(mle_eval(A, n, v.data(), threads), c.A_v)) return fail(4);
-    if (B && !fr_eq(mle_eval(B, l, v.data() + h, threads), c.B_vp)) return fail(4);
+    // A and B, when given, must also be the vectors whose digests the proof carries
+    uint8_t dv[32];
+    if (A) {
+        if (!fr_eq(mle_eval(A, n, v.data(), threads), c.A_v)) return fail(4);
+        vec_digest(dv, A, D, threads);
+        if (memcmp(dv, proof + 56, 32) != 0) return fail(4);
+    }
+    if (B) {
+        if (!fr_eq(mle_eval(B, l, v.data() + h, threads), c.B_vp)) return fail(4);
+        vec_digest(dv, B, N, threads);
+        if (memcmp(dv, proof + 88, 32) != 0) return fail(4);
+    }
     if (m_counts) {
         std::vector<Fr> M(N);
         for (uint64_t j = 0; j < N; ++j) M[j] = fr_from_u64(m_counts[j]);

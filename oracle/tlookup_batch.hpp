@@ -9,24 +9,27 @@
 // with f_k the tlookup summand of instance k (Section 4, second form of the
 // identity) and lambda one more challenge.  All rounds share their challenges.
 //
-// Transcript: SHA256("zkmi/tlookup-batch/v1" || seed || LE64 D || LE64 N || LE64 K);
+// Transcript: SHA256("zkmi/tlookup-batch/v2" || seed || LE64 D || LE64 N || LE64 K);
 // absorb("m", digest(m_k)) for k = 0..K-1; beta = challenge("beta");
+// absorb("A", digest(A_k)), absorb("B", digest(B_k)) for k = 0..K-1 (Protocol 1's
+// order: the inverse vectors are sent after beta and before the sumcheck);
 // alpha = challenge("alpha"); u_t = challenge("u"), t = 0..n-1;
 // lambda = challenge("lambda"); per round absorb("g", 4 values), r = challenge("r");
 // absorb("final", K x 5 claims).
 //
-// Proof bytes: "ZKTB" | u32 version=1 | LE64 D | LE64 N | LE64 K | K x digest(m_k)
+// Proof bytes: "ZKTB" | u32 version=2 | LE64 D | LE64 N | LE64 K | K x digest(m_k)
+//              | K x [digest(A_k) digest(B_k)]
 //              | n x [g(0) g(1) g(2) g(3)] | K x [A~(v) S~(v) B~(v') m~(v') T~(v')].
 #pragma once
 #include "tlookup.hpp"
 
 namespace oracle {
 
-inline size_t tlookup_batch_proof_bytes(int n, uint64_t K) { return 32 + 32 * K + (size_t)n * 128 + 160 * K; }
+inline size_t tlookup_batch_proof_bytes(int n, uint64_t K) { return 32 + 96 * K + (size_t)n * 128 + 160 * K; }
 
 inline Transcript tlookup_batch_transcript(const uint8_t seed[32], uint64_t D, uint64_t N, uint64_t K) {
     Bytes init;
-    init.str("zkmi/tlookup-batch/v1").raw(seed, 32).le64(D).le64(N).le64(K);
+    init.str("zkmi/tlookup-batch/v2").raw(seed, 32).le64(D).le64(N).le64(K);
     return Transcript(init);
 }
 
@@ -51,7 +54,7 @@ inline int tlookup_batch_prove(const uint8_t seed[32], const Fr* const* S_in, co
     Transcript tr = tlookup_batch_transcript(seed, D, N, K);
     uint8_t* out = proof;
     memcpy(out, "ZKTB", 4);
-    out[4] = 1; out[5] = out[6] = out[7] = 0;
+    out[4] = 2; out[5] = out[6] = out[7] = 0;
     for (int i = 0; i < 8; ++i) {
         out[8 + i] = (uint8_t)(D >> (8 * i));
         out[16 + i] = (uint8_t)(N >> (8 * i));
@@ -94,6 +97,16 @@ inline int tlookup_batch_prove(const uint8_t seed[32], const Fr* const* S_in, co
             }
         });
         for (int z : zero_seen) if (z) return E_ZERO_DENOM;
+    }
+    for (uint64_t k = 0; k < K; ++k) {
+        uint8_t dA[32], dB[32];
+        vec_digest(dA, inst[k].A.data(), D, threads);
+        vec_digest(dB, inst[k].B.data(), N, threads);
+        tr.absorb("A", dA, 32);
+        tr.absorb("B", dB, 32);
+        memcpy(out, dA, 32);
+        memcpy(out + 32, dB, 32);
+        out += 64;
     }
 
     Fr alpha = tr.challenge("alpha");
@@ -201,7 +214,7 @@ inline int tlookup_batch_verify(const uint8_t seed[32], const uint8_t* proof, ui
     if (!seed || !proof || !T || K == 0 || K > 8 || n < 0 || l < 0 || N > D) return E_BADARG;
     int h = n - l;
     if (len != tlookup_batch_proof_bytes(n, K)) return E_REJECT;
-    if (memcmp(proof, "ZKTB\x01\0\0\0", 8) != 0) return E_REJECT;
+    if (memcmp(proof, "ZKTB\x02\0\0\0", 8) != 0) return E_REJECT;
     uint64_t Dp = 0, Np = 0, Kp = 0;
     for (int i = 0; i < 8; ++i) {
         Dp |= (uint64_t)proof[8 + i] << (8 * i);
@@ -209,7 +222,7 @@ inline int tlookup_batch_verify(const uint8_t seed[32], const uint8_t* proof, ui
         Kp |= (uint64_t)proof[24 + i] << (8 * i);
     }
     if (Dp != D || Np != N || Kp != K) return E_REJECT;
-    const uint8_t* body = proof + 32 + 32 * K;
+    const uint8_t* body = proof + 32 + 96 * K;
     size_t nfr = (size_t)4 * n + 5 * K;
     std::vector<Fr> el(nfr);
     for (size_t i = 0; i < nfr; ++i) {
@@ -219,6 +232,10 @@ inline int tlookup_batch_verify(const uint8_t seed[32], const uint8_t* proof, ui
     Transcript tr = tlookup_batch_transcript(seed, D, N, K);
     for (uint64_t k = 0; k < K; ++k) tr.absorb("m", proof + 32 + 32 * k, 32);
     Fr beta = tr.challenge("beta");
+    for (uint64_t k = 0; k < K; ++k) {
+        tr.absorb("A", proof + 32 + 32 * K + 64 * k, 32);
+        tr.absorb("B", proof + 32 + 32 * K + 64 * k + 32, 32);
+    }
     Fr alpha = tr.challenge("alpha");
     Fr alpha2 = fr_mul(alpha, alpha);
     std::vector<Fr> u(n), v(n);

@@ -57,6 +57,19 @@ def m_digest(counts, leaf=128):
     return hashlib.sha256(leaves).digest()
 
 
+def vec_digest(vals, leaf=128):
+    """Hash tree over a vector of field elements: leaf i holds elements i, i+L, i+2L, ...
+    (L = n/leaf leaves, one leaf when n < leaf); rows of digests are then hashed in
+    consecutive fours (a last pair in twos) down to one digest."""
+    n = len(vals)
+    L = max(1, n // leaf)
+    row = [hashlib.sha256(b"".join(fr_bytes(vals[x]) for x in range(i, n, L))).digest() for i in range(L)]
+    while len(row) > 1:
+        g = 4 if len(row) >= 4 else 2
+        row = [hashlib.sha256(b"".join(row[i:i + g])).digest() for i in range(0, len(row), g)]
+    return row[0]
+
+
 def round_poly(f, prefix, nvars, X):
     """g_k(X) = sum over rest in {0,1}^(nvars-k-1) of f(prefix, X, rest)."""
     k = len(prefix)
@@ -77,12 +90,15 @@ def tlookup_proof(seed, S, T):
     m = [0] * N
     for s in S:
         m[first[s]] += 1
-    tr = Transcript(b"zkmi/tlookup/v1" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little"))
+    tr = Transcript(b"zkmi/tlookup/v2" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little"))
     md = m_digest(m)
     tr.absorb("m", md)
     beta = tr.challenge("beta")
     A = [pow(beta + s, -1, R) for s in S]
     B = [pow(beta + t, -1, R) for t in T]
+    dA, dB = vec_digest(A), vec_digest(B)
+    tr.absorb("A", dA)
+    tr.absorb("B", dB)
     alpha = tr.challenge("alpha")
     u = [tr.challenge("u") for _ in range(n)]
     scale = pow(pow(2, h, R), -1, R)
@@ -93,7 +109,7 @@ def tlookup_proof(seed, S, T):
         right = scale * mle(B, wt) % R * ((alpha * alpha % R) * eq(u[h:], wt) % R * ((mle(T, wt) + beta) % R) - mle(m, wt)) % R
         return (left + right) % R
 
-    out = b"ZKTL" + (1).to_bytes(4, "little") + D.to_bytes(8, "little") + N.to_bytes(8, "little") + md
+    out = b"ZKTL" + (2).to_bytes(4, "little") + D.to_bytes(8, "little") + N.to_bytes(8, "little") + md + dA + dB
     v = []
     polys = []
     for k in range(n):
@@ -171,8 +187,8 @@ def tlookup_batch_proof(seed, S_list, T_list):
     K, D, N = len(S_list), len(S_list[0]), len(T_list[0])
     n, l = D.bit_length() - 1, N.bit_length() - 1
     h = n - l
-    tr = Transcript(b"zkmi/tlookup-batch/v1" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little") + K.to_bytes(8, "little"))
-    out = b"ZKTB" + (1).to_bytes(4, "little") + D.to_bytes(8, "little") + N.to_bytes(8, "little") + K.to_bytes(8, "little")
+    tr = Transcript(b"zkmi/tlookup-batch/v2" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little") + K.to_bytes(8, "little"))
+    out = b"ZKTB" + (2).to_bytes(4, "little") + D.to_bytes(8, "little") + N.to_bytes(8, "little") + K.to_bytes(8, "little")
     ms = []
     for S, T in zip(S_list, T_list):
         first = {}
@@ -188,6 +204,11 @@ def tlookup_batch_proof(seed, S_list, T_list):
     beta = tr.challenge("beta")
     As = [[pow(beta + s, -1, R) for s in S] for S in S_list]
     Bs = [[pow(beta + t, -1, R) for t in T] for T in T_list]
+    for A, B in zip(As, Bs):
+        dA, dB = vec_digest(A), vec_digest(B)
+        tr.absorb("A", dA)
+        tr.absorb("B", dB)
+        out += dA + dB
     alpha = tr.challenge("alpha")
     u = [tr.challenge("u") for _ in range(n)]
     lam = tr.challenge("lambda")

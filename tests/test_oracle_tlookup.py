@@ -59,6 +59,48 @@ def test_m_digest_against_hashlib(orc):
         assert orc.m_digest(m) == pyref.m_digest([int(c) for c in m])
 
 
+def test_vec_digest_against_hashlib(orc):
+    """The stand-in for the commitments of A and B: strided leaves of 128 elements,
+    then rows of digests hashed in fours (a last pair in twos)."""
+    import hashlib
+    rng = random.Random(7)
+    for n in (1, 2, 4, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 1 << 15):
+        vals = [rng.randrange(R) for _ in range(n)]
+        assert orc.vec_digest(orc.to_bytes(vals), threads=3) == pyref.vec_digest(vals), n
+    # the shape of the tree, spelled out once for n = 512: four leaves, element x in leaf x mod 4
+    vals = [rng.randrange(R) for _ in range(512)]
+    leaves = [hashlib.sha256(b"".join(pyref.fr_bytes(vals[x]) for x in range(i, 512, 4))).digest() for i in range(4)]
+    assert orc.vec_digest(orc.to_bytes(vals)) == hashlib.sha256(b"".join(leaves)).digest()
+    # n = 256: two leaves, hashed as a pair
+    leaves = [hashlib.sha256(b"".join(pyref.fr_bytes(vals[x]) for x in range(i, 256, 2))).digest() for i in range(2)]
+    assert orc.vec_digest(orc.to_bytes(vals[:256])) == hashlib.sha256(leaves[0] + leaves[1]).digest()
+    # below one leaf: the hash of the elements in order
+    assert orc.vec_digest(orc.to_bytes(vals[:8])) == hashlib.sha256(b"".join(pyref.fr_bytes(x) for x in vals[:8])).digest()
+
+
+def test_inverse_vectors_are_sent_before_the_sumcheck(orc):
+    """Protocol 1: A and B go to the verifier after beta and before the sumcheck, so
+    alpha and u must depend on them and beta must not.  The proof carries their
+    digests after that of m; alpha is recomputed here from the transcript rules."""
+    rng = random.Random(36)
+    D, N = 32, 8
+    S, T = _instance(rng, D, N)
+    seed = rng.randbytes(32)
+    rc, proof, info = orc.tlookup_prove(seed, orc.to_bytes(S), orc.to_bytes(T))
+    assert rc == orc.OK and proof[:8] == b"ZKTL" + (2).to_bytes(4, "little")
+    beta = orc.to_ints(info["beta"])[0]
+    A = [pow(beta + s, -1, R) for s in S]
+    B = [pow(beta + t, -1, R) for t in T]
+    assert proof[56:88] == pyref.vec_digest(A) and proof[88:120] == pyref.vec_digest(B)
+    tr = pyref.Transcript(b"zkmi/tlookup/v2" + seed + D.to_bytes(8, "little") + N.to_bytes(8, "little"))
+    tr.absorb("m", proof[24:56])
+    assert tr.challenge("beta") == beta
+    tr.absorb("A", proof[56:88])
+    tr.absorb("B", proof[88:120])
+    assert tr.challenge("alpha") == orc.to_ints(info["alpha"])[0]
+    assert [tr.challenge("u") for _ in range(5)] == orc.to_ints(info["u"])
+
+
 @pytest.mark.parametrize("D,N,dup", [(1, 1, False), (2, 1, False), (8, 1, False), (4, 4, False), (8, 8, True),
                                      (16, 4, False), (16, 2, False), (32, 8, True)])
 def test_proof_equals_brute_force_definition(orc, D, N, dup):
@@ -90,7 +132,7 @@ def test_honest_claim_closed_forms(orc):
     assert np.array_equal(info["sum_A"], info["sum_mB"])
     assert orc.to_ints(info["sum_A"])[0] == sum(pow(beta + s, -1, R) for s in S) % R
     # g_0(0) + g_0(1) = alpha + alpha^2
-    g0 = [int.from_bytes(proof[56 + 32 * i:88 + 32 * i], "little") for i in range(2)]
+    g0 = [int.from_bytes(proof[120 + 32 * i:152 + 32 * i], "little") for i in range(2)]
     assert sum(g0) % R == (alpha + alpha * alpha) % R
 
 
@@ -104,7 +146,7 @@ def test_round_consistency_and_final_identity(orc):
     assert rc == orc.OK
     n, h = 7, 3
     beta, alpha = orc.to_ints(info["beta"])[0], orc.to_ints(info["alpha"])[0]
-    el = [int.from_bytes(proof[56 + 32 * i:88 + 32 * i], "little") for i in range(4 * n + 5)]
+    el = [int.from_bytes(proof[120 + 32 * i:152 + 32 * i], "little") for i in range(4 * n + 5)]
     v, u = orc.to_ints(info["v"]), orc.to_ints(info["u"])
     claim = (alpha + alpha * alpha) % R
     for k in range(n):
@@ -141,7 +183,7 @@ def test_verify_accepts_and_rejects(orc):
     rc, out = orc.tlookup_verify(seed, proof, Tb, D, S=Sb, m=m, A=A, B=B)
     assert rc == orc.OK
     # any single corrupted byte is rejected
-    for pos in list(range(0, 56)) + rng.sample(range(56, len(proof)), 60):
+    for pos in list(range(0, 120)) + rng.sample(range(120, len(proof)), 60):
         bad = bytearray(proof)
         bad[pos] ^= 1 << rng.randrange(8)
         rc, out = orc.tlookup_verify(seed, bytes(bad), Tb, D)
@@ -155,6 +197,14 @@ def test_verify_accepts_and_rejects(orc):
     S2 = Sb.copy()
     S2[3] = Tb[1] if np.array_equal(Sb[3], Tb[0]) else Tb[0]
     assert orc.tlookup_verify(seed, proof, Tb, D, S=S2)[0] == orc.E_REJECT
+    # inverse vectors other than the ones whose digests were sent
+    A2 = A.copy()
+    A2[[0, 1]] = A2[[1, 0]]
+    assert not np.array_equal(A2[0], A[0])
+    assert orc.tlookup_verify(seed, proof, Tb, D, A=A2)[0] == orc.E_REJECT
+    B2 = B.copy()
+    B2[[0, 1]] = B2[[1, 0]]
+    assert orc.tlookup_verify(seed, proof, Tb, D, B=B2)[0] == orc.E_REJECT
 
 
 def test_zero_denominator_is_reported(orc):
@@ -190,4 +240,4 @@ def test_thread_count_does_not_change_bytes(orc):
     Sb, Tb = orc.to_bytes(S), orc.to_bytes(T)
     p1 = orc.tlookup_prove(seed, Sb, Tb, threads=1)[1]
     p5 = orc.tlookup_prove(seed, Sb, Tb, threads=5)[1]
-    assert p1 == p5 and len(p1) == 216 + 128 * 8
+    assert p1 == p5 and len(p1) == 280 + 128 * 8
