@@ -176,18 +176,29 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
  *   alpha + alpha^2 = sum_{x = i (+) j} A(x)(alpha e~(u,x)(S(x)+beta) + 1)
  *                     + (N/D) B(j)(alpha^2 e~(u_[h:],j)(T(j)+beta) - m(j)),  h = log2(D/N),
  * round polynomials sent as their values at X = 0,1,2,3, and the five final
- * claims A~(v), S~(v), B~(v'), m~(v'), T~(v').  The commitments of Protocol 1
- * are outside this library: `seed` (host, 32 bytes) stands in for those of T
- * and S, a digest of m for that of m.
+ * claims A~(v), S~(v), B~(v'), m~(v'), T~(v').
  *
- * Transcript: SHA256("zkmi/tlookup/v1" || seed || LE64 D || LE64 N); absorb("m",
- * digest) ; beta = challenge("beta"); alpha = challenge("alpha"); u_t =
- * challenge("u"), t = 0..n-1; per round absorb("g", 4 values), r = challenge("r");
- * absorb("final", 5 claims).  digest(m) = SHA256 of the concatenated SHA256
- * digests of the leaves of 128 counts, each count 4 little-endian bytes.
+ * The commitments of Protocol 1 are outside this library; digests stand in for
+ * them and enter the transcript where Protocol 1 sends the commitments: `seed`
+ * (host, 32 bytes) for those of T and S, digest(m) before beta is drawn, and
+ * digest(A), digest(B) after beta and BEFORE alpha and u, so that the sumcheck's
+ * randomness depends on the inverse vectors (tlookup-Prove: "P -> V: commitments
+ * of A and B", then the sumcheck).
+ *
+ * Transcript: SHA256("zkmi/tlookup/v2" || seed || LE64 D || LE64 N); absorb("m",
+ * digest(m)); beta = challenge("beta"); absorb("A", digest(A)); absorb("B",
+ * digest(B)); alpha = challenge("alpha"); u_t = challenge("u"), t = 0..n-1; per
+ * round absorb("g", 4 values), r = challenge("r"); absorb("final", 5 claims).
+ * digest(m) = SHA256 of the concatenated SHA256 digests of the leaves of 128
+ * counts, each count 4 little-endian bytes.  digest of a vector of n field
+ * elements (n a power of two): with L = max(1, n/128) leaves, leaf i = SHA256 of
+ * the canonical bytes of elements i, i+L, i+2L, ...; rows of digests are then
+ * hashed in consecutive groups of four (a last pair as a group of two) until one
+ * digest remains.
  *
  * Proof (host buffer, tlookup_proof_bytes(D) bytes):
- *   "ZKTL" | u32 1 | LE64 D | LE64 N | digest(m) | n x 4 elements | 5 elements.
+ *   "ZKTL" | u32 2 | LE64 D | LE64 N | digest(m) | digest(A) | digest(B)
+ *   | n x 4 elements | 5 elements.
  * *len (host) receives the size, also on ZK_E_BUFSZ.  aux: host, may be NULL.
  * ws: device, at least tlookup_workspace_bytes(D, N).  Synchronises the stream.
  *
@@ -225,7 +236,8 @@ int tlookup_prove_with_beta(const uint8_t seed[32], fr_vec S, const uint32_t* id
  * claim in every round and the final identity, recomputes T~(v') from the public
  * table (device), and, for each tensor given in *witness, recomputes that claim
  * from the tensor (standing in for the proofs of evaluation on commitments,
- * which are outside this library).  Returns ZK_OK (accept) or ZK_E_REJECT.
+ * which are outside this library) and, for m, A and B, the digest the proof
+ * carries for it.  Returns ZK_OK (accept) or ZK_E_REJECT.
  * claims: host, may be NULL.  ws: device, tlookup_verify_workspace_bytes(D, N). */
 size_t tlookup_verify_workspace_bytes(size_t D, size_t N);
 int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_vec T, size_t D,
@@ -241,13 +253,15 @@ int tlookup_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, fr_
  * f_i being the summand of tlookup_prove for instance i and lambda one more
  * challenge.  It ends in 5 K claims: A_i~(v), S_i~(v), B_i~(v'), m_i~(v'), T_i~(v').
  *
- * Transcript: SHA256("zkmi/tlookup-batch/v1" || seed || LE64 D || LE64 N || LE64 K);
- * absorb("m", digest(m_i)) for i = 0..K-1; beta, alpha, u_0..u_{n-1} as in
+ * Transcript: SHA256("zkmi/tlookup-batch/v2" || seed || LE64 D || LE64 N || LE64 K);
+ * absorb("m", digest(m_i)) for i = 0..K-1; beta; absorb("A", digest(A_i)),
+ * absorb("B", digest(B_i)) for i = 0..K-1; alpha, u_0..u_{n-1} as in
  * tlookup_prove; lambda = challenge("lambda"); per round absorb("g", 4 values),
  * r = challenge("r"); absorb("final", 5 K claims).
  *
  * Proof (host, tlookup_batch_proof_bytes(D, K) bytes):
- *   "ZKTB" | u32 1 | LE64 D | LE64 N | LE64 K | K digests | n x 4 elements | K x 5 elements. */
+ *   "ZKTB" | u32 2 | LE64 D | LE64 N | LE64 K | K x digest(m_i)
+ *   | K x [digest(A_i) digest(B_i)] | n x 4 elements | K x 5 elements. */
 #define TLOOKUP_BATCH_MAX 8
 
 typedef struct {
@@ -421,6 +435,7 @@ int zkattn_link_verify(const uint8_t seed[32], const uint8_t* proof, size_t len,
  * on the caller's stream (so that kernels are timed where they are launched).
  * State is per host thread.  Phases: "total" (a whole tlookup_prove call),
  * "count" (multiplicities and digest leaves), "inverse" (both batch inversions),
+ * "digest" (the hash trees over A and B),
  * "round_data29" (the large folding rounds, which run on 29-bit limbs: one
  * record per launch of that kernel), "round_data" (every other round kernel
  * launch with a data side, one record each), "round_table" (the table-side

@@ -135,6 +135,7 @@ static const size_t kMailboxMaxInstances = 8;
 static const size_t kMailboxInvB = 1024;    // grand total of the table-side inversion (+16 per instance)
 static const size_t kMailboxInvA = 1032;    // grand total of the data-side inversion (+16 per instance)
 static const size_t kMailboxTableC = 1280;  // the two table-side constants (+16 per instance)
+static const size_t kMailboxDigest = 1536;  // digests of A and B, eight hash-state words each (+16 per instance)
 
 int mailbox_get(Mailbox** out);
 int mailbox_bulk(Mailbox* mb, size_t bytes);
@@ -146,7 +147,7 @@ inline hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
 // Optional timing of phases with HIP events on the caller's stream (see
 // zkmi_profile_* in the public header).  A scope records one start/stop pair.
-enum ProfilePhase { kProfTotal = 0, kProfCount, kProfInverse, kProfRoundData, kProfRoundTable, kProfRound29, kProfPhases };
+enum ProfilePhase { kProfTotal = 0, kProfCount, kProfInverse, kProfRoundData, kProfRoundTable, kProfRound29, kProfDigest, kProfPhases };
 int profile_open(int phase, hipStream_t stream);   // returns a record handle or -1 when profiling is off
 void profile_close(int handle, hipStream_t stream);
 struct ProfileScope {

@@ -239,7 +239,7 @@ int zkmi_profile_reset(void) {
 }
 
 int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms) {
-    static const char* names[kProfPhases] = {"total", "count", "inverse", "round_data", "round_table", "round_data29"};
+    static const char* names[kProfPhases] = {"total", "count", "inverse", "round_data", "round_table", "round_data29", "digest"};
     if (!phase || !records || !total_ms) return ZK_E_BADARG;
     ProfileState& st = profile_state();
     profile_resolve(st);

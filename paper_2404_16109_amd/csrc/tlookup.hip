@@ -157,6 +157,8 @@ struct ProveWs {
     uint32_t* flags;    // [0] duplicate flag, [1] ticket of the final sums, [2..3] smallest bad index (64-bit)
     uint32_t* leaves;   // nleaves * 8 words
     uint32_t nleaves;
+    uint32_t* dig_leaves;  // leaf digests of the vector being hashed (A, then B): max(1, D/128) digests
+    uint32_t* dig_rows;    // the shorter rows of that hash tree above kTreeChunk leaves
     size_t part_blocks; // capacity of the two partial-sum buffers, in workgroups
     uint32_t* partD;    // part_blocks * 5
     uint32_t* partT;    // part_blocks * 6
@@ -171,6 +173,45 @@ static size_t round_blocks_max(size_t D) {
 
 static const size_t kLdsHistMaxRows = (size_t)1 << 16;  // packed 16-bit counters: 128 KiB of LDS
 static const uint32_t kHistParts = 256;                // one workgroup per compute unit
+
+// ---- digest of a vector (stand-in for its commitment) ----------------------------------
+// Scratch: the leaf digests and, for rows longer than kTreeChunk, the rows above
+// them (each at most 1/kTreeChunk of the one below: twice the first is room for all).
+static size_t vec_digest_leaves(size_t n) { return n / kVecLeaf ? n / kVecLeaf : 1; }
+static size_t vec_digest_row_digests(size_t n) {
+    const size_t first = vec_digest_leaves(n) / kTreeChunk;
+    return first ? 2 * first : 1;
+}
+
+// Enqueues the hash tree over v (n elements, n a power of two); the digest's eight
+// state words go to out_words (device memory or the mailbox `words`, in which
+// case seq != 0 publishes completion).
+static void vec_digest_launch(const uint32_t* v, size_t stride, size_t n, uint32_t* leaves, uint32_t* rows,
+                              uint32_t* out_words, uint32_t* words, uint32_t seq, hipStream_t stream) {
+    const size_t L = vec_digest_leaves(n);
+    hipLaunchKernelGGL(k_vec_leaves, dim3(grid_for(L)), dim3(kBlock), 0, stream, leaves, v, stride, n, L);
+    const uint32_t* in = leaves;
+    size_t cnt = L;
+    while (cnt > kTreeChunk) {
+        hipLaunchKernelGGL(k_digest_tree, dim3((unsigned)(cnt / kTreeChunk)), dim3(kBlock), 0, stream, rows, in, kTreeChunk,
+                           (uint32_t*)nullptr, 0u);
+        in = rows;
+        cnt /= kTreeChunk;
+        rows += cnt * 8;
+    }
+    hipLaunchKernelGGL(k_digest_tree, dim3(1), dim3(kBlock), 0, stream, out_words, in, (uint32_t)cnt, words, seq);
+}
+
+// Hash-state words -> the digest's bytes.
+static void digest_bytes(uint8_t out[32], const uint32_t* state_words) {
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t v = state_words[k];
+        out[4 * k] = (uint8_t)(v >> 24);
+        out[4 * k + 1] = (uint8_t)(v >> 16);
+        out[4 * k + 2] = (uint8_t)(v >> 8);
+        out[4 * k + 3] = (uint8_t)v;
+    }
+}
 
 static uint32_t hash_capacity(size_t N) {
     size_t cap = 64;
@@ -198,6 +239,8 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.flags = (uint32_t*)cv.take(64);
     w.nleaves = (uint32_t)div_up(N, kLeafCounts);
     w.leaves = (uint32_t*)cv.take((size_t)w.nleaves * 32);
+    w.dig_leaves = (uint32_t*)cv.take(vec_digest_leaves(D) * 32);
+    w.dig_rows = (uint32_t*)cv.take(vec_digest_row_digests(D) * 32);
     w.part_blocks = round_blocks_max(D);
     w.partD = cv.limbs(w.part_blocks * 5);
     w.partT = cv.limbs(w.part_blocks * 6);
@@ -322,8 +365,9 @@ struct Instance {
     uint32_t* words = nullptr;  // this instance's round sums in the mailbox
     uint32_t* inv_words = nullptr;    // totals of its two inversions (B, then A)
     uint32_t* const_words = nullptr;  // its two table-side constants
+    uint32_t* dig_words = nullptr;    // hash-state words of digest(A), then of digest(B)
     host::F c1, c2, cB, sum_A, lam;
-    uint8_t md[32];
+    uint8_t md[32], dA[32], dB[32];
     BatchInverseJob job_a, job_b;
     bool deferred = false;  // S_i = T[idx_i] is checked through sum A = sum m B after the first round, not while counting
 };
@@ -348,7 +392,7 @@ struct ProveCall {
 };
 
 static size_t batch_proof_bytes(size_t D, size_t K) {
-    return 32 + 32 * K + (size_t)log2_floor(D ? D : 1) * 128 + 160 * K;
+    return 32 + 96 * K + (size_t)log2_floor(D ? D : 1) * 128 + 160 * K;
 }
 
 static int prove_core(const ProveCall& c) {
@@ -384,6 +428,7 @@ static int prove_core(const ProveCall& c) {
         I.words = mb->words + kMailboxSlot * i;
         I.inv_words = mb->words + kMailboxInvB + 16 * i;
         I.const_words = mb->words + kMailboxTableC + 16 * i;
+        I.dig_words = mb->words + kMailboxDigest + 16 * i;
         I.c1 = I.c2 = I.cB = I.sum_A = zero();
     }
     if (cv.overflow()) return ZK_E_BUFSZ;
@@ -415,7 +460,7 @@ static int prove_core(const ProveCall& c) {
     }
 
     uint64_t dims[3] = {D, N, K};
-    Transcript tr(c.batch ? "zkmi/tlookup-batch/v1" : "zkmi/tlookup/v1", c.seed, dims, c.batch ? 3 : 2);
+    Transcript tr(c.batch ? "zkmi/tlookup-batch/v2" : "zkmi/tlookup/v2", c.seed, dims, c.batch ? 3 : 2);
     for (size_t i = 0; i < K; ++i) tr.absorb("m", inst[i].md, 32);
 
     // -- Prove: beta, inverse vectors ---------------------------------------------------------------
@@ -482,6 +527,28 @@ static int prove_core(const ProveCall& c) {
         }
     }
 
+    // The prover sends A and B before the sumcheck (Protocol 1, tlookup-Prove): their
+    // digests, standing in for the commitments, enter the transcript before alpha
+    // and u are drawn.
+    {
+        ProfileScope prof(kProfDigest, stream);
+        const uint32_t seq = mb->next_seq();
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            vec_digest_launch(I.w.A, D, D, I.w.dig_leaves, I.w.dig_rows, I.dig_words, mb->words, 0, stream);
+            vec_digest_launch(I.w.B, N, N, I.w.dig_leaves, I.w.dig_rows, I.dig_words + 8, mb->words, i + 1 == K ? seq : 0,
+                              stream);
+        }
+        ZK_HIP_TRY(hipGetLastError());
+        ZK_TRY(mailbox_wait(mb, seq, stream));
+        for (size_t i = 0; i < K; ++i) {
+            digest_bytes(inst[i].dA, inst[i].dig_words);
+            digest_bytes(inst[i].dB, inst[i].dig_words + 8);
+            tr.absorb("A", inst[i].dA, 32);
+            tr.absorb("B", inst[i].dB, 32);
+        }
+    }
+
     F alpha = tr.challenge("alpha");
     F alpha2 = sqr(alpha);
     F u[32];
@@ -534,7 +601,7 @@ static int prove_core(const ProveCall& c) {
     // -- header -----------------------------------------------------------------------------------------
     uint8_t* out = c.proof;
     memcpy(out, c.batch ? "ZKTB" : "ZKTL", 4);
-    out[4] = 1; out[5] = out[6] = out[7] = 0;
+    out[4] = 2; out[5] = out[6] = out[7] = 0;
     put_le64(out + 8, D);
     put_le64(out + 16, N);
     out += 24;
@@ -545,6 +612,11 @@ static int prove_core(const ProveCall& c) {
     for (size_t i = 0; i < K; ++i) {
         memcpy(out, inst[i].md, 32);
         out += 32;
+    }
+    for (size_t i = 0; i < K; ++i) {
+        memcpy(out, inst[i].dA, 32);
+        memcpy(out + 32, inst[i].dB, 32);
+        out += 64;
     }
 
     // -- rounds -----------------------------------------------------------------------------------------
@@ -866,6 +938,8 @@ static size_t verify_ws_bytes(size_t D, size_t N) {
     Carver cv(nullptr, 0);
     cv.limbs(N);                                   // m as field elements
     cv.take(div_up(N, kLeafCounts) * 32);          // leaf digests
+    cv.take(vec_digest_leaves(D) * 32);            // hash tree over a witness vector
+    cv.take(vec_digest_row_digests(D) * 32);
     cv.take(mle_scratch_bytes(log2_floor(D)));
     return cv.used();
 }
@@ -900,25 +974,30 @@ static int verify_core(const VerifyCall& c) {
     const uint8_t* digests;
     if (c.batch) {
         if (c.len != batch_proof_bytes(D, K)) return ZK_E_REJECT;
-        if (memcmp(proof, "ZKTB\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
+        if (memcmp(proof, "ZKTB\x02\0\0\0", 8) != 0) return ZK_E_REJECT;
         if (get_le64(proof + 8) != D || get_le64(proof + 16) != N || get_le64(proof + 24) != K) return ZK_E_REJECT;
         digests = proof + 32;
     } else {
         if (c.len != tlookup_proof_bytes(D)) return ZK_E_REJECT;
-        if (memcmp(proof, "ZKTL\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
+        if (memcmp(proof, "ZKTL\x02\0\0\0", 8) != 0) return ZK_E_REJECT;
         if (get_le64(proof + 8) != D || get_le64(proof + 16) != N) return ZK_E_REJECT;
         digests = proof + 24;
     }
-    const uint8_t* body = digests + 32 * K;
+    const uint8_t* ab_digests = digests + 32 * K;  // per instance: digest(A), digest(B)
+    const uint8_t* body = ab_digests + 64 * K;
     F el[4 * 32 + 5 * kMailboxMaxInstances];
     const int nel = 4 * n + 5 * (int)K;
     for (int i = 0; i < nel; ++i)
         if (!from_bytes(&el[i], body + 32 * i)) return ZK_E_REJECT;
 
     uint64_t dims[3] = {D, N, K};
-    Transcript tr(c.batch ? "zkmi/tlookup-batch/v1" : "zkmi/tlookup/v1", c.seed, dims, c.batch ? 3 : 2);
+    Transcript tr(c.batch ? "zkmi/tlookup-batch/v2" : "zkmi/tlookup/v2", c.seed, dims, c.batch ? 3 : 2);
     for (size_t i = 0; i < K; ++i) tr.absorb("m", digests + 32 * i, 32);
     F beta = tr.challenge("beta");
+    for (size_t i = 0; i < K; ++i) {
+        tr.absorb("A", ab_digests + 64 * i, 32);
+        tr.absorb("B", ab_digests + 64 * i + 32, 32);
+    }
     F alpha = tr.challenge("alpha");
     F alpha2 = sqr(alpha);
     F u[32], v[32];
@@ -963,6 +1042,20 @@ static int verify_core(const VerifyCall& c) {
     uint32_t* Mfr = cv.limbs(N);
     uint32_t nleaves = (uint32_t)div_up(N, kLeafCounts);
     uint32_t* leaves = (uint32_t*)cv.take((size_t)nleaves * 32);
+    uint32_t* dig_leaves = (uint32_t*)cv.take(vec_digest_leaves(D) * 32);
+    uint32_t* dig_rows = (uint32_t*)cv.take(vec_digest_row_digests(D) * 32);
+    // a witness vector must be the one whose digest the proof carries
+    auto check_digest = [&](const fr_vec& v, size_t count, const uint8_t* want, int* ok) -> int {
+        const uint32_t seq = mb->next_seq();
+        vec_digest_launch(v.limbs, v.stride, count, dig_leaves, dig_rows, mb->words + kMailboxDigest, mb->words, seq, stream);
+        ZK_HIP_TRY(hipGetLastError());
+        ZK_TRY(mailbox_wait(mb, seq, stream));
+        ZK_HIP_TRY(hipStreamSynchronize(stream));
+        uint8_t got[32];
+        digest_bytes(got, mb->words + kMailboxDigest);
+        *ok = memcmp(got, want, 32) == 0 ? 1 : 0;
+        return ZK_OK;
+    };
     auto check = [&](const uint32_t* a, size_t stride, int nv, const F* pt, const F& want, int* ok) -> int {
         Carver scratch = cv;
         uint32_t seq = mb->next_seq();
@@ -988,10 +1081,14 @@ static int verify_core(const VerifyCall& c) {
             if (!vec_ok(wit->A, D)) return ZK_E_BADARG;
             ZK_TRY(check(wit->A.limbs, wit->A.stride, n, v, f[0], &ok));
             if (!ok) return ZK_E_REJECT;
+            ZK_TRY(check_digest(wit->A, D, ab_digests + 64 * i, &ok));
+            if (!ok) return ZK_E_REJECT;
         }
         if (wit->B.limbs) {
             if (!vec_ok(wit->B, N)) return ZK_E_BADARG;
             ZK_TRY(check(wit->B.limbs, wit->B.stride, l, v + h, f[2], &ok));
+            if (!ok) return ZK_E_REJECT;
+            ZK_TRY(check_digest(wit->B, N, ab_digests + 64 * i + 32, &ok));
             if (!ok) return ZK_E_REJECT;
         }
         if (wit->m) {
@@ -1035,7 +1132,7 @@ using namespace zkmi;
 
 extern "C" {
 
-size_t tlookup_proof_bytes(size_t D) { return 56 + (size_t)log2_floor(D ? D : 1) * 128 + 160; }
+size_t tlookup_proof_bytes(size_t D) { return 120 + (size_t)log2_floor(D ? D : 1) * 128 + 160; }
 
 size_t tlookup_workspace_bytes(size_t D, size_t N) {
     if (!is_pow2(D) || !is_pow2(N) || N > D) return 0;

@@ -5,6 +5,7 @@
 #pragma once
 #include "common.h"
 #include "reduce_dev.h"
+#include "sha256_dev.h"
 
 namespace zkmi {
 
@@ -374,18 +375,6 @@ static __global__ void __launch_bounds__(kBlock) k_counts_to_fr(uint32_t* __rest
 
 static const uint32_t kLeafCounts = 128;
 
-__device__ __forceinline__ uint32_t rotr(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
-
-static __constant__ const uint32_t kShaK[64] = {
-    0x428a2f98u, 0x71374491u, 0xb5c0fbcfu, 0xe9b5dba5u, 0x3956c25bu, 0x59f111f1u, 0x923f82a4u, 0xab1c5ed5u,
-    0xd807aa98u, 0x12835b01u, 0x243185beu, 0x550c7dc3u, 0x72be5d74u, 0x80deb1feu, 0x9bdc06a7u, 0xc19bf174u,
-    0xe49b69c1u, 0xefbe4786u, 0x0fc19dc6u, 0x240ca1ccu, 0x2de92c6fu, 0x4a7484aau, 0x5cb0a9dcu, 0x76f988dau,
-    0x983e5152u, 0xa831c66du, 0xb00327c8u, 0xbf597fc7u, 0xc6e00bf3u, 0xd5a79147u, 0x06ca6351u, 0x14292967u,
-    0x27b70a85u, 0x2e1b2138u, 0x4d2c6dfcu, 0x53380d13u, 0x650a7354u, 0x766a0abbu, 0x81c2c92eu, 0x92722c85u,
-    0xa2bfe8a1u, 0xa81a664bu, 0xc24b8b70u, 0xc76c51a3u, 0xd192e819u, 0xd6990624u, 0xf40e3585u, 0x106aa070u,
-    0x19a4c116u, 0x1e376c08u, 0x2748774cu, 0x34b0bcb5u, 0x391c0cb3u, 0x4ed8aa4au, 0x5b9cca4fu, 0x682e6ff3u,
-    0x748f82eeu, 0x78a5636fu, 0x84c87814u, 0x8cc70208u, 0x90befffau, 0xa4506cebu, 0xbef9a3f7u, 0xc67178f2u};
-
 // One thread per leaf: SHA-256 of up to 128 counts as 4-byte little-endian
 // words.  Digest bytes go out in order, 32 per leaf.
 static __global__ void __launch_bounds__(64) k_leaf_digests(uint32_t* __restrict__ out, const uint32_t* __restrict__ m,
@@ -395,8 +384,8 @@ static __global__ void __launch_bounds__(64) k_leaf_digests(uint32_t* __restrict
     uint32_t base = leaf * kLeafCounts;
     uint32_t cnt = N - base < kLeafCounts ? N - base : kLeafCounts;
     uint32_t nblk = (cnt + 3 + 15) / 16;
-    uint32_t h[8] = {0x6a09e667u, 0xbb67ae85u, 0x3c6ef372u, 0xa54ff53au, 0x510e527fu, 0x9b05688cu, 0x1f83d9abu,
-                     0x5be0cd19u};
+    uint32_t h[8];
+    sha256_init(h);
     for (uint32_t b = 0; b < nblk; ++b) {
         uint32_t w[16];
 #pragma unroll
@@ -408,28 +397,103 @@ static __global__ void __launch_bounds__(64) k_leaf_digests(uint32_t* __restrict
             else if (pos == nblk * 16 - 1) v = cnt * 32;  // message length in bits
             w[i] = v;
         }
-        uint32_t s[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) s[i] = h[i];
-#pragma unroll
-        for (int i = 0; i < 64; ++i) {
-            if (i >= 16) {
-                uint32_t x = w[(i + 1) & 15], y = w[(i + 14) & 15];
-                w[i & 15] += (rotr(x, 7) ^ rotr(x, 18) ^ (x >> 3)) + w[(i + 9) & 15] +
-                             (rotr(y, 17) ^ rotr(y, 19) ^ (y >> 10));
-            }
-            uint32_t t1 = s[7] + (rotr(s[4], 6) ^ rotr(s[4], 11) ^ rotr(s[4], 25)) + ((s[4] & s[5]) ^ (~s[4] & s[6])) +
-                          kShaK[i] + w[i & 15];
-            uint32_t t2 = (rotr(s[0], 2) ^ rotr(s[0], 13) ^ rotr(s[0], 22)) +
-                          ((s[0] & s[1]) ^ (s[0] & s[2]) ^ (s[1] & s[2]));
-            s[7] = s[6]; s[6] = s[5]; s[5] = s[4]; s[4] = s[3] + t1;
-            s[3] = s[2]; s[2] = s[1]; s[1] = s[0]; s[0] = t1 + t2;
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i) h[i] += s[i];
+        sha256_compress(h, w);
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) out[leaf * 8 + i] = __builtin_bswap32(h[i]);
+}
+
+// ---- digest of a vector of field elements (stand-in for its commitment) ----------
+//
+// A hash tree over the canonical bytes of the elements: with L = max(1, n/128)
+// leaves, leaf i is the SHA-256 of elements i, i+L, i+2L, ... (so that lane i of a
+// wavefront reads element i + tL in step t: one limb plane of 64 consecutive
+// elements is 256 contiguous bytes); rows of digests are then hashed in
+// consecutive fours (a last pair in twos) down to one.  Digests travel between
+// the kernels as the eight state words of the hash (big-endian words of the
+// digest's bytes).
+static const uint32_t kVecLeaf = 128;
+
+static __global__ void __launch_bounds__(kBlock) k_vec_leaves(uint32_t* __restrict__ out, const uint32_t* __restrict__ v,
+                                                       size_t stride, size_t n, size_t L) {
+    const size_t leaf = blockIdx.x * (size_t)kBlock + threadIdx.x;
+    if (leaf >= L) return;
+    const size_t cnt = n / L;  // elements per leaf: kVecLeaf, or all n (a power of two) when n < kVecLeaf
+    uint32_t h[8];
+    sha256_init(h);
+    for (size_t t = 0; t + 1 < cnt; t += 2) {
+        const Fr a = fr_from_mont(fr_load(v, stride, leaf + t * L));
+        const Fr b = fr_from_mont(fr_load(v, stride, leaf + (t + 1) * L));
+        uint32_t w[16];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            w[k] = __builtin_bswap32(a.l[k]);
+            w[8 + k] = __builtin_bswap32(b.l[k]);
+        }
+        sha256_compress(h, w);
+    }
+    if (cnt == 1) {  // a vector of one element: 32 bytes and the padding in one block
+        const Fr a = fr_from_mont(fr_load(v, stride, leaf));
+        uint32_t w[16];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) w[k] = __builtin_bswap32(a.l[k]);
+        w[8] = 0x80000000u;
+#pragma unroll
+        for (int k = 9; k < 15; ++k) w[k] = 0;
+        w[15] = 256;
+        sha256_compress(h, w);
+    } else {
+        sha256_finish_aligned(h, (uint64_t)cnt * 32);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) out[leaf * 8 + k] = h[k];
+}
+
+// Workgroup b reduces digests [b*chunk, (b+1)*chunk) of `in` to one (chunk a power
+// of two, at most kTreeChunk, and a power of four unless it is the whole row) and
+// writes it to out[8b..8b+8); with seq != 0 (single workgroup, out in the mailbox)
+// it publishes completion.
+static const uint32_t kTreeChunk = 1024;
+
+static __global__ void __launch_bounds__(kBlock) k_digest_tree(uint32_t* out, const uint32_t* __restrict__ in, uint32_t chunk,
+                                                        uint32_t* words, uint32_t seq) {
+    __shared__ uint32_t rows[2][kTreeChunk / 4 * 8];  // the row being read and the one being written (at most chunk/4 digests)
+    // the first row comes from memory; every later one from LDS
+    const uint32_t* base = in + (size_t)blockIdx.x * chunk * 8;
+    uint32_t cnt = chunk;
+    int cur = 0;
+    bool from_lds = false;
+    while (cnt > 1) {
+        const uint32_t group = cnt >= 4 ? 4 : 2;
+        const uint32_t nodes = cnt / group;
+        for (uint32_t node = threadIdx.x; node < nodes; node += kBlock) {
+            uint32_t h[8];
+            sha256_init(h);
+            for (uint32_t part = 0; part < group; part += 2) {
+                uint32_t w[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) {
+                    const uint32_t at = (node * group + part) * 8 + k;
+                    w[k] = from_lds ? rows[cur][at] : base[at];
+                }
+                sha256_compress(h, w);
+            }
+            sha256_finish_aligned(h, (uint64_t)group * 32);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) rows[cur ^ 1][node * 8 + k] = h[k];
+        }
+        __syncthreads();
+        cur ^= 1;
+        from_lds = true;
+        cnt = nodes;
+    }
+    if (threadIdx.x < 8) {
+        const uint32_t v = from_lds ? rows[cur][threadIdx.x] : base[threadIdx.x];
+        out[(size_t)blockIdx.x * 8 + threadIdx.x] = v;
+        if (seq != 0) mailbox_written();
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) mailbox_publish(words, seq);
 }
 
 // ---- pooled eq tables ----------------------------------------------------------------

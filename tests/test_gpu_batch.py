@@ -81,7 +81,7 @@ def test_batch_proof_bytes_equal_oracle(zk, orc, K, D, N, dup):
     assert orc.tlookup_batch_verify(seed, got, Tb, D, S_list=Sb) == 0
     assert claims["v"] == orc.to_ints(info_o["v"])
     n = max(D.bit_length() - 1, 0)
-    body = got[32 + 32 * K + 128 * n:]
+    body = got[32 + 96 * K + 128 * n:]
     for i in range(K):
         for q in range(5):
             off = 32 * (5 * i + q)
@@ -96,7 +96,7 @@ def test_one_instance_batch_is_not_the_single_proof(zk, orc):
     seed = rng.randbytes(32)
     got, _ = _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx)
     rc, single, _ = zk.tlookup_prove(seed, Sv[0], idx[0], Tv[0])
-    assert rc == 0 and single[56:] != got[64:]
+    assert rc == 0 and single[120:] != got[128:]
     assert zk.tlookup_verify_batch(seed, single, Tv, 1 << 8)[0] == zk.ZK_E_REJECT
     assert zk.tlookup_verify(seed, got, Tv[0], 1 << 8)[0] == zk.ZK_E_REJECT
 
@@ -169,8 +169,8 @@ def test_verify_rejects_tampering_and_wrong_witness(zk, orc):
     rc, proof, _ = zk.tlookup_prove_batch(seed, Sv, idx, Tv)
     assert rc == 0 and zk.tlookup_verify_batch(seed, proof, Tv, D, S=Sv)[0] == 0
     n = 8
-    body = 32 + 32 * K
-    for off in (0, 4, 8, 16, 24, 40, 70, body + 3, body + 128 * 3 + 40, body + 128 * n + 5, body + 128 * n + 160 + 33,
+    body = 32 + 96 * K
+    for off in (0, 4, 8, 16, 24, 40, 70, body - 100, body - 30, body + 3, body + 128 * 3 + 40, body + 128 * n + 5, body + 128 * n + 160 + 33,
                 len(proof) - 1):
         bad = bytearray(proof)
         bad[off] ^= 1

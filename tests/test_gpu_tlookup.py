@@ -208,7 +208,7 @@ def test_verify_rejects_tampering_and_wrong_witness(zk, orc):
     _, Ab = orc.fr_inv(orc.fr_axpy(Sb, orc.to_bytes([beta])[0]))
     assert np.array_equal(zk.vec_to_bytes(A), Ab)
     assert orc.tlookup_verify(seed, proof, Tb, D, S=Sb, m=m.cpu().numpy().astype(np.uint64), A=Ab)[0] == 0
-    for pos in list(range(0, 56, 5)) + rng.sample(range(56, len(proof)), 40):
+    for pos in list(range(0, 120, 5)) + rng.sample(range(120, len(proof)), 40):
         bad = bytearray(proof)
         bad[pos] ^= 1 << rng.randrange(8)
         assert zk.tlookup_verify(seed, bytes(bad), Tv, D)[0] == zk.ZK_E_REJECT, pos
@@ -221,6 +221,14 @@ def test_verify_rejects_tampering_and_wrong_witness(zk, orc):
     S2b[3] = Tb[1] if not np.array_equal(Sb[3], Tb[1]) else Tb[0]
     assert zk.tlookup_verify(seed, proof, Tv, D, S=zk.vec_from_bytes(S2b))[0] == zk.ZK_E_REJECT
     assert zk.tlookup_verify(seed, proof, Tv, D, A=B if D == N else shifted)[0] == zk.ZK_E_REJECT
+    # the digests in the proof are those of the inverse vectors (hash tree of the oracle, Protocol 1's stand-in
+    # for their commitments); a witness with two entries swapped has the right multiset but another digest
+    assert proof[56:88] == orc.vec_digest(Ab) and proof[88:120] == orc.vec_digest(zk.vec_to_bytes(B))
+    A2 = zk.Vec(D)
+    A2.data.copy_(A.data)
+    A2.data[:, 0], A2.data[:, 1] = A.data[:, 1].clone(), A.data[:, 0].clone()
+    if not torch.equal(A2.data, A.data):
+        assert zk.tlookup_verify(seed, proof, Tv, D, A=A2)[0] == zk.ZK_E_REJECT
 
 
 def test_same_bytes_when_run_twice(zk, orc):

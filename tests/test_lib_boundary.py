@@ -31,8 +31,8 @@ def test_constants_match_python():
 
 def test_sizes():
     import paper_2404_16109_amd as zk
-    assert zk.tlookup_proof_bytes(1 << 25) == 216 + 128 * 25
-    assert zk.tlookup_proof_bytes(1) == 216
+    assert zk.tlookup_proof_bytes(1 << 25) == 280 + 128 * 25
+    assert zk.tlookup_proof_bytes(1) == 280
     assert zk.tlookup_workspace_bytes(1 << 10, 1 << 8) > 0
     assert zk.tlookup_workspace_bytes(1000, 256) == 0
     assert zk.raw().sumcheck_product_proof_bytes(8) == 16 + 32 + 3 * 96 + 64
