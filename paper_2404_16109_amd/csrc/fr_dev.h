@@ -451,10 +451,16 @@ __device__ __forceinline__ Fr fr_sqr(const Fr& a) { return fr_mul(a, a); }
 // canonical integer (8 limbs, < 2^256) -> Montgomery form
 __device__ __forceinline__ Fr fr_to_mont(const Fr& canonical) { return fr_mul_uniform(canonical, fr_rr()); }
 
-// Montgomery form -> canonical integer in [0, r)
+// Montgomery form -> canonical integer in [0, r): a / 2^256 mod r is the
+// reduction half of a product alone, applied to a as the low half of a wide value.
 __device__ __forceinline__ Fr fr_from_mont(const Fr& a) {
-    Fr one = Fr{{1, 0, 0, 0, 0, 0, 0, 0}};
-    return fr_mul_uniform(a, one);
+    FrWide w;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        w.l[k] = a.l[k];
+        w.l[8 + k] = 0;
+    }
+    return fr_wide_reduce(w);
 }
 
 // Small unsigned integer -> Montgomery form.

@@ -8,7 +8,19 @@
 
 namespace zkmi {
 
-__device__ __forceinline__ uint32_t sha_rotr(uint32_t x, int n) { return (x >> n) | (x << (32 - n)); }
+__device__ __forceinline__ uint32_t sha_rotr(uint32_t x, int n) { return __builtin_amdgcn_alignbit(x, x, (uint32_t)n); }
+
+// Three-input bitwise functions in one instruction (gfx950's v_bitop3_b32; the
+// constant is the truth table with inputs weighted 0xf0, 0xcc, 0xaa).
+__device__ __forceinline__ uint32_t sha_xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+__device__ __forceinline__ uint32_t sha_ch(uint32_t e, uint32_t f, uint32_t g) {  // (e & f) ^ (~e & g)
+    return __builtin_amdgcn_bitop3_b32(e, f, g, 0xca);
+}
+__device__ __forceinline__ uint32_t sha_maj(uint32_t a, uint32_t b, uint32_t c) {  // (a & b) ^ (a & c) ^ (b & c)
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0xe8);
+}
 
 static __constant__ const uint32_t kShaK[64] = {
     0x428a2f98u, 0x71374491u, 0xb5c0fbcfu, 0xe9b5dba5u, 0x3956c25bu, 0x59f111f1u, 0x923f82a4u, 0xab1c5ed5u,
@@ -35,13 +47,12 @@ __device__ __forceinline__ void sha256_compress(uint32_t (&h)[8], uint32_t (&w)[
     for (int i = 0; i < 64; ++i) {
         if (i >= 16) {
             const uint32_t x = w[(i + 1) & 15], y = w[(i + 14) & 15];
-            w[i & 15] += (sha_rotr(x, 7) ^ sha_rotr(x, 18) ^ (x >> 3)) + w[(i + 9) & 15] +
-                         (sha_rotr(y, 17) ^ sha_rotr(y, 19) ^ (y >> 10));
+            w[i & 15] += sha_xor3(sha_rotr(x, 7), sha_rotr(x, 18), x >> 3) + w[(i + 9) & 15] +
+                         sha_xor3(sha_rotr(y, 17), sha_rotr(y, 19), y >> 10);
         }
-        const uint32_t t1 = s[7] + (sha_rotr(s[4], 6) ^ sha_rotr(s[4], 11) ^ sha_rotr(s[4], 25)) +
-                            ((s[4] & s[5]) ^ (~s[4] & s[6])) + kShaK[i] + w[i & 15];
-        const uint32_t t2 = (sha_rotr(s[0], 2) ^ sha_rotr(s[0], 13) ^ sha_rotr(s[0], 22)) +
-                            ((s[0] & s[1]) ^ (s[0] & s[2]) ^ (s[1] & s[2]));
+        const uint32_t t1 = s[7] + sha_xor3(sha_rotr(s[4], 6), sha_rotr(s[4], 11), sha_rotr(s[4], 25)) +
+                            sha_ch(s[4], s[5], s[6]) + kShaK[i] + w[i & 15];
+        const uint32_t t2 = sha_xor3(sha_rotr(s[0], 2), sha_rotr(s[0], 13), sha_rotr(s[0], 22)) + sha_maj(s[0], s[1], s[2]);
         s[7] = s[6]; s[6] = s[5]; s[5] = s[4]; s[4] = s[3] + t1;
         s[3] = s[2]; s[2] = s[1]; s[1] = s[0]; s[0] = t1 + t2;
     }

@@ -157,8 +157,9 @@ struct ProveWs {
     uint32_t* flags;    // [0] duplicate flag, [1] ticket of the final sums, [2..3] smallest bad index (64-bit)
     uint32_t* leaves;   // nleaves * 8 words
     uint32_t nleaves;
-    uint32_t* dig_leaves;  // leaf digests of the vector being hashed (A, then B): max(1, D/128) digests
-    uint32_t* dig_rows;    // the shorter rows of that hash tree above kTreeChunk leaves
+    uint32_t* dig_leaves;  // leaf digests of the hash trees over A and B
+    uint32_t* dig_rows;    // the shorter rows of A's tree above kTreeChunk leaves
+    uint32_t* dig_rows_b;  // the same for B
     size_t part_blocks; // capacity of the two partial-sum buffers, in workgroups
     uint32_t* partD;    // part_blocks * 5
     uint32_t* partT;    // part_blocks * 6
@@ -183,23 +184,64 @@ static size_t vec_digest_row_digests(size_t n) {
     return first ? 2 * first : 1;
 }
 
-// Enqueues the hash tree over v (n elements, n a power of two); the digest's eight
-// state words go to out_words (device memory or the mailbox `words`, in which
-// case seq != 0 publishes completion).
-static void vec_digest_launch(const uint32_t* v, size_t stride, size_t n, uint32_t* leaves, uint32_t* rows,
-                              uint32_t* out_words, uint32_t* words, uint32_t seq, hipStream_t stream) {
-    const size_t L = vec_digest_leaves(n);
-    hipLaunchKernelGGL(k_vec_leaves, dim3(grid_for(L)), dim3(kBlock), 0, stream, leaves, v, stride, n, L);
-    const uint32_t* in = leaves;
-    size_t cnt = L;
-    while (cnt > kTreeChunk) {
-        hipLaunchKernelGGL(k_digest_tree, dim3((unsigned)(cnt / kTreeChunk)), dim3(kBlock), 0, stream, rows, in, kTreeChunk,
-                           (uint32_t*)nullptr, 0u);
-        in = rows;
-        cnt /= kTreeChunk;
-        rows += cnt * 8;
+// Enqueues the hash trees over one or two vectors (n elements each, powers of two;
+// v2 may be null); a digest's eight state words go to its out_words (device
+// memory or the mailbox `words`, in which case seq != 0 publishes completion of
+// the whole call; `ticket`: one zeroed word of device memory, left zero).
+// leaves: room for vec_digest_leaves(n1) + vec_digest_leaves(n2) digests;
+// rows1, rows2: vec_digest_row_digests(n) digests each.
+struct VecDigestJob {
+    const uint32_t* v;
+    size_t stride, n;
+    uint32_t* rows;
+    uint32_t* out_words;
+};
+
+static void vec_digest_launch(const VecDigestJob& one, const VecDigestJob* two, uint32_t* leaves, uint32_t* words,
+                              uint32_t seq, uint32_t* ticket, hipStream_t stream) {
+    const VecDigestJob* jobs[2] = {&one, two};
+    const int njobs = two ? 2 : 1;
+    // the shorter vector's leaves first: its few long chains start at once
+    const int order[2] = {njobs == 2 && two->n < one.n ? 1 : 0, njobs == 2 && two->n < one.n ? 0 : 1};
+    VecLeavesJob lv[2];
+    const uint32_t* in[2];
+    size_t cnt[2];
+    uint32_t* rows[2];
+    size_t total = 0;
+    for (int q = 0; q < 2; ++q) {
+        lv[q] = VecLeavesJob{nullptr, 0, 0, 0, nullptr};
+        if (q >= njobs) continue;
+        const VecDigestJob& j = *jobs[order[q]];
+        lv[q] = VecLeavesJob{j.v, j.stride, j.n, vec_digest_leaves(j.n), leaves + total * 8};
+        in[q] = lv[q].out;
+        cnt[q] = lv[q].L;
+        rows[q] = j.rows;
+        total += lv[q].L;
     }
-    hipLaunchKernelGGL(k_digest_tree, dim3(1), dim3(kBlock), 0, stream, out_words, in, (uint32_t)cnt, words, seq);
+    hipLaunchKernelGGL(k_vec_leaves, dim3(grid_for(total)), dim3(kBlock), 0, stream, lv[0], lv[1]);
+    // up the trees, both rows in one launch, a factor of up to kTreeChunk per launch
+    bool done[2] = {false, njobs < 2};
+    while (!done[0] || !done[1]) {
+        DigestTreeJob tj[2];
+        bool finishing = true;
+        for (int q = 0; q < 2; ++q) {
+            tj[q] = DigestTreeJob{nullptr, nullptr, 0, 0};
+            if (done[q]) continue;
+            const size_t chunk = cnt[q] > kTreeChunk ? kTreeChunk : cnt[q];
+            const size_t blocks = cnt[q] / chunk;
+            uint32_t* out = blocks == 1 ? jobs[order[q]]->out_words : rows[q];
+            tj[q] = DigestTreeJob{in[q], out, (uint32_t)chunk, (uint32_t)blocks};
+            in[q] = out;
+            cnt[q] = blocks;
+            if (blocks == 1) done[q] = true;
+            else {
+                rows[q] += blocks * 8;
+                finishing = false;
+            }
+        }
+        hipLaunchKernelGGL(k_digest_tree, dim3(tj[0].blocks + tj[1].blocks), dim3(kBlock), 0, stream, tj[0], tj[1], words,
+                           finishing ? seq : 0u, ticket);
+    }
 }
 
 // Hash-state words -> the digest's bytes.
@@ -239,8 +281,9 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.flags = (uint32_t*)cv.take(64);
     w.nleaves = (uint32_t)div_up(N, kLeafCounts);
     w.leaves = (uint32_t*)cv.take((size_t)w.nleaves * 32);
-    w.dig_leaves = (uint32_t*)cv.take(vec_digest_leaves(D) * 32);
+    w.dig_leaves = (uint32_t*)cv.take((vec_digest_leaves(D) + vec_digest_leaves(N)) * 32);
     w.dig_rows = (uint32_t*)cv.take(vec_digest_row_digests(D) * 32);
+    w.dig_rows_b = (uint32_t*)cv.take(vec_digest_row_digests(N) * 32);
     w.part_blocks = round_blocks_max(D);
     w.partD = cv.limbs(w.part_blocks * 5);
     w.partT = cv.limbs(w.part_blocks * 6);
@@ -535,9 +578,8 @@ static int prove_core(const ProveCall& c) {
         const uint32_t seq = mb->next_seq();
         for (size_t i = 0; i < K; ++i) {
             Instance& I = inst[i];
-            vec_digest_launch(I.w.A, D, D, I.w.dig_leaves, I.w.dig_rows, I.dig_words, mb->words, 0, stream);
-            vec_digest_launch(I.w.B, N, N, I.w.dig_leaves, I.w.dig_rows, I.dig_words + 8, mb->words, i + 1 == K ? seq : 0,
-                              stream);
+            const VecDigestJob ja{I.w.A, D, D, I.w.dig_rows, I.dig_words}, jb{I.w.B, N, N, I.w.dig_rows_b, I.dig_words + 8};
+            vec_digest_launch(ja, &jb, I.w.dig_leaves, mb->words, i + 1 == K ? seq : 0, I.w.flags + 1, stream);
         }
         ZK_HIP_TRY(hipGetLastError());
         ZK_TRY(mailbox_wait(mb, seq, stream));
@@ -940,6 +982,7 @@ static size_t verify_ws_bytes(size_t D, size_t N) {
     cv.take(div_up(N, kLeafCounts) * 32);          // leaf digests
     cv.take(vec_digest_leaves(D) * 32);            // hash tree over a witness vector
     cv.take(vec_digest_row_digests(D) * 32);
+    cv.take(256);                                  // its ticket
     cv.take(mle_scratch_bytes(log2_floor(D)));
     return cv.used();
 }
@@ -1044,10 +1087,13 @@ static int verify_core(const VerifyCall& c) {
     uint32_t* leaves = (uint32_t*)cv.take((size_t)nleaves * 32);
     uint32_t* dig_leaves = (uint32_t*)cv.take(vec_digest_leaves(D) * 32);
     uint32_t* dig_rows = (uint32_t*)cv.take(vec_digest_row_digests(D) * 32);
+    uint32_t* dig_ticket = (uint32_t*)cv.take(256);
     // a witness vector must be the one whose digest the proof carries
     auto check_digest = [&](const fr_vec& v, size_t count, const uint8_t* want, int* ok) -> int {
         const uint32_t seq = mb->next_seq();
-        vec_digest_launch(v.limbs, v.stride, count, dig_leaves, dig_rows, mb->words + kMailboxDigest, mb->words, seq, stream);
+        const VecDigestJob job{v.limbs, v.stride, count, dig_rows, mb->words + kMailboxDigest};
+        launch_fill_u32(dig_ticket, 1, 0u, stream);
+        vec_digest_launch(job, nullptr, dig_leaves, mb->words, seq, dig_ticket, stream);
         ZK_HIP_TRY(hipGetLastError());
         ZK_TRY(mailbox_wait(mb, seq, stream));
         ZK_HIP_TRY(hipStreamSynchronize(stream));

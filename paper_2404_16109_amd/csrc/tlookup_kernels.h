@@ -414,11 +414,24 @@ static __global__ void __launch_bounds__(64) k_leaf_digests(uint32_t* __restrict
 // digest's bytes).
 static const uint32_t kVecLeaf = 128;
 
-static __global__ void __launch_bounds__(kBlock) k_vec_leaves(uint32_t* __restrict__ out, const uint32_t* __restrict__ v,
-                                                       size_t stride, size_t n, size_t L) {
-    const size_t leaf = blockIdx.x * (size_t)kBlock + threadIdx.x;
-    if (leaf >= L) return;
-    const size_t cnt = n / L;  // elements per leaf: kVecLeaf, or all n (a power of two) when n < kVecLeaf
+// Up to two vectors are hashed by one launch (the table-side vector's few leaves
+// are chains of 65 dependent blocks: next to the tensor-side vector's they cost
+// nothing, on their own a quarter of a millisecond).
+struct VecLeavesJob {
+    const uint32_t* v;
+    size_t stride, n, L;  // L = 0: no such vector
+    uint32_t* out;        // L digests
+};
+
+static __global__ void __launch_bounds__(kBlock) k_vec_leaves(VecLeavesJob first, VecLeavesJob second) {
+    size_t leaf = blockIdx.x * (size_t)kBlock + threadIdx.x;
+    const bool in_first = leaf < first.L;
+    const VecLeavesJob& job = in_first ? first : second;
+    if (!in_first) leaf -= first.L;
+    if (leaf >= job.L) return;
+    const uint32_t* v = job.v;
+    const size_t stride = job.stride, L = job.L;
+    const size_t cnt = job.n / L;  // elements per leaf: kVecLeaf, or all n (a power of two) when n < kVecLeaf
     uint32_t h[8];
     sha256_init(h);
     for (size_t t = 0; t + 1 < cnt; t += 2) {
@@ -446,21 +459,32 @@ static __global__ void __launch_bounds__(kBlock) k_vec_leaves(uint32_t* __restri
         sha256_finish_aligned(h, (uint64_t)cnt * 32);
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) out[leaf * 8 + k] = h[k];
+    for (int k = 0; k < 8; ++k) job.out[leaf * 8 + k] = h[k];
 }
 
-// Workgroup b reduces digests [b*chunk, (b+1)*chunk) of `in` to one (chunk a power
-// of two, at most kTreeChunk, and a power of four unless it is the whole row) and
-// writes it to out[8b..8b+8); with seq != 0 (single workgroup, out in the mailbox)
-// it publishes completion.
+// One step up the tree, again for up to two rows at once: workgroup b of a job
+// reduces digests [b*chunk, (b+1)*chunk) of `in` to one (chunk a power of two, at
+// most kTreeChunk, and a power of four unless it is the whole row) and writes it
+// to out[8b..8b+8).  The launch's last workgroup publishes `seq` if it is not zero
+// (then the launch is the last one writing results into the mailbox `words`).
 static const uint32_t kTreeChunk = 1024;
 
-static __global__ void __launch_bounds__(kBlock) k_digest_tree(uint32_t* out, const uint32_t* __restrict__ in, uint32_t chunk,
-                                                        uint32_t* words, uint32_t seq) {
+struct DigestTreeJob {
+    const uint32_t* in;
+    uint32_t* out;
+    uint32_t chunk;
+    uint32_t blocks;  // 0: no such row
+};
+
+static __global__ void __launch_bounds__(kBlock) k_digest_tree(DigestTreeJob first, DigestTreeJob second, uint32_t* words,
+                                                        uint32_t seq, uint32_t* ticket) {
     __shared__ uint32_t rows[2][kTreeChunk / 4 * 8];  // the row being read and the one being written (at most chunk/4 digests)
+    const bool in_first = blockIdx.x < first.blocks;
+    const DigestTreeJob& job = in_first ? first : second;
+    const uint32_t b = in_first ? blockIdx.x : blockIdx.x - first.blocks;
     // the first row comes from memory; every later one from LDS
-    const uint32_t* base = in + (size_t)blockIdx.x * chunk * 8;
-    uint32_t cnt = chunk;
+    const uint32_t* base = job.in + (size_t)b * job.chunk * 8;
+    uint32_t cnt = job.chunk;
     int cur = 0;
     bool from_lds = false;
     while (cnt > 1) {
@@ -489,11 +513,17 @@ static __global__ void __launch_bounds__(kBlock) k_digest_tree(uint32_t* out, co
     }
     if (threadIdx.x < 8) {
         const uint32_t v = from_lds ? rows[cur][threadIdx.x] : base[threadIdx.x];
-        out[(size_t)blockIdx.x * 8 + threadIdx.x] = v;
-        if (seq != 0) mailbox_written();
+        job.out[(size_t)b * 8 + threadIdx.x] = v;
+        mailbox_written();
     }
     __syncthreads();
-    if (threadIdx.x == 0) mailbox_publish(words, seq);
+    if (seq != 0 && threadIdx.x == 0) {
+        const unsigned done = atomicAdd(ticket, 1u);
+        if (done == gridDim.x - 1) {
+            *ticket = 0;
+            mailbox_publish(words, seq);
+        }
+    }
 }
 
 // ---- pooled eq tables ----------------------------------------------------------------
