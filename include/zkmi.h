@@ -216,6 +216,25 @@ size_t tlookup_proof_bytes(size_t D);
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
 
+/* tlookup_prove from the tensor as the integers it is quantised from:
+ * S_i = X_i + rho Y_i for signed 32-bit device arrays X and Y of D entries (the
+ * pair-table reduction of Section 4, last paragraph: a function table becomes a
+ * set by combining its two columns with a random rho; T is then T_X + rho T_Y as
+ * field elements, as for tlookup_prove), or S_i = X_i with Y and rho both NULL (a
+ * range check).  rho: host, canonical.  The proof is tlookup_prove's for that S,
+ * byte for byte; S is never written out: the inversion and the first round read
+ * eight bytes per entry instead of thirty-two and build beta + S_i from them (two
+ * 32x256-bit products and a two-step reduction), the first fold takes the four
+ * integers of an entry pair straight to a reduced field element.  Row hints idx
+ * are required (for a range check idx_i = X_i - min T).  Shapes with N > 2^16,
+ * D < 4 N or D <= 1024 have no such path: S is written out first, into D * 32
+ * further bytes of workspace (tlookup_small_workspace_bytes accounts for them).
+ * Errors as for tlookup_prove. */
+size_t tlookup_small_workspace_bytes(size_t D, size_t N);
+int tlookup_prove_small(const uint8_t seed[32], const int32_t* X, const int32_t* Y, const fr_t* rho, size_t D,
+                        const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws,
+                        size_t ws_bytes, void* stream);
+
 /* The same proof, byte for byte, for callers that know the table row of every
  * element (idx is required): once S_i = T[idx_i] has been checked, A_i = 1/(beta + S_i)
  * is the table-side inverse B[idx_i], so only the N table entries are inverted and
@@ -455,6 +474,19 @@ int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms);
  * the kernel is started again and answered: it must run to its end.  ZK_OK if
  * both hold, ZK_E_HIP otherwise.  ws: device, at least 1 KiB. */
 int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream);
+
+/* Which kernel runs each sumcheck round of a tlookup proof of K instances of shape
+ * (D, N), and where it reads S from, decided exactly as the prover decides it but
+ * walked on the host alone: no GPU is touched.  from_ints != 0: the plan of
+ * tlookup_prove_small (K = 1; ZK_E_BADARG for shapes that path does not take).
+ * out (host): four integers per round -- kernel (0 first round, 1 large folding
+ * round on 29-bit limbs, 2 data and table side together, 3 one workgroup per
+ * round, 4 resident kernel for all remaining rounds), source of S (0 the caller's
+ * vector, 1 the caller's integer columns, 2 folded 32-bit words in the workspace,
+ * 3 folded 29-bit limb planes in the workspace), arrays arrive as 32-bit words,
+ * arrays leave as 32-bit words (both only meaningful for kernel 1).  Returns the
+ * number of rounds, ZK_E_BUFSZ if cap_rounds is below it. */
+int zkmi_selftest_tlookup_plan(size_t D, size_t N, size_t K, int from_ints, int32_t* out, size_t cap_rounds);
 
 /* SHA-256 of `len` bytes at `data` (host) into out (host, 32 bytes): the hash
  * the transcript is built on, exported so that it can be checked on its own.

@@ -73,6 +73,7 @@ def _load():
         "zkmi_version": (i32, []),
         "zkmi_sha256": (i32, [ctypes.c_char_p, sz, ctypes.c_char_p, i32]),
         "zkmi_selftest_resident_wait": (i32, [vp, sz, vp]),
+        "zkmi_selftest_tlookup_plan": (i32, [sz, sz, sz, i32, P(ctypes.c_int32), sz]),
         "zkmi_profile_enable": (i32, [i32]),
         "zkmi_profile_reset": (i32, []),
         "zkmi_profile_query": (i32, [ctypes.c_char_p, P(ctypes.c_uint64), P(ctypes.c_double)]),
@@ -99,6 +100,8 @@ def _load():
         "tlookup_proof_bytes": (sz, [sz]),
         "tlookup_prove": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_prove_by_rows": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
+        "tlookup_small_workspace_bytes": (sz, [sz, sz]),
+        "tlookup_prove_small": (i32, [vp, vp, vp, P(fr_t), sz, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_prove_with_beta": (i32, [vp, fr_vec, vp, fr_vec, P(fr_t), vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_verify_workspace_bytes": (sz, [sz, sz]),
         "tlookup_verify": (i32, [vp, vp, sz, fr_vec, sz, P(tlookup_witness), P(tlookup_claims), vp, sz, vp]),
@@ -136,11 +139,11 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
+EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_selftest_tlookup_plan", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_sum_noalloc", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
-           "tlookup_prove_by_rows", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
+           "tlookup_prove_by_rows", "tlookup_small_workspace_bytes", "tlookup_prove_small", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
            "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
            "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove", "matmul_sumcheck_prove_i16",
@@ -216,6 +219,14 @@ def zkmi_sha256(data, use_sha_instructions=True):
 def zkmi_selftest_resident_wait():
     ws = _ws(4096)
     return _lib.zkmi_selftest_resident_wait(ws.data_ptr(), ws.numel(), _stream())
+
+
+def zkmi_selftest_tlookup_plan(D, N, K=1, from_ints=False):
+    """Returns (rc, list of (kernel, s_source, in32, out32) per round); runs on the host only."""
+    out = (ctypes.c_int32 * (4 * 32))()
+    rc = _lib.zkmi_selftest_tlookup_plan(D, N, K, 1 if from_ints else 0, out, 32)
+    rounds = [tuple(out[4 * k:4 * k + 4]) for k in range(max(rc, 0))]
+    return rc, rounds
 
 
 def zkmi_profile_enable(on):
@@ -375,6 +386,28 @@ def tlookup_prove(seed, S, idx, T, ws=None, cap=None, forced_beta=None):
         rc = _lib.tlookup_prove_with_beta(_seed(seed), S.c, _idx_ptr(idx), T.c, ctypes.byref(_fr(forced_beta)), proof,
                                           cap, ctypes.byref(ln), ctypes.byref(aux), ws.data_ptr(), ws.numel(),
                                           _stream())
+    info = _aux_dict(aux)
+    info["len"] = ln.value
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b"", info
+
+
+def tlookup_small_workspace_bytes(D, N):
+    return _lib.tlookup_small_workspace_bytes(D, N)
+
+
+def tlookup_prove_small(seed, X, Y, rho, idx, T, ws=None, cap=None):
+    """X, Y: int32 device tensors of D entries (Y and rho may both be None); idx: int32 hints.
+    Returns (rc, proof bytes, aux dict with 'len')."""
+    D = X.numel()
+    assert X.dtype == torch.int32 and X.is_contiguous() and (Y is None or (Y.dtype == torch.int32 and Y.numel() == D))
+    ws = ws if ws is not None else _ws(_lib.tlookup_small_workspace_bytes(D, T.n))
+    cap = tlookup_proof_bytes(D) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    aux = tlookup_aux()
+    rc = _lib.tlookup_prove_small(_seed(seed), X.data_ptr(), Y.data_ptr() if Y is not None else None,
+                                  ctypes.byref(_fr(rho)) if rho is not None else None, D, _idx_ptr(idx), T.c, proof, cap,
+                                  ctypes.byref(ln), ctypes.byref(aux), ws.data_ptr(), ws.numel(), _stream())
     info = _aux_dict(aux)
     info["len"] = ln.value
     return rc, proof.raw[:ln.value] if rc == ZK_OK else b"", info

@@ -18,6 +18,7 @@
 // Cost: about 3 multiplications per element plus a geometric tail.  A zero
 // anywhere makes the grand total zero, which is how it is detected.
 #include "internal.h"
+#include "small_dev.h"
 
 namespace zkmi {
 
@@ -41,13 +42,23 @@ __device__ __forceinline__ Fr bi_load(const uint32_t* __restrict__ src, size_t s
     return shifted ? fr_add(x, shift) : x;
 }
 
+// The first vector of the first level given as small integers (SmallSource, see
+// small_dev.h) instead of field elements.
+__device__ __forceinline__ Fr bi_load_small(const SmallSource& small, size_t i, bool shifted, const Fr& shift) {
+    Fr x;
+    small_source_load(x.l, small, i);
+    return shifted ? fr_add(x, shift) : x;
+}
+
 // prefix_i = product of this thread's elements up to and including i; the
 // thread's total goes to next[tid].
 __global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__ src, size_t ss, size_t n, int shifted,
                                                     Fr shift, uint32_t* __restrict__ prefix, size_t ps,
-                                                    uint32_t* __restrict__ next, size_t ns, BiSecond second) {
+                                                    uint32_t* __restrict__ next, size_t ns, BiSecond second,
+                                                    SmallSource small) {
     size_t tid = blockIdx.x * (size_t)kBlock + threadIdx.x;
     size_t base = blockIdx.x * (size_t)kBlock * kBiK + threadIdx.x;
+    bool from_small = small.x != nullptr;
     if (blockIdx.x * (size_t)kBlock * kBiK >= second.n1) {  // the whole workgroup is in the second vector
         src = second.src;
         ss = second.ss;
@@ -55,6 +66,7 @@ __global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__
         ps = second.ps;
         base -= second.n1;
         n -= second.n1;
+        from_small = false;
     } else if (n > second.n1) {
         n = second.n1;
     }
@@ -63,7 +75,7 @@ __global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__
     for (int j = 0; j < kBiK; ++j) {
         size_t i = base + (size_t)j * kBlock;
         if (i < n) {
-            Fr x = bi_load(src, ss, i, shifted, shift);
+            Fr x = from_small ? bi_load_small(small, i, shifted, shift) : bi_load(src, ss, i, shifted, shift);
             acc = first ? x : fr_mul(acc, x);
             first = false;
             fr_store(prefix, ps, i, acc);
@@ -76,9 +88,10 @@ __global__ void __launch_bounds__(kBlock) k_bi_down(const uint32_t* __restrict__
 __global__ void __launch_bounds__(kBlock) k_bi_up(const uint32_t* __restrict__ src, size_t ss, size_t n, int shifted,
                                                   Fr shift, const uint32_t* prefix, size_t ps,
                                                   const uint32_t* __restrict__ inv_next, size_t is, uint32_t* out,
-                                                  size_t os, BiSecond second) {
+                                                  size_t os, BiSecond second, SmallSource small) {
     size_t tid = blockIdx.x * (size_t)kBlock + threadIdx.x;
     size_t base = blockIdx.x * (size_t)kBlock * kBiK + threadIdx.x;
+    bool from_small = small.x != nullptr;
     if (blockIdx.x * (size_t)kBlock * kBiK >= second.n1) {  // prefix and out are the same buffer (see batch_inverse_end)
         src = second.src;
         ss = second.ss;
@@ -88,6 +101,7 @@ __global__ void __launch_bounds__(kBlock) k_bi_up(const uint32_t* __restrict__ s
         os = second.ps;
         base -= second.n1;
         n -= second.n1;
+        from_small = false;
     } else if (n > second.n1) {
         n = second.n1;
     }
@@ -97,7 +111,7 @@ __global__ void __launch_bounds__(kBlock) k_bi_up(const uint32_t* __restrict__ s
         if (i < n) {
             if (j > 0) {
                 Fr before = fr_load(prefix, ps, i - kBlock);
-                Fr x = bi_load(src, ss, i, shifted, shift);
+                Fr x = from_small ? bi_load_small(small, i, shifted, shift) : bi_load(src, ss, i, shifted, shift);
                 fr_store(out, os, i, fr_mul(inv, before));
                 inv = fr_mul(inv, x);
             } else {
@@ -299,14 +313,23 @@ static BiSecond bi_second_of(const BatchInverseJob& job, int depth) {
     return BiSecond{nullptr, 0, nullptr, 0, SIZE_MAX};
 }
 
+static SmallSource bi_small_of(const BatchInverseJob& job, int depth) {
+    SmallSource none;
+    memset(&none, 0, sizeof none);
+    return depth == 0 && job.small.x ? job.small : none;
+}
+
 bool batch_inverse_can_join(size_t n1) { return n1 % ((size_t)kBlock * kBiK) == 0; }
 
 int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride,
                         size_t n, const host::F& shift, Carver& cv, uint32_t* total_words, uint32_t* flag_words,
                         uint32_t seq, hipStream_t stream, uint32_t* dst2, size_t dst2_stride, const uint32_t* src2,
-                        size_t src2_stride, size_t n2) {
+                        size_t src2_stride, size_t n2, const SmallSource* small) {
     typedef BatchInverseJob::Level Level;
     if (n2 && !batch_inverse_can_join(n)) return ZK_E_BADARG;
+    if (small && n <= kBiTopMax) return ZK_E_BADARG;  // the top kernels read field elements
+    memset(&job.small, 0, sizeof job.small);
+    if (small) job.small = *small;
     job.depth = 0;
     job.shift = to_dev(shift);
     job.n2 = n2;
@@ -328,7 +351,7 @@ int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, 
             bi_launch_wg_level(true, stream, cur.x, cur.xs, cur.n, cur.p, cur.ps, x, m);
         else
             hipLaunchKernelGGL(k_bi_down, dim3(blocks), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n, cur.shifted,
-                               job.shift, cur.p, cur.ps, x, m, bi_second_of(job, job.depth));
+                               job.shift, cur.p, cur.ps, x, m, bi_second_of(job, job.depth), bi_small_of(job, job.depth));
         ++job.depth;
         job.lv[job.depth] = Level{x, m, p, m, m, 0};
     }
@@ -352,7 +375,7 @@ int batch_inverse_end(const BatchInverseJob& job, const host::F& inv_total, hipS
             bi_launch_wg_level(false, stream, cur.x, cur.xs, cur.n, cur.p, cur.ps, up.p, up.ps);
         else
             hipLaunchKernelGGL(k_bi_up, dim3(blocks), dim3(kBlock), 0, stream, cur.x, cur.xs, cur.n, cur.shifted, job.shift,
-                               cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps, bi_second_of(job, d));
+                               cur.p, cur.ps, up.p, up.ps, cur.p, cur.ps, bi_second_of(job, d), bi_small_of(job, d));
     }
     ZK_HIP_TRY(hipGetLastError());
     return ZK_OK;
@@ -364,7 +387,7 @@ int batch_inverse_run(uint32_t* dst, size_t dst_stride, const uint32_t* src, siz
     BatchInverseJob job;
     uint32_t seq = mb->next_seq();
     ZK_TRY(batch_inverse_begin(job, dst, dst_stride, src, src_stride, n, shift, cv, mb->words + kMailboxInvA, mb->words,
-                               seq, stream, nullptr, 0, nullptr, 0, 0));
+                               seq, stream, nullptr, 0, nullptr, 0, 0, nullptr));
     ZK_TRY(mailbox_wait(mb, seq, stream));
     host::F total = from_dev(mb->words + kMailboxInvA);
     if (host::is_zero(total)) return ZK_E_ZERO_DENOM;

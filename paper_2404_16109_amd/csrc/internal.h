@@ -1,6 +1,7 @@
 // Launchers shared between the translation units of the library.
 #pragma once
 #include "common.h"
+#include "small_dev.h"
 
 namespace zkmi {
 
@@ -34,14 +35,16 @@ struct BatchInverseJob {
     size_t src2_stride = 0;
     uint32_t* dst2 = nullptr;
     size_t dst2_stride = 0;
+    SmallSource small;  // small.x not null: the first vector's entries are these integers, not src
 };
 // src2 (n2 elements, may be none: n2 = 0) is inverted into dst2 by the same passes,
 // shifted like src; needs batch_inverse_can_join(n) and scratch for n + n2 elements.
+// small (may be null): src is ignored and the n entries are small integers (small_dev.h).
 bool batch_inverse_can_join(size_t n);
 int batch_inverse_begin(BatchInverseJob& job, uint32_t* dst, size_t dst_stride, const uint32_t* src, size_t src_stride,
                         size_t n, const host::F& shift, Carver& cv, uint32_t* total_words, uint32_t* flag_words,
                         uint32_t seq, hipStream_t stream, uint32_t* dst2, size_t dst2_stride, const uint32_t* src2,
-                        size_t src2_stride, size_t n2);
+                        size_t src2_stride, size_t n2, const SmallSource* small = nullptr);
 int batch_inverse_end(const BatchInverseJob& job, const host::F& inv_total, hipStream_t stream);
 
 // ---- sums -----------------------------------------------------------------

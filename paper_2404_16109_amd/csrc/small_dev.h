@@ -8,6 +8,7 @@
 // Plain C++: the header also compiles for the host, where it is tested against
 // big integers.
 #pragma once
+#include <stddef.h>
 #include <stdint.h>
 
 #if defined(__HIPCC__)
@@ -124,6 +125,67 @@ ZK_SHD void small_fold32(uint32_t (&out)[8], uint32_t a, uint32_t b, const Small
     small_mac32(t, k.plus_a, a);
     small_mac32(t, cd, b < a ? a - b : b - a);
     small_reduce<2>(out, t);  // t < 2^33 r < r 2^64
+}
+
+// A tensor given as small integers: S_i = x_i + rho y_i for signed 32-bit x, y
+// (a pair of columns combined by a field element, Section 4's reduction of a
+// function table to a set; y == nullptr: S_i = x_i).  The constants are in
+// Montgomery form and times 2^64, as in SmallFoldConsts.
+struct SmallSource {
+    const int32_t* x;  // nullptr: there is no such source
+    const int32_t* y;
+    uint32_t plus_one[8], minus_one[8], plus_rho[8], minus_rho[8];
+};
+
+ZK_SHD uint32_t small_abs32(int32_t v) { return v < 0 ? 0u - (uint32_t)v : (uint32_t)v; }
+
+// x + rho y as a reduced field element in Montgomery form.
+ZK_SHD void small_combine32(uint32_t (&out)[8], int32_t x, int32_t y, const SmallSource& k) {
+    uint32_t t[11];
+#pragma unroll
+    for (int j = 0; j < 11; ++j) t[j] = 0;
+    uint32_t cx[8], cy[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        cx[j] = x < 0 ? k.minus_one[j] : k.plus_one[j];
+        cy[j] = y < 0 ? k.minus_rho[j] : k.plus_rho[j];
+    }
+    small_mac32(t, cx, small_abs32(x));
+    small_mac32(t, cy, small_abs32(y));
+    small_reduce<2>(out, t);  // t < 2^32 r < r 2^64
+}
+
+ZK_SHD void small_source_load(uint32_t (&out)[8], const SmallSource& k, size_t i) {
+    small_combine32(out, k.x[i], k.y ? k.y[i] : 0, k);
+}
+
+// The fold of two such entries by a challenge: (x0 + rho y0) + c ((x1 + rho y1) - (x0 + rho y0))
+//   = x0 + c (x1 - x0) + rho y0 + rho c (y1 - y0),
+// four small integers against eight constants (plus and minus of 1, c, rho, rho c;
+// Montgomery form, times 2^64).
+struct SmallFold4 {
+    uint32_t plus_one[8], minus_one[8], plus_c[8], minus_c[8], plus_rho[8], minus_rho[8], plus_rho_c[8], minus_rho_c[8];
+};
+
+ZK_SHD void small_fold_combined(uint32_t (&out)[8], int32_t x0, int32_t y0, int32_t x1, int32_t y1, const SmallFold4& k) {
+    uint32_t t[11];
+#pragma unroll
+    for (int j = 0; j < 11; ++j) t[j] = 0;
+    const int64_t dx = (int64_t)x1 - x0, dy = (int64_t)y1 - y0;  // 33 bits with sign
+    const uint64_t mdx = dx < 0 ? 0ull - (uint64_t)dx : (uint64_t)dx, mdy = dy < 0 ? 0ull - (uint64_t)dy : (uint64_t)dy;
+    uint32_t c0[8], c1[8], c2[8], c3[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        c0[j] = x0 < 0 ? k.minus_one[j] : k.plus_one[j];
+        c1[j] = dx < 0 ? k.minus_c[j] : k.plus_c[j];
+        c2[j] = y0 < 0 ? k.minus_rho[j] : k.plus_rho[j];
+        c3[j] = dy < 0 ? k.minus_rho_c[j] : k.plus_rho_c[j];
+    }
+    small_mac32(t, c0, small_abs32(x0));
+    small_mac64(t, c1, mdx);
+    small_mac32(t, c2, small_abs32(y0));
+    small_mac64(t, c3, mdy);
+    small_reduce<2>(out, t);  // t < (2^31 + 2^32 + 2^31 + 2^32) r < r 2^64
 }
 
 }  // namespace zkmi

@@ -155,6 +155,7 @@ struct ProveWs {
     uint32_t* hist;     // per-workgroup histograms (tables of up to 2^16 rows), else null
     uint32_t hist_parts;
     uint32_t* flags;    // [0] duplicate flag, [1] ticket of the final sums, [2..3] smallest bad index (64-bit)
+    SmallFold4* fold4;  // constants of the first fold when S comes as small integers (tlookup_prove_small)
     uint32_t* leaves;   // nleaves * 8 words
     uint32_t nleaves;
     uint32_t* dig_leaves;  // leaf digests of the hash trees over A and B
@@ -279,6 +280,7 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     w.hist_parts = N <= kLdsHistMaxRows ? kHistParts : 0;
     w.hist = w.hist_parts ? (uint32_t*)cv.take((size_t)w.hist_parts * N * 4) : nullptr;
     w.flags = (uint32_t*)cv.take(64);
+    w.fold4 = (SmallFold4*)cv.take(sizeof(SmallFold4));
     w.nleaves = (uint32_t)div_up(N, kLeafCounts);
     w.leaves = (uint32_t*)cv.take((size_t)w.nleaves * 32);
     w.dig_leaves = (uint32_t*)cv.take((vec_digest_leaves(D) + vec_digest_leaves(N)) * 32);
@@ -371,10 +373,12 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
 }
 
 // Smallest i with S_i != row idx_i of the table (w.rows), or all ones.
-static int find_bad_row(ProveWs& w, fr_vec S, const uint32_t* idx, size_t D, size_t N, uint64_t* bad, hipStream_t stream) {
+static int find_bad_row(ProveWs& w, fr_vec S, const SmallSource& ints, const uint32_t* idx, size_t D, size_t N,
+                        uint64_t* bad, hipStream_t stream) {
+    if (!S.limbs && !ints.x) return ZK_E_BADARG;
     hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags + 2, (size_t)2, 0xffffffffu);
     hipLaunchKernelGGL(k_check_rows, dim3(grid_for(D, kBlock, 16384)), dim3(kBlock), 0, stream, S.limbs, S.stride, D, idx,
-                       w.rows, (uint32_t)N, (unsigned long long*)(w.flags + 2));
+                       w.rows, (uint32_t)N, (unsigned long long*)(w.flags + 2), ints);
     ZK_HIP_TRY(hipGetLastError());
     ZK_HIP_TRY(hipMemcpyAsync(bad, w.flags + 2, 8, hipMemcpyDeviceToHost, stream));
     ZK_HIP_TRY(hipStreamSynchronize(stream));
@@ -424,6 +428,11 @@ struct ProveCall {
     bool batch = false;                    // batched transcript and proof layout
     const fr_t* forced_beta = nullptr;
     bool by_rows = false;                  // A as B[idx_i] instead of inverting beta + S_i
+    // S_0 given as small integers x + rho y (K = 1, hints required, S ignored): see tlookup_prove_small
+    const int32_t* ints_x = nullptr;
+    const int32_t* ints_y = nullptr;
+    const fr_t* ints_rho = nullptr;
+    size_t ints_D = 0;
     uint8_t* proof = nullptr;
     size_t cap = 0;
     size_t* len = nullptr;
@@ -434,6 +443,84 @@ struct ProveCall {
     void* stream = nullptr;
 };
 
+// ---- which kernel runs a round, and where it finds S ---------------------------------
+//
+// Decided in one place, by a function of the shape alone, so that it can be
+// walked on the host without a GPU (zkmi_selftest_tlookup_plan) and checked
+// against the pointers actually handed to a kernel before it is launched.
+enum RoundKernel {
+    kRoundFirst = 0,     // k_round_data0: the first round, nothing to fold
+    kRound29 = 1,        // k_round_data29: large folding rounds on 29-bit limbs
+    kRoundBoth = 2,      // k_round_both: data and table side, the table's variables being bound
+    kRoundOneGroup = 3,  // k_round_small: at most 256 pairs, one workgroup, one round per launch (batched proofs)
+    kRoundResident = 4   // k_tlookup_tail: at most 256 pairs, all remaining rounds in one resident kernel
+};
+enum SSource {
+    kSFromCaller = 0,  // the caller's vector of field elements
+    kSFromInts = 1,    // the caller's integer columns (tlookup_prove_small)
+    kSFromWords = 2,   // the folded copy in the workspace, 32-bit words
+    kSFromPlanes = 3,  // the folded copy in the workspace, 29-bit limb planes
+    kSNowhere = -1     // a plan this library has no kernel for: never launched
+};
+
+struct RoundPlan {
+    int kernel;
+    int s_source;
+    bool table_round;  // the variable being bound is one of the table's
+    bool tiny;         // at most kSmallPairs pairs
+    bool use29;
+    bool in32, out32;  // kRound29: the data arrays arrive as / leave as 32-bit words
+    int lazy_after;    // rounds in a row that have left the arrays in 29-bit planes, this one included
+};
+
+static bool round_on_29_bits(int n, int h, int k) {
+    return k >= 1 && k < h && ((size_t)1 << (n - k - 1)) > kSmallPairs;
+}
+
+// n = log2 D, h = log2(D/N); lazy_rounds: lazy_after of the round before;
+// resident_running: an earlier round has started the resident kernel.
+static RoundPlan plan_round(int n, int h, int k, size_t K, bool from_ints, int lazy_rounds, bool resident_running) {
+    RoundPlan pl;
+    const size_t half = (size_t)1 << (n - k - 1);
+    pl.table_round = k >= h;
+    pl.tiny = k > 0 && half <= kSmallPairs;
+    pl.use29 = round_on_29_bits(n, h, k);
+    pl.in32 = lazy_rounds == 0;
+    pl.out32 = pl.use29 && (!round_on_29_bits(n, h, k + 1) || lazy_rounds + 1 == kMaxLazyRounds);
+    pl.lazy_after = pl.use29 && !pl.out32 ? lazy_rounds + 1 : 0;
+    if (resident_running || (pl.tiny && K == 1 && n - k <= kTailRoundsMax)) pl.kernel = kRoundResident;
+    else if (pl.tiny) pl.kernel = kRoundOneGroup;
+    else if (pl.table_round && k > 0) pl.kernel = kRoundBoth;
+    else if (pl.use29) pl.kernel = kRound29;
+    else pl.kernel = kRoundFirst;
+    if (k <= 1) {
+        // S has not been folded yet (round 0) or is folded by this round's kernel (round 1): it is read where the
+        // caller left it.  Integers are read by the first round's kernel and by the 29-bit kernel only.
+        pl.s_source = from_ints ? kSFromInts : kSFromCaller;
+        if (from_ints && !((k == 0 && pl.kernel == kRoundFirst) || (k == 1 && pl.kernel == kRound29 && pl.in32)))
+            pl.s_source = kSNowhere;
+    } else {
+        pl.s_source = pl.kernel == kRound29 && !pl.in32 ? kSFromPlanes : kSFromWords;
+    }
+    return pl;
+}
+
+// Whether a lookup of this shape can read S as small integers all the way: the
+// multiplicities come from the hints alone (workgroup histograms), the first
+// round and the first fold are kernels of their own that read integers.
+static bool small_source_shape_ok(size_t D, size_t N) {
+    if (!is_pow2(D) || !is_pow2(N) || N > D || N > kLdsHistMaxRows || D <= (size_t)kBlock) return false;
+    const int n = log2_floor(D), h = n - log2_floor(N);
+    if (n < 2) return false;
+    const RoundPlan p0 = plan_round(n, h, 0, 1, true, 0, false);
+    const RoundPlan p1 = plan_round(n, h, 1, 1, true, p0.lazy_after, p0.kernel == kRoundResident);
+    return p0.s_source == kSFromInts && p1.s_source == kSFromInts;
+}
+
+static __global__ void k_store_fold4(SmallFold4 v, SmallFold4* dst) {
+    ((uint32_t*)dst)[threadIdx.x] = ((const uint32_t*)&v)[threadIdx.x];  // 64 words
+}
+
 static size_t batch_proof_bytes(size_t D, size_t K) {
     return 32 + 96 * K + (size_t)log2_floor(D ? D : 1) * 128 + 160 * K;
 }
@@ -441,13 +528,32 @@ static size_t batch_proof_bytes(size_t D, size_t K) {
 static int prove_core(const ProveCall& c) {
     using namespace host;
     const size_t K = c.K;
-    if (!c.seed || !c.S || !c.T || K == 0 || K > kMailboxMaxInstances) return ZK_E_BADARG;
+    const bool from_ints = c.ints_x != nullptr;
+    if (!c.seed || (!c.S && !from_ints) || !c.T || K == 0 || K > kMailboxMaxInstances) return ZK_E_BADARG;
     if (!c.batch && K != 1) return ZK_E_BADARG;
-    const size_t D = c.S[0].n, N = c.T[0].n;
+    const size_t D = from_ints ? c.ints_D : c.S[0].n, N = c.T[0].n;
     if (!is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
+    if (from_ints && (K != 1 || c.batch || c.by_rows || !c.idx || !c.idx[0] || !small_source_shape_ok(D, N))) return ZK_E_BADARG;
+    if (from_ints && ((c.ints_y != nullptr) != (c.ints_rho != nullptr))) return ZK_E_BADARG;
+    if (from_ints && c.ints_rho && !canonical_in_range(*c.ints_rho)) return ZK_E_BADARG;
     for (size_t i = 0; i < K; ++i) {
-        if (c.S[i].n != D || c.T[i].n != N || !vec_ok(c.S[i], D) || !vec_ok(c.T[i], N)) return ZK_E_BADARG;
+        if (c.T[i].n != N || !vec_ok(c.T[i], N)) return ZK_E_BADARG;
+        if (!from_ints && (c.S[i].n != D || !vec_ok(c.S[i], D))) return ZK_E_BADARG;
         if (c.by_rows && !(c.idx && c.idx[i])) return ZK_E_BADARG;
+    }
+    // the tensor as small integers, if it came that way
+    SmallSource ints_src;
+    memset(&ints_src, 0, sizeof ints_src);
+    F ints_rho = zero();
+    const F two64 = mul(from_u64((uint64_t)1 << 32), from_u64((uint64_t)1 << 32));
+    if (from_ints) {
+        if (c.ints_rho) ints_rho = from_canonical(*c.ints_rho);
+        ints_src.x = c.ints_x;
+        ints_src.y = c.ints_y;
+        to_device_limbs(ints_src.plus_one, two64);
+        to_device_limbs(ints_src.minus_one, neg(two64));
+        to_device_limbs(ints_src.plus_rho, mul(ints_rho, two64));
+        to_device_limbs(ints_src.minus_rho, neg(mul(ints_rho, two64)));
     }
     if (c.forced_beta && !canonical_in_range(*c.forced_beta)) return ZK_E_BADARG;
     const int n = log2_floor(D), l = log2_floor(N), h = n - l;
@@ -463,8 +569,8 @@ static int prove_core(const ProveCall& c) {
     for (size_t i = 0; i < K; ++i) {
         Instance& I = inst[i];
         carve_prove(I.w, cv, D, N);
-        I.S = c.S[i];
-        I.T = c.T[i];
+        I.S = from_ints ? fr_vec{nullptr, D, D} : c.S[i];  // with integers there is no vector: every reader of I.S.limbs is
+        I.T = c.T[i];                                       // gated by the round's plan (s_source)
         I.idx = c.idx ? c.idx[i] : nullptr;
         I.b_cur = I.w.B;
         I.b_cur_stride = N;
@@ -481,6 +587,7 @@ static int prove_core(const ProveCall& c) {
     // -- Prep: multiplicities and their digests -------------------------------------------------
     bool defer_all = !c.by_rows;
     for (size_t i = 0; i < K; ++i) defer_all = defer_all && can_defer_check(inst[i].w, inst[i].idx, D);
+    if (from_ints && !defer_all) return ZK_E_BADARG;  // counting would read S as a vector
     for (size_t i = 0; i < K; ++i) {
         uint64_t bad = 0;
         int rc;
@@ -528,14 +635,16 @@ static int prove_core(const ProveCall& c) {
             const uint32_t last = i + 1 == K ? seq : 0;
             if (joined) {
                 ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
-                                           mb->words, last, stream, I.w.B, N, I.T.limbs, I.T.stride, N));
+                                           mb->words, last, stream, I.w.B, N, I.T.limbs, I.T.stride, N,
+                                           from_ints ? &ints_src : nullptr));
             } else {
                 ZK_TRY(batch_inverse_begin(I.job_b, I.w.B, N, I.T.limbs, I.T.stride, N, beta, inv_cv, I.inv_words, mb->words,
                                            0, stream, nullptr, 0, nullptr, 0, 0));
                 jobs[njobs] = &I.job_b;
                 totals[njobs++] = I.inv_words;
                 ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
-                                           mb->words, last, stream, nullptr, 0, nullptr, 0, 0));
+                                           mb->words, last, stream, nullptr, 0, nullptr, 0, 0,
+                                           from_ints ? &ints_src : nullptr));
             }
             jobs[njobs] = &I.job_a;
             totals[njobs++] = I.inv_words + 8;
@@ -674,7 +783,6 @@ static int prove_core(const ProveCall& c) {
     // Rounds that fold the data arrays only and are large run on 29-bit limbs
     // (tlookup_round29.h).  Between two of them the arrays stay in 29-bit planes,
     // unreduced, for at most kMaxLazyRounds rounds in a row.
-    auto on_29_bits = [&](int k) { return k >= 1 && k < h && ((size_t)1 << (n - k - 1)) > kSmallPairs; };
     int lazy_rounds = 0;  // how many rounds in a row have left the data arrays in 29-bit planes
     const F29 beta29 = f29_unpack(to_dev(beta).l);
     // Where round k reads and writes the arrays that change place: S comes from the
@@ -727,11 +835,10 @@ static int prove_core(const ProveCall& c) {
     for (int k = 0; k < n; ++k) {
         const size_t half = (size_t)1 << (n - k - 1);
         const EqSplit eq = ep.round(k);
-        const bool table_round = k >= h;
-        const bool small = k > 0 && half <= kSmallPairs;
-        const bool use29 = on_29_bits(k);
-        const bool in32 = lazy_rounds == 0;
-        const bool out32 = use29 && (!on_29_bits(k + 1) || lazy_rounds + 1 == kMaxLazyRounds);
+        const RoundPlan plan = plan_round(n, h, k, K, from_ints, lazy_rounds, tail_first >= 0);
+        if (plan.s_source == kSNowhere) return ZK_E_BADARG;  // cannot happen: small_source_shape_ok has walked these rounds
+        const bool table_round = plan.table_round;
+        const bool in32 = plan.in32, out32 = plan.out32;
         // pairs per workgroup: a workgroup's pairs must share the high factor of
         // their weights (at most 2^kLoBits pairs, 16 per thread).  As many as that
         // allows, since a thread's closing reduction costs about as much as two
@@ -744,7 +851,7 @@ static int prove_core(const ProveCall& c) {
         const unsigned blocks = (unsigned)(half / span);
         if (blocks > inst[0].w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
 
-        if (small && K == 1 && tail_first < 0 && n - k <= kTailRoundsMax) {
+        if (plan.kernel == kRoundResident && tail_first < 0) {
             // this and every later round in one launch
             Instance& I = inst[0];
             memset(&tail, 0, sizeof tail);
@@ -797,6 +904,12 @@ static int prove_core(const ProveCall& c) {
             d.eq = eq;
             d.partials = w.partD;
             d.pstride = w.part_blocks * 5;
+            memset(&d.ints, 0, sizeof d.ints);
+            if (plan.s_source == kSFromInts && plan.kernel == kRoundFirst) d.ints = ints_src;
+            // every kernel below reads S through d.S.src unless the plan says otherwise: no launch with nothing behind it
+            if ((plan.s_source == kSFromCaller || plan.s_source == kSFromWords) && !d.S.src) return ZK_E_BADARG;
+            if (plan.s_source == kSFromInts && !ints_src.x) return ZK_E_BADARG;
+            if (!d.A.src || !d.partials) return ZK_E_BADARG;
             TableRoundArgs t;
             t.B = mv.B;
             t.T = mv.T;
@@ -809,7 +922,7 @@ static int prove_core(const ProveCall& c) {
             t.partials = w.partT;
             t.pstride = w.part_blocks * 6;
 
-            if (small) {
+            if (plan.kernel == kRoundOneGroup) {
                 // one workgroup, one launch, sums straight to the host
                 ProfileScope prof(kProfRoundData, stream);
                 if (!table_round)
@@ -821,7 +934,7 @@ static int prove_core(const ProveCall& c) {
                 else
                     hipLaunchKernelGGL(k_round_small<2>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
                                        my_seq);
-            } else if (table_round && k > 0) {
+            } else if (plan.kernel == kRoundBoth) {
                 {
                     ProfileScope prof(kProfRoundData, stream);
                     if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
@@ -829,7 +942,7 @@ static int prove_core(const ProveCall& c) {
                 }
                 launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, I.words, mb->words, my_seq,
                                   w.flags + 1, stream);
-            } else if (use29) {
+            } else if (plan.kernel == kRound29) {
                 DataRound29Args d29;
                 // 32-bit words: A in place (stride D), S from the caller's vector or Sf; 29-bit limbs: A29, S29
                 d29.A = PairArray29{w.A, D, w.A29, w.A29 + D / 2, (const uint32_t*)(w.A29 + D) , w.A29, w.A29 + D / 2,
@@ -843,9 +956,31 @@ static int prove_core(const ProveCall& c) {
                 d29.eq = ep.round29(k);
                 d29.partials = d.partials;
                 d29.pstride = d.pstride;
+                d29.sx = nullptr;
+                d29.sy = nullptr;
+                d29.sf = w.fold4;
+                const bool ints_round = plan.s_source == kSFromInts;
+                if (ints_round) {
+                    // constants of x0 + r (x1 - x0) + rho y0 + rho r (y1 - y0), r the first challenge
+                    d29.sx = c.ints_x;
+                    d29.sy = c.ints_y;
+                    SmallFold4 f4;
+                    const F cr = mul(r_prev, two64), crho = mul(ints_rho, two64), crr = mul(crho, r_prev);
+                    to_device_limbs(f4.plus_one, two64);
+                    to_device_limbs(f4.minus_one, neg(two64));
+                    to_device_limbs(f4.plus_c, cr);
+                    to_device_limbs(f4.minus_c, neg(cr));
+                    to_device_limbs(f4.plus_rho, crho);
+                    to_device_limbs(f4.minus_rho, neg(crho));
+                    to_device_limbs(f4.plus_rho_c, crr);
+                    to_device_limbs(f4.minus_rho_c, neg(crr));
+                    hipLaunchKernelGGL(k_store_fold4, dim3(1), dim3(64), 0, stream, f4, w.fold4);
+                }
                 {
                     ProfileScope prof(kProfRound29, stream);
-                    if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    if (ints_round && out32) hipLaunchKernelGGL((k_round_data29<true, true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else if (ints_round) hipLaunchKernelGGL((k_round_data29<true, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (in32) hipLaunchKernelGGL((k_round_data29<true, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (out32) hipLaunchKernelGGL((k_round_data29<false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else hipLaunchKernelGGL((k_round_data29<false, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
@@ -866,7 +1001,7 @@ static int prove_core(const ProveCall& c) {
             }
             ZK_HIP_TRY(hipGetLastError());
         }
-        lazy_rounds = use29 && !out32 ? lazy_rounds + 1 : 0;
+        lazy_rounds = plan.lazy_after;
         ZK_TRY(mailbox_wait(mb, seq, stream));
         read_table_consts();
 
@@ -889,7 +1024,7 @@ static int prove_core(const ProveCall& c) {
                 // (Section 4, first form of the identity); it does not, so some S_i differs
                 // from its row: find the smallest such i by comparing them all.
                 uint64_t bad = UINT64_MAX;
-                ZK_TRY(find_bad_row(I.w, I.S, I.idx, D, N, &bad, stream));
+                ZK_TRY(find_bad_row(I.w, I.S, ints_src, I.idx, D, N, &bad, stream));
                 if (bad == UINT64_MAX) return ZK_E_HIP;  // the sums disagree although every row matches
                 if (c.aux) c.aux->bad_index = bad;
                 if (c.baux) {
@@ -1226,6 +1361,91 @@ static int prove_single(const uint8_t seed[32], fr_vec S, const uint32_t* idx, f
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
     return prove_single(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, ws_bytes, stream);
+}
+
+static __global__ void __launch_bounds__(kBlock) k_small_materialize(uint32_t* __restrict__ dst, size_t ds, size_t n,
+                                                                     SmallSource ints) {
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) {
+        Fr v;
+        small_source_load(v.l, ints, i);
+        fr_store(dst, ds, i, v);
+    }
+}
+
+size_t tlookup_small_workspace_bytes(size_t D, size_t N) {
+    if (!is_pow2(D) || !is_pow2(N) || N > D) return 0;
+    size_t base = align_up(prove_ws_bytes(D, N), 256);
+    return small_source_shape_ok(D, N) ? base : base + D * 32;  // other shapes: S is written out as field elements first
+}
+
+int tlookup_prove_small(const uint8_t seed[32], const int32_t* X, const int32_t* Y, const fr_t* rho, size_t D,
+                        const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws,
+                        size_t ws_bytes, void* stream) {
+    using namespace host;
+    const size_t N = T.n;
+    if (!seed || !X || !idx || (Y != nullptr) != (rho != nullptr)) return ZK_E_BADARG;
+    if (!is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31) || !vec_ok(T, N)) return ZK_E_BADARG;
+    if (rho && !canonical_in_range(*rho)) return ZK_E_BADARG;
+    if (len) *len = tlookup_proof_bytes(D);
+    if (!ws || ws_bytes < tlookup_small_workspace_bytes(D, N)) return ZK_E_BUFSZ;
+    if (small_source_shape_ok(D, N)) {
+        ProveCall c;
+        c.seed = seed;
+        c.K = 1;
+        c.idx = &idx;
+        c.T = &T;
+        c.ints_x = X;
+        c.ints_y = Y;
+        c.ints_rho = rho;
+        c.ints_D = D;
+        c.proof = proof;
+        c.cap = cap;
+        c.len = len;
+        c.aux = aux;
+        c.ws = ws;
+        c.ws_bytes = ws_bytes;
+        c.stream = stream;
+        return prove_core(c);
+    }
+    // a shape whose first fold is not a kernel of its own: the tensor as field elements, then the usual path
+    const size_t base = align_up(prove_ws_bytes(D, N), 256);
+    SmallSource src;
+    memset(&src, 0, sizeof src);
+    const F two64 = mul(from_u64((uint64_t)1 << 32), from_u64((uint64_t)1 << 32));
+    const F r = rho ? from_canonical(*rho) : zero();
+    src.x = X;
+    src.y = Y;
+    to_device_limbs(src.plus_one, two64);
+    to_device_limbs(src.minus_one, neg(two64));
+    to_device_limbs(src.plus_rho, mul(r, two64));
+    to_device_limbs(src.minus_rho, neg(mul(r, two64)));
+    fr_vec S = {(uint32_t*)((uint8_t*)ws + base), D, D};
+    hipLaunchKernelGGL(k_small_materialize, dim3(grid_for(D, kBlock, 16384)), dim3(kBlock), 0, as_stream(stream), S.limbs,
+                       S.stride, D, src);
+    ZK_HIP_TRY(hipGetLastError());
+    return prove_single(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, base, stream);
+}
+
+// The per-round plan of a proof of this shape, walked on the host (no GPU is
+// touched): four integers per round -- kernel, source of S, arrays arrive as
+// 32-bit words, arrays leave as 32-bit words.
+int zkmi_selftest_tlookup_plan(size_t D, size_t N, size_t K, int from_ints, int32_t* out, size_t cap_rounds) {
+    if (!out || !is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31) || K == 0 || K > kMailboxMaxInstances) return ZK_E_BADARG;
+    const int n = log2_floor(D), h = n - log2_floor(N);
+    if ((size_t)n > cap_rounds) return ZK_E_BUFSZ;
+    if (from_ints && (K != 1 || !small_source_shape_ok(D, N))) return ZK_E_BADARG;
+    int lazy = 0;
+    bool resident = false;
+    for (int k = 0; k < n; ++k) {
+        const RoundPlan pl = plan_round(n, h, k, K, from_ints != 0, lazy, resident);
+        out[4 * k] = pl.kernel;
+        out[4 * k + 1] = pl.s_source;
+        out[4 * k + 2] = pl.in32 ? 1 : 0;
+        out[4 * k + 3] = pl.out32 ? 1 : 0;
+        lazy = pl.lazy_after;
+        resident = resident || pl.kernel == kRoundResident;
+    }
+    return n;
 }
 
 int tlookup_prove_by_rows(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,

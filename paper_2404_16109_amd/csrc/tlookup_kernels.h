@@ -6,6 +6,7 @@
 #include "common.h"
 #include "reduce_dev.h"
 #include "sha256_dev.h"
+#include "small_dev.h"
 
 namespace zkmi {
 
@@ -324,12 +325,14 @@ static __global__ void __launch_bounds__(kBlock) k_hist_reduce(uint32_t* __restr
 // is such an index.
 static __global__ void __launch_bounds__(kBlock) k_check_rows(const uint32_t* __restrict__ S, size_t ss, size_t D,
                                                        const uint32_t* __restrict__ idx, const uint4* __restrict__ rows,
-                                                       uint32_t N, unsigned long long* bad) {
+                                                       uint32_t N, unsigned long long* bad, SmallSource ints) {
     for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < D; i += (size_t)gridDim.x * kBlock) {
         const uint32_t r = idx[i];
         bool ok = r < N;
         if (ok) {
-            const Fr x = fr_load(S, ss, i);
+            Fr x;
+            if (ints.x) small_source_load(x.l, ints, i);
+            else x = fr_load(S, ss, i);
             const uint4 lo = rows[2 * (size_t)r], hi = rows[2 * (size_t)r + 1];
             ok = ((lo.x ^ x.l[0]) | (lo.y ^ x.l[1]) | (lo.z ^ x.l[2]) | (lo.w ^ x.l[3]) | (hi.x ^ x.l[4]) | (hi.y ^ x.l[5]) |
                   (hi.z ^ x.l[6]) | (hi.w ^ x.l[7])) == 0;
@@ -611,6 +614,7 @@ struct DataRoundArgs {
     EqSplit eq;
     uint32_t* partials;  // 5 values per workgroup
     size_t pstride;
+    SmallSource ints;    // ints.x not null (first round only): S is given as small integers
 };
 
 // Data side of one round.  With w the weight of a pair and (A0, A1), (S0, S1)
@@ -667,7 +671,12 @@ template <bool FOLD, class Wide>
 __device__ __forceinline__ void data_pair(const DataRoundArgs& g, size_t p, size_t lo_mask, Wide& wide, Fr& sA0, Fr& sA1) {
     Fr a0, a1, s0, s1;
     load_pair<FOLD>(g.A, p, g.half, g.r_prev, a0, a1);
-    load_pair<FOLD>(g.S, p, g.half, g.r_prev, s0, s1);
+    if (!FOLD && g.ints.x) {
+        small_source_load(s0.l, g.ints, p);
+        small_source_load(s1.l, g.ints, p + g.half);
+    } else {
+        load_pair<FOLD>(g.S, p, g.half, g.r_prev, s0, s1);
+    }
     Fr w = fr_load(g.eq.pool, g.eq.stride, g.eq.lo_off + (p & lo_mask));
     sA0 = fr_add(sA0, a0);
     sA1 = fr_add(sA1, a1);

@@ -13,6 +13,7 @@
 // one of them writes fully reduced 32-bit words again.
 #pragma once
 #include "fr29_dev.h"
+#include "small_dev.h"
 #include "tlookup_kernels.h"
 
 namespace zkmi {
@@ -45,6 +46,10 @@ struct DataRound29Args {
     EqSplit eq;  // eq.lo_off: the low table scaled by 2^10 (so times 2^266), eq.hi_off: unscaled
     uint32_t* partials;
     size_t pstride;
+    // SMALL_S: S is given as small integers (small_dev.h) and folded from them
+    const int32_t* sx;
+    const int32_t* sy;      // may be null
+    const SmallFold4* sf;   // device memory: the constants of the fold by r_prev
 };
 
 template <bool WORDS32>
@@ -92,8 +97,26 @@ __device__ __forceinline__ void fold_pair29(const PairArray29& a, size_t p, size
     f29_store<OUT32>(a, p + half, x1);
 }
 
-template <bool IN32, bool OUT32>
+// The pair of S for the first folding round when S comes as small integers:
+// folded entries straight from the four integers each, reduced, then as 29-bit limbs.
+template <bool OUT32>
+__device__ __forceinline__ void fold_pair29_small(const DataRound29Args& g, size_t p, F29& x0, F29& x1) {
+    const size_t half = g.half;
+    auto entry = [&](size_t i0, size_t i1) {
+        uint32_t w[8];
+        small_fold_combined(w, g.sx[i0], g.sy ? g.sy[i0] : 0, g.sx[i1], g.sy ? g.sy[i1] : 0, *g.sf);
+        return f29_unpack(w);
+    };
+    x0 = entry(p, p + 2 * half);
+    f29_store<OUT32>(g.S, p, x0);
+    x1 = entry(p + half, p + 3 * half);
+    f29_store<OUT32>(g.S, p + half, x1);
+}
+
+
+template <bool IN32, bool OUT32, bool SMALL_S = false>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 3))) k_round_data29(DataRound29Args g) {
+    static_assert(!SMALL_S || IN32, "integers are what the first folding round reads");
     __shared__ uint32_t lds[4 * 6 * 8];
     F29Wide wide0 = f29_wide_zero(), wide1 = f29_wide_zero(), wide2 = f29_wide_zero();
     F29 sA0 = f29_zero(), sA1 = f29_zero();
@@ -103,7 +126,8 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 
     for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
         F29 a0, a1, s0, s1;
         fold_pair29<IN32, OUT32>(g.A, p, g.half, g.r_prev, a0, a1);
-        fold_pair29<IN32, OUT32>(g.S, p, g.half, g.r_prev, s0, s1);
+        if constexpr (SMALL_S) fold_pair29_small<OUT32>(g, p, s0, s1);
+        else fold_pair29<IN32, OUT32>(g.S, p, g.half, g.r_prev, s0, s1);
         F29 w;
         {
             uint32_t ww[8];

@@ -48,6 +48,25 @@ void c_fold64(int64_t a, int64_t b, const uint32_t* k32, uint32_t* out) {
     small_fold64(o, a, b, consts_of(k32));
     for (int i = 0; i < 8; ++i) out[i] = o[i];
 }
+void c_combine32(int32_t x, int32_t y, const uint32_t* k32, uint32_t* out) {
+    SmallSource k;
+    k.x = nullptr; k.y = nullptr;
+    for (int i = 0; i < 8; ++i) {
+        k.plus_one[i] = k32[i]; k.minus_one[i] = k32[8 + i]; k.plus_rho[i] = k32[16 + i]; k.minus_rho[i] = k32[24 + i];
+    }
+    uint32_t o[8];
+    small_combine32(o, x, y, k);
+    for (int i = 0; i < 8; ++i) out[i] = o[i];
+}
+void c_fold_combined(int32_t x0, int32_t y0, int32_t x1, int32_t y1, const uint32_t* k64, uint32_t* out) {
+    SmallFold4 k;
+    uint32_t* dst[8] = {k.plus_one, k.minus_one, k.plus_c, k.minus_c, k.plus_rho, k.minus_rho, k.plus_rho_c, k.minus_rho_c};
+    for (int q = 0; q < 8; ++q)
+        for (int i = 0; i < 8; ++i) dst[q][i] = k64[8 * q + i];
+    uint32_t o[8];
+    small_fold_combined(o, x0, y0, x1, y1, k);
+    for (int i = 0; i < 8; ++i) out[i] = o[i];
+}
 void c_fold32(uint32_t a, uint32_t b, const uint32_t* k32, uint32_t* out) {
     uint32_t o[8];
     small_fold32(o, a, b, consts_of(k32));

@@ -100,3 +100,25 @@ def test_fold_of_small_integers(lib):
         b = rng.choice(edge32 + [rng.randrange(2 ** 32)])
         lib.c_fold32(a, b, ptr(k), ptr(out))
         assert value(out) == (a + rho * (b - a)) * s * MONT % R
+
+
+def test_pair_of_columns_combined_and_folded(lib):
+    """x + rho y, and the fold of two such entries by a challenge, for signed 32-bit columns."""
+    lib.c_combine32.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+    lib.c_fold_combined.argtypes = [ctypes.c_int32] * 4 + [ctypes.c_void_p, ctypes.c_void_p]
+    rng = random.Random(4)
+    scale = MONT * pow(2, 64, R)
+    edge = [0, 1, -1, 2 ** 31 - 1, -(2 ** 31)]
+    pick = lambda: rng.choice(edge + [rng.randrange(-(2 ** 31), 2 ** 31)])
+    for _ in range(300):
+        rho, c = rng.choice([0, 1, rng.randrange(R), R - 1]), rng.choice([0, 1, rng.randrange(R), R - 1])
+        k = np.concatenate([words(v * scale % R, 8) for v in (1, -1, rho, -rho)])
+        x, y = pick(), pick()
+        out = np.zeros(8, np.uint32)
+        lib.c_combine32(x, y, ptr(k), ptr(out))
+        assert value(out) == (x + rho * y) * MONT % R
+        k4 = np.concatenate([words(v * scale % R, 8) for v in (1, -1, c, -c, rho, -rho, rho * c, -rho * c)])
+        x1, y1 = pick(), pick()
+        lib.c_fold_combined(x, y, x1, y1, ptr(k4), ptr(out))
+        s0, s1 = x + rho * y, x1 + rho * y1
+        assert value(out) == (s0 + c * (s1 - s0)) * MONT % R
