@@ -39,6 +39,19 @@ struct F29Wide {
 
 static constexpr uint32_t kM29 = (1u << 29) - 1;
 
+// acc + x for a 64-bit accumulator and a 32-bit x.  On the device the sum is
+// written as a multiply-add by a one the compiler cannot see through: a single
+// v_mad_u64_u32, where the plain sum costs a move (to widen x) and a 64-bit add.
+ZK_HD uint64_t f29_acc_add(uint64_t acc, uint32_t x) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t one = 1;
+    asm("" : "+s"(one));
+    return acc + (uint64_t)x * one;
+#else
+    return acc + x;
+#endif
+}
+
 // r in 29-bit limbs.  r = 1 mod 2^29, so the Montgomery digit of a column is
 // its negated low limb and the r_0 term adds exactly that digit.
 #define ZK_R29_LIMBS \
@@ -149,7 +162,7 @@ ZK_HD void f29_column_low(uint64_t& acc, const uint32_t* a, const uint32_t* b, u
 #pragma unroll
     for (int i = 0; i < C; ++i) acc += (uint64_t)m[i] * r[C - i];
     m[C] = (0u - (uint32_t)acc) & kM29;
-    acc += m[C];  // the r_0 term: clears the low 29 bits
+    acc = f29_acc_add(acc, m[C]);  // the r_0 term: clears the low 29 bits
     acc >>= 29;
 }
 
@@ -188,6 +201,47 @@ ZK_HD F29 f29_mul(const F29& a, const F29& b) {
     f29_column_high<15>(acc, a.l, b.l, m, t.l);
     f29_column_high<16>(acc, a.l, b.l, m, t.l);
     t.l[8] = (uint32_t)acc;
+    return t;
+}
+
+// The same with the addend's limb taken into each result column before it is cut:
+// a b / 2^261 + c mod r, normalized, value below a b / 2^261 + r + c.  c must be
+// normalized.  (One pass of carries serves the product and the sum.)
+template <int C>
+ZK_HD void f29_column_high_add(uint64_t& acc, const uint32_t* a, const uint32_t* b, const uint32_t* m, const uint32_t* c,
+                               uint32_t* t) {
+    constexpr uint32_t r[9] = ZK_R29_LIMBS;
+#pragma unroll
+    for (int j = C - 8; j <= 8; ++j) acc += (uint64_t)a[j] * b[C - j];
+#pragma unroll
+    for (int i = C - 8; i <= 8; ++i) acc += (uint64_t)m[i] * r[C - i];
+    acc = f29_acc_add(acc, c[C - 9]);
+    t[C - 9] = (uint32_t)acc & kM29;
+    acc >>= 29;
+}
+
+ZK_HD F29 f29_mul_add(const F29& a, const F29& b, const F29& c) {
+    uint32_t m[9];
+    F29 t;
+    uint64_t acc = 0;
+    f29_column_low<0>(acc, a.l, b.l, m);
+    f29_column_low<1>(acc, a.l, b.l, m);
+    f29_column_low<2>(acc, a.l, b.l, m);
+    f29_column_low<3>(acc, a.l, b.l, m);
+    f29_column_low<4>(acc, a.l, b.l, m);
+    f29_column_low<5>(acc, a.l, b.l, m);
+    f29_column_low<6>(acc, a.l, b.l, m);
+    f29_column_low<7>(acc, a.l, b.l, m);
+    f29_column_low<8>(acc, a.l, b.l, m);
+    f29_column_high_add<9>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<10>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<11>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<12>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<13>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<14>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<15>(acc, a.l, b.l, m, c.l, t.l);
+    f29_column_high_add<16>(acc, a.l, b.l, m, c.l, t.l);
+    t.l[8] = (uint32_t)acc + c.l[8];
     return t;
 }
 
@@ -236,16 +290,16 @@ ZK_HD F29 f29_wide_reduce(const F29Wide& w) {
     uint64_t acc = 0;
 #pragma unroll
     for (int c = 0; c < 9; ++c) {
-        acc += w.l[c];
+        acc = f29_acc_add(acc, w.l[c]);
 #pragma unroll
         for (int i = 0; i < c; ++i) acc += (uint64_t)m[i] * r[c - i];
         m[c] = (0u - (uint32_t)acc) & kM29;
-        acc += m[c];
+        acc = f29_acc_add(acc, m[c]);
         acc >>= 29;
     }
 #pragma unroll
     for (int c = 9; c < 17; ++c) {
-        acc += w.l[c];
+        acc = f29_acc_add(acc, w.l[c]);
 #pragma unroll
         for (int i = c - 8; i <= 8; ++i) acc += (uint64_t)m[i] * r[c - i];
         t.l[c - 9] = (uint32_t)acc & kM29;
@@ -253,6 +307,13 @@ ZK_HD F29 f29_wide_reduce(const F29Wide& w) {
     }
     t.l[8] = (uint32_t)(acc + w.l[17]);
     return t;
+}
+
+// x times one (2^261 mod r as the second factor): the same value mod r, normalized
+// and below x / 2^261 + r, i.e. a lazy value of up to 2^264 brought below 9 r.
+ZK_HD F29 f29_shrink(const F29& x) {
+    constexpr F29 unit = {ZK_ONE261_LIMBS};
+    return f29_mul(x, unit);
 }
 
 // ---- back to the canonical representative ---------------------------------------------

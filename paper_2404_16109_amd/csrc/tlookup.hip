@@ -32,9 +32,18 @@ struct EqPool {
     uint32_t* pool = nullptr;
     size_t stride = 0;
     uint32_t suffix_off[kLoBits + 1];
-    uint32_t suffix29_off[kLoBits + 1];
+    uint32_t suffix29_off[kLoBits + 1];  // within pool29
     uint32_t high_off[32];
+    uint4* pool29 = nullptr;  // the scaled suffix tables as 29-bit limbs, three planes of count29 elements
+    size_t count29 = 0;
     int n = 0;
+
+    static size_t entries29(int n) {
+        size_t total = 0;
+        int smax = n - 1 < kLoBits ? n - 1 : kLoBits;
+        for (int s = 0; s <= smax; ++s) total += (size_t)1 << s;
+        return total ? total : 1;
+    }
 
     static size_t entries(int n) {
         size_t total = 0;
@@ -59,18 +68,15 @@ struct EqPool {
         e.hi_off = e.has_hi ? high_off[k] : 0;
         return e;
     }
-    EqSplit round29(int k) const {
-        EqSplit e = round(k);
-        e.lo_off = suffix29_off[e.lbits];
-        return e;
-    }
 };
 
 static int eq_pool_build(EqPool& ep, const host::F* u, int n, Carver& cv, hipStream_t stream) {
     ep.n = n;
     ep.stride = EqPool::entries(n);
     ep.pool = cv.limbs(ep.stride);
-    if (!ep.pool) return ZK_E_BUFSZ;
+    ep.count29 = EqPool::entries29(n);
+    ep.pool29 = (uint4*)cv.take(ep.count29 * 36);
+    if (!ep.pool || !ep.pool29) return ZK_E_BUFSZ;
     EqPoolArgs args;
     memset(&args, 0, sizeof args);
     for (int t = 0; t < n; ++t) args.u[t] = to_dev(u[t]);
@@ -87,8 +93,11 @@ static int eq_pool_build(EqPool& ep, const host::F* u, int n, Carver& cv, hipStr
     }
     if (n == 0) ep.suffix_off[0] = 0;
     args.scale = to_dev(host::from_u64(1024));
+    args.pool29 = ep.pool29;
+    args.count29 = ep.count29;
+    args.first29 = off;
     for (int s = 0; s <= smax; ++s) {
-        ep.suffix29_off[s] = off;
+        ep.suffix29_off[s] = off - args.first29;
         args.offset[q] = off;
         args.var0[q] = (uint8_t)(n - s);
         args.nvars[q] = (uint8_t)s;
@@ -301,6 +310,7 @@ static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
         carve_prove(w, cv, D, N);
     }
     cv.limbs(EqPool::entries(log2_floor(D)));
+    cv.take(EqPool::entries29(log2_floor(D)) * 36);
     for (size_t i = 0; i < K; ++i) {
         size_t apart = batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N), joined = batch_inverse_scratch_bytes(D + N);
         cv.take(apart > joined ? apart : joined);
@@ -414,6 +424,9 @@ struct Instance {
     uint32_t* const_words = nullptr;  // its two table-side constants
     uint32_t* dig_words = nullptr;    // hash-state words of digest(A), then of digest(B)
     host::F c1, c2, cB, sum_A, lam;
+    host::F claim;       // the running claim of this instance's own sumcheck: f_i's round polynomial at 0 plus at 1
+    host::F fX[4];       // its last round polynomial at X = 0..3
+    host::F sA_prev[2];  // its last round's sums of A at X = 0, 1
     uint8_t md[32], dA[32], dB[32];
     BatchInverseJob job_a, job_b;
     bool deferred = false;  // S_i = T[idx_i] is checked through sum A = sum m B after the first round, not while counting
@@ -837,6 +850,17 @@ static int prove_core(const ProveCall& c) {
         const EqSplit eq = ep.round(k);
         const RoundPlan plan = plan_round(n, h, k, K, from_ints, lazy_rounds, tail_first >= 0);
         if (plan.s_source == kSNowhere) return ZK_E_BADARG;  // cannot happen: small_source_shape_ok has walked these rounds
+        // The 29-bit kernel sums one side of the round only (X = 0, or X = 1 with side1); the other side's two sums
+        // follow from what the prover has already sent: sA0 + sA1 is the previous round's sum of A at its challenge,
+        // g(0) + g(1) the running claim.  The second needs a division by alpha c e~(u_k, X) of the side that was not
+        // summed, so the side is chosen by which of the two is not zero (alternating otherwise, both being equally
+        // good); if alpha c itself is zero, q carries no weight in g and is not needed.
+        const F e_side[2] = {sub(one(), u[k]), u[k]};
+        const F wD = mul(alpha, cD);
+        bool side1 = (k & 1) != 0;
+        if (is_zero(e_side[0])) side1 = false;  // u_k = 1: only g(1) can tell q1, so sum the X = 0 side
+        if (is_zero(e_side[1])) side1 = true;
+        F inv_den = zero();
         const bool table_round = plan.table_round;
         const bool in32 = plan.in32, out32 = plan.out32;
         // pairs per workgroup: a workgroup's pairs must share the high factor of
@@ -945,15 +969,21 @@ static int prove_core(const ProveCall& c) {
             } else if (plan.kernel == kRound29) {
                 DataRound29Args d29;
                 // 32-bit words: A in place (stride D), S from the caller's vector or Sf; 29-bit limbs: A29, S29
-                d29.A = PairArray29{w.A, D, w.A29, w.A29 + D / 2, (const uint32_t*)(w.A29 + D) , w.A29, w.A29 + D / 2,
-                                    (uint32_t*)(w.A29 + D), w.A, D};
-                d29.S = PairArray29{d.S.src, d.S.ss, w.S29, w.S29 + D / 2, (const uint32_t*)(w.S29 + D), w.S29, w.S29 + D / 2,
-                                    (uint32_t*)(w.S29 + D), w.Sf, D / 2};
+                d29.A = Array29{w.A, D, Planes29{w.A29, D / 2}, w.A, D};
+                d29.S = Array29{d.S.src, d.S.ss, Planes29{w.S29, D / 2}, w.Sf, D / 2};
                 d29.half = half;
                 d29.block_span = span;
+                d29.off0 = side1 ? half : 0;
+                d29.off1 = side1 ? 0 : half;
                 d29.r_prev = f29_unpack(to_dev(mul(r_prev, from_u64(32))).l);
                 d29.beta = beta29;
-                d29.eq = ep.round29(k);
+                d29.weights = Planes29{ep.pool29, ep.count29};
+                d29.lo_off = ep.suffix29_off[eq.lbits];
+                d29.lbits = eq.lbits;
+                d29.has_hi = eq.has_hi;
+                d29.hi_pool = ep.pool;
+                d29.hi_stride = ep.stride;
+                d29.hi_off = eq.hi_off;
                 d29.partials = d.partials;
                 d29.pstride = d.pstride;
                 d29.sx = nullptr;
@@ -1002,12 +1032,14 @@ static int prove_core(const ProveCall& c) {
             ZK_HIP_TRY(hipGetLastError());
         }
         lazy_rounds = plan.lazy_after;
+        // while the device works: each instance's running claim, and the inverse the 29-bit round's other side needs
+        for (size_t i = 0; i < K; ++i) inst[i].claim = k == 0 ? add(alpha, alpha2) : interpolate_at(inst[i].fX, 4, r_prev);
+        if (plan.kernel == kRound29 && tail_first < 0 && !is_zero(wD)) inv_den = inv(mul(wD, e_side[side1 ? 0 : 1]));
         ZK_TRY(mailbox_wait(mb, seq, stream));
         read_table_consts();
 
         F e[4], g[4];
-        line_values(e, sub(one(), u[k]), u[k]);
-        const F wD = mul(alpha, cD);
+        line_values(e, e_side[0], e_side[1]);
         const F wT = table_round ? mul(alpha2, cT) : zero();
         half_pow = mul(half_pow, inv2);
         for (int X = 0; X < 4; ++X) g[X] = zero();
@@ -1017,6 +1049,22 @@ static int prove_core(const ProveCall& c) {
             F q0 = from_dev(sums), q1 = from_dev(sums + 8), qi = from_dev(sums + 16);
             if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
             F sA0 = from_dev(sums + 24), sA1 = from_dev(sums + 32);
+            if (plan.kernel == kRound29 && tail_first < 0) {
+                // the kernel has summed one side: (q0, sA0) hold that side's q and sum of A; the other side from
+                // sA(0) + sA(1) = sA_prev(r_prev) and g(0) + g(1) = claim (never a table round: the table side is a constant)
+                const int a = side1 ? 1 : 0;
+                const F tconst = mul(I.cB, half_pow);
+                const F sA_b = sub(add(I.sA_prev[0], mul(r_prev, sub(I.sA_prev[1], I.sA_prev[0]))), sA0);
+                const F g_a = add(add(mul(mul(wD, e_side[a]), q0), sA0), tconst);
+                const F q_b = mul(sub(sub(sub(I.claim, g_a), sA_b), tconst), inv_den);
+                const F q_a = q0, sA_a = sA0;
+                q0 = a == 0 ? q_a : q_b;
+                q1 = a == 0 ? q_b : q_a;
+                sA0 = a == 0 ? sA_a : sA_b;
+                sA1 = a == 0 ? sA_b : sA_a;
+            }
+            I.sA_prev[0] = sA0;
+            I.sA_prev[1] = sA1;
             if (k == 0) I.sum_A = add(sA0, sA1);
             if (k == 0 && I.deferred && !equal(I.sum_A, I.c2)) {
                 // The counts were taken from the hints without looking at S.  Had every
@@ -1045,6 +1093,7 @@ static int prove_core(const ProveCall& c) {
                 F data = add(mul(mul(wD, e[X]), q[X]), sa[X]);
                 F table = table_round ? mul(scale, sub(mul(mul(wT, e[X]), tq[X]), tm[X])) : table_const;
                 F f = add(data, table);
+                I.fX[X] = f;
                 g[X] = add(g[X], K == 1 ? f : mul(I.lam, f));
             }
         }

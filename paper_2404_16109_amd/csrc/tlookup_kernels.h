@@ -5,6 +5,7 @@
 #pragma once
 #include "common.h"
 #include "reduce_dev.h"
+#include "fr29_dev.h"
 #include "sha256_dev.h"
 #include "small_dev.h"
 
@@ -532,16 +533,22 @@ static __global__ void __launch_bounds__(kBlock) k_digest_tree(DigestTreeJob fir
 // ---- pooled eq tables ----------------------------------------------------------------
 
 // Table q covers variables [var0, var0 + nvars) of the point and occupies
-// elements [offset, offset + 2^nvars) of the pool.
+// elements [offset, offset + 2^nvars) of the pool.  Tables marked `scaled` are
+// the weights of the rounds on 29-bit limbs: their entries are multiplied by
+// `scale` and go, as nine 29-bit limbs, into a pool of their own (three planes of
+// `count29` elements, see Planes29 in tlookup_round29.h) at offset - first29.
 struct EqPoolArgs {
     Fr u[32];
     uint32_t offset[64];
     uint8_t var0[64];
     uint8_t nvars[64];
-    uint8_t scaled[64];  // entries of this table are multiplied by `scale`
+    uint8_t scaled[64];
     Fr scale;
     int ntables;
     uint32_t total;
+    uint4* pool29;
+    size_t count29;
+    uint32_t first29;
 };
 
 static __global__ void __launch_bounds__(kBlock) k_eq_pool(uint32_t* __restrict__ pool, size_t stride, EqPoolArgs args) {
@@ -557,8 +564,16 @@ static __global__ void __launch_bounds__(kBlock) k_eq_pool(uint32_t* __restrict_
             Fr f = bit ? args.u[v0 + t] : fr_sub(one, args.u[v0 + t]);
             acc = t == 0 ? f : fr_mul(acc, f);
         }
-        if (args.scaled[q]) acc = fr_mul(acc, args.scale);
-        fr_store(pool, stride, g, acc);
+        if (args.scaled[q]) {
+            acc = fr_mul(acc, args.scale);
+            const F29 v = f29_unpack(acc.l);
+            const size_t i = g - args.first29;
+            args.pool29[i] = make_uint4(v.l[0], v.l[1], v.l[2], v.l[3]);
+            args.pool29[args.count29 + i] = make_uint4(v.l[4], v.l[5], v.l[6], v.l[7]);
+            reinterpret_cast<uint32_t*>(args.pool29 + 2 * args.count29)[i] = v.l[8];
+        } else {
+            fr_store(pool, stride, g, acc);
+        }
     }
 }
 

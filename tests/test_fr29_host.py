@@ -181,3 +181,106 @@ def test_canonical(lib):
         c = np.zeros(8, np.uint32)
         lib.c_canonical_big(ptr(limbs_of(x)), ptr(c))
         assert words_value(c) == x % R
+
+
+def test_mul_add_is_product_plus_addend(lib):
+    rng = random.Random(8)
+    inv = pow(2, -261, R)
+    cases = []
+    for _ in range(300):  # the fold: a padded difference times the challenge, plus an entry below 17 r
+        cases.append((lazy_limbs(rng, 3 * 2 ** 29, 2 ** 29), limbs_of(rng.randrange(R)), limbs_of(rng.randrange(17 * R))))
+    cases.append((arr([3 * 2 ** 29 - 1] * 8 + [2 ** 29]), arr([M29] * 8 + [0x73eda7]), arr([M29] * 8 + [0x7b2ec8])))
+    for a, b, c in cases:
+        out = np.zeros(9, np.uint32)
+        lib.c_mul_add(ptr(a), ptr(b), ptr(c), ptr(out))
+        va, vb, vc, vo = value_of(a), value_of(b), value_of(c), value_of(out)
+        assert vo % R == (va * vb * inv + vc) % R
+        assert vo < va * vb // 2 ** 261 + R + 1 + vc
+        assert all(int(v) <= M29 for v in out[:8])
+
+
+def test_shrink(lib):
+    rng = random.Random(10)
+    for x in [0, 1, R, 272 * R, 2 ** 264 - 1] + [rng.randrange(2 ** 264) for _ in range(200)]:
+        out = np.zeros(9, np.uint32)
+        lib.c_shrink(ptr(limbs_of(x)), ptr(out))
+        vo = value_of(out)
+        assert vo % R == x % R and vo < x * pow(2, 261, R) // 2 ** 261 + R + 1 and all(int(v) <= M29 for v in out[:8])
+        assert vo < 9 * R
+
+
+def _round29_thread(lib, entries, weights, r261, beta, want_peak=True):
+    pairs = len(weights)
+    e = np.concatenate([np.concatenate(p) for p in entries]).astype(np.uint32)
+    w = np.concatenate(weights).astype(np.uint32)
+    folded = np.zeros(36 * pairs, np.uint32)
+    out = np.zeros(27, np.uint32)
+    peak = ctypes.c_uint64(0)
+    lib.c_round29_thread(pairs, ptr(e), ptr(w), ptr(limbs_of(r261)), ptr(limbs_of(beta)), ptr(folded), ptr(out),
+                         ctypes.byref(peak) if want_peak else None)
+    return folded.reshape(pairs, 4, 9), out.reshape(3, 9), peak.value
+
+
+def _check_round29_thread(lib, entries, weights, r261, beta):
+    """The whole per-thread schedule of the large folding rounds against Python integers: the four folds of
+    every pair, the three sums, and every bound the kernel's sums across lanes rely on."""
+    inv = pow(2, -261, R)
+    folded, out, peak = _round29_thread(lib, entries, weights, r261, beta)
+    q0 = qinf = sA0 = 0
+    for j, (pair, w) in enumerate(zip(entries, weights)):
+        y = [value_of(v) for v in pair]
+        want = [(y[0] + (y[2] - y[0]) * r261 * inv) % R, (y[1] + (y[3] - y[1]) * r261 * inv) % R,
+                (y[4] + (y[6] - y[4]) * r261 * inv) % R, (y[5] + (y[7] - y[5]) * r261 * inv) % R]
+        got = [value_of(folded[j][q]) for q in range(4)]
+        assert [g % R for g in got] == want
+        # a fold adds less than 2 r to the entry it starts from, and leaves normalized limbs
+        for g, start in zip(got, (y[0], y[1], y[4], y[5])):
+            assert g < start + 2 * R
+        assert all(int(v) <= M29 for q in range(4) for v in folded[j][q][:8])
+        a0, a1, s0, s1 = want
+        wv = value_of(w)
+        q0 += (a0 * wv * inv) * (s0 + beta)
+        qinf += ((a1 - a0) * wv * inv) * (s1 - s0)
+        sA0 += a0
+    got = [value_of(out[q]) for q in range(3)]
+    assert got[0] % R == q0 * inv % R and got[1] % R == qinf * inv % R and got[2] % R == sA0 % R
+    # what the sums over a wavefront (64 lanes, then one more shrink for sA0, then four wavefronts) need
+    assert all(g < 5 * R for g in got) and all(int(v) <= M29 for q in range(3) for v in out[q][:8])
+    assert peak < 2 ** 32 - 2 ** 29          # no lazy limb came near wrapping between two normalizations
+    return peak
+
+
+def test_round29_thread_schedule_at_its_bounds(lib):
+    """Sixteen pairs per thread, entries at the bound eight lazy rounds can reach (just below 17 r) with every
+    limb full, the largest weight, challenge and beta: the worst case for every accumulator of the schedule."""
+    top17 = (17 * R - 1) >> 232
+    full = arr([M29] * 8 + [top17 - 1])         # all limbs full, value just below 17 r
+    assert 16 * R < value_of(full) < 17 * R
+    zero = arr([0] * 9)
+    rmax = arr([(R - 1 >> (29 * i)) & M29 for i in range(8)] + [(R - 1) >> 232])
+    worst = 0
+    for entries_of_pair in ([full] * 8,                                   # everything at the bound
+                            [zero, full, full, zero, full, zero, zero, full],   # differences at their extremes
+                            [full, zero, zero, full, zero, full, full, zero]):
+        for r261 in (R - 1, 1, pow(2, 261, R)):
+            peak = _check_round29_thread(lib, [entries_of_pair] * 16, [rmax] * 16, r261, R - 1)
+            worst = max(worst, peak)
+    assert worst > 2 ** 31                      # the test does reach the region the bound is about
+    rng = random.Random(11)
+    for pairs in (1, 2, 3, 4, 7, 8, 16):
+        entries = [[limbs_of(rng.randrange(17 * R)) for _ in range(8)] for _ in range(pairs)]
+        weights = [limbs_of(rng.randrange(R)) for _ in range(pairs)]
+        _check_round29_thread(lib, entries, weights, rng.randrange(R), rng.randrange(R))
+
+
+def test_round29_eight_lazy_rounds_in_a_row(lib):
+    """Entries that start below r stay below 17 r through eight folds in a row (what the prover runs before it
+    writes reduced words again), with the challenge that makes every fold add the most."""
+    rng = random.Random(12)
+    vals = [limbs_of(R - 1 - rng.randrange(1000)) for _ in range(8)]
+    for rnd in range(8):
+        folded, out, _ = _round29_thread(lib, [vals], [limbs_of(R - 1)], R - 1, R - 1, want_peak=False)
+        nxt = [folded[0][q].copy() for q in range(4)]
+        assert all(value_of(v) < (1 + 2 * (rnd + 1)) * R for v in nxt)
+        vals = [nxt[0], nxt[1], nxt[2], nxt[3], nxt[2], nxt[3], nxt[0], nxt[1]]
+    assert max(value_of(v) for v in vals) < 17 * R
