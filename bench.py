@@ -2,7 +2,8 @@
 """Benchmark of the tlookup prover hot path on one MI355X.
 
 A "step" is one whole `tlookup_prove` call (multiplicities, digest of m, both
-batch inversions, eq tables, all sumcheck rounds with folding, transcript) on
+batch inversions, the digests of A and B that stand in for their commitments, eq
+tables, all sumcheck rounds with folding, transcript) on
 the 7B-FFN activation-table workload: D = 2^25 elements (2048 x 11008
 activations padded), N = 2^16 table rows, inputs resident in HBM as limb-major
 Montgomery vectors.  Prints one JSON line.
@@ -25,6 +26,8 @@ PEAK_MAD_PER_S = 256 * 64 * 2.4e9      # 256 CUs x 64 lanes x 2.4 GHz, one 32-bi
 MADS_PER_FR_MUL = 112                   # 64 for the 8x8-limb product + 48 for the reduction (two of r's limbs need no multiplier)
 ROUND_DATA_FR_MUL_PER_PAIR_EVAL = 5     # two to weight A0, A1, three products
 ROUND_DATA_FR_MUL_PER_PAIR_FOLD = 4     # two arrays, two folded entries per pair
+PEAK_HBM_BYTES_PER_S = 8e12             # MI355X HBM3E, published
+WHOLE_PROVE_BYTES_PER_ELEMENT = 292     # hints 4 + inversion 96 + rounds 192 (every array read once, written at half size)
 
 
 def fr_mul_model(D, N):
@@ -59,9 +62,35 @@ def measured_traffic():
     return None
 
 
-def cpu_baseline(logD, logN):
+def recorded_fullsize_oracle():
+    """The oracle's wall time on the headline workload at full size, recorded when the
+    expected proof was written (profiles/oracle_c3_fullsize.txt: lines `SECONDS=`, `CORES=`)."""
+    path = os.path.join(ROOT, "profiles", "oracle_c3_fullsize.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for line in open(path):
+        for key in ("SECONDS", "CORES"):
+            if line.startswith(key + "="):
+                vals[key] = float(line.split("=", 1)[1])
+    return vals if len(vals) == 2 else None
+
+
+def measured_whole_prove_traffic():
+    """HBM bytes of one whole prove from the committed counter summary (line `WHOLE_PROVE_BYTES=`)."""
+    path = os.path.join(ROOT, "profiles", "round_data_c3_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("WHOLE_PROVE_BYTES="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def cpu_baseline(logD, logN, full_D, full_N):
     """The oracle as it stands, timed on the host cores on a bounded sample of the
-    same workload (same generator, smaller D)."""
+    same workload (same generator, smaller D); the figure for the full workload is
+    this sample's rate under the fixed work model, and is labelled as such."""
     import numpy as np
     from oracle import pyoracle as orc
     from paper_2404_16109_amd import synth
@@ -75,8 +104,17 @@ def cpu_baseline(logD, logN):
     rc, proof, _ = orc.tlookup_prove(cfg["seed"], S, T, threads=threads)
     dt = time.perf_counter() - t0
     assert rc == 0
-    return {"value": fr_mul_model(1 << logD, 1 << logN) / dt, "unit": "Fr-mul/s", "cores": threads, "kind": "oracle",
-            "sample": "oracle tlookup_prove on the same generator at D=2^%d, N=2^%d: %.1f s wall" % (logD, logN, dt)}
+    out = {"value": fr_mul_model(1 << logD, 1 << logN) / dt, "unit": "Fr-mul/s", "cores": threads, "kind": "oracle",
+           "sample": "oracle tlookup_prove timed in this run on the same generator at D=2^%d, N=2^%d: %.1f s wall on %d "
+                     "threads; value = that sample's rate under the fixed work model (10 multiplications per element "
+                     "and per table row), not a measurement at D=2^%d" % (logD, logN, dt, threads, full_D.bit_length() - 1)}
+    rec = recorded_fullsize_oracle()
+    if rec:
+        out["fullsize_recorded"] = {"seconds": rec["SECONDS"], "cores": int(rec["CORES"]),
+                                    "value": fr_mul_model(full_D, full_N) / rec["SECONDS"],
+                                    "note": "the oracle's own run at D=2^25, N=2^16 that wrote tests/golden/config3_proof.txt "
+                                            "(another machine than this run's: the build container)"}
+    return out
 
 
 def bench_matmul(args, zk, synth, torch, np):
@@ -305,14 +343,15 @@ def main():
     ap.add_argument("--logD", type=int, default=25)
     ap.add_argument("--logN", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-logD", type=int, default=19)
+    ap.add_argument("--cpu-logD", type=int, default=21)
     ap.add_argument("--workload", choices=["c3", "c4", "c5", "link"], default="c3",
                     help="c3: tlookup at D=2^25, N=2^16 (the headline metric); c4: matmul sumcheck 2048x5120x5120; "
                          "c5: batched two-segment attention lookup at D=2^28; link: the sumcheck linking the attention "
                          "workload's tensors, 2^17 x 2048 (c4, c5, link: secondary timings)")
     ap.add_argument("--link-rows", type=int, default=0, help="with --workload link: this many rows of 2048 scores "
                     "instead of the full 40 x 2048 (a power of two)")
-    ap.add_argument("--no-by-rows", action="store_true", help="skip the tlookup_prove_by_rows timing beside the headline")
+    ap.add_argument("--no-variants", "--no-by-rows", dest="no_variants", action="store_true",
+                    help="skip the timings beside the headline (no hints, exact check, A by gather, integer columns)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (reads 2^30 B, writes 2^30 B) so that rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings can be scaled by a kernel of known traffic")
@@ -357,49 +396,86 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    def timed(fn, steps):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            out = fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, out
+
+    # -- the headline: W warm-up steps, then exactly K timed steps, nothing else going on
     first = None
     for _ in range(args.warmup):
         first, _ = step()
-    zk.zkmi_profile_reset()
-    zk.zkmi_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        proof, info = step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    zk.zkmi_profile_enable(False)
+    ms, (proof, info) = timed(step, args.steps)
     assert first is None or proof == first            # exact arithmetic: every run gives the same bytes
     assert info["sum_A"] == info["sum_mB"]            # log-derivative identity at beta
 
-    ms = dt * 1e3 / args.steps
-    # beside the headline: the same proof with A read off the table-side inverses
-    ms_rows = None
-    if not args.no_by_rows:
-        for _ in range(2):
-            rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws)
-            assert rc == 0 and proof_rows == proof
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            rc, proof_rows, _ = zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws)
-        torch.cuda.synchronize()
-        ms_rows = (time.perf_counter() - t0) * 1e3 / args.steps
+    # -- beside it (each checked to give the same proof, two warm-up calls, then timed)
+    beside = {}
+    if not args.no_variants:
+        X = torch.from_numpy(cfg["tx"].astype(np.int32)).cuda()[idx.long()].contiguous()
+        Y = torch.from_numpy(cfg["ty"].astype(np.int32)).cuda()[idx.long()].contiguous()
+        rho = synth.pair_combiner(cfg["seed"])
+        ws_small = torch.empty(zk.tlookup_small_workspace_bytes(D, N), dtype=torch.uint8, device="cuda")
+        variants = {
+            # rows found through the hash of T, every S_i compared with its row while counting
+            "unhinted_ms_per_step": lambda: zk.tlookup_prove(cfg["seed"], S, None, T, ws=ws)[:2],
+            # hints given, but every S_i compared with T[idx_i] up front instead of through the identity
+            "checked_ms_per_step": lambda: zk.tlookup_prove_checked(cfg["seed"], S, idx, T, ws=ws)[:2],
+            # A read off the table-side inverses instead of inverting D elements
+            "by_rows_ms_per_step": lambda: zk.tlookup_prove_by_rows(cfg["seed"], S, idx, T, ws=ws)[:2],
+            # the tensor as two int32 columns (8 bytes per entry instead of 32)
+            "small_ms_per_step": lambda: zk.tlookup_prove_small(cfg["seed"], X, Y, rho, idx, T, ws=ws_small)[:2],
+        }
+        for name, fn in variants.items():
+            for _ in range(2):
+                rc, got = fn()
+                assert rc == 0 and got == proof, name
+            beside[name], _ = timed(fn, args.steps)
+
+    # -- where the time goes: a separate pass with the library's own event pairs on the launch stream
+    zk.zkmi_profile_reset()
+    zk.zkmi_profile_enable(True)
+    psteps = max(1, min(args.steps, 5))
+    timed(step, psteps)
+    zk.zkmi_profile_enable(False)
+    names = ("total", "count", "inverse", "digest", "round_data", "round_table", "round_data29", "round_small")
     phases = {}
-    for name in ("total", "count", "inverse", "round_data", "round_table", "round_data29"):
+    for name in names:
         rc, recs, total_ms = zk.zkmi_profile_query(name)
-        phases[name] = {"records": recs, "ms_per_step": total_ms / args.steps}
-    # round_data: every round kernel with a data side, the dominant one (round_data29) included
-    phases["round_data"] = {"records": phases["round_data"]["records"] + phases["round_data29"]["records"],
-                            "ms_per_step": phases["round_data"]["ms_per_step"] + phases["round_data29"]["ms_per_step"]}
+        phases[name] = {"records": recs, "ms_per_step": total_ms / psteps}
+
     # the dominant kernel: k_round_data29, one launch per large folding round
     rd = phases["round_data29"]
-    launches = rd["records"] / args.steps
+    launches = rd["records"] / psteps
     avg_launch_s = rd["ms_per_step"] * 1e-3 / max(launches, 1)
     pairs29 = round29_pairs(D, N)
     mads_per_launch = pairs29 * (ROUND_DATA_FR_MUL_PER_PAIR_EVAL + ROUND_DATA_FR_MUL_PER_PAIR_FOLD) * MADS_PER_FR_MUL / max(launches, 1)
     bytes_per_launch = pairs29 * 12 * 32 / max(launches, 1)  # per pair: four entries of A and of S read, two of each written
-    achieved = mads_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
+    alu = mads_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
+    hbm = bytes_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
+    traffic = measured_traffic()
+    # the whole prove against both roofs, by the fixed models: 112 multiply-adds per model multiplication, and the
+    # bytes that must move even with perfect fusion (292 per element of S: hints, the inversion's three passes, every
+    # round's arrays read once and written at half size)
+    whole_mads = fr_mul_model(D, N) * MADS_PER_FR_MUL
+    whole_bytes = WHOLE_PROVE_BYTES_PER_ELEMENT * D
+    kernels_ms = sum(phases[k]["ms_per_step"] for k in names if k != "total")
+    total_ms = phases["total"]["ms_per_step"]
+    whole = {
+        "alu_frac": whole_mads / (ms * 1e-3) / PEAK_MAD_PER_S,
+        "hbm_frac": whole_bytes / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S,
+        "fr_mul_per_s": fr_mul_model(D, N) / (ms * 1e-3),
+        "hbm_GBps_algorithmic": whole_bytes / (ms * 1e-3) / 1e9,
+        "hbm_bytes_measured": measured_whole_prove_traffic(),
+        # the share of a prove in which neither roof is touched: the device idle between dependent launches (waiting
+        # for the transcript on the host) plus the kernels of the rounds that are bound by latency
+        "latency_share": (max(total_ms - kernels_ms, 0.0) + phases["round_small"]["ms_per_step"]) / total_ms if total_ms else None,
+    }
+    if whole["hbm_bytes_measured"]:
+        whole["hbm_frac_measured"] = whole["hbm_bytes_measured"] / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S
     out = {
         "metric": "tlookup_prove Fr-mul/s at D=2^%d, N=2^%d (wall ms in ms_per_step)" % (args.logD, args.logN),
         "value": fr_mul_model(D, N) / (ms * 1e-3),
@@ -409,18 +485,24 @@ def main():
         "dtype": "u32x8 (255-bit Montgomery integers)", "data": "synthetic",
         "config": {"workload": "config 3: tlookup SwiGLU/activation pair table at 7B-FFN shape, "
                                "%d x %d activations padded to D=2^%d, N=2^%d" % (rows, cols, args.logD, args.logN),
+                   "path": "tlookup_prove with row hints (idx given: counts from the hints, S checked against them through "
+                           "sum A = sum m B after the first round); the variants beside it prove the same bytes",
                    "D": D, "N": N, "proof_bytes": len(proof), "fr_mul_model": fr_mul_model(D, N)},
         "phases_ms": {k: round(v["ms_per_step"], 4) for k, v in phases.items()},
-        "by_rows_ms_per_step": ms_rows,
-        "roofline": {"bound": "alu", "kernel": "k_round_data29 (the large folding rounds, %d launches per prove)" % len(rounds_on_29_bits(D, N)),
-                     "achieved": achieved / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
-                     "frac": achieved / PEAK_MAD_PER_S, "traffic": measured_traffic(),
+        "commitment_standin_ms": round(phases["digest"]["ms_per_step"], 4),
+        "roofline": {"bound": "hbm" if hbm / PEAK_HBM_BYTES_PER_S >= alu / PEAK_MAD_PER_S else "alu",
+                     "kernel": "k_round_data29 (the large folding rounds, %d launches per prove)" % len(rounds_on_29_bits(D, N)),
+                     "achieved": hbm / 1e9, "peak": PEAK_HBM_BYTES_PER_S / 1e9, "unit": "GB/s",
+                     "frac": hbm / PEAK_HBM_BYTES_PER_S, "traffic": traffic,
                      "launches_per_step": launches, "avg_launch_ms": avg_launch_s * 1e3,
                      "algorithmic_bytes_per_launch": bytes_per_launch,
-                     "hbm_GBps_algorithmic": bytes_per_launch / avg_launch_s / 1e9 if avg_launch_s > 0 else 0.0},
+                     "alu": {"achieved": alu / 1e12, "peak": PEAK_MAD_PER_S / 1e12, "unit": "T int32-mad/s",
+                             "frac": alu / PEAK_MAD_PER_S, "fr_mul_per_pair_model": 9, "fr_mul_per_pair_executed": 8},
+                     "whole_prove": whole},
     }
+    out.update(beside)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.cpu_logD, min(args.logN, args.cpu_logD))
+        out["cpu_baseline"] = cpu_baseline(args.cpu_logD, min(args.logN, args.cpu_logD), D, N)
     print(json.dumps(out))
 
 

@@ -16,7 +16,15 @@
  *
  * Ownership.  The caller owns every buffer: inputs, outputs and workspace.  No
  * entry point allocates device memory; `*_workspace_bytes` says how much
- * workspace a call needs.  Inputs are not modified unless the comment says "in
+ * workspace a call needs.  The library does keep a little state of its own PER
+ * HOST THREAD, allocated by that thread's first call that needs it and kept until
+ * the process ends: 8 KiB of pinned host memory into which kernels write the
+ * handful of sums a step returns, 64 bytes of coherent pinned memory through
+ * which a kernel that stays resident over several sumcheck rounds receives each
+ * round's challenge, a pinned staging buffer for digest leaves that grows to the
+ * largest table seen, and the event pool of zkmi_profile_*.  Calls from
+ * different host threads share nothing; a thread's calls must not overlap.
+ * (fr_sum_noalloc touches none of this.)  Inputs are not modified unless the comment says "in
  * place".  `stream` is a hipStream_t passed as void* (NULL = the null stream);
  * all device work of a call is enqueued on it.  Calls that return host values
  * (proofs, sums, error codes that depend on data) synchronise that stream
@@ -215,6 +223,16 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
 size_t tlookup_proof_bytes(size_t D);
 int tlookup_prove(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                   size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
+
+/* tlookup_prove with every S_i compared with its hinted row T[idx_i] before
+ * anything else is done (while counting), as tlookup_multiplicities does, instead
+ * of through the identity after the first round: the same proof, byte for byte,
+ * for callers who want the membership check to be exact rather than sound up to
+ * (D+N)/|F|.  Costs one more pass over S (36 instead of 4 bytes per element while
+ * counting); timed beside the headline by the benchmark.  Without idx it is
+ * tlookup_prove. */
+int tlookup_prove_checked(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
+                          size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream);
 
 /* tlookup_prove from the tensor as the integers it is quantised from:
  * S_i = X_i + rho Y_i for signed 32-bit device arrays X and Y of D entries (the
@@ -454,11 +472,14 @@ int zkattn_link_verify(const uint8_t seed[32], const uint8_t* proof, size_t len,
  * on the caller's stream (so that kernels are timed where they are launched).
  * State is per host thread.  Phases: "total" (a whole tlookup_prove call),
  * "count" (multiplicities and digest leaves), "inverse" (both batch inversions),
- * "digest" (the hash trees over A and B),
+ * "digest" (the hash trees over A and B), "round_small" (the kernels of the rounds
+ * that are bound by latency: those that also bind a table variable and those of at
+ * most 256 pairs, the resident kernel included),
  * "round_data29" (the large folding rounds, which run on 29-bit limbs: one
- * record per launch of that kernel), "round_data" (every other round kernel
- * launch with a data side, one record each), "round_table" (the table-side
- * round kernel alone).
+ * record per launch of that kernel), "round_data" (the first round's kernel),
+ * "round_table" (the table-side round kernel alone, which only runs when D = N).
+ * A phase that waits for the host in its middle (count, inverse, digest) is
+ * timed from its first launch to its last, the wait included.
  * zkmi_profile_query returns the number of records and their summed duration in
  * milliseconds; call it after the stream has been synchronised.  Unknown phase:
  * ZK_E_BADARG. */

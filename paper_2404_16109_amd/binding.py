@@ -100,6 +100,7 @@ def _load():
         "tlookup_proof_bytes": (sz, [sz]),
         "tlookup_prove": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_prove_by_rows": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
+        "tlookup_prove_checked": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_small_workspace_bytes": (sz, [sz, sz]),
         "tlookup_prove_small": (i32, [vp, vp, vp, P(fr_t), sz, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_prove_with_beta": (i32, [vp, fr_vec, vp, fr_vec, P(fr_t), vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
@@ -143,7 +144,7 @@ EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_s
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_sum_noalloc", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
-           "tlookup_prove_by_rows", "tlookup_small_workspace_bytes", "tlookup_prove_small", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
+           "tlookup_prove_by_rows", "tlookup_prove_checked", "tlookup_small_workspace_bytes", "tlookup_prove_small", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
            "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
            "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove", "matmul_sumcheck_prove_i16",
@@ -366,6 +367,20 @@ def tlookup_prove_by_rows(seed, S, idx, T, ws=None, cap=None):
     ln = ctypes.c_size_t(0)
     aux = tlookup_aux()
     rc = _lib.tlookup_prove_by_rows(_seed(seed), S.c, _idx_ptr(idx), T.c, proof, cap, ctypes.byref(ln), ctypes.byref(aux),
+                                    ws.data_ptr(), ws.numel(), _stream())
+    info = _aux_dict(aux)
+    info["len"] = ln.value
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b"", info
+
+
+def tlookup_prove_checked(seed, S, idx, T, ws=None, cap=None):
+    """Returns (rc, proof bytes, aux dict with 'len')."""
+    ws = ws if ws is not None else _ws(tlookup_workspace_bytes(S.n, T.n))
+    cap = tlookup_proof_bytes(S.n) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    aux = tlookup_aux()
+    rc = _lib.tlookup_prove_checked(_seed(seed), S.c, _idx_ptr(idx), T.c, proof, cap, ctypes.byref(ln), ctypes.byref(aux),
                                     ws.data_ptr(), ws.numel(), _stream())
     info = _aux_dict(aux)
     info["len"] = ln.value

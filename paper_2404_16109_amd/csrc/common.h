@@ -147,7 +147,7 @@ inline hipStream_t as_stream(void* s) { return (hipStream_t)s; }
 
 // Optional timing of phases with HIP events on the caller's stream (see
 // zkmi_profile_* in the public header).  A scope records one start/stop pair.
-enum ProfilePhase { kProfTotal = 0, kProfCount, kProfInverse, kProfRoundData, kProfRoundTable, kProfRound29, kProfDigest, kProfPhases };
+enum ProfilePhase { kProfTotal = 0, kProfCount, kProfInverse, kProfRoundData, kProfRoundTable, kProfRound29, kProfDigest, kProfRoundSmall, kProfPhases };
 int profile_open(int phase, hipStream_t stream);   // returns a record handle or -1 when profiling is off
 void profile_close(int handle, hipStream_t stream);
 struct ProfileScope {

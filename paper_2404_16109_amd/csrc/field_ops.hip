@@ -5,6 +5,7 @@
 
 #include <atomic>
 #include <chrono>
+#include <thread>
 #include <vector>
 
 #include "common.h"
@@ -33,9 +34,14 @@ uint32_t device_spin_limit() { return g_spin_limit.load(); }
 
 int mailbox_wait(Mailbox* mb, uint32_t seq, hipStream_t stream) {
     volatile uint32_t* flag = mb->words + kMailboxFlag;
-    // about 20 ms of spinning covers every kernel of the library; beyond that
-    // (or if the flag never comes) the stream's own completion decides
+    // About 20 ms of pure spinning covers every kernel of the library at its usual
+    // sizes.  Beyond that the flag is still what is waited for, but the stream is
+    // asked now and then whether it has run dry or failed: a stream that has
+    // finished without the flag showing means the kernel that should have set it
+    // is gone.  The stream is never blocked on: a resident kernel may be waiting,
+    // inside that stream, for the very answer this wait stands before.
     const auto start = std::chrono::steady_clock::now();
+    bool patient = false;
     for (;;) {
         for (int spin = 0; spin < 2048; ++spin) {
             if (*flag == seq) {
@@ -44,11 +50,17 @@ int mailbox_wait(Mailbox* mb, uint32_t seq, hipStream_t stream) {
             }
             __builtin_ia32_pause();
         }
-        if (std::chrono::steady_clock::now() - start > std::chrono::milliseconds(20)) break;
+        if (!patient && std::chrono::steady_clock::now() - start > std::chrono::milliseconds(20)) patient = true;
+        if (patient) {
+            const hipError_t q = hipStreamQuery(stream);
+            if (q == hipSuccess) {
+                std::atomic_thread_fence(std::memory_order_acquire);
+                return *flag == seq ? ZK_OK : ZK_E_HIP;
+            }
+            if (q != hipErrorNotReady) return ZK_E_HIP;
+            std::this_thread::yield();
+        }
     }
-    ZK_HIP_TRY(hipStreamSynchronize(stream));
-    std::atomic_thread_fence(std::memory_order_acquire);
-    return *flag == seq ? ZK_OK : ZK_E_HIP;
 }
 
 int mailbox_bulk(Mailbox* mb, size_t bytes) {
@@ -239,7 +251,7 @@ int zkmi_profile_reset(void) {
 }
 
 int zkmi_profile_query(const char* phase, uint64_t* records, double* total_ms) {
-    static const char* names[kProfPhases] = {"total", "count", "inverse", "round_data", "round_table", "round_data29", "digest"};
+    static const char* names[kProfPhases] = {"total", "count", "inverse", "round_data", "round_table", "round_data29", "digest", "round_small"};
     if (!phase || !records || !total_ms) return ZK_E_BADARG;
     ProfileState& st = profile_state();
     profile_resolve(st);

@@ -325,13 +325,11 @@ static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
 static bool can_defer_check(const ProveWs& w, const uint32_t* idx, size_t D) { return w.hist && idx && D > (size_t)kBlock; }
 
 static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_t D, size_t N, uint64_t* bad_index,
-                      Mailbox* mb, hipStream_t stream, bool defer_check = false) {
+                      Mailbox* mb, hipStream_t stream, bool defer_check = false, bool counts_as_fr = false) {
     if (defer_check && !can_defer_check(w, idx, D)) return ZK_E_BADARG;
     uint32_t cap = w.cap_mask + 1;
-    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(cap)), dim3(kBlock), 0, stream, w.slots, (size_t)cap, kEmptySlot);
-    hipLaunchKernelGGL(k_fill_u32, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.m, N, 0u);
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags, (size_t)2, 0u);
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(kBlock), 0, stream, w.flags + 2, (size_t)2, 0xffffffffu);
+    hipLaunchKernelGGL(k_count_init, dim3(grid_for((size_t)cap + N + 4)), dim3(kBlock), 0, stream, w.slots, (size_t)cap, w.m,
+                       N, w.flags);
     hipLaunchKernelGGL(k_hash_build, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.slots, w.cap_mask, T.limbs, T.stride,
                        (uint32_t)N, w.flags);
     hipLaunchKernelGGL(k_canon_rows, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.canon, w.rows, w.slots, w.cap_mask,
@@ -368,6 +366,8 @@ static int count_rows(ProveWs& w, fr_vec S, const uint32_t* idx, fr_vec T, size_
     }
     hipLaunchKernelGGL(k_leaf_digests, dim3((unsigned)div_up(w.nleaves, 64)), dim3(64), 0, stream, w.leaves, w.m,
                        (uint32_t)N, w.nleaves);
+    // the counts as field elements (w.M), while the host is busy with the digest
+    if (counts_as_fr) hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, w.M, N, w.m, N);
     ZK_HIP_TRY(hipGetLastError());
     ZK_TRY(mailbox_bulk(mb, (size_t)w.nleaves * 32 + 16));
     ZK_HIP_TRY(hipMemcpyAsync(mb->bulk, w.flags, 16, hipMemcpyDeviceToHost, stream));
@@ -441,6 +441,7 @@ struct ProveCall {
     bool batch = false;                    // batched transcript and proof layout
     const fr_t* forced_beta = nullptr;
     bool by_rows = false;                  // A as B[idx_i] instead of inverting beta + S_i
+    bool check_upfront = false;            // compare every S_i with its hinted row while counting (no deferred check)
     // S_0 given as small integers x + rho y (K = 1, hints required, S ignored): see tlookup_prove_small
     const int32_t* ints_x = nullptr;
     const int32_t* ints_y = nullptr;
@@ -598,7 +599,7 @@ static int prove_core(const ProveCall& c) {
     ProfileScope prof_total(kProfTotal, stream);
 
     // -- Prep: multiplicities and their digests -------------------------------------------------
-    bool defer_all = !c.by_rows;
+    bool defer_all = !c.by_rows && !c.check_upfront;
     for (size_t i = 0; i < K; ++i) defer_all = defer_all && can_defer_check(inst[i].w, inst[i].idx, D);
     if (from_ints && !defer_all) return ZK_E_BADARG;  // counting would read S as a vector
     for (size_t i = 0; i < K; ++i) {
@@ -609,7 +610,7 @@ static int prove_core(const ProveCall& c) {
             // with hints, the inverse vectors themselves tell whether S_i = T[idx_i] everywhere (see the first round);
             // all instances or none, so that the first instance at fault is the one reported
             inst[i].deferred = defer_all;
-            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, D, N, &bad, mb, stream, inst[i].deferred);
+            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, D, N, &bad, mb, stream, inst[i].deferred, true);
         }
         if (rc == ZK_E_NOT_IN_TABLE) {
             if (c.aux) c.aux->bad_index = bad;
@@ -629,8 +630,6 @@ static int prove_core(const ProveCall& c) {
     // -- Prove: beta, inverse vectors ---------------------------------------------------------------
     F beta = tr.challenge("beta");
     if (c.forced_beta) beta = from_canonical(*c.forced_beta);
-    for (size_t i = 0; i < K; ++i)
-        hipLaunchKernelGGL(k_counts_to_fr, dim3(grid_for(N)), dim3(kBlock), 0, stream, inst[i].w.M, N, inst[i].w.m, N);
     if (!c.by_rows) {
         // all inversions share one wait: the down passes, one round trip, one host
         // inversion (of the product of all grand totals), the up passes.  The table
@@ -905,7 +904,7 @@ static int prove_core(const ProveCall& c) {
             tail.spin_limit = device_spin_limit();
             mailbox_channel_reset(mb);
             {
-                ProfileScope prof(kProfRoundData, stream);
+                ProfileScope prof(kProfRoundSmall, stream);
                 hipLaunchKernelGGL(k_tlookup_tail, dim3(1), dim3(kSmallThreads), 0, stream, tail);
             }
             ZK_HIP_TRY(hipGetLastError());
@@ -948,7 +947,7 @@ static int prove_core(const ProveCall& c) {
 
             if (plan.kernel == kRoundOneGroup) {
                 // one workgroup, one launch, sums straight to the host
-                ProfileScope prof(kProfRoundData, stream);
+                ProfileScope prof(kProfRoundSmall, stream);
                 if (!table_round)
                     hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
                                        my_seq);
@@ -960,7 +959,7 @@ static int prove_core(const ProveCall& c) {
                                        my_seq);
             } else if (plan.kernel == kRoundBoth) {
                 {
-                    ProfileScope prof(kProfRoundData, stream);
+                    ProfileScope prof(kProfRoundSmall, stream);
                     if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
                     else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
                 }
@@ -1388,8 +1387,9 @@ int tlookup_multiplicities(uint32_t* m, fr_vec S, const uint32_t* idx, fr_vec T,
 
 static int prove_single(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, const fr_t* forced_beta,
                         bool by_rows, uint8_t* proof, size_t cap, size_t* len, tlookup_aux* aux, void* ws,
-                        size_t ws_bytes, void* stream) {
+                        size_t ws_bytes, void* stream, bool check_upfront = false) {
     ProveCall c;
+    c.check_upfront = check_upfront;
     c.seed = seed;
     c.K = 1;
     c.S = &S;
@@ -1495,6 +1495,11 @@ int zkmi_selftest_tlookup_plan(size_t D, size_t N, size_t K, int from_ints, int3
         resident = resident || pl.kernel == kRoundResident;
     }
     return n;
+}
+
+int tlookup_prove_checked(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
+                          size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
+    return prove_single(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, ws_bytes, stream, true);
 }
 
 int tlookup_prove_by_rows(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,

@@ -369,6 +369,18 @@ static __global__ void __launch_bounds__(kBlock) k_fill_u32(uint32_t* p, size_t 
     for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < n; i += (size_t)gridDim.x * kBlock) p[i] = v;
 }
 
+// What counting starts from, in one launch: empty hash slots, zero counts, and the
+// four flag words (duplicate flag and ticket zero, smallest bad index all ones).
+static __global__ void __launch_bounds__(kBlock) k_count_init(uint32_t* __restrict__ slots, size_t cap,
+                                                       uint32_t* __restrict__ m, size_t N, uint32_t* __restrict__ flags) {
+    const size_t total = cap + N + 4;
+    for (size_t i = blockIdx.x * (size_t)kBlock + threadIdx.x; i < total; i += (size_t)gridDim.x * kBlock) {
+        if (i < cap) slots[i] = kEmptySlot;
+        else if (i < cap + N) m[i - cap] = 0;
+        else flags[i - cap - N] = i - cap - N < 2 ? 0u : 0xffffffffu;
+    }
+}
+
 static __global__ void __launch_bounds__(kBlock) k_counts_to_fr(uint32_t* __restrict__ dst, size_t ds,
                                                          const uint32_t* __restrict__ m, size_t N) {
     for (size_t j = blockIdx.x * (size_t)kBlock + threadIdx.x; j < N; j += (size_t)gridDim.x * kBlock)

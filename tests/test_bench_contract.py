@@ -24,6 +24,12 @@ def test_more_than_one_gpu_is_refused():
     assert not any(line.startswith("{") for line in res.stdout.splitlines())      # no result line
 
 
+def test_recorded_fullsize_oracle_time_is_read():
+    b = load_bench()
+    rec = b.recorded_fullsize_oracle()
+    assert rec and rec["SECONDS"] > 60 and rec["CORES"] >= 1
+
+
 def test_work_models():
     b = load_bench()
     D, N = 1 << 25, 1 << 16
@@ -37,6 +43,8 @@ def test_work_models():
     # nine multiplications of 112 multiply-adds per pair against 256 CUs x 64 lanes x 2.4 GHz
     assert (b.ROUND_DATA_FR_MUL_PER_PAIR_EVAL + b.ROUND_DATA_FR_MUL_PER_PAIR_FOLD, b.MADS_PER_FR_MUL) == (9, 112)
     assert b.PEAK_MAD_PER_S == 256 * 64 * 2.4e9
+    # the whole prove against the HBM roof: 292 bytes per element that must move even with perfect fusion, 8 TB/s
+    assert (b.WHOLE_PROVE_BYTES_PER_ELEMENT, b.PEAK_HBM_BYTES_PER_S) == (4 + 96 + 192, 8e12)
     # the linking sumcheck: 11, 15, then 13 multiplications per pair, and one per entry for each digit tensor's value
     Dl = 1 << 10
     assert b.link_fr_mul_model(Dl) == 11 * (Dl // 2) + 15 * (Dl // 4) + 13 * (Dl // 4 - 1) + 2 * Dl

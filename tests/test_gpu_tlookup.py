@@ -61,6 +61,8 @@ def test_proof_bytes_equal_oracle(zk, orc, D, N, dup):
     assert rc == 0 and proof3 == orc.tlookup_prove(seed, Sb, Tb)[1] and info3["sum_A"] == info3["sum_mB"]
     rc, proof2, _ = zk.tlookup_prove(seed, Sv, None, Tv)  # rows found by the library
     assert rc == 0 and proof2 == orc.tlookup_prove(seed, Sb, Tb)[1]
+    rc, proof4, info4 = zk.tlookup_prove_checked(seed, Sv, idx, Tv)   # rows given, every S_i compared with its row up front
+    assert rc == 0 and proof4 == proof2 and info4["sum_A"] == info4["sum_mB"]
     # inputs are not modified
     assert np.array_equal(zk.vec_to_bytes(Sv), Sb) and np.array_equal(zk.vec_to_bytes(Tv), Tb)
 
@@ -141,6 +143,8 @@ def test_not_in_table_reports_smallest_index(zk, orc):
         assert rc == zk.ZK_E_NOT_IN_TABLE == rc_o and bad == bad_o == 777
         rc, _, info = zk.tlookup_prove(b"\x01" * 32, Sv, given, Tv)
         assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 777
+        rc, _, info = zk.tlookup_prove_checked(b"\x01" * 32, Sv, given, Tv)
+        assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 777
     assert zk.tlookup_prove_by_rows(b"\x01" * 32, Sv, idx, Tv)[0] == zk.ZK_E_NOT_IN_TABLE
     assert zk.tlookup_prove_by_rows(b"\x01" * 32, Sv, None, Tv)[0] == zk.ZK_E_BADARG
     # a wrong row hint is an error even if the value is in the table
@@ -150,6 +154,8 @@ def test_not_in_table_reports_smallest_index(zk, orc):
     assert zk.tlookup_multiplicities(good, wrong, Tv)[0] == zk.ZK_E_NOT_IN_TABLE
     # the prover compares S with the hinted rows while it inverts; hints out of range fail the same way
     rc, _, info = zk.tlookup_prove(b"\x01" * 32, good, wrong, Tv)
+    assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 5
+    rc, _, info = zk.tlookup_prove_checked(b"\x01" * 32, good, wrong, Tv)
     assert rc == zk.ZK_E_NOT_IN_TABLE and info["bad_index"] == 5
     wrong[3] = 64
     wrong[2000] = 0xFFFFFFF
