@@ -436,3 +436,18 @@ def zkattn_link_verify(seed, proof, rows, cols, bases, Zp=None, X_list=None, Y=N
         _p(None if Zp is None else _c(Zp).reshape(-1, 32)), _ptr_array(keep_x),
         _p(None if Y is None else _c(Y).reshape(-1, 32)), _ptr_array(keep_y),
         _p(None if yhat is None else _c(yhat).reshape(-1, 32)), None, threads or default_threads())
+
+
+def zkattn_link_verify_point(seed, proof, rows, cols, bases, threads=None):
+    """The oracle's verifier without tensors; returns (rc, the sumcheck point v as canonical bytes)."""
+    bases = _c(bases).reshape(-1, 32)
+    K = bases.shape[0]
+    n = max((rows * cols).bit_length() - 1, 0)
+    pb = np.frombuffer(bytes(proof), dtype=np.uint8).copy() if len(proof) else np.zeros(1, dtype=np.uint8)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    point = np.zeros((max(n, 1), 32), dtype=np.uint8)
+    none = [None] * K
+    rc = lib().oracle_zkattn_link_verify(
+        _p(seedb), _p(pb), _u64(len(proof)), _u64(rows), _u64(cols), _u64(K), _p(bases), None, _ptr_array(none), None,
+        _ptr_array(none), None, _p(point), threads or default_threads())
+    return rc, point[:n]

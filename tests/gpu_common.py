@@ -45,3 +45,41 @@ def first_difference(a, b):
         if a[i] != b[i]:
             return i
     return n
+
+
+def link_tensors(cfg):
+    """The tensors of zkAttn's closing sumcheck for a synth.attention_link config, on
+    the GPU: digits X^(k), segment outputs Y^(k) = table_k[X^(k)], Y = Y^(0) Y^(1),
+    Z' = -(X^(0) + 2^16 X^(1)) and the row sums yhat, as field vectors (built with
+    the library's elementwise calls) and as the integers they are (for the integer
+    entry point).  Returns (Zp, X, Y, Yk, yhat, ints)."""
+    rows, cols = cfg["rows"], cfg["cols"]
+    D = rows * cols
+    X, Yk = [], []
+    ints = {"X": [], "Yk": []}
+    yprod = None
+    for k in range(2):
+        xi = torch.from_numpy(cfg["x"][k].astype(np.int32)).cuda()
+        xv = zk.Vec(D)
+        assert zk.fr_from_i32(xv, xi) == 0
+        X.append(xv)
+        yi = torch.from_numpy(cfg["ty"][k].astype(np.int32)).cuda()[xi.long()]
+        yv = zk.Vec(D)
+        assert zk.fr_from_i32(yv, yi) == 0
+        Yk.append(yv)
+        yprod = yi.long() if yprod is None else yprod * yi.long()
+        ints["X"].append(xi)
+        ints["Yk"].append(yi)
+    yhat_int = yprod.reshape(rows, cols).sum(dim=1).cpu().numpy().astype(np.uint64)
+    ints["Y"] = yprod
+    Y = zk.Vec(D)
+    assert zk.fr_mul(Y, Yk[0], Yk[1]) == 0
+    Zp = zk.Vec(D)
+    assert zk.fr_axpy(Zp, X[0], cfg["bases"][1], X[1]) == 0
+    assert zk.fr_mul_scalar(Zp, Zp, synth.BLS12_381_R - 1) == 0
+    canon = np.zeros((rows, 32), dtype=np.uint8)
+    canon[:, :8] = yhat_int.astype("<u8").view(np.uint8).reshape(rows, 8)
+    yhat = zk.vec_from_bytes(canon)
+    ints["Zp"] = -(ints["X"][0].long() + cfg["bases"][1] * ints["X"][1].long())
+    ints["yhat"] = yhat_int
+    return Zp, X, Y, Yk, yhat, ints
