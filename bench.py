@@ -27,7 +27,7 @@ MADS_PER_FR_MUL = 112                   # 64 for the 8x8-limb product + 48 for t
 ROUND_DATA_FR_MUL_PER_PAIR_EVAL = 5     # two to weight A0, A1, three products
 ROUND_DATA_FR_MUL_PER_PAIR_FOLD = 4     # two arrays, two folded entries per pair
 PEAK_HBM_BYTES_PER_S = 8e12             # MI355X HBM3E, published
-WHOLE_PROVE_BYTES_PER_ELEMENT = 292     # hints 4 + inversion 96 + rounds 192 (every array read once, written at half size)
+WHOLE_PROVE_BYTES_PER_ELEMENT = 292     # hints 4 + inversion 96 + 192 (every version of A and S counted once, when a round reads it)
 
 
 def fr_mul_model(D, N):

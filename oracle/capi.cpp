@@ -8,6 +8,7 @@
 
 #include "product.hpp"
 #include "tlookup_batch.hpp"
+#include "tlookup_multi.hpp"
 #include "zkattn_link.hpp"
 
 #if !defined(__BYTE_ORDER__) || __BYTE_ORDER__ != __ORDER_LITTLE_ENDIAN__
@@ -187,6 +188,25 @@ int oracle_tlookup_batch_verify(const uint8_t seed[32], const uint8_t* proof, ui
                                 uint64_t K, uint64_t D, uint64_t N, const uint8_t* const* S,
                                 const uint64_t* const* m_counts, uint8_t* v_out, int threads) {
     return tlookup_batch_verify(seed, proof, len, reinterpret_cast<const Fr* const*>(T), K, D, N,
+                                reinterpret_cast<const Fr* const*>(S), m_counts, v_out ? as_fr(v_out) : nullptr,
+                                threads);
+}
+
+uint64_t oracle_tlookup_multi_proof_bytes(uint64_t n_max, uint64_t K) { return tlookup_multi_proof_bytes((int)n_max, K); }
+
+// S, T: arrays of K pointers; D, N: K lengths.  aux: beta | alpha | lambda | K x (sum_A, sum_mB).
+int oracle_tlookup_multi_prove(const uint8_t seed[32], const uint8_t* const* S, const uint8_t* const* T, uint64_t K,
+                               const uint64_t* D, const uint64_t* N, uint8_t* proof, uint64_t cap, uint64_t* len,
+                               uint8_t* aux, uint8_t* v_out, uint64_t* bad_instance, uint64_t* bad_index, int threads) {
+    return tlookup_multi_prove(seed, reinterpret_cast<const Fr* const*>(S), reinterpret_cast<const Fr* const*>(T), K, D,
+                               N, proof, cap, len, aux ? as_fr(aux) : nullptr, v_out ? as_fr(v_out) : nullptr,
+                               bad_instance, bad_index, threads);
+}
+
+int oracle_tlookup_multi_verify(const uint8_t seed[32], const uint8_t* proof, uint64_t len, const uint8_t* const* T,
+                                uint64_t K, const uint64_t* D, const uint64_t* N, const uint8_t* const* S,
+                                const uint64_t* const* m_counts, uint8_t* v_out, int threads) {
+    return tlookup_multi_verify(seed, proof, len, reinterpret_cast<const Fr* const*>(T), K, D, N,
                                 reinterpret_cast<const Fr* const*>(S), m_counts, v_out ? as_fr(v_out) : nullptr,
                                 threads);
 }

@@ -39,6 +39,7 @@ def lib():
         _lib.oracle_tlookup_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_product_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_tlookup_batch_proof_bytes.restype = ctypes.c_uint64
+        _lib.oracle_tlookup_multi_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_matmul_proof_bytes.restype = ctypes.c_uint64
         _lib.oracle_link_proof_bytes.restype = ctypes.c_uint64
     return _lib
@@ -342,6 +343,44 @@ def tlookup_batch_verify(seed, proof, T_list, D, S_list=None, m_list=None, threa
     S_arr = None if keep_s is None else _ptr_array(keep_s)
     return lib().oracle_tlookup_batch_verify(_p(seedb), _p(pb), _u64(len(proof)), _ptr_array(T_list), _u64(K), _u64(D),
                                              _u64(N), S_arr, m_arr, None, threads or default_threads())
+
+
+def tlookup_multi_prove(seed, S_list, T_list, threads=None):
+    """Several instances of any shapes, one sumcheck.  Returns (rc, proof, info)."""
+    S_list = [_c(s).reshape(-1, 32) for s in S_list]
+    T_list = [_c(t).reshape(-1, 32) for t in T_list]
+    K = len(S_list)
+    Ds = np.array([s.shape[0] for s in S_list], dtype=np.uint64)
+    Ns = np.array([t.shape[0] for t in T_list], dtype=np.uint64)
+    n = max(max(int(d).bit_length() - 1, 0) for d in Ds)
+    cap = int(lib().oracle_tlookup_multi_proof_bytes(_u64(n), _u64(K)))
+    proof = np.zeros(cap, dtype=np.uint8)
+    ln = ctypes.c_uint64(0)
+    aux = np.zeros((3 + 2 * K, 32), dtype=np.uint8)
+    v = np.zeros((max(n, 1), 32), dtype=np.uint8)
+    bad_i, bad_x = ctypes.c_uint64(0), ctypes.c_uint64(0)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    rc = lib().oracle_tlookup_multi_prove(_p(seedb), _ptr_array(S_list), _ptr_array(T_list), _u64(K), _p(Ds), _p(Ns),
+                                          _p(proof), _u64(cap), ctypes.byref(ln), _p(aux), _p(v), ctypes.byref(bad_i),
+                                          ctypes.byref(bad_x), threads or default_threads())
+    info = {"beta": aux[0], "alpha": aux[1], "lambda": aux[2], "sum_A": aux[3::2], "sum_mB": aux[4::2], "v": v[:n],
+            "bad_instance": bad_i.value, "bad_index": bad_x.value}
+    return rc, proof[:ln.value].tobytes() if rc == OK else b"", info
+
+
+def tlookup_multi_verify(seed, proof, T_list, D_list, S_list=None, m_list=None, threads=None):
+    T_list = [_c(t).reshape(-1, 32) for t in T_list]
+    K = len(T_list)
+    Ds = np.array([int(d) for d in D_list], dtype=np.uint64)
+    Ns = np.array([t.shape[0] for t in T_list], dtype=np.uint64)
+    pb = np.frombuffer(bytes(proof), dtype=np.uint8).copy() if len(proof) else np.zeros(1, dtype=np.uint8)
+    seedb = _c(np.frombuffer(bytes(seed), dtype=np.uint8))
+    keep_m = None if m_list is None else [None if m is None else np.ascontiguousarray(m, dtype=np.uint64) for m in m_list]
+    m_arr = None if keep_m is None else _ptr_array(keep_m)
+    keep_s = None if S_list is None else [None if s is None else _c(s).reshape(-1, 32) for s in S_list]
+    S_arr = None if keep_s is None else _ptr_array(keep_s)
+    return lib().oracle_tlookup_multi_verify(_p(seedb), _p(pb), _u64(len(proof)), _ptr_array(T_list), _u64(K), _p(Ds),
+                                             _p(Ns), S_arr, m_arr, None, threads or default_threads())
 
 
 # ---- product sumcheck / matmul ----------------------------------------------

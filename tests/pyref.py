@@ -242,6 +242,75 @@ def tlookup_batch_proof(seed, S_list, T_list):
     return out, {"beta": beta, "alpha": alpha, "lambda": lam, "v": v, "first_claim": first_claim, "m": ms}
 
 
+def tlookup_multi_proof(seed, S_list, T_list):
+    """K tlookup instances of any shapes (D_k, N_k) under one sumcheck over n = max_k log2 D_k
+    variables.  Instance k lives on the last n_k = log2 D_k of them and its summand does not
+    depend on the first n - n_k: f = sum_k lambda^k 2^-(n - n_k) f_k(w[n - n_k:]), f_k built on
+    u[n - n_k:].  Everything from the definitions."""
+    K = len(S_list)
+    Ds, Ns = [len(S) for S in S_list], [len(T) for T in T_list]
+    ns = [D.bit_length() - 1 for D in Ds]
+    hs = [ns[k] - (Ns[k].bit_length() - 1) for k in range(K)]
+    n = max(ns)
+    init = b"zkmi/tlookup-multi/v1" + seed + K.to_bytes(8, "little")
+    out = b"ZKTM" + (1).to_bytes(4, "little") + K.to_bytes(8, "little")
+    for D, N in zip(Ds, Ns):
+        init += D.to_bytes(8, "little") + N.to_bytes(8, "little")
+        out += D.to_bytes(8, "little") + N.to_bytes(8, "little")
+    tr = Transcript(init)
+    ms = []
+    for S, T in zip(S_list, T_list):
+        first = {}
+        for j, t in enumerate(T):
+            first.setdefault(t, j)
+        m = [0] * len(T)
+        for s in S:
+            m[first[s]] += 1
+        ms.append(m)
+        md = m_digest(m)
+        tr.absorb("m", md)
+        out += md
+    beta = tr.challenge("beta")
+    As = [[pow(beta + s, -1, R) for s in S] for S in S_list]
+    Bs = [[pow(beta + t, -1, R) for t in T] for T in T_list]
+    for A, B in zip(As, Bs):
+        dA, dB = vec_digest(A), vec_digest(B)
+        tr.absorb("A", dA)
+        tr.absorb("B", dB)
+        out += dA + dB
+    alpha = tr.challenge("alpha")
+    u = [tr.challenge("u") for _ in range(n)]
+    lam = tr.challenge("lambda")
+
+    def f(w):
+        total = 0
+        for k in range(K):
+            skip = n - ns[k]
+            wk, uk = w[skip:], u[skip:]
+            wt, ut = wk[hs[k]:], uk[hs[k]:]
+            A, S, B, T, m = As[k], S_list[k], Bs[k], T_list[k], ms[k]
+            left = mle(A, wk) * ((alpha * eq(uk, wk) % R) * ((mle(S, wk) + beta) % R) + 1) % R
+            right = pow(pow(2, hs[k], R), -1, R) * mle(B, wt) % R * ((alpha * alpha % R) * eq(ut, wt) % R * ((mle(T, wt) + beta) % R) - mle(m, wt)) % R
+            total += pow(lam, k, R) * pow(pow(2, skip, R), -1, R) % R * (left + right)
+        return total % R
+
+    v, polys = [], []
+    for k in range(n):
+        g = [round_poly(f, v, n, X) for X in range(4)]
+        polys.append(g)
+        msg = b"".join(fr_bytes(y) for y in g)
+        out += msg
+        tr.absorb("g", msg)
+        v.append(tr.challenge("r"))
+    fin = b""
+    for k in range(K):
+        vk = v[n - ns[k]:]
+        vt = vk[hs[k]:]
+        fin += b"".join(fr_bytes(y) for y in [mle(As[k], vk), mle(S_list[k], vk), mle(Bs[k], vt), mle(ms[k], vt), mle(T_list[k], vt)])
+    out += fin
+    return out, {"beta": beta, "alpha": alpha, "lambda": lam, "v": v, "polys": polys, "m": ms}
+
+
 def zkattn_link_proof(seed, Zp, X, Y, Yk, yhat, bases, rows, cols):
     """The sumcheck linking zkAttn's tensors (Protocol 2, last step) from the
     definitions: every round polynomial is the sum of the summand, built from
