@@ -333,6 +333,48 @@ int tlookup_verify_batch(const uint8_t seed[32], const uint8_t* proof, size_t le
                          const tlookup_witness* witness, tlookup_batch_claims* claims, void* ws, size_t ws_bytes,
                          void* stream);
 
+/* ---- lookups of different shapes under one sumcheck ---------------------------- */
+
+/* Some layers look one tensor up in two tables in a row whose lengths differ, and
+ * the tensors' lengths with them (LayerNorm, Section 6.1.3: first the scaling
+ * down of the per-row statistic, then the table of 1/sqrt).  The paper proves
+ * such lookups one by one, which ends them at unrelated points; here K instances
+ * (S_i, T_i) of ANY shapes (D_i, N_i) run under ONE sumcheck, so that all 5 K
+ * claims are at (suffixes of) one point.  With n_i = log2 D_i, n = max_i n_i and
+ * skip_i = n - n_i, instance i lives on the LAST n_i of the n variables and its
+ * summand does not depend on the first skip_i:
+ *   f(x) = sum_i lambda^i 2^-skip_i f_i(x_[skip_i:]),   claim = (sum_i lambda^i)(alpha + alpha^2),
+ * f_i the summand of tlookup_prove built with u_[skip_i:].  The claims of
+ * instance i are A_i~, S_i~ at v_[skip_i:] and B_i~, m_i~, T_i~ at
+ * v_[skip_i + log2(D_i/N_i):].
+ *
+ * Transcript: SHA256("zkmi/tlookup-multi/v1" || seed || LE64 K || K x (LE64 D_i, LE64 N_i)),
+ * then exactly as tlookup_prove_batch (digests of all m_i; beta; digests of all
+ * A_i, B_i; alpha; u_0..u_{n-1}; lambda; rounds; final).
+ *
+ * Proof (host, tlookup_multi_proof_bytes(D, K) bytes):
+ *   "ZKTM" | u32 1 | LE64 K | K x (LE64 D_i, LE64 N_i) | K x digest(m_i)
+ *   | K x [digest(A_i) digest(B_i)] | n x 4 elements | K x 5 elements.
+ *
+ * S, T: host arrays of K descriptors of device vectors; S[i].n = D_i and
+ * T[i].n = N_i give the shapes (powers of two, N_i <= D_i <= 2^31).  idx, aux,
+ * errors, stream: as tlookup_prove_batch.  ws: device,
+ * tlookup_multi_workspace_bytes(D, N, K) with D, N host arrays of the K lengths.
+ * In claims (tlookup_verify_multi) nvars = n and v holds the n challenges. */
+size_t tlookup_multi_proof_bytes(const size_t* D, size_t K);
+size_t tlookup_multi_workspace_bytes(const size_t* D, const size_t* N, size_t K);
+int tlookup_prove_multi(const uint8_t seed[32], const fr_vec* S, const uint32_t* const* idx, const fr_vec* T, size_t K,
+                        uint8_t* proof, size_t cap, size_t* len, tlookup_batch_aux* aux, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/* Its verifier.  D: host array of the K tensor lengths (the tables' lengths are
+ * T[i].n).  witness as in tlookup_verify_batch.  ws: device,
+ * tlookup_multi_verify_workspace_bytes(D, N, K). */
+size_t tlookup_multi_verify_workspace_bytes(const size_t* D, const size_t* N, size_t K);
+int tlookup_verify_multi(const uint8_t seed[32], const uint8_t* proof, size_t len, const fr_vec* T, const size_t* D,
+                         size_t K, const tlookup_witness* witness, tlookup_batch_claims* claims, void* ws,
+                         size_t ws_bytes, void* stream);
+
 /* ---- product sumcheck and matrix multiplication (Sections 3.3, 6.1.1) -------- */
 
 /* Sumcheck of sum_{x in {0,1}^d} a(x) b(x) = claim over vectors of 2^d elements

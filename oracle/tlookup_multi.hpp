@@ -111,11 +111,15 @@ inline int tlookup_multi_prove(const uint8_t seed[32], const Fr* const* S_in, co
             I.B[j] = fr_inv(den);
             I.M[j] = fr_from_u64(I.counts[j]);
         }
-        for (uint64_t i = 0; i < D[k]; ++i) {
-            Fr den = fr_add(beta, I.S[i]);
-            if (fr_is_zero(den)) return E_ZERO_DENOM;
-            I.A[i] = fr_inv(den);
-        }
+        std::vector<int> zero_seen(std::max(1, threads), 0);
+        parallel_ranges(D[k], threads, [&](size_t lo, size_t hi, int w) {
+            for (size_t i = lo; i < hi; ++i) {
+                Fr den = fr_add(beta, I.S[i]);
+                if (fr_is_zero(den)) { zero_seen[w] = 1; return; }
+                I.A[i] = fr_inv(den);
+            }
+        });
+        for (int z : zero_seen) if (z) return E_ZERO_DENOM;
     }
     for (uint64_t k = 0; k < K; ++k) {
         uint8_t dA[32], dB[32];

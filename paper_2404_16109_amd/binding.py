@@ -112,6 +112,13 @@ def _load():
                                       vp]),
         "tlookup_verify_batch": (i32, [vp, vp, sz, P(fr_vec), sz, sz, P(tlookup_witness), P(tlookup_batch_claims), vp,
                                        sz, vp]),
+        "tlookup_multi_proof_bytes": (sz, [P(sz), sz]),
+        "tlookup_multi_workspace_bytes": (sz, [P(sz), P(sz), sz]),
+        "tlookup_prove_multi": (i32, [vp, P(fr_vec), P(vp), P(fr_vec), sz, vp, sz, P(sz), P(tlookup_batch_aux), vp, sz,
+                                      vp]),
+        "tlookup_multi_verify_workspace_bytes": (sz, [P(sz), P(sz), sz]),
+        "tlookup_verify_multi": (i32, [vp, vp, sz, P(fr_vec), P(sz), sz, P(tlookup_witness), P(tlookup_batch_claims), vp,
+                                       sz, vp]),
         "sumcheck_product_proof_bytes": (sz, [sz]),
         "sumcheck_product_workspace_bytes": (sz, [sz]),
         "sumcheck_prove_product": (i32, [vp, fr_vec, fr_vec, P(fr_t), vp, sz, P(sz), vp, sz, vp]),
@@ -146,6 +153,8 @@ EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_s
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
            "tlookup_prove_by_rows", "tlookup_prove_checked", "tlookup_small_workspace_bytes", "tlookup_prove_small", "tlookup_prove_with_beta", "tlookup_verify_workspace_bytes", "tlookup_verify",
            "tlookup_batch_proof_bytes", "tlookup_batch_workspace_bytes", "tlookup_prove_batch", "tlookup_verify_batch",
+           "tlookup_multi_proof_bytes", "tlookup_multi_workspace_bytes", "tlookup_prove_multi",
+           "tlookup_multi_verify_workspace_bytes", "tlookup_verify_multi",
            "sumcheck_product_proof_bytes", "sumcheck_product_workspace_bytes", "sumcheck_prove_product",
            "sumcheck_verify_product", "matmul_proof_bytes", "matmul_workspace_bytes", "matmul_sumcheck_prove", "matmul_sumcheck_prove_i16",
            "matmul_verify_workspace_bytes", "matmul_sumcheck_verify", "zkattn_link_proof_bytes",
@@ -497,6 +506,68 @@ def tlookup_verify_batch(seed, proof, T, D, S=None, A=None, B=None, m=None, ws=N
     pb = ctypes.create_string_buffer(bytes(proof), max(len(proof), 1))
     rc = _lib.tlookup_verify_batch(_seed(seed), pb, len(proof), Tv, K, D, wit, ctypes.byref(claims), ws.data_ptr(),
                                    ws.numel(), _stream())
+    out = {}
+    if rc == ZK_OK:
+        out = {"lambda": _fr_int(claims.lambda_), "v": [_fr_int(claims.v[t]) for t in range(claims.nvars)],
+               "value": [[_fr_int(claims.value[i][q]) for q in range(5)] for i in range(K)]}
+    return rc, out
+
+
+def _sizes(values):
+    return (ctypes.c_size_t * len(values))(*[int(v) for v in values])
+
+
+def tlookup_multi_proof_bytes(Ds):
+    return _lib.tlookup_multi_proof_bytes(_sizes(Ds), len(Ds))
+
+
+def tlookup_multi_workspace_bytes(Ds, Ns):
+    return _lib.tlookup_multi_workspace_bytes(_sizes(Ds), _sizes(Ns), len(Ds))
+
+
+def tlookup_prove_multi(seed, S, idx, T, ws=None, cap=None):
+    """Lookups of any shapes under one sumcheck.  S, T: lists of K Vec (their lengths are the shapes); idx: None or a
+    list of K (tensor or None).  Returns (rc, proof bytes, aux dict with 'len')."""
+    K = len(S)
+    assert len(T) == K and (idx is None or len(idx) == K)
+    Ds, Ns = [s.n for s in S], [t.n for t in T]
+    ws = ws if ws is not None else _ws(tlookup_multi_workspace_bytes(Ds, Ns))
+    cap = tlookup_multi_proof_bytes(Ds) if cap is None else cap
+    proof = ctypes.create_string_buffer(max(cap, 1))
+    ln = ctypes.c_size_t(0)
+    aux = tlookup_batch_aux()
+    Sv = (fr_vec * K)(*[s.c for s in S])
+    Tv = (fr_vec * K)(*[t.c for t in T])
+    Iv = None
+    if idx is not None:
+        Iv = (ctypes.c_void_p * K)(*[_idx_ptr(i) for i in idx])
+    rc = _lib.tlookup_prove_multi(_seed(seed), Sv, Iv, Tv, K, proof, cap, ctypes.byref(ln), ctypes.byref(aux),
+                                  ws.data_ptr(), ws.numel(), _stream())
+    info = {"beta": _fr_int(aux.beta), "alpha": _fr_int(aux.alpha), "lambda": _fr_int(aux.lambda_),
+            "sum_A": [_fr_int(aux.sum_A[i]) for i in range(min(K, TLOOKUP_BATCH_MAX))],
+            "sum_mB": [_fr_int(aux.sum_mB[i]) for i in range(min(K, TLOOKUP_BATCH_MAX))],
+            "bad_instance": int(aux.bad_instance), "bad_index": int(aux.bad_index), "len": ln.value}
+    return rc, proof.raw[:ln.value] if rc == ZK_OK else b"", info
+
+
+def tlookup_verify_multi(seed, proof, T, Ds, S=None, A=None, B=None, m=None, ws=None):
+    """T: list of K Vec; Ds: the K tensor lengths; S, A, B, m: None or lists of K (entries may be None).
+    Returns (rc, claims dict); instance i's claims are at v[len(v) - log2 Ds[i]:]."""
+    K = len(T)
+    Ns = [t.n for t in T]
+    ws = ws if ws is not None else _ws(_lib.tlookup_multi_verify_workspace_bytes(_sizes(Ds), _sizes(Ns), K))
+    Tv = (fr_vec * K)(*[t.c for t in T])
+    wit = None
+    if any(x is not None for x in (S, A, B, m)):
+        def member(lst, i):
+            return lst[i].c if lst is not None and lst[i] is not None else _EMPTY
+        wit = (tlookup_witness * K)(*[
+            tlookup_witness(member(S, i), member(A, i), member(B, i),
+                            m[i].data_ptr() if m is not None and m[i] is not None else None) for i in range(K)])
+    claims = tlookup_batch_claims()
+    pb = ctypes.create_string_buffer(bytes(proof), max(len(proof), 1))
+    rc = _lib.tlookup_verify_multi(_seed(seed), pb, len(proof), Tv, _sizes(Ds), K, wit, ctypes.byref(claims),
+                                   ws.data_ptr(), ws.numel(), _stream())
     out = {}
     if rc == ZK_OK:
         out = {"lambda": _fr_int(claims.lambda_), "v": [_fr_int(claims.v[t]) for t in range(claims.nvars)],

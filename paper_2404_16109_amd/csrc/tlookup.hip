@@ -301,21 +301,38 @@ static int carve_prove(ProveWs& w, Carver& cv, size_t D, size_t N) {
     return ZK_OK;
 }
 
-// K instances of one shape: their buffers, the shared weight tables, and the
-// scratch of the 2K inversions that are in flight together.
-static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
+// K instances: their buffers, one pool of weight tables per distinct length of
+// the tensors, and the scratch of the 2K inversions that are in flight together.
+// The order here is the order prove_core carves in.
+static size_t prove_ws_bytes_shapes(const size_t* D, const size_t* N, size_t K) {
     Carver cv(nullptr, 0);
     for (size_t i = 0; i < K; ++i) {
         ProveWs w;
-        carve_prove(w, cv, D, N);
+        carve_prove(w, cv, D[i], N[i]);
     }
-    cv.limbs(EqPool::entries(log2_floor(D)));
-    cv.take(EqPool::entries29(log2_floor(D)) * 36);
     for (size_t i = 0; i < K; ++i) {
-        size_t apart = batch_inverse_scratch_bytes(D) + batch_inverse_scratch_bytes(N), joined = batch_inverse_scratch_bytes(D + N);
+        bool seen = false;
+        for (size_t j = 0; j < i; ++j) seen = seen || D[j] == D[i];
+        if (seen) continue;
+        cv.limbs(EqPool::entries(log2_floor(D[i])));
+        cv.take(EqPool::entries29(log2_floor(D[i])) * 36);
+    }
+    for (size_t i = 0; i < K; ++i) {
+        size_t apart = batch_inverse_scratch_bytes(D[i]) + batch_inverse_scratch_bytes(N[i]),
+               joined = batch_inverse_scratch_bytes(D[i] + N[i]);
         cv.take(apart > joined ? apart : joined);
     }
     return cv.used();
+}
+
+static size_t prove_ws_bytes(size_t D, size_t N, size_t K = 1) {
+    size_t Ds[kMailboxMaxInstances], Ns[kMailboxMaxInstances];
+    if (K > kMailboxMaxInstances) K = kMailboxMaxInstances;
+    for (size_t i = 0; i < K; ++i) {
+        Ds[i] = D;
+        Ns[i] = N;
+    }
+    return prove_ws_bytes_shapes(Ds, Ns, K);
 }
 
 // Multiplicities into w.m (and the digest leaves into w.leaves).  Returns
@@ -403,7 +420,7 @@ static void digest_of_leaves(uint8_t out[32], const uint8_t* leaves, uint32_t nl
 
 // ---- prover --------------------------------------------------------------------------------------
 //
-// One routine proves K instances of a common shape with a single sumcheck over
+// One routine proves K instances with a single sumcheck over
 //   f = sum_i lambda^i f_i,   claim_0 = (sum_i lambda^i)(alpha + alpha^2),
 // f_i the tlookup summand of instance i; beta, alpha, u and the round challenges
 // are shared.  tlookup_prove is K = 1 without lambda and with its own transcript
@@ -412,10 +429,26 @@ static void digest_of_leaves(uint8_t out[32], const uint8_t* leaves, uint32_t nl
 // on the stream, each instance's sums land in its own part of the mailbox, only
 // the last launch of a round publishes, and the host adds the instances' round
 // polynomials weighted by lambda^i.
+//
+// Shapes may differ (tlookup_prove_multi).  The sumcheck then has n = max_i n_i
+// variables, instance i lives on the last n_i of them (skip_i = n - n_i) and
+//   f = sum_i lambda^i 2^-skip_i f_i(x_[skip_i:]),  f_i built with u_[skip_i:]:
+// in a round k < skip_i the instance is a constant, (alpha + alpha^2) 2^(skip_i-k-1)
+// before its weight, which the host adds without any device work; from round
+// skip_i on it runs the rounds of a proof of its own ("local round" k - skip_i)
+// with the shared challenges, and all instances reach their last round together.
 
 struct Instance {
     ProveWs w;
     fr_vec S, T;
+    size_t D = 0, N = 0;             // its shape: n = log2 D, l = log2 N, h = n - l;
+    int n = 0, l = 0, h = 0, skip = 0;  // skip: the rounds of the whole proof before its own first
+    const EqPool* ep = nullptr;      // weight tables for u_[skip:]
+    host::F cD, cT;                  // products of e~(u_t, r_t) over its bound variables (all / the table's)
+    host::F half_pow;                // 2^-(local round + 1)
+    host::F scale;                   // 2^-h
+    int lazy_rounds = 0;             // how many of its rounds in a row have left the data arrays in 29-bit planes
+    host::F inv_den;                 // what the one-sided round's other side is divided by (this round)
     const uint32_t* idx = nullptr;
     uint32_t* b_cur = nullptr;  // where B lives at the moment (it ping-pongs while folding)
     size_t b_cur_stride = 0;
@@ -439,6 +472,7 @@ struct ProveCall {
     const uint32_t* const* idx = nullptr;  // may be null, entries may be null
     const fr_vec* T = nullptr;
     bool batch = false;                    // batched transcript and proof layout
+    bool multi = false;                    // batched, and the instances' shapes may differ (S[i].n, T[i].n)
     const fr_t* forced_beta = nullptr;
     bool by_rows = false;                  // A as B[idx_i] instead of inverting beta + S_i
     bool check_upfront = false;            // compare every S_i with its hinted row while counting (no deferred check)
@@ -539,22 +573,31 @@ static size_t batch_proof_bytes(size_t D, size_t K) {
     return 32 + 96 * K + (size_t)log2_floor(D ? D : 1) * 128 + 160 * K;
 }
 
+// "ZKTM" | u32 1 | LE64 K | K x (LE64 D_i, LE64 N_i) | K digests of m | K x [digest(A) digest(B)] | rounds | K x 5 claims
+static size_t multi_proof_bytes(int n_max, size_t K) { return 16 + 16 * K + 96 * K + (size_t)n_max * 128 + 160 * K; }
+
 static int prove_core(const ProveCall& c) {
     using namespace host;
     const size_t K = c.K;
     const bool from_ints = c.ints_x != nullptr;
     if (!c.seed || (!c.S && !from_ints) || !c.T || K == 0 || K > kMailboxMaxInstances) return ZK_E_BADARG;
-    if (!c.batch && K != 1) return ZK_E_BADARG;
-    const size_t D = from_ints ? c.ints_D : c.S[0].n, N = c.T[0].n;
-    if (!is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
-    if (from_ints && (K != 1 || c.batch || c.by_rows || !c.idx || !c.idx[0] || !small_source_shape_ok(D, N))) return ZK_E_BADARG;
+    if (!c.batch && (K != 1 || c.multi)) return ZK_E_BADARG;
+    if (from_ints && (K != 1 || c.batch || c.by_rows || !c.idx || !c.idx[0])) return ZK_E_BADARG;
+    // shapes: one for all, unless the call says they may differ
+    size_t Ds[kMailboxMaxInstances], Ns[kMailboxMaxInstances];
+    int n = 0;  // variables of the sumcheck: those of the longest instance
+    for (size_t i = 0; i < K; ++i) {
+        Ds[i] = from_ints ? c.ints_D : c.S[c.multi ? i : 0].n;
+        Ns[i] = c.T[c.multi ? i : 0].n;
+        if (!is_pow2(Ds[i]) || !is_pow2(Ns[i]) || Ns[i] > Ds[i] || Ds[i] > ((size_t)1 << 31)) return ZK_E_BADARG;
+        if (c.T[i].n != Ns[i] || !vec_ok(c.T[i], Ns[i])) return ZK_E_BADARG;
+        if (!from_ints && (c.S[i].n != Ds[i] || !vec_ok(c.S[i], Ds[i]))) return ZK_E_BADARG;
+        if (c.by_rows && !(c.idx && c.idx[i])) return ZK_E_BADARG;
+        if (log2_floor(Ds[i]) > n) n = log2_floor(Ds[i]);
+    }
+    if (from_ints && !small_source_shape_ok(Ds[0], Ns[0])) return ZK_E_BADARG;
     if (from_ints && ((c.ints_y != nullptr) != (c.ints_rho != nullptr))) return ZK_E_BADARG;
     if (from_ints && c.ints_rho && !canonical_in_range(*c.ints_rho)) return ZK_E_BADARG;
-    for (size_t i = 0; i < K; ++i) {
-        if (c.T[i].n != N || !vec_ok(c.T[i], N)) return ZK_E_BADARG;
-        if (!from_ints && (c.S[i].n != D || !vec_ok(c.S[i], D))) return ZK_E_BADARG;
-        if (c.by_rows && !(c.idx && c.idx[i])) return ZK_E_BADARG;
-    }
     // the tensor as small integers, if it came that way
     SmallSource ints_src;
     memset(&ints_src, 0, sizeof ints_src);
@@ -570,29 +613,39 @@ static int prove_core(const ProveCall& c) {
         to_device_limbs(ints_src.minus_rho, neg(mul(ints_rho, two64)));
     }
     if (c.forced_beta && !canonical_in_range(*c.forced_beta)) return ZK_E_BADARG;
-    const int n = log2_floor(D), l = log2_floor(N), h = n - l;
-    const size_t need = c.batch ? batch_proof_bytes(D, K) : tlookup_proof_bytes(D);
+    const size_t need = c.multi ? multi_proof_bytes(n, K) : c.batch ? batch_proof_bytes(Ds[0], K) : tlookup_proof_bytes(Ds[0]);
     if (c.len) *c.len = need;
     if (!c.proof || c.cap < need) return ZK_E_BUFSZ;
-    if (!c.ws || c.ws_bytes < prove_ws_bytes(D, N, K)) return ZK_E_BUFSZ;
+    if (!c.ws || c.ws_bytes < prove_ws_bytes_shapes(Ds, Ns, K)) return ZK_E_BUFSZ;
     hipStream_t stream = as_stream(c.stream);
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
     Carver cv(c.ws, c.ws_bytes);
     Instance inst[kMailboxMaxInstances];
+    const F inv2 = inv(from_u64(2));
     for (size_t i = 0; i < K; ++i) {
         Instance& I = inst[i];
-        carve_prove(I.w, cv, D, N);
-        I.S = from_ints ? fr_vec{nullptr, D, D} : c.S[i];  // with integers there is no vector: every reader of I.S.limbs is
-        I.T = c.T[i];                                       // gated by the round's plan (s_source)
+        I.D = Ds[i];
+        I.N = Ns[i];
+        I.n = log2_floor(I.D);
+        I.l = log2_floor(I.N);
+        I.h = I.n - I.l;
+        I.skip = n - I.n;
+        carve_prove(I.w, cv, I.D, I.N);
+        I.S = from_ints ? fr_vec{nullptr, I.D, I.D} : c.S[i];  // with integers there is no vector: every reader of I.S.limbs
+        I.T = c.T[i];                                           // is gated by the round's plan (s_source)
         I.idx = c.idx ? c.idx[i] : nullptr;
         I.b_cur = I.w.B;
-        I.b_cur_stride = N;
+        I.b_cur_stride = I.N;
         I.words = mb->words + kMailboxSlot * i;
         I.inv_words = mb->words + kMailboxInvB + 16 * i;
         I.const_words = mb->words + kMailboxTableC + 16 * i;
         I.dig_words = mb->words + kMailboxDigest + 16 * i;
         I.c1 = I.c2 = I.cB = I.sum_A = zero();
+        I.cD = I.cT = I.half_pow = one();
+        I.inv_den = zero();
+        I.scale = one();
+        for (int t = 0; t < I.h; ++t) I.scale = mul(I.scale, inv2);
     }
     if (cv.overflow()) return ZK_E_BUFSZ;
 
@@ -600,7 +653,7 @@ static int prove_core(const ProveCall& c) {
 
     // -- Prep: multiplicities and their digests -------------------------------------------------
     bool defer_all = !c.by_rows && !c.check_upfront;
-    for (size_t i = 0; i < K; ++i) defer_all = defer_all && can_defer_check(inst[i].w, inst[i].idx, D);
+    for (size_t i = 0; i < K; ++i) defer_all = defer_all && can_defer_check(inst[i].w, inst[i].idx, inst[i].D);
     if (from_ints && !defer_all) return ZK_E_BADARG;  // counting would read S as a vector
     for (size_t i = 0; i < K; ++i) {
         uint64_t bad = 0;
@@ -610,7 +663,8 @@ static int prove_core(const ProveCall& c) {
             // with hints, the inverse vectors themselves tell whether S_i = T[idx_i] everywhere (see the first round);
             // all instances or none, so that the first instance at fault is the one reported
             inst[i].deferred = defer_all;
-            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, D, N, &bad, mb, stream, inst[i].deferred, true);
+            rc = count_rows(inst[i].w, inst[i].S, inst[i].idx, inst[i].T, inst[i].D, inst[i].N, &bad, mb, stream,
+                            inst[i].deferred, true);
         }
         if (rc == ZK_E_NOT_IN_TABLE) {
             if (c.aux) c.aux->bad_index = bad;
@@ -623,8 +677,22 @@ static int prove_core(const ProveCall& c) {
         digest_of_leaves(inst[i].md, mb->bulk + 16, inst[i].w.nleaves);
     }
 
-    uint64_t dims[3] = {D, N, K};
-    Transcript tr(c.batch ? "zkmi/tlookup-batch/v2" : "zkmi/tlookup/v2", c.seed, dims, c.batch ? 3 : 2);
+    uint64_t dims[1 + 2 * kMailboxMaxInstances];
+    int ndims;
+    if (c.multi) {
+        dims[0] = K;
+        for (size_t i = 0; i < K; ++i) {
+            dims[1 + 2 * i] = inst[i].D;
+            dims[2 + 2 * i] = inst[i].N;
+        }
+        ndims = 1 + 2 * (int)K;
+    } else {
+        dims[0] = inst[0].D;
+        dims[1] = inst[0].N;
+        dims[2] = K;
+        ndims = c.batch ? 3 : 2;
+    }
+    Transcript tr(c.multi ? "zkmi/tlookup-multi/v1" : c.batch ? "zkmi/tlookup-batch/v2" : "zkmi/tlookup/v2", c.seed, dims, ndims);
     for (size_t i = 0; i < K; ++i) tr.absorb("m", inst[i].md, 32);
 
     // -- Prove: beta, inverse vectors ---------------------------------------------------------------
@@ -638,13 +706,14 @@ static int prove_core(const ProveCall& c) {
         ProfileScope prof(kProfInverse, stream);
         Carver inv_cv = cv;
         const uint32_t seq = mb->next_seq();
-        const bool joined = batch_inverse_can_join(D) && D > (size_t)kBlock;
         BatchInverseJob* jobs[2 * kMailboxMaxInstances];
         const uint32_t* totals[2 * kMailboxMaxInstances];
         size_t njobs = 0;
         for (size_t i = 0; i < K; ++i) {
             Instance& I = inst[i];
+            const size_t D = I.D, N = I.N;
             const uint32_t last = i + 1 == K ? seq : 0;
+            const bool joined = batch_inverse_can_join(D) && D > (size_t)kBlock;
             if (joined) {
                 ZK_TRY(batch_inverse_begin(I.job_a, I.w.A, D, I.S.limbs, I.S.stride, D, beta, inv_cv, I.inv_words + 8,
                                            mb->words, last, stream, I.w.B, N, I.T.limbs, I.T.stride, N,
@@ -682,6 +751,7 @@ static int prove_core(const ProveCall& c) {
         ProfileScope prof(kProfInverse, stream);
         for (size_t i = 0; i < K; ++i) {
             Instance& I = inst[i];
+            const size_t D = I.D, N = I.N;
             Carver inv_cv = cv;
             ZK_TRY(batch_inverse_run(I.w.B, N, I.T.limbs, I.T.stride, N, beta, inv_cv, mb, stream));
             hipLaunchKernelGGL(k_rows_of, dim3(grid_for(N)), dim3(kBlock), 0, stream, I.w.rows, I.w.B, N, (uint32_t)N);
@@ -699,7 +769,7 @@ static int prove_core(const ProveCall& c) {
         const uint32_t seq = mb->next_seq();
         for (size_t i = 0; i < K; ++i) {
             Instance& I = inst[i];
-            const VecDigestJob ja{I.w.A, D, D, I.w.dig_rows, I.dig_words}, jb{I.w.B, N, N, I.w.dig_rows_b, I.dig_words + 8};
+            const VecDigestJob ja{I.w.A, I.D, I.D, I.w.dig_rows, I.dig_words}, jb{I.w.B, I.N, I.N, I.w.dig_rows_b, I.dig_words + 8};
             vec_digest_launch(ja, &jb, I.w.dig_leaves, mb->words, i + 1 == K ? seq : 0, I.w.flags + 1, stream);
         }
         ZK_HIP_TRY(hipGetLastError());
@@ -718,11 +788,25 @@ static int prove_core(const ProveCall& c) {
     for (int t = 0; t < n; ++t) u[t] = tr.challenge("u");
     F lambda = one();
     if (c.batch) lambda = tr.challenge("lambda");
-    inst[0].lam = one();
-    for (size_t i = 1; i < K; ++i) inst[i].lam = mul(inst[i - 1].lam, lambda);
+    // an instance's weight in f: lambda^i, times 2^-skip when it is shorter than the longest
+    {
+        F lam_pow = one();
+        for (size_t i = 0; i < K; ++i) {
+            inst[i].lam = lam_pow;
+            for (int t = 0; t < inst[i].skip; ++t) inst[i].lam = mul(inst[i].lam, inv2);
+            lam_pow = mul(lam_pow, lambda);
+        }
+    }
 
-    EqPool ep;
-    ZK_TRY(eq_pool_build(ep, u, n, cv, stream));
+    // weight tables: instance i uses u_[skip_i:], so instances of one length share a pool
+    EqPool pools[kMailboxMaxInstances];
+    for (size_t i = 0; i < K; ++i) {
+        for (size_t j = 0; j < i && !inst[i].ep; ++j)
+            if (inst[j].D == inst[i].D) inst[i].ep = inst[j].ep;
+        if (inst[i].ep) continue;
+        ZK_TRY(eq_pool_build(pools[i], u + inst[i].skip, inst[i].n, cv, stream));
+        inst[i].ep = &pools[i];
+    }
 
     // -- table-side constants ---------------------------------------------------------------------
     // c1 = sum_j e'_j B_j (T_j+beta), c2 = sum_j m_j B_j.  e' = e~(u_[h:], .) is the
@@ -730,6 +814,9 @@ static int prove_core(const ProveCall& c) {
     // round needs the constant, only c2 is reported.
     for (size_t i = 0; i < K; ++i) {
         Instance& I = inst[i];
+        const size_t N = I.N;
+        const int h = I.h;
+        const EqPool& ep = *I.ep;
         TableConstArgs a;
         a.B = I.w.B; a.bs = N;
         a.T = I.T.limbs; a.ts = I.T.stride;
@@ -763,14 +850,26 @@ static int prove_core(const ProveCall& c) {
 
     // -- header -----------------------------------------------------------------------------------------
     uint8_t* out = c.proof;
-    memcpy(out, c.batch ? "ZKTB" : "ZKTL", 4);
-    out[4] = 2; out[5] = out[6] = out[7] = 0;
-    put_le64(out + 8, D);
-    put_le64(out + 16, N);
-    out += 24;
-    if (c.batch) {
-        put_le64(out, K);
-        out += 8;
+    if (c.multi) {
+        memcpy(out, "ZKTM", 4);
+        out[4] = 1; out[5] = out[6] = out[7] = 0;
+        put_le64(out + 8, K);
+        out += 16;
+        for (size_t i = 0; i < K; ++i) {
+            put_le64(out, inst[i].D);
+            put_le64(out + 8, inst[i].N);
+            out += 16;
+        }
+    } else {
+        memcpy(out, c.batch ? "ZKTB" : "ZKTL", 4);
+        out[4] = 2; out[5] = out[6] = out[7] = 0;
+        put_le64(out + 8, inst[0].D);
+        put_le64(out + 16, inst[0].N);
+        out += 24;
+        if (c.batch) {
+            put_le64(out, K);
+            out += 8;
+        }
     }
     for (size_t i = 0; i < K; ++i) {
         memcpy(out, inst[i].md, 32);
@@ -783,33 +882,28 @@ static int prove_core(const ProveCall& c) {
     }
 
     // -- rounds -----------------------------------------------------------------------------------------
-    F scale = one();  // 2^-h
-    {
-        F half = inv(from_u64(2));
-        for (int i = 0; i < h; ++i) scale = mul(scale, half);
-    }
-    const F inv2 = inv(from_u64(2));
-    F half_pow = one();       // 2^-(k+1) in round k
-    F cD = one(), cT = one();  // products of e~(u_t, r_t) over bound variables
+    // Below, k counts the rounds of the whole proof and kk = k - skip those of one
+    // instance ("local"): an instance's kernels, plan and arrays only ever see kk.
     F r_prev = zero();
     // Rounds that fold the data arrays only and are large run on 29-bit limbs
     // (tlookup_round29.h).  Between two of them the arrays stay in 29-bit planes,
     // unreduced, for at most kMaxLazyRounds rounds in a row.
-    int lazy_rounds = 0;  // how many rounds in a row have left the data arrays in 29-bit planes
     const F29 beta29 = f29_unpack(to_dev(beta).l);
-    // Where round k reads and writes the arrays that change place: S comes from the
-    // caller's vector until it has been folded once, T likewise, and B alternates
+    // Where local round kk reads and writes the arrays that change place: S comes from
+    // the caller's vector until it has been folded once, T likewise, and B alternates
     // between its two buffers on every fold (it has two readers).  b_cur: where B is
     // before the round; returns where it is afterwards.
     struct Moving {
         PairArray S, B, T;
     };
-    auto moving_arrays = [&](int k, const Instance& I, uint32_t*& b_cur, size_t& b_stride) {
+    auto moving_arrays = [&](int kk, const Instance& I, uint32_t*& b_cur, size_t& b_stride) {
         const ProveWs& w = I.w;
+        const size_t D = I.D, N = I.N;
+        const int h = I.h;
         Moving m;
-        if (k <= 1) m.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
+        if (kk <= 1) m.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
         else m.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
-        if (k > h) {
+        if (kk > h) {
             uint32_t* other = b_cur == w.B ? w.Bf : w.B;
             size_t other_stride = b_cur == w.B ? N / 2 : N;
             m.B = PairArray{b_cur, b_stride, other, other_stride};
@@ -818,24 +912,25 @@ static int prove_core(const ProveCall& c) {
         } else {
             m.B = PairArray{b_cur, b_stride, b_cur, b_stride};
         }
-        if (k <= h + 1) m.T = PairArray{I.T.limbs, I.T.stride, w.Tf, N / 2};
+        if (kk <= h + 1) m.T = PairArray{I.T.limbs, I.T.stride, w.Tf, N / 2};
         else m.T = PairArray{w.Tf, N / 2, w.Tf, N / 2};
         return m;
     };
     auto final_arrays = [&](const Instance& I, const uint32_t* b_cur, size_t b_stride) {
         const ProveWs& w = I.w;
+        const size_t D = I.D, N = I.N;
         FinalArgs f;
         memset(&f, 0, sizeof f);
         f.count = 5;
-        const bool d_fold = n >= 1, t_fold = l >= 1;
+        const bool d_fold = I.n >= 1, t_fold = I.l >= 1;
         // A, S, B, m, T in the order of the proof
         f.p[0] = w.A; f.stride[0] = D; f.fold[0] = d_fold;
-        if (n <= 1) { f.p[1] = I.S.limbs; f.stride[1] = I.S.stride; }
+        if (I.n <= 1) { f.p[1] = I.S.limbs; f.stride[1] = I.S.stride; }
         else { f.p[1] = w.Sf; f.stride[1] = D / 2; }
         f.fold[1] = d_fold;
         f.p[2] = b_cur; f.stride[2] = b_stride; f.fold[2] = t_fold;
         f.p[3] = w.M; f.stride[3] = N; f.fold[3] = t_fold;
-        if (l <= 1) { f.p[4] = I.T.limbs; f.stride[4] = I.T.stride; }
+        if (I.l <= 1) { f.p[4] = I.T.limbs; f.stride[4] = I.T.stride; }
         else { f.p[4] = w.Tf; f.stride[4] = N / 2; }
         f.fold[4] = t_fold;
         return f;
@@ -845,38 +940,32 @@ static int prove_core(const ProveCall& c) {
     int tail_first = -1;  // the round the resident kernel was launched for, if it is running
     TailGuard tail_guard{mb, stream};
     for (int k = 0; k < n; ++k) {
-        const size_t half = (size_t)1 << (n - k - 1);
-        const EqSplit eq = ep.round(k);
-        const RoundPlan plan = plan_round(n, h, k, K, from_ints, lazy_rounds, tail_first >= 0);
-        if (plan.s_source == kSNowhere) return ZK_E_BADARG;  // cannot happen: small_source_shape_ok has walked these rounds
         // The 29-bit kernel sums one side of the round only (X = 0, or X = 1 with side1); the other side's two sums
         // follow from what the prover has already sent: sA0 + sA1 is the previous round's sum of A at its challenge,
         // g(0) + g(1) the running claim.  The second needs a division by alpha c e~(u_k, X) of the side that was not
         // summed, so the side is chosen by which of the two is not zero (alternating otherwise, both being equally
         // good); if alpha c itself is zero, q carries no weight in g and is not needed.
         const F e_side[2] = {sub(one(), u[k]), u[k]};
-        const F wD = mul(alpha, cD);
         bool side1 = (k & 1) != 0;
         if (is_zero(e_side[0])) side1 = false;  // u_k = 1: only g(1) can tell q1, so sum the X = 0 side
         if (is_zero(e_side[1])) side1 = true;
-        F inv_den = zero();
-        const bool table_round = plan.table_round;
-        const bool in32 = plan.in32, out32 = plan.out32;
-        // pairs per workgroup: a workgroup's pairs must share the high factor of
-        // their weights (at most 2^kLoBits pairs, 16 per thread).  As many as that
-        // allows, since a thread's closing reduction costs about as much as two
-        // pairs, but at least 512 workgroups while the round is large enough;
-        // small rounds get one pair per thread
-        size_t span = half / 512;
-        if (span < (size_t)kBlock) span = (size_t)kBlock;
-        if (span > ((size_t)1 << kLoBits)) span = (size_t)1 << kLoBits;
-        if (span > half) span = half;
-        const unsigned blocks = (unsigned)(half / span);
-        if (blocks > inst[0].w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
+        // the last instance that has kernels in this round publishes it (the longest instance always has)
+        size_t last_active = 0;
+        for (size_t i = 0; i < K; ++i)
+            if (k >= inst[i].skip) last_active = i;
+        RoundPlan plans[kMailboxMaxInstances] = {};
+        for (size_t i = 0; i < K; ++i) {
+            const Instance& I = inst[i];
+            if (k < I.skip) continue;
+            plans[i] = plan_round(I.n, I.h, k - I.skip, K, from_ints, I.lazy_rounds, tail_first >= 0);
+            if (plans[i].s_source == kSNowhere) return ZK_E_BADARG;  // cannot happen: small_source_shape_ok has walked these rounds
+        }
 
-        if (plan.kernel == kRoundResident && tail_first < 0) {
-            // this and every later round in one launch
+        if (K == 1 && plans[0].kernel == kRoundResident && tail_first < 0) {
+            // this and every later round in one launch (K = 1, so k is the instance's own count)
             Instance& I = inst[0];
+            const size_t D = I.D, N = I.N;
+            const int h = I.h;
             memset(&tail, 0, sizeof tail);
             tail.A = PairArray{I.w.A, D, I.w.A, D};
             tail.M = PairArray{I.w.M, N, I.w.M, N};
@@ -891,7 +980,7 @@ static int prove_core(const ProveCall& c) {
                 rd.S = m.S;
                 rd.B = m.B;
                 rd.T = m.T;
-                rd.eq = ep.round(j);
+                rd.eq = I.ep->round(j);
                 rd.half = (size_t)1 << (n - j - 1);
                 rd.table = j < h ? 0 : j == h ? 1 : 2;
             }
@@ -914,9 +1003,29 @@ static int prove_core(const ProveCall& c) {
         const uint32_t seq = tail_first >= 0 ? tail.out_seq[k - tail_first] : mb->next_seq();
         for (size_t i = 0; i < K && tail_first < 0; ++i) {
             Instance& I = inst[i];
+            if (k < I.skip) continue;
             ProveWs& w = I.w;
-            const uint32_t my_seq = i + 1 == K ? seq : 0;  // the last instance's last launch publishes the round
-            const Moving mv = moving_arrays(k, I, I.b_cur, I.b_cur_stride);
+            const size_t D = I.D, N = I.N;
+            const int h = I.h, kk = k - I.skip;
+            const RoundPlan& plan = plans[i];
+            const size_t half = (size_t)1 << (I.n - kk - 1);
+            const EqSplit eq = I.ep->round(kk);
+            const EqPool& ep = *I.ep;
+            const bool table_round = plan.table_round;
+            const bool in32 = plan.in32, out32 = plan.out32;
+            // pairs per workgroup: a workgroup's pairs must share the high factor of
+            // their weights (at most 2^kLoBits pairs, 16 per thread).  As many as that
+            // allows, since a thread's closing reduction costs about as much as two
+            // pairs, but at least 512 workgroups while the round is large enough;
+            // small rounds get one pair per thread
+            size_t span = half / 512;
+            if (span < (size_t)kBlock) span = (size_t)kBlock;
+            if (span > ((size_t)1 << kLoBits)) span = (size_t)1 << kLoBits;
+            if (span > half) span = half;
+            const unsigned blocks = (unsigned)(half / span);
+            if (blocks > w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
+            const uint32_t my_seq = i == last_active ? seq : 0;  // the last instance's last launch publishes the round
+            const Moving mv = moving_arrays(kk, I, I.b_cur, I.b_cur_stride);
             DataRoundArgs d;
             d.A = PairArray{w.A, D, w.A, D};
             d.S = mv.S;
@@ -951,7 +1060,7 @@ static int prove_core(const ProveCall& c) {
                 if (!table_round)
                     hipLaunchKernelGGL(k_round_small<0>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
                                        my_seq);
-                else if (k == h)
+                else if (kk == h)
                     hipLaunchKernelGGL(k_round_small<1>, dim3(1), dim3(kSmallThreads), 0, stream, d, t, I.words, mb->words,
                                        my_seq);
                 else
@@ -960,7 +1069,7 @@ static int prove_core(const ProveCall& c) {
             } else if (plan.kernel == kRoundBoth) {
                 {
                     ProfileScope prof(kProfRoundSmall, stream);
-                    if (k > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
+                    if (kk > h) hipLaunchKernelGGL(k_round_both<true>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
                     else hipLaunchKernelGGL(k_round_both<false>, dim3(blocks, 3), dim3(kBlock), 0, stream, d, t);
                 }
                 launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, I.words, mb->words, my_seq,
@@ -1021,7 +1130,7 @@ static int prove_core(const ProveCall& c) {
                     ProfileScope prof(kProfRoundData, stream);
                     hipLaunchKernelGGL(k_round_data0, dim3(blocks), dim3(kBlock), 0, stream, d);
                 }
-                if (table_round) {  // only with k == 0, i.e. D == N
+                if (table_round) {  // only with kk == 0, i.e. D == N
                     ProfileScope prof(kProfRoundTable, stream);
                     hipLaunchKernelGGL(k_round_table<false>, dim3(blocks), dim3(kBlock), 0, stream, t);
                 }
@@ -1030,32 +1139,58 @@ static int prove_core(const ProveCall& c) {
             }
             ZK_HIP_TRY(hipGetLastError());
         }
-        lazy_rounds = plan.lazy_after;
         // while the device works: each instance's running claim, and the inverse the 29-bit round's other side needs
-        for (size_t i = 0; i < K; ++i) inst[i].claim = k == 0 ? add(alpha, alpha2) : interpolate_at(inst[i].fX, 4, r_prev);
-        if (plan.kernel == kRound29 && tail_first < 0 && !is_zero(wD)) inv_den = inv(mul(wD, e_side[side1 ? 0 : 1]));
+        // (instances of one length share it)
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            if (k < I.skip) continue;
+            I.lazy_rounds = plans[i].lazy_after;
+            I.claim = k == I.skip ? add(alpha, alpha2) : interpolate_at(I.fX, 4, r_prev);
+            I.inv_den = zero();
+            const F wD = mul(alpha, I.cD);
+            if (plans[i].kernel != kRound29 || tail_first >= 0 || is_zero(wD)) continue;
+            bool shared = false;
+            for (size_t j = 0; j < i && !shared; ++j)
+                if (k >= inst[j].skip && inst[j].skip == I.skip && plans[j].kernel == kRound29) {
+                    I.inv_den = inst[j].inv_den;  // same bound variables, same product of weights
+                    shared = true;
+                }
+            if (!shared) I.inv_den = inv(mul(wD, e_side[side1 ? 0 : 1]));
+        }
         ZK_TRY(mailbox_wait(mb, seq, stream));
         read_table_consts();
 
         F e[4], g[4];
         line_values(e, e_side[0], e_side[1]);
-        const F wT = table_round ? mul(alpha2, cT) : zero();
-        half_pow = mul(half_pow, inv2);
         for (int X = 0; X < 4; ++X) g[X] = zero();
         for (size_t i = 0; i < K; ++i) {
             Instance& I = inst[i];
+            if (k < I.skip) {
+                // not one of this instance's variables: its summand is the same at every X, and over the rest of the
+                // cube it sums to 2^(skip - k - 1) times its whole sum alpha + alpha^2 (before its weight 2^-skip)
+                F f = add(alpha, alpha2);
+                for (int t = 0; t < I.skip - k - 1; ++t) f = add(f, f);
+                for (int X = 0; X < 4; ++X) g[X] = add(g[X], mul(I.lam, f));
+                continue;
+            }
+            const int kk = k - I.skip;
+            const RoundPlan& plan = plans[i];
+            const bool table_round = plan.table_round;
+            const F wD = mul(alpha, I.cD);
+            const F wT = table_round ? mul(alpha2, I.cT) : zero();
+            I.half_pow = mul(I.half_pow, inv2);
             const uint32_t* sums = I.words;
             F q0 = from_dev(sums), q1 = from_dev(sums + 8), qi = from_dev(sums + 16);
-            if (k == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
+            if (kk == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
             F sA0 = from_dev(sums + 24), sA1 = from_dev(sums + 32);
+            const F table_const = mul(I.cB, I.half_pow);
             if (plan.kernel == kRound29 && tail_first < 0) {
                 // the kernel has summed one side: (q0, sA0) hold that side's q and sum of A; the other side from
                 // sA(0) + sA(1) = sA_prev(r_prev) and g(0) + g(1) = claim (never a table round: the table side is a constant)
                 const int a = side1 ? 1 : 0;
-                const F tconst = mul(I.cB, half_pow);
                 const F sA_b = sub(add(I.sA_prev[0], mul(r_prev, sub(I.sA_prev[1], I.sA_prev[0]))), sA0);
-                const F g_a = add(add(mul(mul(wD, e_side[a]), q0), sA0), tconst);
-                const F q_b = mul(sub(sub(sub(I.claim, g_a), sA_b), tconst), inv_den);
+                const F g_a = add(add(mul(mul(wD, e_side[a]), q0), sA0), table_const);
+                const F q_b = mul(sub(sub(sub(I.claim, g_a), sA_b), table_const), I.inv_den);
                 const F q_a = q0, sA_a = sA0;
                 q0 = a == 0 ? q_a : q_b;
                 q1 = a == 0 ? q_b : q_a;
@@ -1064,14 +1199,14 @@ static int prove_core(const ProveCall& c) {
             }
             I.sA_prev[0] = sA0;
             I.sA_prev[1] = sA1;
-            if (k == 0) I.sum_A = add(sA0, sA1);
-            if (k == 0 && I.deferred && !equal(I.sum_A, I.c2)) {
+            if (kk == 0) I.sum_A = add(sA0, sA1);
+            if (kk == 0 && I.deferred && !equal(I.sum_A, I.c2)) {
                 // The counts were taken from the hints without looking at S.  Had every
                 // S_i been the hinted row, sum_i 1/(beta+S_i) = sum_j m_j/(beta+T_j) would hold
                 // (Section 4, first form of the identity); it does not, so some S_i differs
                 // from its row: find the smallest such i by comparing them all.
                 uint64_t bad = UINT64_MAX;
-                ZK_TRY(find_bad_row(I.w, I.S, ints_src, I.idx, D, N, &bad, stream));
+                ZK_TRY(find_bad_row(I.w, I.S, ints_src, I.idx, I.D, I.N, &bad, stream));
                 if (bad == UINT64_MAX) return ZK_E_HIP;  // the sums disagree although every row matches
                 if (c.aux) c.aux->bad_index = bad;
                 if (c.baux) {
@@ -1087,13 +1222,12 @@ static int prove_core(const ProveCall& c) {
                 quad_values(tq, from_dev(sums + 40), from_dev(sums + 48), from_dev(sums + 56));
                 quad_values(tm, from_dev(sums + 64), from_dev(sums + 72), from_dev(sums + 80));
             }
-            const F table_const = mul(I.cB, half_pow);
             for (int X = 0; X < 4; ++X) {
                 F data = add(mul(mul(wD, e[X]), q[X]), sa[X]);
-                F table = table_round ? mul(scale, sub(mul(mul(wT, e[X]), tq[X]), tm[X])) : table_const;
+                F table = table_round ? mul(I.scale, sub(mul(mul(wT, e[X]), tq[X]), tm[X])) : table_const;
                 F f = add(data, table);
                 I.fX[X] = f;
-                g[X] = add(g[X], K == 1 ? f : mul(I.lam, f));
+                g[X] = add(g[X], !c.batch ? f : mul(I.lam, f));
             }
         }
         for (int X = 0; X < 4; ++X) to_bytes(out + 32 * X, g[X]);
@@ -1101,8 +1235,12 @@ static int prove_core(const ProveCall& c) {
         out += 128;
         F r = tr.challenge("r");
         F er = add(mul(sub(one(), u[k]), sub(one(), r)), mul(u[k], r));
-        cD = mul(cD, er);
-        if (table_round) cT = mul(cT, er);
+        for (size_t i = 0; i < K; ++i) {
+            Instance& I = inst[i];
+            if (k < I.skip) continue;
+            I.cD = mul(I.cD, er);
+            if (plans[i].table_round) I.cT = mul(I.cT, er);
+        }
         r_prev = r;
         if (tail_first >= 0) mailbox_send_challenge(mb, tail.cmd_seq[k - tail_first], to_dev(r).l);
     }
@@ -1130,7 +1268,7 @@ static int prove_core(const ProveCall& c) {
         for (size_t i = 0; i < K; ++i) {
             for (int q = 0; q < 5; ++q) {
                 F v = from_dev(inst[i].words + 8 * q);
-                if (q == 0 && n == 0) inst[i].sum_A = v;
+                if (q == 0 && inst[i].n == 0) inst[i].sum_A = v;
                 to_bytes(out, v);
                 out += 32;
             }
@@ -1178,6 +1316,8 @@ struct VerifyCall {
     const fr_vec* T = nullptr;
     size_t D = 0;
     bool batch = false;
+    bool multi = false;            // shapes may differ: lengths of the tensors in Ds, of the tables in T[i].n
+    const size_t* Ds = nullptr;
     const tlookup_witness* wit = nullptr;  // K entries, or null
     tlookup_claims* claims = nullptr;      // single proof
     tlookup_batch_claims* bclaims = nullptr;
@@ -1188,25 +1328,46 @@ struct VerifyCall {
 
 static int verify_core(const VerifyCall& c) {
     using namespace host;
-    const size_t K = c.K, D = c.D;
-    if (!c.seed || !c.proof || !c.T || K == 0 || K > kMailboxMaxInstances || (!c.batch && K != 1)) return ZK_E_BADARG;
-    const size_t N = c.T[0].n;
-    if (!is_pow2(D) || !is_pow2(N) || N > D || D > ((size_t)1 << 31)) return ZK_E_BADARG;
-    for (size_t i = 0; i < K; ++i)
-        if (c.T[i].n != N || !vec_ok(c.T[i], N)) return ZK_E_BADARG;
-    if (!c.ws || c.ws_bytes < verify_ws_bytes(D, N)) return ZK_E_BUFSZ;
-    const int n = log2_floor(D), l = log2_floor(N), h = n - l;
+    const size_t K = c.K;
+    if (!c.seed || !c.proof || !c.T || K == 0 || K > kMailboxMaxInstances || (!c.batch && (K != 1 || c.multi))) return ZK_E_BADARG;
+    if (c.multi && !c.Ds) return ZK_E_BADARG;
+    // shapes: n variables in all; instance i has n_i of them, the last ones (skip_i = n - n_i)
+    size_t Ds[kMailboxMaxInstances], Ns[kMailboxMaxInstances];
+    int ns[kMailboxMaxInstances], ls[kMailboxMaxInstances], hs[kMailboxMaxInstances], skips[kMailboxMaxInstances];
+    int n = 0;
+    size_t D_max = 1, N_max = 1;
+    for (size_t i = 0; i < K; ++i) {
+        Ds[i] = c.multi ? c.Ds[i] : c.D;
+        Ns[i] = c.T[c.multi ? i : 0].n;
+        if (!is_pow2(Ds[i]) || !is_pow2(Ns[i]) || Ns[i] > Ds[i] || Ds[i] > ((size_t)1 << 31)) return ZK_E_BADARG;
+        if (c.T[i].n != Ns[i] || !vec_ok(c.T[i], Ns[i])) return ZK_E_BADARG;
+        ns[i] = log2_floor(Ds[i]);
+        ls[i] = log2_floor(Ns[i]);
+        hs[i] = ns[i] - ls[i];
+        if (ns[i] > n) n = ns[i];
+        if (Ds[i] > D_max) D_max = Ds[i];
+        if (Ns[i] > N_max) N_max = Ns[i];
+    }
+    for (size_t i = 0; i < K; ++i) skips[i] = n - ns[i];
+    if (!c.ws || c.ws_bytes < verify_ws_bytes(D_max, N_max)) return ZK_E_BUFSZ;
     const uint8_t* proof = c.proof;
     const uint8_t* digests;
-    if (c.batch) {
-        if (c.len != batch_proof_bytes(D, K)) return ZK_E_REJECT;
+    if (c.multi) {
+        if (c.len != multi_proof_bytes(n, K)) return ZK_E_REJECT;
+        if (memcmp(proof, "ZKTM\x01\0\0\0", 8) != 0) return ZK_E_REJECT;
+        if (get_le64(proof + 8) != K) return ZK_E_REJECT;
+        for (size_t i = 0; i < K; ++i)
+            if (get_le64(proof + 16 + 16 * i) != Ds[i] || get_le64(proof + 24 + 16 * i) != Ns[i]) return ZK_E_REJECT;
+        digests = proof + 16 + 16 * K;
+    } else if (c.batch) {
+        if (c.len != batch_proof_bytes(Ds[0], K)) return ZK_E_REJECT;
         if (memcmp(proof, "ZKTB\x02\0\0\0", 8) != 0) return ZK_E_REJECT;
-        if (get_le64(proof + 8) != D || get_le64(proof + 16) != N || get_le64(proof + 24) != K) return ZK_E_REJECT;
+        if (get_le64(proof + 8) != Ds[0] || get_le64(proof + 16) != Ns[0] || get_le64(proof + 24) != K) return ZK_E_REJECT;
         digests = proof + 32;
     } else {
-        if (c.len != tlookup_proof_bytes(D)) return ZK_E_REJECT;
+        if (c.len != tlookup_proof_bytes(Ds[0])) return ZK_E_REJECT;
         if (memcmp(proof, "ZKTL\x02\0\0\0", 8) != 0) return ZK_E_REJECT;
-        if (get_le64(proof + 8) != D || get_le64(proof + 16) != N) return ZK_E_REJECT;
+        if (get_le64(proof + 8) != Ds[0] || get_le64(proof + 16) != Ns[0]) return ZK_E_REJECT;
         digests = proof + 24;
     }
     const uint8_t* ab_digests = digests + 32 * K;  // per instance: digest(A), digest(B)
@@ -1216,8 +1377,22 @@ static int verify_core(const VerifyCall& c) {
     for (int i = 0; i < nel; ++i)
         if (!from_bytes(&el[i], body + 32 * i)) return ZK_E_REJECT;
 
-    uint64_t dims[3] = {D, N, K};
-    Transcript tr(c.batch ? "zkmi/tlookup-batch/v2" : "zkmi/tlookup/v2", c.seed, dims, c.batch ? 3 : 2);
+    uint64_t dims[1 + 2 * kMailboxMaxInstances];
+    int ndims;
+    if (c.multi) {
+        dims[0] = K;
+        for (size_t i = 0; i < K; ++i) {
+            dims[1 + 2 * i] = Ds[i];
+            dims[2 + 2 * i] = Ns[i];
+        }
+        ndims = 1 + 2 * (int)K;
+    } else {
+        dims[0] = Ds[0];
+        dims[1] = Ns[0];
+        dims[2] = K;
+        ndims = c.batch ? 3 : 2;
+    }
+    Transcript tr(c.multi ? "zkmi/tlookup-multi/v1" : c.batch ? "zkmi/tlookup-batch/v2" : "zkmi/tlookup/v2", c.seed, dims, ndims);
     for (size_t i = 0; i < K; ++i) tr.absorb("m", digests + 32 * i, 32);
     F beta = tr.challenge("beta");
     for (size_t i = 0; i < K; ++i) {
@@ -1245,18 +1420,18 @@ static int verify_core(const VerifyCall& c) {
     }
     const F* fin = &el[4 * n];
     tr.absorb("final", body + 128 * n, 160 * K);
-    F scale = one();
-    {
-        F half = inv(from_u64(2));
-        for (int i = 0; i < h; ++i) scale = mul(scale, half);
-    }
-    F e_full = eq_point(u, v, n), e_tab = eq_point(u + h, v + h, l);
+    const F inv2 = inv(from_u64(2));
     F total = zero();
     for (size_t i = 0; i < K; ++i) {
         const F* f = fin + 5 * i;
+        const int skip = skips[i], h = hs[i];
+        F scale = one(), weight = lam[i];  // 2^-h; lambda^i 2^-skip
+        for (int t = 0; t < h; ++t) scale = mul(scale, inv2);
+        for (int t = 0; t < skip; ++t) weight = mul(weight, inv2);
+        const F e_full = eq_point(u + skip, v + skip, ns[i]), e_tab = eq_point(u + skip + h, v + skip + h, ls[i]);
         F lhs = mul(f[0], add(mul(mul(alpha, e_full), add(f[1], beta)), one()));
         F rhs = mul(scale, mul(f[2], sub(mul(mul(alpha2, e_tab), add(f[4], beta)), f[3])));
-        total = add(total, mul(lam[i], add(lhs, rhs)));
+        total = add(total, mul(weight, add(lhs, rhs)));
     }
     if (!equal(total, claim)) return ZK_E_REJECT;
 
@@ -1265,16 +1440,15 @@ static int verify_core(const VerifyCall& c) {
     Mailbox* mb;
     ZK_TRY(mailbox_get(&mb));
     Carver cv(c.ws, c.ws_bytes);
-    uint32_t* Mfr = cv.limbs(N);
-    uint32_t nleaves = (uint32_t)div_up(N, kLeafCounts);
-    uint32_t* leaves = (uint32_t*)cv.take((size_t)nleaves * 32);
-    uint32_t* dig_leaves = (uint32_t*)cv.take(vec_digest_leaves(D) * 32);
-    uint32_t* dig_rows = (uint32_t*)cv.take(vec_digest_row_digests(D) * 32);
+    uint32_t* Mfr = cv.limbs(N_max);
+    uint32_t* leaves = (uint32_t*)cv.take(div_up(N_max, kLeafCounts) * 32);
+    uint32_t* dig_leaves = (uint32_t*)cv.take(vec_digest_leaves(D_max) * 32);
+    uint32_t* dig_rows = (uint32_t*)cv.take(vec_digest_row_digests(D_max) * 32);
     uint32_t* dig_ticket = (uint32_t*)cv.take(256);
     // a witness vector must be the one whose digest the proof carries
-    auto check_digest = [&](const fr_vec& v, size_t count, const uint8_t* want, int* ok) -> int {
+    auto check_digest = [&](const fr_vec& vec, size_t count, const uint8_t* want, int* ok) -> int {
         const uint32_t seq = mb->next_seq();
-        const VecDigestJob job{v.limbs, v.stride, count, dig_rows, mb->words + kMailboxDigest};
+        const VecDigestJob job{vec.limbs, vec.stride, count, dig_rows, mb->words + kMailboxDigest};
         launch_fill_u32(dig_ticket, 1, 0u, stream);
         vec_digest_launch(job, nullptr, dig_leaves, mb->words, seq, dig_ticket, stream);
         ZK_HIP_TRY(hipGetLastError());
@@ -1296,26 +1470,31 @@ static int verify_core(const VerifyCall& c) {
     };
     for (size_t i = 0; i < K; ++i) {
         const F* f = fin + 5 * i;
+        const size_t D = Ds[i], N = Ns[i];
+        const int ni = ns[i], l = ls[i];
+        const F* vd = v + skips[i];          // the instance's point
+        const F* vt = vd + hs[i];            // its table's
+        const uint32_t nleaves = (uint32_t)div_up(N, kLeafCounts);
         int ok = 0;
-        ZK_TRY(check(c.T[i].limbs, c.T[i].stride, l, v + h, f[4], &ok));
+        ZK_TRY(check(c.T[i].limbs, c.T[i].stride, l, vt, f[4], &ok));
         if (!ok) return ZK_E_REJECT;
         if (!c.wit) continue;
         const tlookup_witness* wit = c.wit + i;
         if (wit->S.limbs) {
             if (!vec_ok(wit->S, D)) return ZK_E_BADARG;
-            ZK_TRY(check(wit->S.limbs, wit->S.stride, n, v, f[1], &ok));
+            ZK_TRY(check(wit->S.limbs, wit->S.stride, ni, vd, f[1], &ok));
             if (!ok) return ZK_E_REJECT;
         }
         if (wit->A.limbs) {
             if (!vec_ok(wit->A, D)) return ZK_E_BADARG;
-            ZK_TRY(check(wit->A.limbs, wit->A.stride, n, v, f[0], &ok));
+            ZK_TRY(check(wit->A.limbs, wit->A.stride, ni, vd, f[0], &ok));
             if (!ok) return ZK_E_REJECT;
             ZK_TRY(check_digest(wit->A, D, ab_digests + 64 * i, &ok));
             if (!ok) return ZK_E_REJECT;
         }
         if (wit->B.limbs) {
             if (!vec_ok(wit->B, N)) return ZK_E_BADARG;
-            ZK_TRY(check(wit->B.limbs, wit->B.stride, l, v + h, f[2], &ok));
+            ZK_TRY(check(wit->B.limbs, wit->B.stride, l, vt, f[2], &ok));
             if (!ok) return ZK_E_REJECT;
             ZK_TRY(check_digest(wit->B, N, ab_digests + 64 * i + 32, &ok));
             if (!ok) return ZK_E_REJECT;
@@ -1326,7 +1505,7 @@ static int verify_core(const VerifyCall& c) {
                                (uint32_t)N, nleaves);
             ZK_TRY(mailbox_bulk(mb, (size_t)nleaves * 32));
             ZK_HIP_TRY(hipMemcpyAsync(mb->bulk, leaves, (size_t)nleaves * 32, hipMemcpyDeviceToHost, stream));
-            ZK_TRY(check(Mfr, N, l, v + h, f[3], &ok));
+            ZK_TRY(check(Mfr, N, l, vt, f[3], &ok));
             if (!ok) return ZK_E_REJECT;
             uint8_t md[32];
             digest_of_leaves(md, mb->bulk, nleaves);
@@ -1575,6 +1754,79 @@ int tlookup_verify_batch(const uint8_t seed[32], const uint8_t* proof, size_t le
     c.T = T;
     c.D = D;
     c.batch = true;
+    c.wit = witness;
+    c.bclaims = claims;
+    c.ws = ws;
+    c.ws_bytes = ws_bytes;
+    c.stream = stream;
+    return verify_core(c);
+}
+
+static bool multi_shapes_ok(const size_t* D, const size_t* N, size_t K) {
+    if (!D || !N || K == 0 || K > TLOOKUP_BATCH_MAX) return false;
+    for (size_t i = 0; i < K; ++i)
+        if (!is_pow2(D[i]) || !is_pow2(N[i]) || N[i] > D[i] || D[i] > ((size_t)1 << 31)) return false;
+    return true;
+}
+
+size_t tlookup_multi_proof_bytes(const size_t* D, size_t K) {
+    if (!D || K == 0 || K > TLOOKUP_BATCH_MAX) return 0;
+    int n = 0;
+    for (size_t i = 0; i < K; ++i) {
+        if (!is_pow2(D[i])) return 0;
+        if (log2_floor(D[i]) > n) n = log2_floor(D[i]);
+    }
+    return multi_proof_bytes(n, K);
+}
+
+size_t tlookup_multi_workspace_bytes(const size_t* D, const size_t* N, size_t K) {
+    if (!multi_shapes_ok(D, N, K)) return 0;
+    return prove_ws_bytes_shapes(D, N, K);
+}
+
+int tlookup_prove_multi(const uint8_t seed[32], const fr_vec* S, const uint32_t* const* idx, const fr_vec* T, size_t K,
+                        uint8_t* proof, size_t cap, size_t* len, tlookup_batch_aux* aux, void* ws, size_t ws_bytes,
+                        void* stream) {
+    ProveCall c;
+    c.seed = seed;
+    c.K = K;
+    c.S = S;
+    c.idx = idx;
+    c.T = T;
+    c.batch = true;
+    c.multi = true;
+    c.proof = proof;
+    c.cap = cap;
+    c.len = len;
+    c.baux = aux;
+    c.ws = ws;
+    c.ws_bytes = ws_bytes;
+    c.stream = stream;
+    return prove_core(c);
+}
+
+size_t tlookup_multi_verify_workspace_bytes(const size_t* D, const size_t* N, size_t K) {
+    if (!multi_shapes_ok(D, N, K)) return 0;
+    size_t D_max = 1, N_max = 1;
+    for (size_t i = 0; i < K; ++i) {
+        if (D[i] > D_max) D_max = D[i];
+        if (N[i] > N_max) N_max = N[i];
+    }
+    return verify_ws_bytes(D_max, N_max);
+}
+
+int tlookup_verify_multi(const uint8_t seed[32], const uint8_t* proof, size_t len, const fr_vec* T, const size_t* D,
+                         size_t K, const tlookup_witness* witness, tlookup_batch_claims* claims, void* ws,
+                         size_t ws_bytes, void* stream) {
+    VerifyCall c;
+    c.seed = seed;
+    c.proof = proof;
+    c.len = len;
+    c.K = K;
+    c.T = T;
+    c.Ds = D;
+    c.batch = true;
+    c.multi = true;
     c.wit = witness;
     c.bclaims = claims;
     c.ws = ws;

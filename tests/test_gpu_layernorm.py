@@ -6,9 +6,13 @@ full scale) goes through two lookups one after the other,
 the first keeping the second's table small, as in Example 4.2.  There is one
 value per row, so the tensors are far shorter than the tables: each is padded to
 its table's length with a value the table holds (Section 4 pads D to a multiple
-of N), the two lookups have different shapes and are proved one by one, and the
-downscaling is tied to them by the linear relation between the multilinear
-extensions at the first proof's point.  Each proof must equal the oracle's."""
+of N), and the two lookups have different shapes.  Proved one by one they end
+at two unrelated points, and the downscaling can only be tied to the first
+(the linear relation between the multilinear extensions at that proof's
+point).  Proved under one sumcheck (tlookup_prove_multi) they end at one point,
+the shorter lookup at its last ten coordinates, and the V' of the downscaling
+and the V' of the compound lookup can be checked to be one tensor.  Each proof
+must equal the oracle's."""
 import numpy as np
 import pytest
 import torch
@@ -119,6 +123,45 @@ def test_layernorm_lookups(zk, orc):
     rc, _, claims = prove_both(zk, orc, t, d)
     assert rc == 0
     assert openings_consistent(zk, d, claims) == (True, True, True)
+
+
+def test_layernorm_lookups_under_one_sumcheck(zk, orc):
+    """Both lookups in one proof: their claims are at one point v (12 coordinates) and at its last 10."""
+    t = statistics()
+    d = build(zk, t)
+    gamma = 1 << LOG_GAMMA
+    S, T, idx = [d["R1"], d["S2"]], [d["T1"], d["T2"]], [d["idx1"], d["idx2"]]
+    Ds = [d["D1"], d["D2"]]
+    rc, proof, _ = zk.tlookup_prove_multi(t["seed"], S, idx, T)
+    assert rc == 0
+    rc_o, want, _ = orc.tlookup_multi_prove(t["seed"], [zk.vec_to_bytes(x) for x in S], [zk.vec_to_bytes(x) for x in T])
+    assert rc_o == 0 and proof == want
+    rc, claims = zk.tlookup_verify_multi(t["seed"], proof, T, Ds, S=S)
+    assert rc == 0
+    v = claims["v"]
+    assert len(v) == LOG_B
+    v1 = v[LOG_B - LOG_GAMMA:]                       # the downscaling lookup's point
+    ev = lambda vec, pt: zk.fr_mle_eval(vec, pt)[1]
+    r1, s2 = claims["value"][0][1], claims["value"][1][1]
+    assert r1 == ev(d["R1"], v1) and s2 == ev(d["S2"], v)
+    # the downscaling relation at v1, the pairing at v
+    assert ev(d["V"], v1) == (gamma * ev(d["Vq1"], v1) + r1) % R
+    assert s2 == (ev(d["Vq2"], v) + d["rho"] * ev(d["Y"], v)) % R
+    # ... and, what two separate proofs cannot give: the V' of the two relations is one tensor.  Padded with zeros from
+    # 2^10 to 2^12 entries its extension is (1 - v_0)(1 - v_1) times the shorter one's at the last ten coordinates.
+    assert ev(d["Vq2"], v) == (1 - v[0]) * (1 - v[1]) % R * ev(d["Vq1"], v1) % R
+    # a V' that differs between the two lookups (both still valid lookups) fails exactly that check
+    other = dict(t, Vq=t["Vq"].copy())
+    other["Vq"][9] = (other["Vq"][9] + 1) % (1 << LOG_B)
+    other["Y"] = inv_sqrt_table()[other["Vq"]]
+    d2 = build(zk, other)
+    S = [d["R1"], d2["S2"]]
+    rc, proof, _ = zk.tlookup_prove_multi(t["seed"], S, [d["idx1"], d2["idx2"]], T)
+    assert rc == 0
+    rc, claims = zk.tlookup_verify_multi(t["seed"], proof, T, Ds, S=S)
+    assert rc == 0
+    v = claims["v"]
+    assert ev(d2["Vq2"], v) != (1 - v[0]) * (1 - v[1]) % R * ev(d["Vq1"], v[2:]) % R
 
 
 def test_a_tensor_shorter_than_its_table_is_refused(zk):

@@ -1,0 +1,166 @@
+"""GPU parity: tlookup instances of different shapes under one sumcheck (what a
+layer with two lookups in a row needs so that all claims end at one point; the
+reading is described with tlookup_prove_multi in include/zkmi.h) through the C
+boundary against the CPU oracle.  Integer work throughout: the bar is equality
+of bytes."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from tests.gpu_common import first_difference
+from tests.pyref import R
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def zk():
+    import paper_2404_16109_amd as zk
+    assert torch.cuda.is_available()
+    return zk
+
+
+def _instances(orc, zk, rng, shapes, dup=False):
+    Sb, Tb, Sv, Tv, idx = [], [], [], [], []
+    for D, N in shapes:
+        T, seen = [], set()
+        while len(T) < N:
+            t = rng.randrange(R)
+            if t not in seen:
+                seen.add(t)
+                T.append(t)
+        if dup and N >= 4:
+            T[N - 1] = T[1]
+        rows = np.array([rng.randrange(N) for _ in range(D)]) if D <= 1 << 14 else \
+            np.random.default_rng(rng.randrange(1 << 30)).integers(0, N, size=D)
+        tb = orc.to_bytes(T)
+        sb = tb[rows]
+        Tb.append(tb)
+        Sb.append(sb)
+        Sv.append(zk.vec_from_bytes(sb))
+        Tv.append(zk.vec_from_bytes(tb))
+        idx.append(torch.from_numpy(rows.astype(np.int32)).cuda())
+    return Sb, Tb, Sv, Tv, idx
+
+
+SHAPES = [
+    [(1, 1), (1, 1)],                                   # no round at all
+    [(2, 1), (1, 1)],
+    [(8, 2), (4, 4)],
+    [(4, 4), (8, 2)],                                   # the longer one second
+    [(16, 4), (2, 1), (8, 8)],
+    [(1 << 10, 1 << 4), (1 << 8, 1 << 8)],
+    [(1 << 10, 1 << 10), (1 << 12, 1 << 12)],           # the shapes of LayerNorm's two lookups
+    [(1 << 12, 1 << 4), (1 << 14, 1 << 6), (1 << 9, 1 << 9)],
+    [(1 << 13, 1 << 5), (1 << 13, 1 << 9)],             # equal lengths, different tables
+    [(1 << 14, 1 << 10), (1 << 18, 1 << 6)],            # the long one runs rounds on 29-bit limbs while the short one waits
+    [(1 << 17, 1 << 7), (1 << 16, 1 << 5), (1 << 17, 1 << 12)],  # 29-bit rounds of instances that start at different rounds
+]
+
+
+@pytest.mark.parametrize("shapes", SHAPES, ids=lambda sh: "+".join("%dx%d" % s for s in sh))
+def test_multi_proof_bytes_equal_oracle(zk, orc, shapes):
+    rng = random.Random(8100 + sum(D * 7 + N for D, N in shapes))
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, shapes, dup=len(shapes) == 3)
+    K = len(shapes)
+    Ds = [D for D, _ in shapes]
+    seed = rng.randbytes(32)
+    rc_o, want, info_o = orc.tlookup_multi_prove(seed, Sb, Tb)
+    rc_g, got, info_g = zk.tlookup_prove_multi(seed, Sv, idx, Tv)      # rows given
+    assert rc_o == 0 and rc_g == 0
+    assert len(got) == zk.tlookup_multi_proof_bytes(Ds) == info_g["len"]
+    assert first_difference(got, want) == -1
+    for key in ("beta", "alpha", "lambda"):
+        assert [info_g[key]] == orc.to_ints(info_o[key])
+    assert info_g["sum_A"] == orc.to_ints(info_o["sum_A"]) and info_g["sum_mB"] == orc.to_ints(info_o["sum_mB"])
+    assert info_g["sum_A"] == info_g["sum_mB"]
+    rc, again, _ = zk.tlookup_prove_multi(seed, Sv, None, Tv)           # rows found by the library
+    assert rc == 0 and again == got
+    for i in range(K):  # inputs are not modified
+        assert np.array_equal(zk.vec_to_bytes(Sv[i]), Sb[i]) and np.array_equal(zk.vec_to_bytes(Tv[i]), Tb[i])
+    # both verifiers accept, and agree on the point and the claims
+    rc, claims = zk.tlookup_verify_multi(seed, got, Tv, Ds, S=Sv)
+    assert rc == 0
+    assert orc.tlookup_multi_verify(seed, got, Tb, Ds, S_list=Sb) == 0
+    assert claims["v"] == orc.to_ints(info_o["v"])
+    n = max(D.bit_length() - 1 for D in Ds)
+    body = got[16 + 16 * K + 96 * K + 128 * n:]
+    for i in range(K):
+        for q in range(5):
+            off = 32 * (5 * i + q)
+            assert claims["value"][i][q] == int.from_bytes(body[off:off + 32], "little")
+    # every instance's S claim is its tensor's multilinear extension at ITS suffix of the one point
+    for i in range(K):
+        ni = Ds[i].bit_length() - 1
+        rc, val = zk.fr_mle_eval(Sv[i], claims["v"][n - ni:])
+        assert rc == 0 and val == claims["value"][i][1]
+
+
+def test_multi_with_witnesses_and_corruption(zk, orc):
+    rng = random.Random(31)
+    shapes = [(1 << 11, 1 << 5), (1 << 9, 1 << 7)]
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, shapes)
+    Ds = [D for D, _ in shapes]
+    seed = rng.randbytes(32)
+    rc, proof, info = zk.tlookup_prove_multi(seed, Sv, idx, Tv)
+    assert rc == 0
+    ms = []
+    for i in range(2):
+        rc, m, _ = zk.tlookup_multiplicities(Sv[i], idx[i], Tv[i])
+        assert rc == 0
+        ms.append(m)
+    assert zk.tlookup_verify_multi(seed, proof, Tv, Ds, S=Sv, m=ms)[0] == 0
+    counts = [m.cpu().numpy().astype(np.uint64) for m in ms]
+    assert orc.tlookup_multi_verify(seed, proof, Tb, Ds, S_list=Sb, m_list=counts) == 0
+    # the inverse vectors as witnesses: A_i = 1 / (beta + S_i), recomputed here from the oracle's field arithmetic
+    beta = info["beta"]
+    A = [zk.vec_from_bytes(orc.to_bytes([pow((beta + int.from_bytes(row.tobytes(), "little")) % R, -1, R) for row in sb]))
+         for sb in Sb]
+    assert zk.tlookup_verify_multi(seed, proof, Tv, Ds, A=A)[0] == 0
+    assert zk.tlookup_verify_multi(seed, proof, Tv, Ds, A=A[::-1] if Ds[0] == Ds[1] else [A[0], None])[0] == 0
+    wrong = orc.to_bytes([1] * Ds[1])
+    assert zk.tlookup_verify_multi(seed, proof, Tv, Ds, A=[None, zk.vec_from_bytes(wrong)])[0] == zk.ZK_E_REJECT
+    # another order of the instances, other shapes, a flipped bit anywhere
+    assert zk.tlookup_verify_multi(seed, proof, Tv[::-1], Ds[::-1])[0] == zk.ZK_E_REJECT
+    for pos in rng.sample(range(len(proof)), 40):
+        bad = bytearray(proof)
+        bad[pos] ^= 1 << rng.randrange(8)
+        assert zk.tlookup_verify_multi(seed, bytes(bad), Tv, Ds)[0] == zk.ZK_E_REJECT, pos
+
+
+def test_multi_not_in_table_names_the_instance(zk, orc):
+    rng = random.Random(13)
+    shapes = [(1 << 12, 1 << 5), (1 << 9, 1 << 5), (1 << 10, 1 << 3)]
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, shapes)
+    bad_value = next(x for x in range(1, 1 << 20) if orc.to_bytes([x])[0].tobytes() not in
+                     {row.tobytes() for row in Tb[1]})
+    sb = Sb[1].copy()
+    sb[77] = orc.to_bytes([bad_value])[0]
+    sb[300] = orc.to_bytes([bad_value])[0]
+    Sb[1] = sb
+    Sv[1] = zk.vec_from_bytes(sb)
+    seed = rng.randbytes(32)
+    rc_o, _, info_o = orc.tlookup_multi_prove(seed, Sb, Tb)
+    rc_g, proof, info_g = zk.tlookup_prove_multi(seed, Sv, None, Tv)
+    assert rc_o == -2 and rc_g == zk.ZK_E_NOT_IN_TABLE and proof == b""
+    assert (info_g["bad_instance"], info_g["bad_index"]) == (info_o["bad_instance"], info_o["bad_index"]) == (1, 77)
+    # with (now wrong) hints the short instance is only caught in its own first round, two rounds into the proof
+    rc_g, proof, info_g = zk.tlookup_prove_multi(seed, Sv, idx, Tv)
+    assert rc_g == zk.ZK_E_NOT_IN_TABLE and proof == b"" and (info_g["bad_instance"], info_g["bad_index"]) == (1, 77)
+
+
+def test_multi_bad_arguments(zk, orc):
+    rng = random.Random(17)
+    Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, [(1 << 8, 1 << 4), (1 << 6, 1 << 6)])
+    seed = rng.randbytes(32)
+    assert zk.tlookup_multi_proof_bytes([1 << 8, 1 << 6]) == 16 + 32 + 192 + 8 * 128 + 320
+    assert zk.tlookup_multi_workspace_bytes([1 << 8, 3], [1 << 4, 1]) == 0
+    assert zk.tlookup_multi_workspace_bytes([1 << 4], [1 << 8]) == 0
+    rc, proof, info = zk.tlookup_prove_multi(seed, Sv, idx, Tv, cap=100)
+    assert rc == zk.ZK_E_BUFSZ and info["len"] == zk.tlookup_multi_proof_bytes([1 << 8, 1 << 6])
+    small_ws = torch.empty(1024, dtype=torch.uint8, device="cuda")
+    assert zk.tlookup_prove_multi(seed, Sv, idx, Tv, ws=small_ws)[0] == zk.ZK_E_BUFSZ
+    # the batched entry point of one shape still refuses unequal shapes
+    assert zk.tlookup_prove_batch(seed, Sv, idx, Tv)[0] == zk.ZK_E_BADARG
