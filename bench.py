@@ -34,15 +34,34 @@ def fr_mul_model(D, N):
     return 10 * D + 10 * N
 
 
-def rounds_on_29_bits(D, N):
-    """The rounds the dominant kernel (k_round_data29) runs: after the first, before
-    the table's variables, while more than 256 pairs remain."""
+def first_two_rounds_share_a_pass(D, N):
+    """From a vector of field elements the first pass over A and S yields the sums of the first two rounds and folds
+    nothing; the first launch of k_round_data29 is then round 2, which binds two variables at once."""
     n, h = D.bit_length() - 1, (D // N).bit_length() - 1
-    return [k for k in range(1, h) if (D >> (k + 1)) > 256]
+    return h >= 3 and (D >> 3) > 256
 
 
-def round29_pairs(D, N):
-    return sum(D >> (k + 1) for k in rounds_on_29_bits(D, N))
+def rounds_on_29_bits(D, N, from_ints=False):
+    """The rounds the dominant kernel (k_round_data29) runs: after the first (after the first two, when those share
+    a pass), before the table's variables, while more than 256 pairs remain."""
+    n, h = D.bit_length() - 1, (D // N).bit_length() - 1
+    first = 2 if not from_ints and first_two_rounds_share_a_pass(D, N) else 1
+    return [k for k in range(first, h) if (D >> (k + 1)) > 256]
+
+
+def round29_work(D, N):
+    """(pairs, algorithmic field multiplications, algorithmic bytes) of all launches of k_round_data29 in one prove.
+    Per pair a round folds four entries of A and four of S into two of each (4 multiplications, 12 entries of 32 B
+    moved), weights two entries and forms three products: 9 multiplications.  The round that binds two variables at
+    once folds sixteen entries into four (12 multiplications, 20 entries moved): 17."""
+    pairs = muls = moved = 0
+    for k in rounds_on_29_bits(D, N):
+        p = D >> (k + 1)
+        two = k == 2 and first_two_rounds_share_a_pass(D, N)
+        pairs += p
+        muls += p * ((12 if two else ROUND_DATA_FR_MUL_PER_PAIR_FOLD) + ROUND_DATA_FR_MUL_PER_PAIR_EVAL)
+        moved += p * (20 if two else 12) * 32
+    return pairs, muls, moved
 
 
 def measured_traffic():
@@ -485,9 +504,9 @@ def main():
     rd = phases["round_data29"]
     launches = rd["records"] / psteps
     avg_launch_s = rd["ms_per_step"] * 1e-3 / max(launches, 1)
-    pairs29 = round29_pairs(D, N)
-    mads_per_launch = pairs29 * (ROUND_DATA_FR_MUL_PER_PAIR_EVAL + ROUND_DATA_FR_MUL_PER_PAIR_FOLD) * MADS_PER_FR_MUL / max(launches, 1)
-    bytes_per_launch = pairs29 * 12 * 32 / max(launches, 1)  # per pair: four entries of A and of S read, two of each written
+    pairs29, muls29, moved29 = round29_work(D, N)
+    mads_per_launch = muls29 * MADS_PER_FR_MUL / max(launches, 1)
+    bytes_per_launch = moved29 / max(launches, 1)
     alu = mads_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
     hbm = bytes_per_launch / avg_launch_s if avg_launch_s > 0 else 0.0
     traffic = measured_traffic()

@@ -245,6 +245,70 @@ ZK_HD F29 f29_mul_add(const F29& a, const F29& b, const F29& c) {
     return t;
 }
 
+// Three products under one reduction: (a0 b0 + a1 b1 + a2 b2) / 2^261 + c mod r,
+// normalized, value below (a0 b0 + a1 b1 + a2 b2) / 2^261 + r + c.  All seven operands
+// normalized (limbs below 2^29): a column then holds at most 27 + 9 products of
+// 2^58 each, below 2^64.  Costs 243 + 81 multiply-adds where three separate
+// products cost 486.
+template <int C>
+ZK_HD void f29_column3_low(uint64_t& acc, const uint32_t* a0, const uint32_t* b0, const uint32_t* a1, const uint32_t* b1,
+                           const uint32_t* a2, const uint32_t* b2, uint32_t* m) {
+    constexpr uint32_t r[9] = ZK_R29_LIMBS;
+#pragma unroll
+    for (int j = 0; j <= C; ++j) acc += (uint64_t)a0[j] * b0[C - j];
+#pragma unroll
+    for (int j = 0; j <= C; ++j) acc += (uint64_t)a1[j] * b1[C - j];
+#pragma unroll
+    for (int j = 0; j <= C; ++j) acc += (uint64_t)a2[j] * b2[C - j];
+#pragma unroll
+    for (int i = 0; i < C; ++i) acc += (uint64_t)m[i] * r[C - i];
+    m[C] = (0u - (uint32_t)acc) & kM29;
+    acc = f29_acc_add(acc, m[C]);
+    acc >>= 29;
+}
+
+template <int C>
+ZK_HD void f29_column3_high_add(uint64_t& acc, const uint32_t* a0, const uint32_t* b0, const uint32_t* a1, const uint32_t* b1,
+                                const uint32_t* a2, const uint32_t* b2, const uint32_t* m, const uint32_t* c, uint32_t* t) {
+    constexpr uint32_t r[9] = ZK_R29_LIMBS;
+#pragma unroll
+    for (int j = C - 8; j <= 8; ++j) acc += (uint64_t)a0[j] * b0[C - j];
+#pragma unroll
+    for (int j = C - 8; j <= 8; ++j) acc += (uint64_t)a1[j] * b1[C - j];
+#pragma unroll
+    for (int j = C - 8; j <= 8; ++j) acc += (uint64_t)a2[j] * b2[C - j];
+#pragma unroll
+    for (int i = C - 8; i <= 8; ++i) acc += (uint64_t)m[i] * r[C - i];
+    acc = f29_acc_add(acc, c[C - 9]);
+    t[C - 9] = (uint32_t)acc & kM29;
+    acc >>= 29;
+}
+
+ZK_HD F29 f29_mul3_add(const F29& a0, const F29& b0, const F29& a1, const F29& b1, const F29& a2, const F29& b2, const F29& c) {
+    uint32_t m[9];
+    F29 t;
+    uint64_t acc = 0;
+    f29_column3_low<0>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<1>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<2>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<3>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<4>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<5>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<6>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<7>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_low<8>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m);
+    f29_column3_high_add<9>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<10>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<11>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<12>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<13>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<14>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<15>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    f29_column3_high_add<16>(acc, a0.l, b0.l, a1.l, b1.l, a2.l, b2.l, m, c.l, t.l);
+    t.l[8] = (uint32_t)acc + c.l[8];
+    return t;
+}
+
 // ---- sums of products, unreduced --------------------------------------------------
 
 ZK_HD F29Wide f29_wide_zero() {

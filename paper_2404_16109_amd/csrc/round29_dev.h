@@ -42,6 +42,24 @@ ZK_HD void round29_begin(Round29Sums& t) {
 // y0 + r (y2 - y0), normalized, below y0 + 1.8 r.  r: the challenge times 2^261.
 ZK_HD F29 round29_fold(const F29& y0, const F29& y2, const F29& r) { return f29_mul_add(f29_sub(y2, y0), r, y0); }
 
+// Two variables bound at once, for entries that nothing has folded yet (fully
+// reduced): with y_c the four entries of a quad, c = 2 x_0 + x_1,
+//   y_00 + r0 (y_10 - y_00) + r1 (y_01 - y_00) + r0 r1 (y_11 - y_01 - y_10 + y_00),
+// which is what binding x_0 with r0 and then x_1 with r1 gives; the three products
+// share one reduction.  r0, r1, r01 = r0 r1: times 2^261, normalized, below r.
+// Normalized, below y_00 + 124 r r / 2^261 + r < y_00 + 2.8 r, so below 3.8 r: within
+// what two single folds may reach (5 r).
+struct Round29Fold2 {
+    F29 r0, r1, r01;
+};
+
+ZK_HD F29 round29_fold2(const F29& y00, const F29& y01, const F29& y10, const F29& y11, const Round29Fold2& r) {
+    const F29 dx = f29_normalize(f29_sub(y10, y00));                                           // below 41 r
+    const F29 dy = f29_normalize(f29_sub(y01, y00));
+    const F29 dxy = f29_normalize(f29_sub(f29_add(y11, y00), f29_normalize(f29_add(y01, y10))));  // below 42 r
+    return f29_mul3_add(dx, r.r0, dy, r.r1, dxy, r.r01, y00);
+}
+
 // w: the weight in the form that makes w a0 come out in the vectors' form.
 ZK_HD void round29_pair(Round29Sums& t, const F29& a0, const F29& a1, const F29& s0, const F29& s1, const F29& w,
                         const F29& beta) {

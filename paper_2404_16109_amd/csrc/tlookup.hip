@@ -449,6 +449,7 @@ struct Instance {
     host::F scale;                   // 2^-h
     int lazy_rounds = 0;             // how many of its rounds in a row have left the data arrays in 29-bit planes
     host::F inv_den;                 // what the one-sided round's other side is divided by (this round)
+    host::F pass01[9];               // kRoundFirstTwo's sums: c20, c21, qd, T, qe, then the sums of A_00, A_01, A_10, A_11
     const uint32_t* idx = nullptr;
     uint32_t* b_cur = nullptr;  // where B lives at the moment (it ping-pongs while folding)
     size_t b_cur_stride = 0;
@@ -501,7 +502,9 @@ enum RoundKernel {
     kRound29 = 1,        // k_round_data29: large folding rounds on 29-bit limbs
     kRoundBoth = 2,      // k_round_both: data and table side, the table's variables being bound
     kRoundOneGroup = 3,  // k_round_small: at most 256 pairs, one workgroup, one round per launch (batched proofs)
-    kRoundResident = 4   // k_tlookup_tail: at most 256 pairs, all remaining rounds in one resident kernel
+    kRoundResident = 4,  // k_tlookup_tail: at most 256 pairs, all remaining rounds in one resident kernel
+    kRoundFirstTwo = 5,  // k_round_data01: the first pass, which yields the sums of the first two rounds
+    kRoundNoPass = 6     // the second round after kRoundFirstTwo: the host has everything, nothing is launched
 };
 enum SSource {
     kSFromCaller = 0,  // the caller's vector of field elements
@@ -518,11 +521,19 @@ struct RoundPlan {
     bool tiny;         // at most kSmallPairs pairs
     bool use29;
     bool in32, out32;  // kRound29: the data arrays arrive as / leave as 32-bit words
-    int lazy_after;    // rounds in a row that have left the arrays in 29-bit planes, this one included
+    bool fold2;        // kRound29: binds the two previous variables at once (after kRoundFirstTwo, kRoundNoPass)
+    int lazy_after;    // folds since the data arrays were last fully reduced, if they are in 29-bit planes now
 };
 
 static bool round_on_29_bits(int n, int h, int k) {
     return k >= 1 && k < h && ((size_t)1 << (n - k - 1)) > kSmallPairs;
+}
+
+// Whether the first pass over the data serves the first two rounds (round01_dev.h)
+// and the third round's kernel binds two variables at once: the three rounds must
+// all bind data variables only, and the third must be one of the 29-bit kernel's.
+static bool first_two_rounds_share_a_pass(int n, int h, bool from_ints) {
+    return !from_ints && h >= 3 && round_on_29_bits(n, h, 2);
 }
 
 // n = log2 D, h = log2(D/N); lazy_rounds: lazy_after of the round before;
@@ -536,6 +547,18 @@ static RoundPlan plan_round(int n, int h, int k, size_t K, bool from_ints, int l
     pl.in32 = lazy_rounds == 0;
     pl.out32 = pl.use29 && (!round_on_29_bits(n, h, k + 1) || lazy_rounds + 1 == kMaxLazyRounds);
     pl.lazy_after = pl.use29 && !pl.out32 ? lazy_rounds + 1 : 0;
+    pl.fold2 = false;
+    if (first_two_rounds_share_a_pass(n, h, from_ints) && k <= 2) {
+        // rounds 0 and 1 from one pass that folds nothing, round 2 binds both their variables
+        pl.kernel = k == 0 ? kRoundFirstTwo : k == 1 ? kRoundNoPass : kRound29;
+        pl.use29 = k == 2;
+        pl.in32 = true;
+        pl.out32 = k == 2 && !round_on_29_bits(n, h, 3);
+        pl.fold2 = k == 2;
+        pl.lazy_after = k == 2 && !pl.out32 ? 2 : 0;
+        pl.s_source = kSFromCaller;
+        return pl;
+    }
     if (resident_running || (pl.tiny && K == 1 && n - k <= kTailRoundsMax)) pl.kernel = kRoundResident;
     else if (pl.tiny) pl.kernel = kRoundOneGroup;
     else if (pl.table_round && k > 0) pl.kernel = kRoundBoth;
@@ -884,7 +907,7 @@ static int prove_core(const ProveCall& c) {
     // -- rounds -----------------------------------------------------------------------------------------
     // Below, k counts the rounds of the whole proof and kk = k - skip those of one
     // instance ("local"): an instance's kernels, plan and arrays only ever see kk.
-    F r_prev = zero();
+    F r_prev = zero(), r_prev2 = zero();  // the challenges of the last round and of the one before it
     // Rounds that fold the data arrays only and are large run on 29-bit limbs
     // (tlookup_round29.h).  Between two of them the arrays stay in 29-bit planes,
     // unreduced, for at most kMaxLazyRounds rounds in a row.
@@ -896,12 +919,12 @@ static int prove_core(const ProveCall& c) {
     struct Moving {
         PairArray S, B, T;
     };
-    auto moving_arrays = [&](int kk, const Instance& I, uint32_t*& b_cur, size_t& b_stride) {
+    auto moving_arrays = [&](int kk, const Instance& I, uint32_t*& b_cur, size_t& b_stride, bool s_unfolded) {
         const ProveWs& w = I.w;
         const size_t D = I.D, N = I.N;
         const int h = I.h;
         Moving m;
-        if (kk <= 1) m.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
+        if (s_unfolded) m.S = PairArray{I.S.limbs, I.S.stride, w.Sf, D / 2};
         else m.S = PairArray{w.Sf, D / 2, w.Sf, D / 2};
         if (kk > h) {
             uint32_t* other = b_cur == w.B ? w.Bf : w.B;
@@ -949,17 +972,18 @@ static int prove_core(const ProveCall& c) {
         bool side1 = (k & 1) != 0;
         if (is_zero(e_side[0])) side1 = false;  // u_k = 1: only g(1) can tell q1, so sum the X = 0 side
         if (is_zero(e_side[1])) side1 = true;
-        // the last instance that has kernels in this round publishes it (the longest instance always has)
-        size_t last_active = 0;
-        for (size_t i = 0; i < K; ++i)
-            if (k >= inst[i].skip) last_active = i;
+        // the last instance that has kernels in this round publishes it; a round in which no instance has any (every
+        // active one is in the second round of a pass that served two) is answered by the host alone
         RoundPlan plans[kMailboxMaxInstances] = {};
+        size_t last_launch = K;
         for (size_t i = 0; i < K; ++i) {
             const Instance& I = inst[i];
             if (k < I.skip) continue;
             plans[i] = plan_round(I.n, I.h, k - I.skip, K, from_ints, I.lazy_rounds, tail_first >= 0);
             if (plans[i].s_source == kSNowhere) return ZK_E_BADARG;  // cannot happen: small_source_shape_ok has walked these rounds
+            if (plans[i].kernel != kRoundNoPass) last_launch = i;
         }
+        const bool any_launch = last_launch < K || tail_first >= 0;
 
         if (K == 1 && plans[0].kernel == kRoundResident && tail_first < 0) {
             // this and every later round in one launch (K = 1, so k is the instance's own count)
@@ -976,7 +1000,7 @@ static int prove_core(const ProveCall& c) {
             size_t b_at_stride = I.b_cur_stride;
             for (int j = k; j < n; ++j) {
                 TailRound& rd = tail.round[j - k];
-                Moving m = moving_arrays(j, I, b_at, b_at_stride);
+                Moving m = moving_arrays(j, I, b_at, b_at_stride, j <= 1);
                 rd.S = m.S;
                 rd.B = m.B;
                 rd.T = m.T;
@@ -1000,10 +1024,10 @@ static int prove_core(const ProveCall& c) {
             tail_guard.armed = true;
             tail_first = k;
         }
-        const uint32_t seq = tail_first >= 0 ? tail.out_seq[k - tail_first] : mb->next_seq();
+        const uint32_t seq = tail_first >= 0 ? tail.out_seq[k - tail_first] : any_launch ? mb->next_seq() : 0;
         for (size_t i = 0; i < K && tail_first < 0; ++i) {
             Instance& I = inst[i];
-            if (k < I.skip) continue;
+            if (k < I.skip || plans[i].kernel == kRoundNoPass) continue;
             ProveWs& w = I.w;
             const size_t D = I.D, N = I.N;
             const int h = I.h, kk = k - I.skip;
@@ -1024,8 +1048,8 @@ static int prove_core(const ProveCall& c) {
             if (span > half) span = half;
             const unsigned blocks = (unsigned)(half / span);
             if (blocks > w.part_blocks) return ZK_E_BUFSZ;  // cannot happen: see round_blocks_max
-            const uint32_t my_seq = i == last_active ? seq : 0;  // the last instance's last launch publishes the round
-            const Moving mv = moving_arrays(kk, I, I.b_cur, I.b_cur_stride);
+            const uint32_t my_seq = i == last_launch ? seq : 0;  // the last instance's last launch publishes the round
+            const Moving mv = moving_arrays(kk, I, I.b_cur, I.b_cur_stride, kk <= 1 || plan.fold2);
             DataRoundArgs d;
             d.A = PairArray{w.A, D, w.A, D};
             d.S = mv.S;
@@ -1054,7 +1078,41 @@ static int prove_core(const ProveCall& c) {
             t.partials = w.partT;
             t.pstride = w.part_blocks * 6;
 
-            if (plan.kernel == kRoundOneGroup) {
+            if (plan.kernel == kRoundFirstTwo) {
+                // one pass for this round and the next: nothing is folded, the weights are the next round's
+                const size_t quarter = half / 2;
+                const EqSplit eq1 = ep.round(kk + 1);
+                size_t span01 = quarter / 512;
+                if (span01 < (size_t)kBlock) span01 = (size_t)kBlock;
+                if (span01 > (size_t)kBlock * kRound01MaxQuads) span01 = (size_t)kBlock * kRound01MaxQuads;
+                if (span01 > quarter) span01 = quarter;
+                const unsigned blocks01 = (unsigned)(quarter / span01);
+                if (blocks01 > w.part_blocks || span01 > ((size_t)1 << eq1.lbits) || !I.S.limbs) return ZK_E_BADARG;  // cannot happen
+                DataRound01Args d01;
+                d01.A = w.A;
+                d01.as = D;
+                d01.S = I.S.limbs;
+                d01.ss = I.S.stride;
+                d01.quarter = quarter;
+                d01.block_span = span01;
+                d01.weights = Planes29{ep.pool29, ep.count29};
+                d01.lo_off = ep.suffix29_off[eq1.lbits];
+                d01.lbits = eq1.lbits;
+                d01.has_hi = eq1.has_hi;
+                d01.hi_pool = ep.pool;
+                d01.hi_stride = ep.stride;
+                d01.hi_off = eq1.hi_off;
+                d01.partD = w.partD;
+                d01.pstrideD = w.part_blocks * 5;
+                d01.partT = w.partT;
+                d01.pstrideT = w.part_blocks * 6;
+                {
+                    ProfileScope prof(kProfRoundData, stream);
+                    hipLaunchKernelGGL(k_round_data01, dim3(blocks01), dim3(kBlock), 0, stream, d01);
+                }
+                launch_final_sum2(w.partD, d01.pstrideD, 5, w.partT, d01.pstrideT, 6, blocks01, I.words, mb->words, my_seq,
+                                  w.flags + 1, stream);
+            } else if (plan.kernel == kRoundOneGroup) {
                 // one workgroup, one launch, sums straight to the host
                 ProfileScope prof(kProfRoundSmall, stream);
                 if (!table_round)
@@ -1084,6 +1142,8 @@ static int prove_core(const ProveCall& c) {
                 d29.off0 = side1 ? half : 0;
                 d29.off1 = side1 ? 0 : half;
                 d29.r_prev = f29_unpack(to_dev(mul(r_prev, from_u64(32))).l);
+                d29.r_first = f29_unpack(to_dev(mul(r_prev2, from_u64(32))).l);
+                d29.r_both = f29_unpack(to_dev(mul(mul(r_prev2, r_prev), from_u64(32))).l);
                 d29.beta = beta29;
                 d29.weights = Planes29{ep.pool29, ep.count29};
                 d29.lo_off = ep.suffix29_off[eq.lbits];
@@ -1116,7 +1176,10 @@ static int prove_core(const ProveCall& c) {
                 }
                 {
                     ProfileScope prof(kProfRound29, stream);
-                    if (ints_round && out32) hipLaunchKernelGGL((k_round_data29<true, true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    if (plan.fold2 && (ints_round || !in32)) return ZK_E_BADARG;  // cannot happen: see plan_round
+                    if (plan.fold2 && out32) hipLaunchKernelGGL((k_round_data29<true, true, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else if (plan.fold2) hipLaunchKernelGGL((k_round_data29<true, false, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    else if (ints_round && out32) hipLaunchKernelGGL((k_round_data29<true, true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (ints_round) hipLaunchKernelGGL((k_round_data29<true, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
                     else if (in32) hipLaunchKernelGGL((k_round_data29<true, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
@@ -1157,8 +1220,8 @@ static int prove_core(const ProveCall& c) {
                 }
             if (!shared) I.inv_den = inv(mul(wD, e_side[side1 ? 0 : 1]));
         }
-        ZK_TRY(mailbox_wait(mb, seq, stream));
-        read_table_consts();
+        if (any_launch) ZK_TRY(mailbox_wait(mb, seq, stream));
+        if (k > 0 || any_launch) read_table_consts();
 
         F e[4], g[4];
         line_values(e, e_side[0], e_side[1]);
@@ -1180,9 +1243,33 @@ static int prove_core(const ProveCall& c) {
             const F wT = table_round ? mul(alpha2, I.cT) : zero();
             I.half_pow = mul(I.half_pow, inv2);
             const uint32_t* sums = I.words;
-            F q0 = from_dev(sums), q1 = from_dev(sums + 8), qi = from_dev(sums + 16);
-            if (kk == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
-            F sA0 = from_dev(sums + 24), sA1 = from_dev(sums + 32);
+            F q0, q1, qi, sA0, sA1;
+            if (plan.kernel == kRoundFirstTwo) {
+                // the pass has summed, with the NEXT round's weights, what this round and the next are made of
+                // (round01_dev.h): this round's leading coefficient splits by the next variable
+                for (int q = 0; q < 9; ++q) I.pass01[q] = from_dev(sums + 8 * q);
+                q0 = q1 = one();
+                qi = add(mul(sub(one(), u[k + 1]), I.pass01[0]), mul(u[k + 1], I.pass01[1]));
+                sA0 = add(I.pass01[5], I.pass01[6]);
+                sA1 = add(I.pass01[7], I.pass01[8]);
+            } else if (plan.kernel == kRoundNoPass) {
+                // every sum of this round is a polynomial of degree two in the challenge r before it
+                const F& r = r_prev;
+                const F t = mul(r, sub(one(), r));
+                const F* P = I.pass01;
+                q0 = sub(one(), mul(t, P[0]));
+                q1 = sub(one(), mul(t, P[1]));
+                qi = add(P[2], mul(r, add(sub(sub(P[3], P[2]), P[4]), mul(r, P[4]))));  // qd + r (T - qd - qe) + r^2 qe
+                sA0 = add(P[5], mul(r, sub(P[7], P[5])));
+                sA1 = add(P[6], mul(r, sub(P[8], P[6])));
+            } else {
+                q0 = from_dev(sums);
+                q1 = from_dev(sums + 8);
+                qi = from_dev(sums + 16);
+                if (kk == 0) q0 = q1 = one();  // A (S + beta) = 1 everywhere and the weights sum to 1
+                sA0 = from_dev(sums + 24);
+                sA1 = from_dev(sums + 32);
+            }
             const F table_const = mul(I.cB, I.half_pow);
             if (plan.kernel == kRound29 && tail_first < 0) {
                 // the kernel has summed one side: (q0, sA0) hold that side's q and sum of A; the other side from
@@ -1241,6 +1328,7 @@ static int prove_core(const ProveCall& c) {
             I.cD = mul(I.cD, er);
             if (plans[i].table_round) I.cT = mul(I.cT, er);
         }
+        r_prev2 = r_prev;
         r_prev = r;
         if (tail_first >= 0) mailbox_send_challenge(mb, tail.cmd_seq[k - tail_first], to_dev(r).l);
     }

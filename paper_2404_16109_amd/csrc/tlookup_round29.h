@@ -14,6 +14,7 @@
 // why at most kMaxLazyRounds rounds run back to back before one of them writes
 // fully reduced 32-bit words again.
 #pragma once
+#include "round01_dev.h"
 #include "round29_dev.h"
 #include "small_dev.h"
 #include "tlookup_kernels.h"
@@ -60,6 +61,8 @@ struct DataRound29Args {
     // sA0) and p + off1; (off0, off1) = (0, half) sums the X = 0 side of the round, (half, 0) the X = 1 side.
     size_t off0, off1;
     F29 r_prev;  // the challenge times 2^261
+    F29 r_first; // FOLD2: the challenge before it (the first round's), and the product of the two, times 2^261
+    F29 r_both;
     F29 beta;    // times 2^256, like the vectors
     Planes29 weights;  // the pool of low weight tables, entries times 2^266 (a weighted entry then has the vectors' form)
     uint32_t lo_off;   // this round's table in it
@@ -103,14 +106,26 @@ __device__ __forceinline__ void array29_store(const Array29& a, size_t i, const 
 
 // Binds the previous variable for the two entries p0 and p1 of a pair: x = y + r (y' - y)
 // with y at the entry's index and y' at that plus 2*half, written back (to the
-// entry's index) and returned.
-template <bool IN32, bool OUT32>
-__device__ __forceinline__ void fold_pair29(const Array29& a, size_t p0, size_t p1, size_t half, const F29& r, F29& x0,
-                                            F29& x1) {
-    x0 = round29_fold(array29_load<IN32>(a, p0), array29_load<IN32>(a, p0 + 2 * half), r);
-    array29_store<OUT32>(a, p0, x0);
-    x1 = round29_fold(array29_load<IN32>(a, p1), array29_load<IN32>(a, p1 + 2 * half), r);
-    array29_store<OUT32>(a, p1, x1);
+// entry's index) and returned.  FOLD2 binds the two previous variables at once
+// (the first pass has served two rounds and folded nothing): the entry at i comes
+// from the four at i + c Q, c = 2 x_0 + x_1, Q = 2*half (round29_fold2).
+template <bool IN32, bool OUT32, bool FOLD2>
+__device__ __forceinline__ void fold_pair29(const Array29& a, size_t p0, size_t p1, size_t half, const F29& r,
+                                            const Round29Fold2& r2, F29& x0, F29& x1) {
+    if constexpr (FOLD2) {
+        const size_t Q = 2 * half;
+        x0 = round29_fold2(array29_load<IN32>(a, p0), array29_load<IN32>(a, p0 + Q), array29_load<IN32>(a, p0 + 2 * Q),
+                           array29_load<IN32>(a, p0 + 3 * Q), r2);
+        array29_store<OUT32>(a, p0, x0);
+        x1 = round29_fold2(array29_load<IN32>(a, p1), array29_load<IN32>(a, p1 + Q), array29_load<IN32>(a, p1 + 2 * Q),
+                           array29_load<IN32>(a, p1 + 3 * Q), r2);
+        array29_store<OUT32>(a, p1, x1);
+    } else {
+        x0 = round29_fold(array29_load<IN32>(a, p0), array29_load<IN32>(a, p0 + 2 * half), r);
+        array29_store<OUT32>(a, p0, x0);
+        x1 = round29_fold(array29_load<IN32>(a, p1), array29_load<IN32>(a, p1 + 2 * half), r);
+        array29_store<OUT32>(a, p1, x1);
+    }
 }
 
 // The pair of S for the first folding round when S comes as small integers:
@@ -158,19 +173,21 @@ __device__ __forceinline__ F29 wave_sum29(F29 v) {
     return out;
 }
 
-template <bool IN32, bool OUT32, bool INTS = false>
+template <bool IN32, bool OUT32, bool INTS = false, bool FOLD2 = false>
 __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 3))) k_round_data29(DataRound29Args g) {
     static_assert(!INTS || IN32, "integers are what the first folding round reads");
+    static_assert(!FOLD2 || (IN32 && !INTS), "two variables at once are bound from the arrays as they came");
     __shared__ uint32_t lds[4 * 3 * 9];
     Round29Sums sums;
     round29_begin(sums);
     const size_t start = blockIdx.x * g.block_span;
     const size_t lo_mask = ((size_t)1 << g.lbits) - 1;
+    const Round29Fold2 r2{g.r_first, g.r_prev, g.r_both};
     for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
         F29 a0, a1, s0, s1;
-        fold_pair29<IN32, OUT32>(g.A, p + g.off0, p + g.off1, g.half, g.r_prev, a0, a1);
+        fold_pair29<IN32, OUT32, FOLD2>(g.A, p + g.off0, p + g.off1, g.half, g.r_prev, r2, a0, a1);
         if constexpr (INTS) fold_pair29_ints<OUT32>(g, p + g.off0, p + g.off1, s0, s1);
-        else fold_pair29<IN32, OUT32>(g.S, p + g.off0, p + g.off1, g.half, g.r_prev, s0, s1);
+        else fold_pair29<IN32, OUT32, FOLD2>(g.S, p + g.off0, p + g.off1, g.half, g.r_prev, r2, s0, s1);
         const F29 w = planes29_load(g.weights, g.lo_off + (p & lo_mask));
         round29_pair(sums, a0, a1, s0, s1, w, g.beta);
     }
@@ -203,6 +220,97 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 
         fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 5 + slot, out);
     } else if (threadIdx.x < 5) {
         fr_store(g.partials, g.pstride, (size_t)blockIdx.x * 5 + (threadIdx.x == 3 ? 1 : 4), fr_zero());
+    }
+}
+
+// ---- the first pass, serving the first two rounds (round01_dev.h) -------------------
+//
+// Workgroup b covers the quads p in [b * block_span, (b + 1) * block_span) of the
+// first quarter of the arrays (entries at p + c * quarter, c = 0..3), at most
+// kRound01MaxQuads per thread.  Weights are the SECOND round's (its pairs are
+// indexed by p), low table in 29-bit planes, the high factor applied once per
+// workgroup.  Out, per workgroup: c20, c21, qd, T, qe (partD, five per workgroup)
+// and the four sums of A followed by two zeros (partT, six per workgroup).
+struct DataRound01Args {
+    const uint32_t* A;
+    size_t as;
+    const uint32_t* S;
+    size_t ss;
+    size_t quarter;
+    size_t block_span;
+    Planes29 weights;
+    uint32_t lo_off;
+    int lbits;
+    int has_hi;
+    const uint32_t* hi_pool;
+    size_t hi_stride;
+    uint32_t hi_off;
+    uint32_t* partD;
+    size_t pstrideD;
+    uint32_t* partT;
+    size_t pstrideT;
+};
+
+__device__ __forceinline__ F29 words29_load(const uint32_t* base, size_t stride, size_t i) {
+    uint32_t w[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w[k] = base[k * stride + i];
+    return f29_unpack(w);
+}
+
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 2))) k_round_data01(DataRound01Args g) {
+    __shared__ uint32_t lds[4 * 9 * 9];
+    Round01Sums sums;
+    round01_begin(sums);
+    const size_t start = blockIdx.x * g.block_span;
+    const size_t lo_mask = ((size_t)1 << g.lbits) - 1;
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
+        // A's entries first and done with before S's are loaded: with both in flight the registers do not suffice
+        Round01Weighted x;
+        {
+            F29 a[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) a[c] = words29_load(g.A, g.as, p + c * g.quarter);
+            const F29 w = planes29_load(g.weights, g.lo_off + (p & lo_mask));
+            round01_quad_a(sums, a, w, x);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            F29 s[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) s[c] = words29_load(g.S, g.ss, p + c * g.quarter);
+            round01_quad_s(sums, s, x);
+        }
+    }
+    F29 tot[9];
+    round01_end(sums, tot);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int q = 0; q < 9; ++q) {
+        tot[q] = wave_sum29(tot[q]);  // below 96 r
+        if (lane == 0) {
+#pragma unroll
+            for (int k = 0; k < 9; ++k) lds[(wave * 9 + q) * 9 + k] = tot[q].l[k];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 9) {
+        const int q = threadIdx.x;
+        F29 v = f29_zero();
+        for (int w = 0; w < 4; ++w) {
+#pragma unroll
+            for (int k = 0; k < 9; ++k) v.l[k] += lds[(w * 9 + q) * 9 + k];
+        }
+        Fr out;
+        f29_canonical_big(out.l, f29_normalize(v));  // below 384 r < 2^264
+        if (q < 5) {
+            if (g.has_hi) out = fr_mul(out, fr_load(g.hi_pool, g.hi_stride, g.hi_off + (start >> g.lbits)));
+            fr_store(g.partD, g.pstrideD, (size_t)blockIdx.x * 5 + q, out);
+        } else {
+            fr_store(g.partT, g.pstrideT, (size_t)blockIdx.x * 6 + (q - 5), out);
+        }
+    } else if (threadIdx.x < 11) {
+        fr_store(g.partT, g.pstrideT, (size_t)blockIdx.x * 6 + (threadIdx.x - 5), fr_zero());
     }
 }
 

@@ -1,6 +1,7 @@
 // Host build of the 29-bit-limb field arithmetic (csrc/fr29_dev.h) with a C
 // interface, so that tests can compare it with Python's big integers.  Compiled
 // with g++ by tests/test_fr29_host.py; nothing here runs on a GPU.
+#include "../../paper_2404_16109_amd/csrc/round01_dev.h"
 #include "../../paper_2404_16109_amd/csrc/round29_dev.h"
 
 using namespace zkmi;
@@ -66,6 +67,41 @@ void c_round29_thread(int pairs, const uint32_t* entries, const uint32_t* weight
     round29_end(t, o);
     for (int q = 0; q < 3; ++q) f29_out(out + 9 * q, o[q]);
     if (peak) *peak = top;
+}
+// One thread of the first pass when it serves two rounds, as the kernel runs it: `quads` quads, each given by its four
+// entries of A then its four of S (c = 2 x_0 + x_1; nine limbs each) and its weight.  out: the thread's nine sums
+// (c20, c21, qd, T, qe, then the four sums of A).  peak (may be null): the largest value a limb of the unreduced sums
+// held at the end, before they are normalized.
+void c_round01_thread(int quads, const uint32_t* entries, const uint32_t* weights, uint32_t* out, uint64_t* peak) {
+    Round01Sums t;
+    round01_begin(t);
+    for (int j = 0; j < quads; ++j) {
+        const uint32_t* e = entries + 72 * j;
+        F29 a[4], s[4];
+        for (int c = 0; c < 4; ++c) { a[c] = f29_of(e + 9 * c); s[c] = f29_of(e + 36 + 9 * c); }
+        Round01Weighted x;
+        round01_quad_a(t, a, f29_of(weights + 9 * j), x);
+        round01_quad_s(t, s, x);
+    }
+    if (peak) {
+        uint64_t top = 0;
+        const F29Wide* wide[5] = {&t.c20, &t.c21, &t.qd, &t.T, &t.qe};
+        for (int q = 0; q < 5; ++q) for (int c = 0; c < 18; ++c) if (wide[q]->l[c] > top) top = wide[q]->l[c];
+        for (int q = 0; q < 4; ++q) for (int c = 0; c < 9; ++c) if (t.sa[q].l[c] > top) top = t.sa[q].l[c];
+        *peak = top;
+    }
+    F29 o[9];
+    round01_end(t, o);
+    for (int q = 0; q < 9; ++q) f29_out(out + 9 * q, o[q]);
+}
+// An entry bound by two challenges at once, as the kernel does after that pass: y: the four entries y_00 y_01 y_10
+// y_11; r_first, r and their product, each times 2^261.
+void c_fold2(const uint32_t* y, const uint32_t* r_first, const uint32_t* r, const uint32_t* r_both, uint32_t* out) {
+    const Round29Fold2 r2{f29_of(r_first), f29_of(r), f29_of(r_both)};
+    f29_out(out, round29_fold2(f29_of(y), f29_of(y + 9), f29_of(y + 18), f29_of(y + 27), r2));
+}
+void c_mul3_add(const uint32_t* v, uint32_t* out) {
+    f29_out(out, f29_mul3_add(f29_of(v), f29_of(v + 9), f29_of(v + 18), f29_of(v + 27), f29_of(v + 36), f29_of(v + 45), f29_of(v + 54)));
 }
 void c_canonical(const uint32_t* l, uint32_t* w) { F29 a; for (int i = 0; i < 9; ++i) a.l[i] = l[i]; f29_canonical(w, a); }
 void c_canonical_big(const uint32_t* l, uint32_t* w) { F29 a; for (int i = 0; i < 9; ++i) a.l[i] = l[i]; f29_canonical_big(w, a); }

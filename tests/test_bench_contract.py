@@ -35,11 +35,18 @@ def test_work_models():
     D, N = 1 << 25, 1 << 16
     # the headline's model: ten multiplications per tensor entry and per table row
     assert b.fr_mul_model(D, N) == 10 * D + 10 * N
-    # the dominant kernel runs the rounds after the first, before the table's variables, above 256 pairs
-    assert b.rounds_on_29_bits(D, N) == list(range(1, 9))
-    assert b.round29_pairs(D, N) == sum(D >> (k + 1) for k in range(1, 9)) == D // 2 - D // 512
-    assert b.rounds_on_29_bits(1 << 12, 1 << 4) == [1, 2]            # pairs 1024 and 512; 256 is the resident kernel's
+    # the dominant kernel runs the rounds before the table's variables, above 256 pairs, after the first round -- or, from
+    # a vector of field elements, after the first two, which share the first pass
+    assert b.first_two_rounds_share_a_pass(D, N)
+    assert b.rounds_on_29_bits(D, N) == list(range(2, 9)) and b.rounds_on_29_bits(D, N, from_ints=True) == list(range(1, 9))
+    pairs, muls, moved = b.round29_work(D, N)
+    assert pairs == sum(D >> (k + 1) for k in range(2, 9)) == D // 4 - D // 512
+    # round 2 binds two variables (17 multiplications, 20 entries per pair), rounds 3..8 one (9 and 12)
+    assert muls == 17 * (D >> 3) + 9 * (D // 8 - D // 512) and moved == 32 * (20 * (D >> 3) + 12 * (D // 8 - D // 512))
+    assert b.rounds_on_29_bits(1 << 12, 1 << 4) == [2]               # 512 pairs; 256 is the resident kernel's
+    assert b.rounds_on_29_bits(1 << 12, 1 << 4, from_ints=True) == [1, 2]
     assert b.rounds_on_29_bits(1 << 12, 1 << 11) == []               # the table's variables start at the second round
+    assert b.rounds_on_29_bits(1 << 12, 1 << 10) == [1]              # ... at the third: no pass can serve two rounds
     # nine multiplications of 112 multiply-adds per pair against 256 CUs x 64 lanes x 2.4 GHz
     assert (b.ROUND_DATA_FR_MUL_PER_PAIR_EVAL + b.ROUND_DATA_FR_MUL_PER_PAIR_FOLD, b.MADS_PER_FR_MUL) == (9, 112)
     assert b.PEAK_MAD_PER_S == 256 * 64 * 2.4e9

@@ -284,3 +284,129 @@ def test_round29_eight_lazy_rounds_in_a_row(lib):
         assert all(value_of(v) < (1 + 2 * (rnd + 1)) * R for v in nxt)
         vals = [nxt[0], nxt[1], nxt[2], nxt[3], nxt[2], nxt[3], nxt[0], nxt[1]]
     assert max(value_of(v) for v in vals) < 17 * R
+
+
+def _round01_thread(lib, entries, weights):
+    quads = len(weights)
+    e = np.concatenate([np.concatenate(q) for q in entries]).astype(np.uint32)
+    w = np.concatenate(weights).astype(np.uint32)
+    out = np.zeros(81, np.uint32)
+    peak = ctypes.c_uint64(0)
+    lib.c_round01_thread(quads, ptr(e), ptr(w), ptr(out), ctypes.byref(peak))
+    return out.reshape(9, 9), peak.value
+
+
+def _check_round01_thread(lib, entries, weights):
+    """The per-thread schedule of the first pass when it serves two rounds, against Python integers: the five sums of
+    products and the four sums of A, and every bound the kernel's sums across lanes rely on."""
+    inv = pow(2, -261, R)
+    out, peak = _round01_thread(lib, entries, weights)
+    want = [0] * 9
+    for quad, w in zip(entries, weights):
+        a = [value_of(v) for v in quad[:4]]
+        s = [value_of(v) for v in quad[4:]]
+        wv = value_of(w)
+        B = lambda x, y: x * wv * inv * y
+        want[0] += B(a[2] - a[0], s[2] - s[0])
+        want[1] += B(a[3] - a[1], s[3] - s[1])
+        want[2] += B(a[1] - a[0], s[1] - s[0])
+        want[3] += B(a[3] - a[2], s[3] - s[2])
+        want[4] += B(a[3] - a[1] - a[2] + a[0], s[3] - s[1] - s[2] + s[0])
+        for c in range(4):
+            want[5 + c] += a[c]
+    got = [value_of(out[q]) for q in range(9)]
+    for q in range(9):
+        assert got[q] % R == (want[q] * inv if q < 5 else want[q]) % R, q
+    # what the sums over a wavefront (64 lanes) and then over four wavefronts need
+    assert all(g < 1.5 * R for g in got) and all(int(v) <= M29 for q in range(9) for v in out[q][:8])
+    assert peak <= 2 ** 32 - 8               # no lazy limb wrapped before the closing normalization
+    return peak
+
+
+def test_round01_thread_schedule_at_its_bounds(lib):
+    """Eight quads per thread, every entry the largest a reduced element can be or zero, so that every difference is
+    at an extreme, with the largest weight: the worst case for the accumulators of the first pass."""
+    rmax = limbs_of(R - 1)
+    zero = arr([0] * 9)
+    worst = 0
+    patterns = [[rmax] * 8,
+                [zero, rmax, rmax, zero, rmax, zero, zero, rmax],
+                [rmax, zero, zero, rmax, zero, rmax, rmax, zero],
+                [zero, zero, rmax, rmax, rmax, rmax, zero, zero],
+                [rmax, zero, rmax, zero, zero, rmax, zero, rmax]]
+    for pat in patterns:
+        worst = max(worst, _check_round01_thread(lib, [pat] * 8, [rmax] * 8))
+    assert worst > 2 ** 31                   # the test does reach the region the bound is about
+    rng = random.Random(21)
+    for quads in (1, 2, 3, 5, 8):
+        entries = [[limbs_of(rng.randrange(R)) for _ in range(8)] for _ in range(quads)]
+        weights = [limbs_of(rng.randrange(R)) for _ in range(quads)]
+        _check_round01_thread(lib, entries, weights)
+
+
+def test_round01_sums_give_the_second_round(lib):
+    """With A_c (S_c + beta) = 1 for every entry, the second round's sums after a first challenge r are the polynomials
+    in r that the prover forms from the pass's sums: checked here on Python integers against folding first."""
+    rng = random.Random(22)
+    quads = 6
+    beta = rng.randrange(R)
+    S = [[rng.randrange(R) for _ in range(4)] for _ in range(quads)]
+    A = [[pow(beta + s, -1, R) for s in q] for q in S]
+    w = [rng.randrange(R) for _ in range(quads)]
+    wsum = sum(w) % R
+    B = lambda f: sum(w[j] * f(A[j], S[j]) for j in range(quads)) % R
+    c20 = B(lambda a, s: (a[2] - a[0]) * (s[2] - s[0]))
+    c21 = B(lambda a, s: (a[3] - a[1]) * (s[3] - s[1]))
+    qd = B(lambda a, s: (a[1] - a[0]) * (s[1] - s[0]))
+    T = B(lambda a, s: (a[3] - a[2]) * (s[3] - s[2]))
+    qe = B(lambda a, s: (a[3] - a[1] - a[2] + a[0]) * (s[3] - s[1] - s[2] + s[0]))
+    r = rng.randrange(R)
+    fold = lambda y: ((y[0] + r * (y[2] - y[0])) % R, (y[1] + r * (y[3] - y[1])) % R)
+    Af, Sf = [fold(a) for a in A], [fold(s) for s in S]
+    q0 = sum(w[j] * Af[j][0] * (Sf[j][0] + beta) for j in range(quads)) % R
+    q1 = sum(w[j] * Af[j][1] * (Sf[j][1] + beta) for j in range(quads)) % R
+    qinf = sum(w[j] * (Af[j][1] - Af[j][0]) * (Sf[j][1] - Sf[j][0]) for j in range(quads)) % R
+    t = r * (1 - r)
+    assert q0 == (wsum - t * c20) % R and q1 == (wsum - t * c21) % R     # the weights of a whole round sum to one
+    assert qinf == (qd + r * (T - qd - qe) + r * r * qe) % R
+
+
+def test_mul3_add_is_three_products_under_one_reduction(lib):
+    rng = random.Random(24)
+    inv = pow(2, -261, R)
+    full = value_of([M29] * 8 + [(42 * R) >> 232])   # every limb full, value about 42 r: the largest a normalized difference gets
+    for trial in range(60):
+        if trial == 0:
+            vals = [full, R - 1, full, R - 1, full, R - 1, value_of([M29] * 8 + [(17 * R) >> 232])]
+        else:
+            vals = [rng.randrange(42 * R), rng.randrange(R), rng.randrange(42 * R), rng.randrange(R),
+                    rng.randrange(42 * R), rng.randrange(R), rng.randrange(17 * R)]
+        out = np.zeros(9, np.uint32)
+        lib.c_mul3_add(ptr(np.concatenate([limbs_of(v) for v in vals])), ptr(out))
+        prod = vals[0] * vals[1] + vals[2] * vals[3] + vals[4] * vals[5]
+        got = value_of(out)
+        assert got % R == (prod * inv + vals[6]) % R
+        assert got < prod // 2 ** 261 + R + vals[6] + 1 and all(int(v) <= M29 for v in out[:8])
+
+
+def test_fold2_binds_two_variables(lib):
+    rng = random.Random(23)
+    inv = pow(2, -261, R)
+    rmax = R - 1
+    for trial in range(60):
+        if trial < 4:   # entries at their extremes, so that every difference is, with the largest challenges
+            y = [[rmax, rmax, rmax, rmax], [0, rmax, rmax, 0], [rmax, 0, 0, rmax], [0, 0, 0, rmax]][trial]
+            r0 = r1 = rmax
+        else:
+            y = [rng.randrange(R) for _ in range(4)]
+            r0, r1 = rng.randrange(R), rng.randrange(R)
+        r01 = r0 * r1 * inv % R       # the product of the two, again times 2^261
+        out = np.zeros(9, np.uint32)
+        lib.c_fold2(ptr(np.concatenate([limbs_of(v) for v in y])), ptr(limbs_of(r0)), ptr(limbs_of(r1)), ptr(limbs_of(r01)),
+                    ptr(out))
+        # bind x_0 (entries y_00, y_10 and y_01, y_11), then x_1
+        lo = y[0] + (y[2] - y[0]) * r0 * inv
+        hi = y[1] + (y[3] - y[1]) * r0 * inv
+        assert value_of(out) % R == (lo + (hi - lo) * r1 * inv) % R
+        # within what two single folds may add: below its first entry + 2.8 r, normalized
+        assert value_of(out) < y[0] + 2.8 * R and all(int(v) <= M29 for v in out[:8])

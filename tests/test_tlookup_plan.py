@@ -3,10 +3,12 @@ reads S from), walked on the host without a GPU through the same function the
 prover uses.  What is pinned here is what a kernel launch relies on: a round
 never has a source of S the library has no kernel for, integers are read only by
 the two kernels written for them, and a round reads the layout the round before
-it has written."""
+it has written.  From a vector of field elements the first pass may serve the
+first two rounds (FIRST_TWO, then NO_PASS: nothing launched), after which the
+29-bit kernel binds two variables at once from the caller's arrays."""
 import pytest
 
-FIRST, R29, BOTH, ONE_GROUP, RESIDENT = 0, 1, 2, 3, 4
+FIRST, R29, BOTH, ONE_GROUP, RESIDENT, FIRST_TWO, NO_PASS = 0, 1, 2, 3, 4, 5, 6
 CALLER, INTS, WORDS, PLANES = 0, 1, 2, 3
 
 
@@ -19,9 +21,15 @@ def _check_chain(rounds):
     """Round k >= 2 reads what round k-1 wrote: 29-bit planes after a 29-bit round that
     did not write words, 32-bit words otherwise; a 29-bit round that reads planes has
     in32 = 0."""
+    shared = len(rounds) > 0 and rounds[0][0] == FIRST_TWO
+    if shared:
+        # one pass for two rounds, then both variables bound at once from the arrays as the caller left them
+        assert len(rounds) >= 3 and rounds[1][0] == NO_PASS and rounds[2][0] == R29
+        assert [r[1] for r in rounds[:3]] == [CALLER] * 3 and rounds[2][2] == 1
+    assert all(r[0] not in (FIRST_TWO, NO_PASS) for r in rounds[2:]) and (shared or all(r[0] != NO_PASS for r in rounds))
     for k, (kernel, src, in32, out32) in enumerate(rounds):
         assert src in (CALLER, INTS, WORDS, PLANES), (k, src)
-        if k <= 1:
+        if k <= 1 or (shared and k == 2):
             assert src in (CALLER, INTS)
             continue
         pk, _, _, pout32 = rounds[k - 1]
@@ -47,10 +55,11 @@ def test_plan_of_the_shape_that_once_faulted():
     assert rounds[2][1] == PLANES and rounds[2][3] == 1      # reads planes, writes words for the resident kernel
     assert all(r[1] == WORDS for r in rounds[3:])
     _check_chain(rounds)
-    # the same shape from a vector: same kernels, S from the caller in rounds 0 and 1
+    # the same shape from a vector: the first pass serves two rounds, the third binds both variables from the caller's S
     rc, from_vec = _plan(zk, 1 << 12, 1 << 4)
-    assert [r[0] for r in from_vec] == [r[0] for r in rounds]
-    assert [r[1] for r in from_vec[:2]] == [CALLER, CALLER] and from_vec[2:] == rounds[2:]
+    assert [r[0] for r in from_vec] == [FIRST_TWO, NO_PASS, R29] + [RESIDENT] * 9
+    assert [r[1] for r in from_vec[:3]] == [CALLER] * 3 and from_vec[2][2:] == (1, 1) and from_vec[3:] == rounds[3:]
+    _check_chain(from_vec)
 
 
 def test_plan_of_the_headline_shape_matches_the_bench_model():
@@ -59,10 +68,13 @@ def test_plan_of_the_headline_shape_matches_the_bench_model():
     for from_ints in (False, True):
         rc, rounds = _plan(zk, 1 << 25, 1 << 16, from_ints=from_ints)
         assert rc == 25
-        assert [k for k, r in enumerate(rounds) if r[0] == R29] == bench.rounds_on_29_bits(1 << 25, 1 << 16)
+        assert [k for k, r in enumerate(rounds) if r[0] == R29] == bench.rounds_on_29_bits(1 << 25, 1 << 16, from_ints)
         assert [r[0] for r in rounds[9:16]] == [BOTH] * 7 and [r[0] for r in rounds[16:]] == [RESIDENT] * 9
-        # eight lazy rounds at most: round 1 arrives as words, round 8 leaves as words
-        assert rounds[1][2] == 1 and rounds[8][3] == 1 and all(r[3] == 0 for r in rounds[1:8])
+        # eight folds at most before reduced words are written again: the first 29-bit round arrives as words, round 8
+        # leaves as words
+        first29 = 1 if from_ints else 2
+        assert rounds[first29][2] == 1 and rounds[8][3] == 1 and all(r[3] == 0 for r in rounds[first29:8])
+        assert (rounds[0][0], rounds[1][0]) == ((FIRST, R29) if from_ints else (FIRST_TWO, NO_PASS))
         _check_chain(rounds)
 
 
