@@ -32,11 +32,11 @@
 
 namespace zkmi {
 
-static constexpr int kRound01MaxQuads = 8;  // quads per thread between two reductions of its sums
+static constexpr int kRound01MaxQuads = 16;  // quads per thread (its lazy sums are normalized after every seven)
 
 struct Round01Sums {
-    F29Wide c20, c21, qd, T, qe;  // unreduced 18-limb integers, limbs lazy (at most eight additions each)
-    F29 sa[4];                    // sums of A_00, A_01, A_10, A_11: lazy limbs, at most eight additions
+    F29Wide c20, c21, qd, T, qe;  // unreduced 18-limb integers, limbs lazy (at most seven additions between normalizations)
+    F29 sa[4];                    // sums of A_00, A_01, A_10, A_11: lazy limbs, likewise
     int quads;
 };
 
@@ -83,25 +83,36 @@ ZK_HD void round01_quad_a(Round01Sums& t, const F29 (&a)[4], const F29& w, Round
     x.wd1 = f29_normalize(f29_add(x.wd0, x.we));
 }
 
-// s[c]: the quad's entries of S.  Differences of S are normalized (the first factor
-// of a product must be): each below 41 r, the mixed one below 42 r.
+// s[c]: the quad's entries of S.
 ZK_HD void round01_quad_s(Round01Sums& t, const F29 (&s)[4], const Round01Weighted& x) {
-    f29_wide_mac(t.c20, f29_normalize(f29_sub(s[2], s[0])), x.wx0);
+    // one factor of a product must be normalized, the other may have limbs up to 1.5 * 2^30: the weighted differences
+    // of A are normalized (all but the mixed one), so the plain differences of S (below 41 r) can stay as they are
+    f29_wide_mac(t.c20, x.wx0, f29_sub(s[2], s[0]));
     round01_one_at_a_time();
-    f29_wide_mac(t.c21, f29_normalize(f29_sub(s[3], s[1])), x.wx1);
+    f29_wide_mac(t.c21, x.wx1, f29_sub(s[3], s[1]));
     round01_one_at_a_time();
-    f29_wide_mac(t.qd, f29_normalize(f29_sub(s[1], s[0])), x.wd0);
+    f29_wide_mac(t.qd, x.wd0, f29_sub(s[1], s[0]));
     round01_one_at_a_time();
-    f29_wide_mac(t.T, f29_normalize(f29_sub(s[3], s[2])), x.wd1);
+    f29_wide_mac(t.T, x.wd1, f29_sub(s[3], s[2]));
     round01_one_at_a_time();
+    // the mixed difference of S (below 42 r) is normalized, the mixed weighted difference of A is not
     f29_wide_mac(t.qe, f29_normalize(f29_sub(f29_add(s[3], s[0]), f29_normalize(f29_add(s[1], s[2])))), x.we);
     ++t.quads;
+    if (t.quads % 7 == 0) {  // a normalized limb (below 2^29) has room for seven additions of as much
+        f29_wide_normalize(t.c20);
+        f29_wide_normalize(t.c21);
+        f29_wide_normalize(t.qd);
+        f29_wide_normalize(t.T);
+        f29_wide_normalize(t.qe);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) t.sa[c] = f29_normalize(t.sa[c]);
+    }
 }
 
-// The thread's nine sums, each normalized and below 1.5 r (so that sums over a
-// wavefront and then over four wavefronts stay below 2^264, about 565 r): out[0..4] = c20, c21, qd, T, qe (divided by
+// The thread's nine sums, each normalized and below 2 r (so that a sum over a
+// wavefront stays below 2^264, about 565 r): out[0..4] = c20, c21, qd, T, qe (divided by
 // 2^261 like any product), out[5..8] = the four sums of A.
-// at most 8 * 42 r * 7.2 r / 2^261 + r < 36 r once reduced, below 1.5 r after the shrink
+// at most 16 * 42 r * 7.2 r / 2^261 + r < 70 r once reduced, below 2 r after the shrink
 ZK_HD F29 round01_finish(F29Wide& w) {
     f29_wide_normalize(w);
     return f29_shrink(f29_wide_reduce(w));
@@ -113,7 +124,7 @@ ZK_HD void round01_end(Round01Sums& t, F29 (&out)[9]) {
     out[2] = round01_finish(t.qd);
     out[3] = round01_finish(t.T);
     out[4] = round01_finish(t.qe);
-    out[5] = f29_shrink(f29_normalize(t.sa[0]));  // below 8 r before, 1.2 r after
+    out[5] = f29_shrink(f29_normalize(t.sa[0]));  // below 16 r before, 1.3 r after
     out[6] = f29_shrink(f29_normalize(t.sa[1]));
     out[7] = f29_shrink(f29_normalize(t.sa[2]));
     out[8] = f29_shrink(f29_normalize(t.sa[3]));

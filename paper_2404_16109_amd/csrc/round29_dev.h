@@ -24,7 +24,7 @@
 namespace zkmi {
 
 static constexpr int kMaxLazyRounds = 8;       // values stay below 17 r
-static constexpr int kRound29MaxPairs = 16;    // pairs per thread: the sum of 16 entries stays below 2^264
+static constexpr int kRound29MaxPairs = 22;    // pairs per thread: the sum of 22 entries (374 r) stays below 2^264 (565 r)
 
 struct Round29Sums {
     F29Wide q0, qinf;  // sums of products as unreduced 18-limb integers, limbs lazy between normalizations
@@ -75,16 +75,17 @@ ZK_HD void round29_pair(Round29Sums& t, const F29& a0, const F29& a1, const F29&
     }
 }
 
-// The thread's three sums, each normalized and below 5 r (so that the sum over a
-// wavefront stays below 2^264): out[0] = q0, out[1] = qinf, out[2] = sA0, the
+// The thread's three sums, each normalized and below 6.3 r (so that the sum over a
+// wavefront, at most 403 r, stays below 2^264, about 565 r): out[0] = q0, out[1] = qinf, out[2] = sA0, the
 // first two divided by 2^261 like any product.
 ZK_HD void round29_end(Round29Sums& t, F29 (&out)[3]) {
     f29_wide_normalize(t.q0);
     f29_wide_normalize(t.qinf);
     const F29 q0 = f29_wide_reduce(t.q0), qinf = f29_wide_reduce(t.qinf);
-    out[0] = f29_shrink(q0);    // below 16 * 2 r * 18 r / 2^261 + r < 9 r, then below 1.2 r
-    out[1] = f29_shrink(qinf);  // below 16 * 57 r * 6 r / 2^261 + r < 76 r (top limb below 2^29), then below 2.1 r
-    out[2] = f29_shrink(f29_normalize(t.sA0));     // below 16 * 17 r = 272 r < 2^264, then below 4.7 r
+    // with r / 2^261 about 1 / 70.7 and at most kRound29MaxPairs pairs:
+    out[0] = f29_shrink(q0);    // below 22 * 2 r * 18 r / 2^261 + r < 13 r, then below 1.2 r
+    out[1] = f29_shrink(qinf);  // below 22 * 57 r * 6 r / 2^261 + r < 108 r (top limb below 2^30), then below 2.6 r
+    out[2] = f29_shrink(f29_normalize(t.sA0));     // below 22 * 17 r = 374 r < 2^264, then below 6.3 r
 }
 
 }  // namespace zkmi

@@ -1133,12 +1133,19 @@ static int prove_core(const ProveCall& c) {
                 launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 6, blocks, I.words, mb->words, my_seq,
                                   w.flags + 1, stream);
             } else if (plan.kernel == kRound29) {
+                // as many pairs per workgroup as its weights' shared factor allows, but at least 512 workgroups while the
+                // round is large enough (measured: fewer, longer workgroups beat 1024 or 2048 shorter ones, and
+                // workgroups of three or two wavefronts are slower than of four)
+                const unsigned threads29 = (unsigned)kBlock;
+                const size_t span29 = span;
+                const unsigned blocks29 = blocks;
+                if (span29 > (size_t)threads29 * kRound29MaxPairs) return ZK_E_BUFSZ;  // cannot happen
                 DataRound29Args d29;
                 // 32-bit words: A in place (stride D), S from the caller's vector or Sf; 29-bit limbs: A29, S29
                 d29.A = Array29{w.A, D, Planes29{w.A29, D / 2}, w.A, D};
                 d29.S = Array29{d.S.src, d.S.ss, Planes29{w.S29, D / 2}, w.Sf, D / 2};
                 d29.half = half;
-                d29.block_span = span;
+                d29.block_span = span29;
                 d29.off0 = side1 ? half : 0;
                 d29.off1 = side1 ? 0 : half;
                 d29.r_prev = f29_unpack(to_dev(mul(r_prev, from_u64(32))).l);
@@ -1177,16 +1184,16 @@ static int prove_core(const ProveCall& c) {
                 {
                     ProfileScope prof(kProfRound29, stream);
                     if (plan.fold2 && (ints_round || !in32)) return ZK_E_BADARG;  // cannot happen: see plan_round
-                    if (plan.fold2 && out32) hipLaunchKernelGGL((k_round_data29<true, true, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else if (plan.fold2) hipLaunchKernelGGL((k_round_data29<true, false, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else if (ints_round && out32) hipLaunchKernelGGL((k_round_data29<true, true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else if (ints_round) hipLaunchKernelGGL((k_round_data29<true, false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else if (in32) hipLaunchKernelGGL((k_round_data29<true, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else if (out32) hipLaunchKernelGGL((k_round_data29<false, true>), dim3(blocks), dim3(kBlock), 0, stream, d29);
-                    else hipLaunchKernelGGL((k_round_data29<false, false>), dim3(blocks), dim3(kBlock), 0, stream, d29);
+                    if (plan.fold2 && out32) hipLaunchKernelGGL((k_round_data29<true, true, false, true>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else if (plan.fold2) hipLaunchKernelGGL((k_round_data29<true, false, false, true>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else if (ints_round && out32) hipLaunchKernelGGL((k_round_data29<true, true, true>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else if (ints_round) hipLaunchKernelGGL((k_round_data29<true, false, true>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else if (in32 && out32) hipLaunchKernelGGL((k_round_data29<true, true>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else if (in32) hipLaunchKernelGGL((k_round_data29<true, false>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else if (out32) hipLaunchKernelGGL((k_round_data29<false, true>), dim3(blocks29), dim3(threads29), 0, stream, d29);
+                    else hipLaunchKernelGGL((k_round_data29<false, false>), dim3(blocks29), dim3(threads29), 0, stream, d29);
                 }
-                launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 0, blocks, I.words, mb->words, my_seq,
+                launch_final_sum2(w.partD, d.pstride, 5, w.partT, t.pstride, 0, blocks29, I.words, mb->words, my_seq,
                                   w.flags + 1, stream);
             } else {
                 {  // the first round (every later one is small, binds a table variable, or runs on 29-bit limbs)

@@ -146,8 +146,8 @@ __device__ __forceinline__ void fold_pair29_ints(const DataRound29Args& g, size_
 
 // Sums of lazy values over a wavefront: limbs are added lane to lane (data-parallel
 // moves, as in reduce_dev.h) and carried every second step, before they can
-// outgrow their words.  v: normalized, below 4.8 r; the result, in every lane, is
-// normalized and below 64 times that (below 2^264).
+// outgrow their words.  v: normalized, below 8 r; the result, in every lane, is
+// normalized and below 64 times that (below 2^264, which is about 565 r).
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ F29 dpp_add29(const F29& v) {
     F29 o;
@@ -183,7 +183,7 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 
     const size_t start = blockIdx.x * g.block_span;
     const size_t lo_mask = ((size_t)1 << g.lbits) - 1;
     const Round29Fold2 r2{g.r_first, g.r_prev, g.r_both};
-    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += kBlock) {
+    for (size_t p = start + threadIdx.x; p < start + g.block_span; p += blockDim.x) {  // at most kRound29MaxPairs times
         F29 a0, a1, s0, s1;
         fold_pair29<IN32, OUT32, FOLD2>(g.A, p + g.off0, p + g.off1, g.half, g.r_prev, r2, a0, a1);
         if constexpr (INTS) fold_pair29_ints<OUT32>(g, p + g.off0, p + g.off1, s0, s1);
@@ -193,12 +193,11 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 
     }
     F29 tot[3];
     round29_end(sums, tot);
-    // over the wavefront, then over the workgroup's four wavefronts through LDS
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // over the wavefront, then over the workgroup's wavefronts (two to four) through LDS
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
-        tot[q] = wave_sum29(tot[q]);                // below 77 r, 135 r, 308 r
-        if (q == 2) tot[q] = f29_shrink(tot[q]);    // four of them must stay below 2^264: below 5.4 r
+        tot[q] = f29_shrink(wave_sum29(tot[q]));  // below 77 r, 166 r, 403 r, then below 2.1 r, 3.4 r, 6.7 r
         if (lane == 0) {
 #pragma unroll
             for (int k = 0; k < 9; ++k) lds[(wave * 3 + q) * 9 + k] = tot[q].l[k];
@@ -208,12 +207,12 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 
     if (threadIdx.x < 3) {
         const int q = threadIdx.x;
         F29 v = f29_zero();
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < nwaves; ++w) {
 #pragma unroll
             for (int k = 0; k < 9; ++k) v.l[k] += lds[(w * 3 + q) * 9 + k];
         }
         Fr out;
-        f29_canonical_big(out.l, f29_normalize(v));  // below 540 r < 2^264
+        f29_canonical(out.l, f29_normalize(v));  // below 27 r < 2^261
         if (q < 2 && g.has_hi) out = fr_mul(out, fr_load(g.hi_pool, g.hi_stride, g.hi_off + (start >> g.lbits)));
         // q0, qinf, sA0 at the places the five sums of a round have in a workgroup's partial values
         const int slot = q == 0 ? 0 : q == 1 ? 2 : 3;
@@ -287,7 +286,7 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
     for (int q = 0; q < 9; ++q) {
-        tot[q] = wave_sum29(tot[q]);  // below 96 r
+        tot[q] = f29_shrink(wave_sum29(tot[q]));  // below 128 r, then below 2.9 r
         if (lane == 0) {
 #pragma unroll
             for (int k = 0; k < 9; ++k) lds[(wave * 9 + q) * 9 + k] = tot[q].l[k];
@@ -302,7 +301,7 @@ __global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(2, 
             for (int k = 0; k < 9; ++k) v.l[k] += lds[(w * 9 + q) * 9 + k];
         }
         Fr out;
-        f29_canonical_big(out.l, f29_normalize(v));  // below 384 r < 2^264
+        f29_canonical(out.l, f29_normalize(v));  // below 12 r < 2^261
         if (q < 5) {
             if (g.has_hi) out = fr_mul(out, fr_load(g.hi_pool, g.hi_stride, g.hi_off + (start >> g.lbits)));
             fr_store(g.partD, g.pstrideD, (size_t)blockIdx.x * 5 + q, out);

@@ -71,23 +71,35 @@ void c_round29_thread(int pairs, const uint32_t* entries, const uint32_t* weight
 // One thread of the first pass when it serves two rounds, as the kernel runs it: `quads` quads, each given by its four
 // entries of A then its four of S (c = 2 x_0 + x_1; nine limbs each) and its weight.  out: the thread's nine sums
 // (c20, c21, qd, T, qe, then the four sums of A).  peak (may be null): the largest value a limb of the unreduced sums
-// held at the end, before they are normalized.
+// held before a normalization.
 void c_round01_thread(int quads, const uint32_t* entries, const uint32_t* weights, uint32_t* out, uint64_t* peak) {
     Round01Sums t;
     round01_begin(t);
+    uint64_t top = 0;
+    auto look = [&](const Round01Sums& u) {
+        const F29Wide* wide[5] = {&u.c20, &u.c21, &u.qd, &u.T, &u.qe};
+        for (int q = 0; q < 5; ++q) for (int c = 0; c < 18; ++c) if (wide[q]->l[c] > top) top = wide[q]->l[c];
+        for (int q = 0; q < 4; ++q) for (int c = 0; c < 9; ++c) if (u.sa[q].l[c] > top) top = u.sa[q].l[c];
+    };
     for (int j = 0; j < quads; ++j) {
         const uint32_t* e = entries + 72 * j;
         F29 a[4], s[4];
         for (int c = 0; c < 4; ++c) { a[c] = f29_of(e + 9 * c); s[c] = f29_of(e + 36 + 9 * c); }
+        if (peak && j % 7 == 6) {
+            // what the lazy limbs hold just before this quad's normalization: run the quad on a copy without it
+            Round01Sums probe = t;
+            probe.quads = 0;
+            Round01Weighted y;
+            round01_quad_a(probe, a, f29_of(weights + 9 * j), y);
+            round01_quad_s(probe, s, y);
+            look(probe);
+        }
         Round01Weighted x;
         round01_quad_a(t, a, f29_of(weights + 9 * j), x);
         round01_quad_s(t, s, x);
     }
     if (peak) {
-        uint64_t top = 0;
-        const F29Wide* wide[5] = {&t.c20, &t.c21, &t.qd, &t.T, &t.qe};
-        for (int q = 0; q < 5; ++q) for (int c = 0; c < 18; ++c) if (wide[q]->l[c] > top) top = wide[q]->l[c];
-        for (int q = 0; q < 4; ++q) for (int c = 0; c < 9; ++c) if (t.sa[q].l[c] > top) top = t.sa[q].l[c];
+        look(t);
         *peak = top;
     }
     F29 o[9];
