@@ -1134,8 +1134,8 @@ static int prove_core(const ProveCall& c) {
                                   w.flags + 1, stream);
             } else if (plan.kernel == kRound29) {
                 // as many pairs per workgroup as its weights' shared factor allows, but at least 512 workgroups while the
-                // round is large enough (measured: fewer, longer workgroups beat 1024 or 2048 shorter ones, and
-                // workgroups of three or two wavefronts are slower than of four)
+                // round is large enough (measured: 1024 workgroups do the same, 2048 and workgroups of three or two
+                // wavefronts are slower)
                 const unsigned threads29 = (unsigned)kBlock;
                 const size_t span29 = span;
                 const unsigned blocks29 = blocks;

@@ -174,7 +174,7 @@ __device__ __forceinline__ F29 wave_sum29(F29 v) {
 }
 
 template <bool IN32, bool OUT32, bool INTS = false, bool FOLD2 = false>
-__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(3, 3))) k_round_data29(DataRound29Args g) {
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4))) k_round_data29(DataRound29Args g) {
     static_assert(!INTS || IN32, "integers are what the first folding round reads");
     static_assert(!FOLD2 || (IN32 && !INTS), "two variables at once are bound from the arrays as they came");
     __shared__ uint32_t lds[4 * 3 * 9];
