@@ -13,6 +13,12 @@
 // and high remaining variables).  The table side is the constant
 // 2^-(k+1) * c_B while the variable being bound is not one of the table's, and
 // 2^-h (alpha^2 c'_k e~(u_k,X) qT(X) - bm(X)) afterwards.
+//
+// Which kernel computes a round's sums is decided by plan_round.  From a vector
+// of field elements the first pass over A and S yields the sums of the first TWO
+// rounds (round01_dev.h) and the third round's kernel binds both variables at
+// once; in the large folding rounds the kernel sums one side of the round (X = 0
+// or X = 1) and the other side follows here from the running claim.
 #include "internal.h"
 #include "tlookup_kernels.h"
 #include "tlookup_round29.h"
