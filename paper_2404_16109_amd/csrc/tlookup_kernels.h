@@ -450,9 +450,21 @@ static __global__ void __launch_bounds__(kBlock) k_vec_leaves(VecLeavesJob first
     const size_t cnt = job.n / L;  // elements per leaf: kVecLeaf, or all n (a power of two) when n < kVecLeaf
     uint32_t h[8];
     sha256_init(h);
+    // the next two elements are asked for before the current two are hashed: one block is some 1400 instructions
+    // during which their loads can be on the way
+    Fr next_a = fr_zero(), next_b = fr_zero();
+    if (cnt >= 2) {
+        next_a = fr_load(v, stride, leaf);
+        next_b = fr_load(v, stride, leaf + L);
+    }
     for (size_t t = 0; t + 1 < cnt; t += 2) {
-        const Fr a = fr_from_mont(fr_load(v, stride, leaf + t * L));
-        const Fr b = fr_from_mont(fr_load(v, stride, leaf + (t + 1) * L));
+        const Fr raw_a = next_a, raw_b = next_b;
+        if (t + 3 < cnt) {
+            next_a = fr_load(v, stride, leaf + (t + 2) * L);
+            next_b = fr_load(v, stride, leaf + (t + 3) * L);
+        }
+        const Fr a = fr_from_mont(raw_a);
+        const Fr b = fr_from_mont(raw_b);
         uint32_t w[16];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
