@@ -164,3 +164,52 @@ def test_multi_bad_arguments(zk, orc):
     assert zk.tlookup_prove_multi(seed, Sv, idx, Tv, ws=small_ws)[0] == zk.ZK_E_BUFSZ
     # the batched entry point of one shape still refuses unequal shapes
     assert zk.tlookup_prove_batch(seed, Sv, idx, Tv)[0] == zk.ZK_E_BADARG
+
+
+def test_multi_at_the_headline_shape(zk, orc):
+    """The headline lookup (2^25 entries, 2^16 rows) together with a much shorter one (2^20 entries, 2^10 rows) under one
+    sumcheck.  The oracle's prover at this size takes minutes, so: the oracle's verifier replays every round and the final
+    identity and recomputes both T~; the device verifier recomputes the S, A and m claims from tensors obtained
+    independently of the prover (A by the library's batch inversion at the reported beta, checked on a sample by the
+    oracle; m against a count of the row numbers); and the short instance's S claim is its extension at the last 20
+    coordinates of the point."""
+    from paper_2404_16109_amd import synth
+    from tests.gpu_common import device_table_and_tensor
+    cfgs = [synth.activation_table(rows=2048, cols=11008, logD=25, logN=16),
+            synth.activation_table(rows=64, cols=11008, logD=20, logN=10)]
+    Sv, Tv, idx = [], [], []
+    for cfg in cfgs:
+        sv, tv, ix = device_table_and_tensor(cfg)
+        Sv.append(sv); Tv.append(tv); idx.append(ix)
+    Ds = [c["D"] for c in cfgs]
+    seed = cfgs[0]["seed"]
+    rc, proof, info = zk.tlookup_prove_multi(seed, Sv, idx, Tv)
+    assert rc == 0 and info["sum_A"][:2] == info["sum_mB"][:2]
+    rc, again, _ = zk.tlookup_prove_multi(seed, Sv, idx, Tv)
+    assert rc == 0 and again == proof
+    Tb = [zk.vec_to_bytes(t) for t in Tv]
+    assert orc.tlookup_multi_verify(seed, proof, Tb, Ds) == 0
+    rc, claims = zk.tlookup_verify_multi(seed, proof, Tv, Ds, S=Sv)
+    assert rc == 0 and len(claims["v"]) == 25
+    rc, val = zk.fr_mle_eval(Sv[1], claims["v"][5:])
+    assert rc == 0 and val == claims["value"][1][1]
+    rng = np.random.default_rng(3)
+    for i in range(2):
+        D, N = Ds[i], cfgs[i]["N"]
+        rc, m, _ = zk.tlookup_multiplicities(Sv[i], idx[i], Tv[i])
+        counts = m.cpu().numpy().astype(np.int64)
+        assert rc == 0 and np.array_equal(counts, np.bincount(cfgs[i]["idx"], minlength=N))
+        shifted, A = zk.Vec(D), zk.Vec(D)
+        assert zk.fr_add_scalar(shifted, Sv[i], info["beta"]) == 0 and zk.fr_batch_inverse(A, shifted) == 0
+        sample = np.concatenate([[0, D // 2, D - 1], rng.integers(0, D, 60)])
+        pick = torch.from_numpy(sample).cuda()
+        sub_x, sub_a = zk.Vec(len(sample)), zk.Vec(len(sample))
+        sub_x.data.copy_(shifted.data.index_select(1, pick))
+        sub_a.data.copy_(A.data.index_select(1, pick))
+        rc_o, inv = orc.fr_inv(zk.vec_to_bytes(sub_x))
+        assert rc_o == 0 and np.array_equal(inv, zk.vec_to_bytes(sub_a))
+        del shifted
+        wit_S, wit_A, wit_m = [None, None], [None, None], [None, None]
+        wit_S[i], wit_A[i], wit_m[i] = Sv[i], A, m
+        assert zk.tlookup_verify_multi(seed, proof, Tv, Ds, S=wit_S, A=wit_A, m=wit_m)[0] == 0
+        del A
