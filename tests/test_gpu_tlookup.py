@@ -51,7 +51,11 @@ def _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx):
 @pytest.mark.parametrize("D,N,dup", [(1, 1, False), (2, 1, False), (2, 2, False), (8, 1, False), (8, 8, True),
                                      (16, 4, False), (64, 2, False), (1 << 10, 1 << 4, True), (1 << 13, 1 << 13, False),
                                      (1 << 15, 1 << 8, False), (1 << 16, 1 << 14, True),
-                                     (1 << 17, 1 << 17, False)])
+                                     (1 << 17, 1 << 17, False),
+                                     # around the shapes whose first pass serves two rounds (three data-only rounds, the
+                                     # third above 256 pairs): just inside, just outside, the third as the last data round
+                                     (1 << 12, 1 << 9, False), (1 << 12, 1 << 10, False), (1 << 13, 1 << 10, True),
+                                     (1 << 16, 1 << 13, False), (1 << 19, 1 << 16, False), (1 << 20, 1 << 3, True)])
 def test_proof_bytes_equal_oracle(zk, orc, D, N, dup):
     rng = random.Random(1000 + D + N)
     Sb, Tb, Sv, Tv, idx = _random_instance(orc, zk, rng, D, N, dup)
