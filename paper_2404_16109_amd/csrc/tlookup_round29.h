@@ -1,18 +1,21 @@
-// Data side of the large folding rounds of the tlookup sumcheck (Section 4, the
-// second form of the identity; Section 3.3 for the protocol), on 29-bit limbs.
+// Data side of the large rounds of the tlookup sumcheck (Section 4, the second form
+// of the identity; Section 3.3 for the protocol), on 29-bit limbs: the first pass,
+// which serves the first two rounds (k_round_data01, schedule in round01_dev.h), and
+// the large folding rounds (k_round_data29, schedule in round29_dev.h).
 //
-// These rounds are bound by instruction issue, so they run on fr29_dev.h's
-// arithmetic (one multiply-add per limb product, no carry folds, lazy sums) and
-// compute only what cannot be had otherwise: per pair the two folds of A and of S,
-// the two weighted entries of A, and the sums q0 = sum w A0 (S0+beta),
-// qinf = sum w (A1-A0)(S1-S0) and sA0 = sum A0 (round29_dev.h has the per-thread
-// schedule and its bounds).  The round's other two sums, q1 and sA1, follow on the
-// host from the running claim and from the previous round's sums of A.
+// These kernels move data at close to the rate of a plain copy only if their
+// arithmetic keeps up, so they run on fr29_dev.h's multiplier (one multiply-add per
+// limb product, no carry folds, lazy sums) and compute only what cannot be had
+// otherwise.  A folding round forms per pair the two folds of A and of S, the two
+// weighted entries of A, and the sums q0 = sum w A0 (S0+beta), qinf = sum w (A1-A0)(S1-S0)
+// and sA0 = sum A0; the round's other two sums, q1 and sA1, follow on the host from
+// the running claim and from the previous round's sums of A.  The first of these
+// rounds after k_round_data01 binds two variables at once (FOLD2).
 //
 // Arrays between such rounds hold 29-bit limbs, normalized but not reduced: every
 // fold adds up to 2 r to the bound on the values (they start below r), which is
-// why at most kMaxLazyRounds rounds run back to back before one of them writes
-// fully reduced 32-bit words again.
+// why at most kMaxLazyRounds folds happen before a round writes fully reduced
+// 32-bit words again.
 #pragma once
 #include "round01_dev.h"
 #include "round29_dev.h"
