@@ -213,3 +213,23 @@ def test_multi_at_the_headline_shape(zk, orc):
         wit_S[i], wit_A[i], wit_m[i] = Sv[i], A, m
         assert zk.tlookup_verify_multi(seed, proof, Tv, Ds, S=wit_S, A=wit_A, m=wit_m)[0] == 0
         del A
+
+
+def test_multi_random_shape_mixes(zk, orc):
+    """Forty seeded mixes of two to five instances with lengths from 1 to 2^15 and any table length that fits, rows
+    given for some instances and not for others: every proof equal to the oracle's."""
+    rng = random.Random(2718)
+    for trial in range(40):
+        K = rng.randrange(2, 6)
+        shapes = []
+        for _ in range(K):
+            n = rng.randrange(0, 16)
+            shapes.append((1 << n, 1 << rng.randrange(0, n + 1)))
+        Sb, Tb, Sv, Tv, idx = _instances(orc, zk, rng, shapes, dup=trial % 3 == 0)
+        seed = rng.randbytes(32)
+        hints = [ix if rng.random() < 0.6 else None for ix in idx]
+        rc_o, want, _ = orc.tlookup_multi_prove(seed, Sb, Tb)
+        rc_g, got, _ = zk.tlookup_prove_multi(seed, Sv, hints, Tv)
+        assert rc_o == 0 and rc_g == 0, (trial, shapes)
+        assert first_difference(got, want) == -1, (trial, shapes)
+        assert zk.tlookup_verify_multi(seed, got, Tv, [D for D, _ in shapes], S=Sv)[0] == 0, (trial, shapes)
