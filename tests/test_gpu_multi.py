@@ -46,6 +46,7 @@ def _instances(orc, zk, rng, shapes, dup=False):
 
 
 SHAPES = [
+    [(1 << 10, 1 << 4)],                                # one instance alone (its small rounds in the resident kernel)
     [(1, 1), (1, 1)],                                   # no round at all
     [(2, 1), (1, 1)],
     [(8, 2), (4, 4)],

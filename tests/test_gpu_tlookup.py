@@ -248,3 +248,20 @@ def test_same_bytes_when_run_twice(zk, orc):
     first = zk.tlookup_prove(seed, Sv, idx, Tv)[1]
     again = zk.tlookup_prove(seed, Sv, idx, Tv)[1]
     assert first and first == again
+
+
+def test_random_shapes_up_to_2_pow_18(zk, orc):
+    """Sixteen seeded shapes between 2^13 and 2^18 entries with any table length that fits (rounds on 29-bit limbs of
+    every length, the first pass serving two rounds or not, tables bound early or late): proofs equal to the oracle's,
+    with and without row hints, and the same from the checked and the gathering entry points."""
+    rng = random.Random(31415)
+    for trial in range(16):
+        n = rng.randrange(13, 19)
+        l = rng.randrange(0, n + 1)
+        Sb, Tb, Sv, Tv, idx = _random_instance(orc, zk, rng, 1 << n, 1 << l, dup=trial % 4 == 0)
+        seed = rng.randbytes(32)
+        proof, _ = _compare(zk, orc, seed, Sb, Tb, Sv, Tv, idx)
+        for fn in (lambda: zk.tlookup_prove(seed, Sv, None, Tv), lambda: zk.tlookup_prove_checked(seed, Sv, idx, Tv),
+                   lambda: zk.tlookup_prove_by_rows(seed, Sv, idx, Tv)):
+            rc, again, _ = fn()
+            assert rc == 0 and again == proof, (trial, n, l)
