@@ -24,6 +24,8 @@
  * round's challenge, a pinned staging buffer for digest leaves that grows to the
  * largest table seen, and the event pool of zkmi_profile_*.  Calls from
  * different host threads share nothing; a thread's calls must not overlap.
+ * zkmi_thread_init makes that allocation at a time of the caller's choosing and
+ * zkmi_thread_release gives the pinned memory back (both are optional).
  * (fr_sum_noalloc touches none of this.)  Inputs are not modified unless the comment says "in
  * place".  `stream` is a hipStream_t passed as void* (NULL = the null stream);
  * all device work of a call is enqueued on it.  Calls that return host values
@@ -508,6 +510,15 @@ size_t zkattn_link_verify_workspace_bytes(size_t rows, size_t cols);
 int zkattn_link_verify(const uint8_t seed[32], const uint8_t* proof, size_t len, size_t rows, size_t cols, size_t K,
                        const fr_t* bases, const zkattn_link_witness* witness, zkattn_link_claims* claims, void* ws,
                        size_t ws_bytes, void* stream);
+
+/* The calling host thread's pinned state (see Ownership), for callers that want no
+ * allocation inside their first proof: zkmi_thread_init allocates it now, with
+ * the staging buffer sized for tables of up to max_table_rows rows (a longer
+ * table later makes it grow once more); zkmi_thread_release frees it (a later
+ * call allocates it again).  Neither may overlap another call of the same
+ * thread.  Errors: ZK_E_HIP if the runtime refuses. */
+int zkmi_thread_init(size_t max_table_rows);
+int zkmi_thread_release(void);
 
 /* ---- measurement support ------------------------------------------------------
  * For benchmarks: the library can time its own phases with HIP events recorded

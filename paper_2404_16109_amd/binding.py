@@ -97,6 +97,8 @@ def _load():
         "fr_mle_eval": (i32, [P(fr_t), fr_vec, P(fr_t), i32, vp, sz, vp]),
         "tlookup_workspace_bytes": (sz, [sz, sz]),
         "tlookup_multiplicities": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(ctypes.c_uint64), vp]),
+        "zkmi_thread_init": (i32, [sz]),
+        "zkmi_thread_release": (i32, []),
         "tlookup_proof_bytes": (sz, [sz]),
         "tlookup_prove": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
         "tlookup_prove_by_rows": (i32, [vp, fr_vec, vp, fr_vec, vp, sz, P(sz), P(tlookup_aux), vp, sz, vp]),
@@ -147,7 +149,7 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ["zkmi_version", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_selftest_tlookup_plan", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
+EXPORTS = ["zkmi_version", "zkmi_thread_init", "zkmi_thread_release", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_selftest_tlookup_plan", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_sum_noalloc", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
@@ -237,6 +239,14 @@ def zkmi_selftest_tlookup_plan(D, N, K=1, from_ints=False):
     rc = _lib.zkmi_selftest_tlookup_plan(D, N, K, 1 if from_ints else 0, out, 32)
     rounds = [tuple(out[4 * k:4 * k + 4]) for k in range(max(rc, 0))]
     return rc, rounds
+
+
+def zkmi_thread_init(max_table_rows):
+    return _lib.zkmi_thread_init(max_table_rows)
+
+
+def zkmi_thread_release():
+    return _lib.zkmi_thread_release()
 
 
 def zkmi_profile_enable(on):

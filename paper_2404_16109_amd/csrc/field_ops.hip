@@ -13,8 +13,10 @@
 
 namespace zkmi {
 
+static thread_local Mailbox t_mailbox;  // this host thread's pinned state
+
 int mailbox_get(Mailbox** out) {
-    static thread_local Mailbox mb;
+    Mailbox& mb = t_mailbox;
     if (!mb.words) {
         void* p = nullptr;
         ZK_HIP_TRY(hipHostMalloc(&p, kMailboxWords * sizeof(uint32_t), hipHostMallocDefault));
@@ -233,6 +235,26 @@ int zkmi_sha256(const uint8_t* data, size_t len, uint8_t out[32], int use_sha_in
     h.finish(out);
     flag = available;
     return used;
+}
+
+int zkmi_thread_init(size_t max_table_rows) {
+    Mailbox* mb;
+    ZK_TRY(mailbox_get(&mb));
+    // the staging buffer holds a table's leaf digests (one per 128 rows, 32 bytes each) and two status words
+    return mailbox_bulk(mb, div_up(max_table_rows ? max_table_rows : 1, (size_t)128) * 32 + 16);
+}
+
+int zkmi_thread_release(void) {
+    Mailbox& mb = t_mailbox;
+    hipError_t first = hipSuccess;
+    void* blocks[3] = {mb.words, mb.cmd, mb.bulk};
+    for (void* p : blocks) {
+        if (!p) continue;
+        const hipError_t e = hipHostFree(p);
+        if (first == hipSuccess) first = e;
+    }
+    mb = Mailbox();
+    return first == hipSuccess ? ZK_OK : ZK_E_HIP;
 }
 
 int zkmi_profile_enable(int on) {

@@ -68,3 +68,33 @@ def test_two_threads_prove_at_once(zk, orc):
         assert len(got[which]) == 6
         for rc, proof in got[which]:
             assert rc == 0 and proof == want[which]
+
+
+def test_thread_state_can_be_made_and_given_back(zk, orc):
+    """zkmi_thread_init allocates the calling thread's pinned state ahead of the first proof; zkmi_thread_release frees
+    it, after which the next call allocates it again: proofs are the same before, between and after."""
+    rng = random.Random(99)
+    sb, tb, S, T, idx = _instance(orc, zk, rng, 1 << 13, 1 << 9)
+    seed = rng.randbytes(32)
+    rc, want, _ = orc.tlookup_prove(seed, sb, tb)
+    assert rc == 0
+
+    def worker(out):
+        try:
+            out.append(zk.zkmi_thread_init(1 << 9))
+            out.append(zk.tlookup_prove(seed, S, idx, T)[:2])
+            out.append(zk.zkmi_thread_release())
+            out.append(zk.zkmi_thread_release())             # nothing left to free: still fine
+            out.append(zk.tlookup_prove(seed, S, idx, T)[:2])  # allocates again by itself
+            out.append(zk.zkmi_thread_release())
+        except Exception as e:
+            out.append(repr(e))
+
+    got = []
+    t = threading.Thread(target=worker, args=(got,))
+    t.start()
+    t.join()
+    torch.cuda.synchronize()
+    assert got == [0, (0, want), 0, 0, (0, want), 0]
+    # the main thread's own state is untouched by another thread's release
+    assert zk.tlookup_prove(seed, S, idx, T)[:2] == (0, want)
