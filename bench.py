@@ -529,6 +529,16 @@ def main():
     }
     if whole["hbm_bytes_measured"]:
         whole["hbm_frac_measured"] = whole["hbm_bytes_measured"] / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S
+    # every phase of the prove against the HBM roof, by the bytes it cannot avoid (per element of S: the hints read
+    # once; S read and A written by the inversion, its prefix products written and read once; A read by the hash tree;
+    # A and S read by the pass that serves the first two rounds; the folding rounds by round29_work)
+    phase_bytes = {"count": 4 * D, "inverse": 96 * D, "digest": 32 * D, "round_data": 64 * D, "round_data29": moved29}
+    phase_bound = {"count": "LDS atomics", "inverse": "hbm", "digest": "alu (SHA-256 instruction issue)",
+                   "round_data": "alu (two wavefronts per SIMD)", "round_data29": "hbm and alu, balanced"}
+    whole["phases"] = {
+        k: {"ms": round(phases[k]["ms_per_step"], 4), "algorithmic_bytes": b, "bound": phase_bound[k],
+            "hbm_frac": (b / (phases[k]["ms_per_step"] * 1e-3) / PEAK_HBM_BYTES_PER_S) if phases[k]["ms_per_step"] > 0 else None}
+        for k, b in phase_bytes.items()}
     out = {
         "metric": "tlookup_prove Fr-mul/s at D=2^%d, N=2^%d (wall ms in ms_per_step)" % (args.logD, args.logN),
         "value": fr_mul_model(D, N) / (ms * 1e-3),
