@@ -18,10 +18,11 @@
  * entry point allocates device memory; `*_workspace_bytes` says how much
  * workspace a call needs.  The library does keep a little state of its own PER
  * HOST THREAD, allocated by that thread's first call that needs it and kept until
- * the process ends: 8 KiB of pinned host memory into which kernels write the
- * handful of sums a step returns, 64 bytes of coherent pinned memory through
- * which a kernel that stays resident over several sumcheck rounds receives each
- * round's challenge, a pinned staging buffer for digest leaves that grows to the
+ * the process ends: 18 KiB of pinned host memory into which kernels write the
+ * handful of sums a step returns (and, at the end of a single tlookup proof, the
+ * five arrays of at most 64 elements from which the host finishes the rounds),
+ * 64 bytes of coherent pinned memory through which a kernel that stays resident
+ * over several sumcheck rounds receives each round's challenge, a pinned staging buffer for digest leaves that grows to the
  * largest table seen, and the event pool of zkmi_profile_*.  Calls from
  * different host threads share nothing; a thread's calls must not overlap.
  * zkmi_thread_init makes that allocation at a time of the caller's choosing and
@@ -555,7 +556,10 @@ int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream);
  * tlookup_prove_small (K = 1; ZK_E_BADARG for shapes that path does not take).
  * out (host): four integers per round -- kernel (0 first round, 1 large folding
  * round on 29-bit limbs, 2 data and table side together, 3 one workgroup per
- * round, 4 resident kernel for all remaining rounds), source of S (0 the caller's
+ * round, 4 resident kernel, 5 the first pass when it serves the first two rounds,
+ * 6 the second of those two: no kernel, 7 no kernel either: the resident kernel
+ * has handed the arrays, at most 64 elements each, to the host, which runs the
+ * round itself), source of S (0 the caller's
  * vector, 1 the caller's integer columns, 2 folded 32-bit words in the workspace,
  * 3 folded 29-bit limb planes in the workspace), arrays arrive as 32-bit words,
  * arrays leave as 32-bit words (both only meaningful for kernel 1).  Returns the

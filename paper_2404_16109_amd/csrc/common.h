@@ -126,8 +126,12 @@ struct TailGuard {
 // never outlive a host that has stopped talking to it by more than a fraction
 // of a second.
 uint32_t device_spin_limit();
-static const size_t kMailboxWords = 2048;
 static const size_t kMailboxFlag = 2040;    // the flag word
+// Behind the result words: the arrays a single proof hands to the host once they are short enough for the host to
+// finish the sumcheck by itself (five arrays of at most kMailboxShipEntries elements, eight words each).
+static const size_t kMailboxShip = 2048;
+static const size_t kMailboxShipEntries = 64;
+static const size_t kMailboxWords = kMailboxShip + 5 * kMailboxShipEntries * 8;
 // A tlookup instance's round sums (eleven values) and final claims start at
 // kMailboxSlot * instance; up to eight instances share the mailbox.
 static const size_t kMailboxSlot = 96;

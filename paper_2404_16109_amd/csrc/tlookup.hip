@@ -510,7 +510,9 @@ enum RoundKernel {
     kRoundOneGroup = 3,  // k_round_small: at most 256 pairs, one workgroup, one round per launch (batched proofs)
     kRoundResident = 4,  // k_tlookup_tail: at most 256 pairs, all remaining rounds in one resident kernel
     kRoundFirstTwo = 5,  // k_round_data01: the first pass, which yields the sums of the first two rounds
-    kRoundNoPass = 6     // the second round after kRoundFirstTwo: the host has everything, nothing is launched
+    kRoundNoPass = 6,    // the second round after kRoundFirstTwo: the host has everything, nothing is launched
+    kRoundHost = 7       // at most kHostPairs pairs of a single proof: the resident kernel has handed the arrays to the
+                         // host, which runs the round itself (HostTail)
 };
 enum SSource {
     kSFromCaller = 0,  // the caller's vector of field elements
@@ -529,6 +531,72 @@ struct RoundPlan {
     bool in32, out32;  // kRound29: the data arrays arrive as / leave as 32-bit words
     bool fold2;        // kRound29: binds the two previous variables at once (after kRoundFirstTwo, kRoundNoPass)
     int lazy_after;    // folds since the data arrays were last fully reduced, if they are in 29-bit planes now
+};
+
+// The last rounds of a single proof on the host.  A round of the resident kernel costs a trip to the host and back
+// (about thirty microseconds) whatever it computes; a round of 32 pairs is some six hundred multiplications, which
+// the host does in a fraction of that.  So once a round has at most kHostPairs pairs, the resident kernel binds the
+// last challenge, writes the five arrays (at most 64 elements each) into the mailbox and ends, and the host computes
+// the remaining rounds' sums, folds and final claims from them: the same sums over the same arrays (Section 3.3's
+// sumcheck, Section 4's summand), exact arithmetic, so the same bytes.
+static const size_t kHostPairs = kMailboxShipEntries / 2;
+
+struct HostTail {
+    host::F A[kMailboxShipEntries], S[kMailboxShipEntries], B[kMailboxShipEntries], M[kMailboxShipEntries],
+        T[kMailboxShipEntries];
+    host::F W[kHostPairs];  // this round's weights e~(u_rest, p), p < half
+    bool on = false;
+    int first = 0;  // the first round the host runs
+
+    // e~((u_0 .. u_{m-1}), p) for p < 2^m, u_0 belonging to the top bit of p
+    void weights(const host::F* u, int m) {
+        using namespace host;
+        W[0] = one();
+        for (int t = 0; t < m; ++t) {
+            for (size_t e = (size_t)1 << t; e-- > 0;) {
+                const F hi = mul(W[e], u[t]);
+                W[2 * e] = sub(W[e], hi);
+                W[2 * e + 1] = hi;
+            }
+        }
+    }
+    // the round's eleven sums in the order the kernels report them: q0, q1, qinf, sA0, sA1, then the table side's
+    // t0, t1, tinf, m0, m1, minf (zero unless a table variable is being bound)
+    void sums(size_t half, bool table_round, const host::F& beta, host::F out[11]) const {
+        using namespace host;
+        for (int q = 0; q < 11; ++q) out[q] = zero();
+        for (size_t p = 0; p < half; ++p) {
+            const F wa0 = mul(W[p], A[p]), wa1 = mul(W[p], A[p + half]);
+            out[0] = add(out[0], mul(wa0, add(S[p], beta)));
+            out[1] = add(out[1], mul(wa1, add(S[p + half], beta)));
+            out[2] = add(out[2], mul(sub(wa1, wa0), sub(S[p + half], S[p])));
+            out[3] = add(out[3], A[p]);
+            out[4] = add(out[4], A[p + half]);
+            if (!table_round) continue;
+            const F wb0 = mul(W[p], B[p]), wb1 = mul(W[p], B[p + half]);
+            out[5] = add(out[5], mul(wb0, add(T[p], beta)));
+            out[6] = add(out[6], mul(wb1, add(T[p + half], beta)));
+            out[7] = add(out[7], mul(sub(wb1, wb0), sub(T[p + half], T[p])));
+            out[8] = add(out[8], mul(B[p], M[p]));
+            out[9] = add(out[9], mul(B[p + half], M[p + half]));
+            out[10] = add(out[10], mul(sub(B[p + half], B[p]), sub(M[p + half], M[p])));
+        }
+    }
+    // binds the round's variable to r and moves the weights on to the next round
+    void fold(size_t half, bool table_round, const host::F& r) {
+        using namespace host;
+        auto bind = [&](F* x) {
+            for (size_t p = 0; p < half; ++p) x[p] = add(x[p], mul(r, sub(x[p + half], x[p])));
+        };
+        bind(A);
+        bind(S);
+        if (table_round) {
+            bind(B);
+            bind(M);
+            bind(T);
+        }
+        for (size_t p = 0; p < half / 2; ++p) W[p] = add(W[p], W[p + half / 2]);  // the next variable summed out
+    }
 };
 
 static bool round_on_29_bits(int n, int h, int k) {
@@ -565,7 +633,8 @@ static RoundPlan plan_round(int n, int h, int k, size_t K, bool from_ints, int l
         pl.s_source = kSFromCaller;
         return pl;
     }
-    if (resident_running || (pl.tiny && K == 1 && n - k <= kTailRoundsMax)) pl.kernel = kRoundResident;
+    if (resident_running && K == 1 && half <= kHostPairs) pl.kernel = kRoundHost;
+    else if (resident_running || (pl.tiny && K == 1 && n - k <= kTailRoundsMax)) pl.kernel = kRoundResident;
     else if (pl.tiny) pl.kernel = kRoundOneGroup;
     else if (pl.table_round && k > 0) pl.kernel = kRoundBoth;
     else if (pl.use29) pl.kernel = kRound29;
@@ -968,6 +1037,7 @@ static int prove_core(const ProveCall& c) {
     TlookupTailArgs tail;
     int tail_first = -1;  // the round the resident kernel was launched for, if it is running
     TailGuard tail_guard{mb, stream};
+    HostTail host_tail;
     for (int k = 0; k < n; ++k) {
         // The 29-bit kernel sums one side of the round only (X = 0, or X = 1 with side1); the other side's two sums
         // follow from what the prover has already sent: sA0 + sA1 is the previous round's sum of A at its challenge,
@@ -1001,10 +1071,14 @@ static int prove_core(const ProveCall& c) {
             tail.M = PairArray{I.w.M, N, I.w.M, N};
             tail.beta = to_dev(beta);
             tail.r_prev = to_dev(r_prev);
-            tail.nrounds = n - k;
+            // the kernel's rounds: up to the first one short enough for the host (kRoundHost), if there is one
+            int k_host = n - 6 > k + 1 ? n - 6 : k + 1;  // the first j > k with 2^(n-j-1) <= kHostPairs
+            static_assert(kHostPairs == 32, "k_host above is written for 32 pairs");
+            if (k_host > n) k_host = n;
+            tail.nrounds = k_host - k;
             uint32_t* b_at = I.b_cur;
             size_t b_at_stride = I.b_cur_stride;
-            for (int j = k; j < n; ++j) {
+            for (int j = k; j < k_host; ++j) {
                 TailRound& rd = tail.round[j - k];
                 Moving m = moving_arrays(j, I, b_at, b_at_stride, j <= 1);
                 rd.S = m.S;
@@ -1015,6 +1089,26 @@ static int prove_core(const ProveCall& c) {
                 rd.table = j < h ? 0 : j == h ? 1 : 2;
             }
             tail.fin = final_arrays(I, b_at, b_at_stride);
+            if (k_host < n) {
+                // what the kernel hands over after round k_host - 1: the data arrays with that round's variable still
+                // to bind, the table's arrays likewise once its variables are being bound, as they came before that
+                const int j_last = k_host - 1;
+                const uint32_t n_data = (uint32_t)1 << (n - k_host);
+                const bool table_bound = j_last >= h;
+                const uint32_t n_table = table_bound ? n_data : (uint32_t)N;
+                if (n_data > kMailboxShipEntries || n_table > kMailboxShipEntries) return ZK_E_BADARG;  // cannot happen: N <= 2^(n - h)
+                TailShip& sh = tail.ship;
+                sh.out = mb->words + kMailboxShip;
+                sh.p[0] = I.w.A; sh.stride[0] = D; sh.n_out[0] = n_data; sh.fold[0] = 1;
+                sh.p[1] = I.w.Sf; sh.stride[1] = D / 2; sh.n_out[1] = n_data; sh.fold[1] = 1;
+                sh.p[2] = b_at; sh.stride[2] = b_at_stride; sh.n_out[2] = n_table; sh.fold[2] = table_bound;
+                sh.p[3] = I.w.M; sh.stride[3] = N; sh.n_out[3] = n_table; sh.fold[3] = table_bound;
+                if (j_last >= h + 1) { sh.p[4] = I.w.Tf; sh.stride[4] = N / 2; }
+                else { sh.p[4] = I.T.limbs; sh.stride[4] = I.T.stride; }
+                sh.n_out[4] = n_table; sh.fold[4] = table_bound;
+                host_tail.on = true;
+                host_tail.first = k_host;
+            }
             tail.out_words = I.words;
             tail.words = mb->words;
             tail.cmd = mb->cmd;
@@ -1030,7 +1124,18 @@ static int prove_core(const ProveCall& c) {
             tail_guard.armed = true;
             tail_first = k;
         }
-        const uint32_t seq = tail_first >= 0 ? tail.out_seq[k - tail_first] : any_launch ? mb->next_seq() : 0;
+        const bool host_round = host_tail.on && k >= host_tail.first;
+        if (host_round && k == host_tail.first) {
+            // the resident kernel's last message: the arrays, from here on the host's
+            ZK_TRY(mailbox_wait(mb, tail.out_seq[tail.nrounds], stream));
+            tail_guard.armed = false;
+            const uint32_t* at = mb->words + kMailboxShip;
+            F* const arrays[5] = {host_tail.A, host_tail.S, host_tail.B, host_tail.M, host_tail.T};
+            for (int q = 0; q < 5; ++q)
+                for (uint32_t j = 0; j < tail.ship.n_out[q]; ++j, at += 8) arrays[q][j] = from_dev(at);
+            host_tail.weights(u + k + 1, n - k - 1);
+        }
+        const uint32_t seq = host_round ? 0 : tail_first >= 0 ? tail.out_seq[k - tail_first] : any_launch ? mb->next_seq() : 0;
         for (size_t i = 0; i < K && tail_first < 0; ++i) {
             Instance& I = inst[i];
             if (k < I.skip || plans[i].kernel == kRoundNoPass) continue;
@@ -1233,7 +1338,7 @@ static int prove_core(const ProveCall& c) {
                 }
             if (!shared) I.inv_den = inv(mul(wD, e_side[side1 ? 0 : 1]));
         }
-        if (any_launch) ZK_TRY(mailbox_wait(mb, seq, stream));
+        if (any_launch && !host_round) ZK_TRY(mailbox_wait(mb, seq, stream));
         if (k > 0 || any_launch) read_table_consts();
 
         F e[4], g[4];
@@ -1257,7 +1362,15 @@ static int prove_core(const ProveCall& c) {
             I.half_pow = mul(I.half_pow, inv2);
             const uint32_t* sums = I.words;
             F q0, q1, qi, sA0, sA1;
-            if (plan.kernel == kRoundFirstTwo) {
+            F hs[11];  // kRoundHost: the round's sums, computed here
+            if (plan.kernel == kRoundHost) {
+                host_tail.sums((size_t)1 << (I.n - kk - 1), table_round, beta, hs);
+                q0 = hs[0];
+                q1 = hs[1];
+                qi = hs[2];
+                sA0 = hs[3];
+                sA1 = hs[4];
+            } else if (plan.kernel == kRoundFirstTwo) {
                 // the pass has summed, with the NEXT round's weights, what this round and the next are made of
                 // (round01_dev.h): this round's leading coefficient splits by the next variable
                 for (int q = 0; q < 9; ++q) I.pass01[q] = from_dev(sums + 8 * q);
@@ -1318,7 +1431,10 @@ static int prove_core(const ProveCall& c) {
             F q[4], sa[4], tq[4], tm[4];
             quad_values(q, q0, q1, qi);
             line_values(sa, sA0, sA1);
-            if (table_round) {
+            if (table_round && plan.kernel == kRoundHost) {
+                quad_values(tq, hs[5], hs[6], hs[7]);
+                quad_values(tm, hs[8], hs[9], hs[10]);
+            } else if (table_round) {
                 quad_values(tq, from_dev(sums + 40), from_dev(sums + 48), from_dev(sums + 56));
                 quad_values(tm, from_dev(sums + 64), from_dev(sums + 72), from_dev(sums + 80));
             }
@@ -1343,12 +1459,17 @@ static int prove_core(const ProveCall& c) {
         }
         r_prev2 = r_prev;
         r_prev = r;
-        if (tail_first >= 0) mailbox_send_challenge(mb, tail.cmd_seq[k - tail_first], to_dev(r).l);
+        if (tail_first >= 0 && k - tail_first < tail.nrounds) mailbox_send_challenge(mb, tail.cmd_seq[k - tail_first], to_dev(r).l);
+        if (host_round) host_tail.fold((size_t)1 << (n - k - 1), plans[0].table_round, r);
     }
 
     // -- final claims -------------------------------------------------------------------------------------
     {
-        if (tail_first >= 0) {
+        if (host_tail.on) {
+            // the host has bound the last variable itself: each array's first element is its claim
+            const F* const arrays[5] = {host_tail.A, host_tail.S, host_tail.B, host_tail.M, host_tail.T};
+            for (int q = 0; q < 5; ++q) to_device_limbs(inst[0].words + 8 * q, arrays[q][0]);
+        } else if (tail_first >= 0) {
             // the resident kernel writes them after the last challenge
             ZK_TRY(mailbox_wait(mb, tail.out_seq[tail.nrounds], stream));
             tail_guard.armed = false;

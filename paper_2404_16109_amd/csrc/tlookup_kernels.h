@@ -944,12 +944,24 @@ struct TailRound {
     int table;          // as k_round_small's TABLE
 };
 
+// What the resident kernel hands to the host after its last round, if the host runs the remaining rounds itself:
+// the five arrays A, S, B, m, T as they stand then, each with its pending variable (if it has one) bound to the
+// last challenge, n_out[q] elements of array q one after the other, eight Montgomery words per element.
+struct TailShip {
+    uint32_t* out;  // pinned host memory; null: the kernel runs every round and writes the final claims
+    const uint32_t* p[5];
+    size_t stride[5];
+    uint32_t n_out[5];
+    int fold[5];
+};
+
 struct TlookupTailArgs {
     PairArray A, M;
     Fr beta, r_prev;
     TailRound round[kTailRoundsMax];
     int nrounds;
     FinalArgs fin;      // where the five arrays end up (fin.r is not used)
+    TailShip ship;
     uint32_t* out_words;   // this proof's slot in the mailbox
     uint32_t* words;       // the mailbox (flag)
     const uint32_t* cmd;
@@ -1056,7 +1068,23 @@ static __global__ void __launch_bounds__(kSmallThreads) k_tlookup_tail(TlookupTa
         __syncthreads();
         if (!ok) break;  // the same for every thread
     }
-    if (ok && threadIdx.x < (unsigned)g.fin.count) {
+    if (ok && g.ship.out) {
+        // the host takes over: the arrays with the last challenge bound (at most 64 elements each)
+        const uint32_t total = g.ship.n_out[0] + g.ship.n_out[1] + g.ship.n_out[2] + g.ship.n_out[3] + g.ship.n_out[4];
+        for (uint32_t t = threadIdx.x; t < total; t += kSmallThreads) {
+            int q = 0;
+            uint32_t j = t;
+            while (q < 4 && j >= g.ship.n_out[q]) {
+                j -= g.ship.n_out[q];
+                ++q;
+            }
+            Fr v = fr_load(g.ship.p[q], g.ship.stride[q], j);
+            if (g.ship.fold[q]) v = fr_fold(v, fr_load(g.ship.p[q], g.ship.stride[q], j + g.ship.n_out[q]), r);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) g.ship.out[8 * (size_t)t + k] = v.l[k];
+            mailbox_written();
+        }
+    } else if (ok && threadIdx.x < (unsigned)g.fin.count) {
         const int q = threadIdx.x;
         Fr v = fr_load(g.fin.p[q], g.fin.stride[q], 0);
         if (g.fin.fold[q]) v = fr_fold(v, fr_load(g.fin.p[q], g.fin.stride[q], 1), r);

@@ -5,10 +5,12 @@ never has a source of S the library has no kernel for, integers are read only by
 the two kernels written for them, and a round reads the layout the round before
 it has written.  From a vector of field elements the first pass may serve the
 first two rounds (FIRST_TWO, then NO_PASS: nothing launched), after which the
-29-bit kernel binds two variables at once from the caller's arrays."""
+29-bit kernel binds two variables at once from the caller's arrays.  The last
+rounds of a single proof (at most 32 pairs, once the resident kernel has run) are
+the host's (HOST)."""
 import pytest
 
-FIRST, R29, BOTH, ONE_GROUP, RESIDENT, FIRST_TWO, NO_PASS = 0, 1, 2, 3, 4, 5, 6
+FIRST, R29, BOTH, ONE_GROUP, RESIDENT, FIRST_TWO, NO_PASS, HOST = 0, 1, 2, 3, 4, 5, 6, 7
 CALLER, INTS, WORDS, PLANES = 0, 1, 2, 3
 
 
@@ -50,14 +52,14 @@ def test_plan_of_the_shape_that_once_faulted():
     assert rc == 12
     assert rounds[0][:2] == (FIRST, INTS)
     assert rounds[1][:3] == (R29, INTS, 1)
-    # pairs 1024 (round 1) and 512 (round 2) run on 29-bit limbs, 256 pairs and below in the resident kernel
-    assert [r[0] for r in rounds] == [FIRST, R29, R29] + [RESIDENT] * 9
+    # pairs 1024 (round 1) and 512 (round 2) run on 29-bit limbs, 256 to 64 pairs in the resident kernel, the rest on the host
+    assert [r[0] for r in rounds] == [FIRST, R29, R29] + [RESIDENT] * 3 + [HOST] * 6
     assert rounds[2][1] == PLANES and rounds[2][3] == 1      # reads planes, writes words for the resident kernel
     assert all(r[1] == WORDS for r in rounds[3:])
     _check_chain(rounds)
     # the same shape from a vector: the first pass serves two rounds, the third binds both variables from the caller's S
     rc, from_vec = _plan(zk, 1 << 12, 1 << 4)
-    assert [r[0] for r in from_vec] == [FIRST_TWO, NO_PASS, R29] + [RESIDENT] * 9
+    assert [r[0] for r in from_vec] == [FIRST_TWO, NO_PASS, R29] + [RESIDENT] * 3 + [HOST] * 6
     assert [r[1] for r in from_vec[:3]] == [CALLER] * 3 and from_vec[2][2:] == (1, 1) and from_vec[3:] == rounds[3:]
     _check_chain(from_vec)
 
@@ -69,7 +71,7 @@ def test_plan_of_the_headline_shape_matches_the_bench_model():
         rc, rounds = _plan(zk, 1 << 25, 1 << 16, from_ints=from_ints)
         assert rc == 25
         assert [k for k, r in enumerate(rounds) if r[0] == R29] == bench.rounds_on_29_bits(1 << 25, 1 << 16, from_ints)
-        assert [r[0] for r in rounds[9:16]] == [BOTH] * 7 and [r[0] for r in rounds[16:]] == [RESIDENT] * 9
+        assert [r[0] for r in rounds[9:16]] == [BOTH] * 7 and [r[0] for r in rounds[16:]] == [RESIDENT] * 3 + [HOST] * 6
         # eight folds at most before reduced words are written again: the first 29-bit round arrives as words, round 8
         # leaves as words
         first29 = 1 if from_ints else 2
@@ -88,7 +90,15 @@ def test_every_shape_has_a_kernel_for_every_round():
                 assert rc == n
                 _check_chain(rounds)
                 if K == 2:
-                    assert all(r[0] != RESIDENT for r in rounds)
+                    assert all(r[0] not in (RESIDENT, HOST) for r in rounds)
+                # the host's rounds: the last ones, at most 32 pairs each, and only after the resident kernel has run
+                kinds = [r[0] for r in rounds]
+                if HOST in kinds:
+                    first = kinds.index(HOST)
+                    assert first >= 1 and kinds[first - 1] == RESIDENT and kinds[first:] == [HOST] * (n - first)
+                    assert first == max(n - 6, kinds.index(RESIDENT) + 1)
+                elif RESIDENT in kinds:
+                    assert kinds.index(RESIDENT) == n - 1  # the resident kernel's only round is the last one
             rc, rounds = _plan(zk, D, N, from_ints=True)
             takes_ints = zk.tlookup_small_workspace_bytes(D, N) == -(-zk.tlookup_workspace_bytes(D, N) // 256) * 256
             if rc < 0:
