@@ -381,8 +381,8 @@ int tlookup_verify_multi(const uint8_t seed[32], const uint8_t* proof, size_t le
 /* ---- product sumcheck and matrix multiplication (Sections 3.3, 6.1.1) -------- */
 
 /* Sumcheck of sum_{x in {0,1}^d} a(x) b(x) = claim over vectors of 2^d elements
- * (device, both folded IN PLACE: on return element 0 of each holds its final
- * value, the rest is scratch).  Round polynomials (degree 2) are sent as values
+ * (device, both folded IN PLACE: they are the prover's scratch, their contents
+ * on return are unspecified; the final values are in the proof).  Round polynomials (degree 2) are sent as values
  * at X = 0,1,2.  Transcript: SHA256("zkmi/sumcheck-product/v1" || seed || LE64 d);
  * absorb("claim", claim); per round absorb("g", 3 values), r = challenge("r");
  * absorb("final", a~(r), b~(r)).

@@ -48,8 +48,19 @@ __global__ void __launch_bounds__(kBlock) k_round_product(ProductRoundArgs g) {
 // challenge on the command channel, folds and goes on; at the end it writes the
 // two final values.  Every thread takes every barrier, and a wait that fails
 // ends the kernel for all of them.
+//
+// The very last rounds are the host's: a round of 64 pairs is a few hundred
+// multiplications, which the host does in a fraction of the thirty microseconds a
+// trip to it and back costs.  So the kernel stops before the first round of at
+// most kHostPairs pairs (if it has run a round by then), binds the last challenge,
+// writes both arrays (at most 2 kHostPairs elements each) behind the mailbox's
+// result words and ends; the host computes the remaining rounds' sums, folds and
+// the two final values itself -- the same sums over the same values, exact
+// arithmetic, so the same bytes.
 static const int kTailThreads = 1024;
 static const size_t kTailPairs = 1024;
+static const size_t kHostPairs = 64;
+static_assert(2 * 2 * kHostPairs * 8 <= kMailboxWords - kMailboxShip, "both arrays fit behind the result words");
 
 struct ProductTailArgs {
     uint32_t* a;
@@ -65,6 +76,9 @@ struct ProductTailArgs {
     uint32_t out_seq[33];  // [i]: the sums of round i are there; [nrounds]: the final values are
     uint32_t cmd_seq[32];  // [i]: the challenge of round i
     uint32_t spin_limit;
+    // not zero: after the last round both arrays go to the host instead of the final values, ship_count elements
+    // of a, then of b, each with that round's variable bound, eight words per element from words[kMailboxShip] on
+    uint32_t ship_count;
 };
 
 static __global__ void __launch_bounds__(kTailThreads) k_product_tail(ProductTailArgs g) {
@@ -116,7 +130,18 @@ static __global__ void __launch_bounds__(kTailThreads) k_product_tail(ProductTai
         if (!ok) break;   // the same for every thread
         fold = true;
     }
-    if (ok && threadIdx.x < 2) {
+    if (ok && g.ship_count) {
+        for (uint32_t t = threadIdx.x; t < 2 * g.ship_count; t += kTailThreads) {
+            const bool first = t < g.ship_count;
+            const uint32_t* arr = first ? g.a : g.b;
+            const size_t stride = first ? g.as : g.bs;
+            const uint32_t j = first ? t : t - g.ship_count;
+            Fr v = fr_fold(fr_load(arr, stride, j), fr_load(arr, stride, j + g.ship_count), r);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) g.words[kMailboxShip + 8 * (size_t)t + k] = v.l[k];
+            mailbox_written();
+        }
+    } else if (ok && threadIdx.x < 2) {
         const uint32_t* arr = threadIdx.x == 0 ? g.a : g.b;
         const size_t stride = threadIdx.x == 0 ? g.as : g.bs;
         Fr v = fr_fold(fr_load(arr, stride, 0), fr_load(arr, stride, 1), r);
@@ -203,7 +228,11 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         memset(&g, 0, sizeof g);
         g.a = a; g.as = as; g.b = b; g.bs = bs;
         g.half0 = (size_t)1 << (d - tail_first - 1);
-        g.nrounds = d - tail_first;
+        // the kernel's rounds end before the first one (after its own first) of at most kHostPairs pairs
+        int k_host = tail_first + 1;
+        while (k_host < d && ((size_t)1 << (d - k_host - 1)) > kHostPairs) ++k_host;
+        g.nrounds = k_host - tail_first;
+        g.ship_count = k_host < d ? (uint32_t)1 << (d - k_host) : 0;
         g.fold_first = tail_first > 0;
         g.r_prev = to_dev(r_prev);
         g.words = mb->words;
@@ -225,6 +254,28 @@ static int product_rounds_run(host::Transcript& tr, uint32_t* a, size_t as, uint
         guard.armed = false;
         ZK_HIP_TRY(hipStreamSynchronize(stream));  // everything of this call has left the device
         F fa = from_dev(mb->words), fb = from_dev(mb->words + 8);
+        if (g.ship_count) {
+            // the host's rounds, on the arrays the kernel has handed over
+            F ha[2 * kHostPairs], hb[2 * kHostPairs];
+            const uint32_t* at = mb->words + kMailboxShip;
+            for (uint32_t j = 0; j < g.ship_count; ++j, at += 8) ha[j] = from_dev(at);
+            for (uint32_t j = 0; j < g.ship_count; ++j, at += 8) hb[j] = from_dev(at);
+            for (size_t half = g.ship_count / 2; half >= 1; half >>= 1) {
+                F g0 = zero(), g1 = zero(), lead = zero();
+                for (size_t p = 0; p < half; ++p) {
+                    g0 = add(g0, mul(ha[p], hb[p]));
+                    g1 = add(g1, mul(ha[p + half], hb[p + half]));
+                    lead = add(lead, mul(sub(ha[p + half], ha[p]), sub(hb[p + half], hb[p])));
+                }
+                emit_round(g0, g1, lead);
+                for (size_t p = 0; p < half; ++p) {
+                    ha[p] = add(ha[p], mul(r_prev, sub(ha[p + half], ha[p])));
+                    hb[p] = add(hb[p], mul(r_prev, sub(hb[p + half], hb[p])));
+                }
+            }
+            fa = ha[0];
+            fb = hb[0];
+        }
         to_bytes(out, fa);
         to_bytes(out + 32, fb);
         tr.absorb("final", out, 64);
