@@ -508,7 +508,7 @@ enum RoundKernel {
     kRound29 = 1,        // k_round_data29: large folding rounds on 29-bit limbs
     kRoundBoth = 2,      // k_round_both: data and table side, the table's variables being bound
     kRoundOneGroup = 3,  // k_round_small: at most 256 pairs, one workgroup, one round per launch (batched proofs)
-    kRoundResident = 4,  // k_tlookup_tail: at most 256 pairs, all remaining rounds in one resident kernel
+    kRoundResident = 4,  // k_tlookup_tail: at most 256 pairs, one resident kernel over these rounds (until kRoundHost)
     kRoundFirstTwo = 5,  // k_round_data01: the first pass, which yields the sums of the first two rounds
     kRoundNoPass = 6,    // the second round after kRoundFirstTwo: the host has everything, nothing is launched
     kRoundHost = 7       // at most kHostPairs pairs of a single proof: the resident kernel has handed the arrays to the
@@ -1033,7 +1033,7 @@ static int prove_core(const ProveCall& c) {
         f.fold[4] = t_fold;
         return f;
     };
-    // A single proof runs all its small rounds in one resident kernel (k_tlookup_tail).
+    // A single proof runs its small rounds in one resident kernel (k_tlookup_tail) and the very last on the host.
     TlookupTailArgs tail;
     int tail_first = -1;  // the round the resident kernel was launched for, if it is running
     TailGuard tail_guard{mb, stream};
