@@ -566,6 +566,23 @@ int zkmi_selftest_resident_wait(void* ws, size_t ws_bytes, void* stream);
  * number of rounds, ZK_E_BUFSZ if cap_rounds is below it. */
 int zkmi_selftest_tlookup_plan(size_t D, size_t N, size_t K, int from_ints, int32_t* out, size_t cap_rounds);
 
+/* The rounds a single tlookup proof leaves to the host (kernel code 7 above), on
+ * arrays and challenges of the caller's choosing; no GPU is touched.  All
+ * pointers are host memory, all elements canonical.  A, S: n_data elements
+ * (2..64, a power of two); B, M, T: n_table elements (a power of two, at most
+ * n_data).  The rounds bind log2(n_data) variables, the top bit of the index
+ * first; the table's arrays take part from the round on in which as many
+ * variables are left as they have.  u_rest: the log2(n_data) - 1 coordinates
+ * of u that belong to the variables after the first of these rounds (weights
+ * e~(u_rest, p) for its pairs p).  challenges: one per round.  sums: eleven per
+ * round (q0, q1, qinf, sA0, sA1, then the table side's t0, t1, tinf, m0, m1, minf,
+ * zero while the table's arrays take no part), as the kernels report them
+ * (Section 4's summand split into its sums over a round's pairs).  finals: what
+ * is left of A, S, B, m, T.  Returns the number of rounds. */
+int zkmi_selftest_host_rounds(const fr_t* A, const fr_t* S, const fr_t* B, const fr_t* M, const fr_t* T, size_t n_data,
+                              size_t n_table, const fr_t* u_rest, const fr_t* beta, const fr_t* challenges, fr_t* sums,
+                              fr_t* finals);
+
 /* SHA-256 of `len` bytes at `data` (host) into out (host, 32 bytes): the hash
  * the transcript is built on, exported so that it can be checked on its own.
  * use_sha_instructions: 0 = the portable compression function, 1 = the x86 SHA

@@ -74,6 +74,7 @@ def _load():
         "zkmi_sha256": (i32, [ctypes.c_char_p, sz, ctypes.c_char_p, i32]),
         "zkmi_selftest_resident_wait": (i32, [vp, sz, vp]),
         "zkmi_selftest_tlookup_plan": (i32, [sz, sz, sz, i32, P(ctypes.c_int32), sz]),
+        "zkmi_selftest_host_rounds": (i32, [P(fr_t)] * 5 + [sz, sz, P(fr_t), P(fr_t), P(fr_t), P(fr_t), P(fr_t)]),
         "zkmi_profile_enable": (i32, [i32]),
         "zkmi_profile_reset": (i32, []),
         "zkmi_profile_query": (i32, [ctypes.c_char_p, P(ctypes.c_uint64), P(ctypes.c_double)]),
@@ -149,7 +150,7 @@ def _load():
 
 
 _lib = _load()
-EXPORTS = ["zkmi_version", "zkmi_thread_init", "zkmi_thread_release", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_selftest_tlookup_plan", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
+EXPORTS = ["zkmi_version", "zkmi_thread_init", "zkmi_thread_release", "zkmi_sha256", "zkmi_selftest_resident_wait", "zkmi_selftest_tlookup_plan", "zkmi_selftest_host_rounds", "zkmi_profile_enable", "zkmi_profile_reset", "zkmi_profile_query", "fr_constants", "fr_from_i32", "fr_from_canonical", "fr_to_canonical", "fr_add", "fr_sub",
            "fr_mul", "fr_add_scalar", "fr_mul_scalar", "fr_axpy", "fr_batch_inverse_workspace_bytes",
            "fr_batch_inverse", "fr_sum_workspace_bytes", "fr_sum", "fr_sum_noalloc", "fr_eq_table", "fr_mle_eval_workspace_bytes",
            "fr_mle_eval", "tlookup_workspace_bytes", "tlookup_multiplicities", "tlookup_proof_bytes", "tlookup_prove",
@@ -239,6 +240,21 @@ def zkmi_selftest_tlookup_plan(D, N, K=1, from_ints=False):
     rc = _lib.zkmi_selftest_tlookup_plan(D, N, K, 1 if from_ints else 0, out, 32)
     rounds = [tuple(out[4 * k:4 * k + 4]) for k in range(max(rc, 0))]
     return rc, rounds
+
+
+def zkmi_selftest_host_rounds(A, S, B, M, T, u_rest, beta, challenges):
+    """The host's rounds on lists of integers; returns (rc, sums: 11 per round, finals: 5); runs on the host only."""
+    def arr(xs):
+        out = (fr_t * max(len(xs), 1))()
+        for i, x in enumerate(xs):
+            out[i] = _fr(x)
+        return out
+    rounds = max(len(A).bit_length() - 1, 1)
+    sums = (fr_t * (11 * rounds))()
+    finals = (fr_t * 5)()
+    rc = _lib.zkmi_selftest_host_rounds(arr(A), arr(S), arr(B), arr(M), arr(T), len(A), len(B), arr(u_rest), _fr(beta),
+                                        arr(challenges), sums, finals)
+    return rc, [_fr_int(x) for x in sums], [_fr_int(x) for x in finals]
 
 
 def zkmi_thread_init(max_table_rows):

@@ -1898,6 +1898,45 @@ int zkmi_selftest_tlookup_plan(size_t D, size_t N, size_t K, int from_ints, int3
     return n;
 }
 
+// The host's rounds (HostTail) on arrays and challenges of the caller's choosing: no GPU is touched.
+int zkmi_selftest_host_rounds(const fr_t* A, const fr_t* S, const fr_t* B, const fr_t* M, const fr_t* T, size_t n_data,
+                              size_t n_table, const fr_t* u_rest, const fr_t* beta, const fr_t* challenges, fr_t* sums,
+                              fr_t* finals) {
+    using namespace host;
+    if (!A || !S || !B || !M || !T || !beta || !sums || !finals) return ZK_E_BADARG;
+    if (!is_pow2(n_data) || !is_pow2(n_table) || n_data < 2 || n_data > kMailboxShipEntries || n_table > n_data) return ZK_E_BADARG;
+    const int d = log2_floor(n_data);
+    if (d > 1 && !u_rest) return ZK_E_BADARG;
+    if (!challenges) return ZK_E_BADARG;
+    for (int t = 0; t < d - 1; ++t)
+        if (!canonical_in_range(u_rest[t])) return ZK_E_BADARG;
+    for (int t = 0; t < d; ++t)
+        if (!canonical_in_range(challenges[t])) return ZK_E_BADARG;
+    if (!canonical_in_range(*beta)) return ZK_E_BADARG;
+    HostTail ht;
+    const fr_t* const src[5] = {A, S, B, M, T};
+    F* const dst[5] = {ht.A, ht.S, ht.B, ht.M, ht.T};
+    for (int q = 0; q < 5; ++q)
+        for (size_t j = 0; j < (q < 2 ? n_data : n_table); ++j) {
+            if (!canonical_in_range(src[q][j])) return ZK_E_BADARG;
+            dst[q][j] = from_canonical(src[q][j]);
+        }
+    F us[8];
+    for (int t = 0; t < d - 1; ++t) us[t] = from_canonical(u_rest[t]);
+    ht.weights(us, d - 1);
+    const F b = from_canonical(*beta);
+    int round = 0;
+    for (size_t half = n_data / 2; half >= 1; half >>= 1, ++round) {
+        const bool table_round = 2 * half <= n_table;
+        F out[11];
+        ht.sums(half, table_round, b, out);
+        for (int q = 0; q < 11; ++q) sums[11 * round + q] = to_canonical(out[q]);
+        ht.fold(half, table_round, from_canonical(challenges[round]));
+    }
+    for (int q = 0; q < 5; ++q) finals[q] = to_canonical(dst[q][0]);
+    return d;
+}
+
 int tlookup_prove_checked(const uint8_t seed[32], fr_vec S, const uint32_t* idx, fr_vec T, uint8_t* proof, size_t cap,
                           size_t* len, tlookup_aux* aux, void* ws, size_t ws_bytes, void* stream) {
     return prove_single(seed, S, idx, T, nullptr, false, proof, cap, len, aux, ws, ws_bytes, stream, true);
