@@ -63,6 +63,23 @@ __device__ __forceinline__ uint32_t hash_find(const uint32_t* __restrict__ slots
     return kEmptySlot;
 }
 
+// The same through the row-major copy of the table (k_canon_rows): a candidate row
+// is one 32-byte access instead of eight words from eight limb planes.
+__device__ __forceinline__ uint32_t hash_find_rows(const uint32_t* __restrict__ slots, uint32_t cap_mask,
+                                                   const uint4* __restrict__ rows, const Fr& v) {
+    uint32_t pos = fr_hash(v) & cap_mask;
+    for (uint32_t step = 0; step <= cap_mask; ++step) {
+        uint32_t cur = slots[pos];
+        if (cur == kEmptySlot) return kEmptySlot;
+        const uint4 lo = rows[2 * (size_t)cur], hi = rows[2 * (size_t)cur + 1];
+        const uint32_t diff = (lo.x ^ v.l[0]) | (lo.y ^ v.l[1]) | (lo.z ^ v.l[2]) | (lo.w ^ v.l[3]) |
+                              (hi.x ^ v.l[4]) | (hi.y ^ v.l[5]) | (hi.z ^ v.l[6]) | (hi.w ^ v.l[7]);
+        if (diff == 0) return cur;
+        pos = (pos + 1) & cap_mask;
+    }
+    return kEmptySlot;
+}
+
 // canon[j] = lowest row with the value of row j; rows[j] = row j of T as eight
 // consecutive words, so that a lookup by row number is one 32-byte access
 // instead of eight accesses to eight limb planes.
@@ -152,7 +169,7 @@ static __global__ void __launch_bounds__(kBlock) k_count(uint32_t* m, const uint
                     row = kEmptySlot;
                 }
             } else {
-                row = hash_find(slots, cap_mask, T, ts, v);
+                row = hash_find_rows(slots, cap_mask, rows, v);
             }
             if (row == kEmptySlot) atomicMin(bad, (unsigned long long)i);
         }
@@ -199,8 +216,8 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
         const size_t pass_end = pass_begin + chunk < D ? pass_begin + chunk : D;
         // whole wavefronts iterate together so that the cross-lane merge sees all 64
         // lanes; several elements per thread per trip keep more loads in flight
-        // (two when S is read as well, eight when only the hints are)
-        constexpr int E = CHECK_S ? 2 : 8;
+        // (four when S is read as well, eight when only the hints are)
+        constexpr int E = 8;
         for (size_t base = pass_begin; base < pass_end; base += E * kHistThreads) {
             size_t i[E];
             bool in_range[E];
@@ -235,7 +252,7 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
                     }
                     row[e] = r;
                 } else {
-                    if constexpr (CHECK_S) row[e] = hash_find(slots, cap_mask, T, ts, v[e]);
+                    if constexpr (CHECK_S) row[e] = hash_find_rows(slots, cap_mask, rows, v[e]);
                 }
                 // without the comparison a hint out of range is left for the caller's check to report
                 if (CHECK_S && row[e] == kEmptySlot) atomicMin(bad, (unsigned long long)i[e]);
