@@ -1072,9 +1072,8 @@ static int prove_core(const ProveCall& c) {
             tail.beta = to_dev(beta);
             tail.r_prev = to_dev(r_prev);
             // the kernel's rounds: up to the first one short enough for the host (kRoundHost), if there is one
-            int k_host = n - 6 > k + 1 ? n - 6 : k + 1;  // the first j > k with 2^(n-j-1) <= kHostPairs
-            static_assert(kHostPairs == 32, "k_host above is written for 32 pairs");
-            if (k_host > n) k_host = n;
+            int k_host = k + 1;
+            while (k_host < n && ((size_t)1 << (n - k_host - 1)) > kHostPairs) ++k_host;
             tail.nrounds = k_host - k;
             uint32_t* b_at = I.b_cur;
             size_t b_at_stride = I.b_cur_stride;
