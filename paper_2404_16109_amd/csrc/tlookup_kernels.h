@@ -127,7 +127,7 @@ __device__ __forceinline__ void count_merged(uint32_t* m, uint32_t row, bool val
         unsigned long long todo = __ballot(pending);
         if (todo == 0) return;
         int leader = __ffsll((long long)todo) - 1;
-        uint32_t lead_row = __shfl(row, leader, 64);
+        uint32_t lead_row = (uint32_t)__builtin_amdgcn_readlane((int)row, leader);  // leader is wave-uniform: no trip through LDS
         bool mine = pending && row == lead_row;
         uint32_t run = (uint32_t)__popcll(__ballot(mine));
         if (run >= 32) hot.add(m, lead_row, run);
@@ -265,7 +265,7 @@ k_count_lds(uint32_t* m, uint32_t* __restrict__ part, const uint32_t* __restrict
                     unsigned long long todo = __ballot(pending);
                     if (todo == 0) break;
                     int leader = __ffsll((long long)todo) - 1;
-                    uint32_t lead_row = __shfl(row[e], leader, 64);
+                    uint32_t lead_row = (uint32_t)__builtin_amdgcn_readlane((int)row[e], leader);  // wave-uniform lane: no trip through LDS
                     bool same_row = pending && row[e] == lead_row;
                     uint32_t run = (uint32_t)__popcll(__ballot(same_row));
                     // A long run goes to the wavefront's running total and a run of a few
